@@ -1,0 +1,441 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself -- brute
+force, a closed form, an identity from the paper, or a library routine on a special case.
+
+Citations name the paper's algorithms / equations / sections.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.optimize
+
+import oracle as O
+from workloads import random_tensor, uniform_factors
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def tview(T):
+    """numpy view indexed [i1, i2, i3]."""
+    return T.transpose(2, 1, 0)
+
+
+def signed_factors(dims, R, seed):
+    return [2.0 * u - 1.0 for u in uniform_factors(dims, R, seed)]
+
+
+def reconstruct(U, lam=None):
+    lam = np.ones(U[0].shape[1]) if lam is None else lam
+    return np.einsum("r,ir,jr,kr->ijk", lam, U[0], U[1], U[2])
+
+
+def krp(A, B):
+    """Column-wise Kronecker product with A's row index the slow one (notation section)."""
+    return np.einsum("ir,jr->ijr", A, B).reshape(A.shape[0] * B.shape[0], A.shape[1])
+
+
+# ------------------------------------------------------------------ MTTKRP (Alg. 1, MTTKRP line)
+
+@pytest.mark.parametrize("dims", [(5, 4, 3), (3, 5, 4), (1, 2, 3)])
+def test_mttkrp_brute_force_triple_loop(dims):
+    R = 2
+    T = random_tensor(dims, 11, signed=True)
+    U = signed_factors(dims, R, 12)
+    Tn = tview(T)
+    I1, I2, I3 = dims
+    want = [np.zeros((I1, R)), np.zeros((I2, R)), np.zeros((I3, R))]
+    for i1 in range(I1):
+        for i2 in range(I2):
+            for i3 in range(I3):
+                for r in range(R):
+                    t = Tn[i1, i2, i3]
+                    want[0][i1, r] += t * U[1][i2, r] * U[2][i3, r]
+                    want[1][i2, r] += t * U[0][i1, r] * U[2][i3, r]
+                    want[2][i3, r] += t * U[0][i1, r] * U[1][i2, r]
+    for mode in (1, 2, 3):
+        got = O.mttkrp(T, U, mode)
+        assert np.allclose(got, want[mode - 1], rtol=1e-13, atol=1e-14), mode
+
+
+def test_mttkrp_is_unfolding_times_explicit_krp():
+    # "the mode-n unfolding is multiplied with the Khatri-Rao product of all factor matrices except U(n)"
+    dims, R = (17, 13, 11), 7
+    T = random_tensor(dims, 21, signed=True)
+    U = signed_factors(dims, R, 22)
+    Tn = tview(T)
+    T1 = Tn.reshape(dims[0], -1)                       # columns indexed (i2, i3), i2 slow
+    T2 = Tn.transpose(1, 0, 2).reshape(dims[1], -1)    # (i1, i3)
+    T3 = Tn.transpose(2, 0, 1).reshape(dims[2], -1)    # (i1, i2)
+    want = [T1 @ krp(U[1], U[2]), T2 @ krp(U[0], U[2]), T3 @ krp(U[0], U[1])]
+    for mode in (1, 2, 3):
+        got = O.mttkrp(T, U, mode)
+        scale = np.abs(want[mode - 1]).max()
+        assert np.abs(got - want[mode - 1]).max() <= 1e-13 * scale * 50, mode
+
+
+def test_fused_mttkrp_column_blocks_equal_solo_results_bitwise():
+    # Eq. (1)/(2): the fused MTTKRP of concatenated factors is the concatenation of the solo MTTKRPs.
+    dims, ranks = (9, 8, 7), [1, 3, 2, 5, 11]
+    T = random_tensor(dims, 31, signed=True)
+    facs = [signed_factors(dims, r, 40 + k) for k, r in enumerate(ranks)]
+    fused = [np.hstack([f[n] for f in facs]) for n in range(3)]
+    for mode in (1, 2, 3):
+        big = O.mttkrp(T, fused, mode)
+        c = 0
+        for f, r in zip(facs, ranks):
+            solo = O.mttkrp(T, f, mode)
+            assert np.array_equal(big[:, c:c + r], solo), (mode, r)
+            c += r
+
+
+def test_mttkrp_element_matches_exact_sum():
+    dims, R = (6, 5, 4), 3
+    T = random_tensor(dims, 51, signed=True)
+    U = signed_factors(dims, R, 52)
+    Tn = tview(T)
+    for mode, row, col in [(1, 2, 1), (2, 4, 0), (3, 3, 2)]:
+        terms = []
+        for a in range(dims[0]):
+            for b in range(dims[1]):
+                for c in range(dims[2]):
+                    idx = (a, b, c)
+                    if idx[mode - 1] != row:
+                        continue
+                    others = [n for n in range(3) if n != mode - 1]
+                    k = U[others[0]][idx[others[0]], col] * U[others[1]][idx[others[1]], col]
+                    terms.append(Tn[a, b, c] * k)
+        v, sa = O.mttkrp_element(T, U, mode, row, col)
+        assert abs(v - math.fsum(terms)) <= 4e-16 * math.fsum(abs(t) for t in terms)
+        assert abs(sa - math.fsum(abs(t) for t in terms)) <= 1e-15 * sa
+        assert abs(O.mttkrp(T, U, mode)[row, col] - v) <= 1e-14 * sa
+
+
+# ------------------------------------------------------------------ Gram / Hadamard / solve
+
+def test_gram_of_khatri_rao_is_hadamard_of_grams():
+    # Alg. 1, Hadamard line: (A kr B)^T (A kr B) = A^T A * B^T B
+    A, B = signed_factors((13, 9, 1), 6, 61)[:2]
+    H = O.hadamard(O.gram(A), O.gram(B))
+    K = krp(A, B)
+    assert np.allclose(H, K.T @ K, rtol=1e-13, atol=1e-13)
+    assert np.array_equal(H, H.T)
+    assert np.allclose(O.gram(A), A.T @ A, rtol=1e-14, atol=1e-14)
+
+
+def test_norm_sq():
+    T = random_tensor((7, 6, 5), 71, signed=True)
+    assert abs(O.norm_sq(T) - math.fsum((T.ravel() ** 2).tolist())) <= 1e-14 * O.norm_sq(T)
+
+
+def test_cholesky_and_solve_against_lapack():
+    rng = np.random.default_rng(5)
+    for R in (1, 2, 5, 20):
+        A = rng.standard_normal((R + 3, R))
+        H = A.T @ A
+        rc, L = O.cholesky(H)
+        assert rc == 0
+        assert np.allclose(L, np.linalg.cholesky(H), rtol=1e-12, atol=1e-13)
+        assert np.allclose(np.triu(L, 1), 0.0)
+        b = rng.standard_normal(R)
+        x = O.cholesky_solve(L, b)
+        assert np.allclose(H @ x, b, rtol=0, atol=1e-10 * np.linalg.cond(H))
+        assert np.allclose(x, np.linalg.solve(H, b), rtol=1e-9, atol=1e-12 * np.linalg.cond(H))
+
+
+def test_cholesky_rejects_non_positive_definite():
+    assert O.cholesky(np.array([[1.0, 2.0], [2.0, 1.0]]))[0] == 1
+    assert O.cholesky(np.array([[0.0, 0.0], [0.0, 1.0]]))[0] == 1
+    assert O.cholesky(np.array([[np.nan]]))[0] == 1
+    assert O.cholesky(np.array([[np.inf]]))[0] == 1
+
+
+# ------------------------------------------------------------------ one ALS iteration (Alg. 1)
+
+def _lstsq_als_iteration(Tn, U):
+    """One ALS sweep where every update is the plain linear least-squares problem
+    min || T_(n)^T - KRP U_n^T ||, solved by LAPACK's SVD-based lstsq (not normal equations)."""
+    U = [u.copy() for u in U]
+    lam = None
+    unf = [Tn.reshape(Tn.shape[0], -1), Tn.transpose(1, 0, 2).reshape(Tn.shape[1], -1),
+           Tn.transpose(2, 0, 1).reshape(Tn.shape[2], -1)]
+    for n in range(3):
+        a, b = [m for m in range(3) if m != n]
+        K = krp(U[a], U[b])
+        X = np.linalg.lstsq(K, unf[n].T, rcond=None)[0].T
+        lam = np.linalg.norm(X, axis=0)
+        U[n] = X / lam
+    return U, lam
+
+
+def test_one_iteration_equals_three_least_squares_solves():
+    dims, R = (10, 9, 8), 3
+    T = random_tensor(dims, 81) + reconstruct(uniform_factors(dims, R, 82)).transpose(2, 1, 0)
+    init = uniform_factors(dims, R, 83)
+    m = O.Model(T, init, tol=-1.0, max_iters=5)
+    U, lam = init, None
+    for it in range(3):
+        m.iterate()
+        U, lam = _lstsq_als_iteration(tview(T), U)
+        s = m.state()
+        for n in range(3):
+            assert np.allclose(s["U"][n], U[n], rtol=1e-9, atol=1e-11), (it, n)
+        assert np.allclose(s["lam"], lam, rtol=1e-9)
+        assert np.allclose(np.linalg.norm(s["U"][2], axis=0), 1.0, rtol=1e-14)
+
+
+def test_fast_error_and_fit_equal_explicit_reconstruction():
+    # Alg. 1, error line (sign of the middle term corrected): e = ||T - T_hat||^2.
+    dims, R = (9, 7, 8), 4
+    T = random_tensor(dims, 91)
+    m = O.Model(T, uniform_factors(dims, R, 92), tol=-1.0, max_iters=20)
+    nT = np.linalg.norm(T)
+    for it in range(6):
+        m.iterate()
+        s = m.state()
+        res = tview(T) - reconstruct(s["U"], s["lam"])
+        e = float((res ** 2).sum())
+        assert abs(s["err"] - e) <= 1e-12 * nT ** 2, it
+        assert abs(s["fit"] - (1.0 - math.sqrt(e) / nT)) <= 1e-11, it
+
+
+def test_error_never_increases_and_noise_free_tensor_is_recovered():
+    dims, R = (20, 15, 10), 3
+    true = uniform_factors(dims, R, 101)
+    T = np.ascontiguousarray(reconstruct(true).transpose(2, 1, 0))
+    r = O.cp_als(T, uniform_factors(dims, R, 102), tol=-1.0, max_iters=400)
+    h = r["fit_history"]
+    assert len(h) == 400
+    # exact least squares per mode => the error cannot go up; near fit 1 the fast formula cancels
+    # ||T||^2 against two terms of the same size, so the fit is only resolved to about sqrt(eps)
+    far = h < 1.0 - 1e-4
+    assert far.sum() > 5 and np.all(np.diff(h[far]) >= -1e-12)
+    assert np.all(np.diff(h) >= -5e-8)
+    assert 1.0 - h[-1] < 1e-6
+    rel = np.linalg.norm(tview(T) - reconstruct(r["U"], r["lam"])) / np.linalg.norm(T)
+    assert rel < 1e-7
+    # factor congruence with the truth, up to permutation
+    for n in range(3):
+        tn = true[n] / np.linalg.norm(true[n], axis=0)
+        Cg = np.abs(tn.T @ r["U"][n])
+        assert np.all(Cg.max(axis=1) > 1 - 1e-6)
+
+
+def test_rank_one_als_is_the_higher_order_power_method():
+    dims = (8, 7, 6)
+    T = random_tensor(dims, 111)
+    Tn = tview(T)
+    u = [x[:, 0].copy() for x in uniform_factors(dims, 1, 112)]
+    m = O.Model(T, [x[:, None] for x in u], tol=-1.0, max_iters=10)
+    lam = 1.0
+    for it in range(4):
+        m.iterate()
+        # R = 1: H is the scalar (u_a.u_a)(u_b.u_b) and the update is the contraction divided by it
+        v = np.einsum("ijk,j,k->i", Tn, u[1], u[2]) / ((u[1] @ u[1]) * (u[2] @ u[2]))
+        u[0] = v / np.linalg.norm(v)
+        v = np.einsum("ijk,i,k->j", Tn, u[0], u[2]) / ((u[0] @ u[0]) * (u[2] @ u[2]))
+        u[1] = v / np.linalg.norm(v)
+        v = np.einsum("ijk,i,j->k", Tn, u[0], u[1]) / ((u[0] @ u[0]) * (u[1] @ u[1]))
+        lam = np.linalg.norm(v)
+        u[2] = v / lam
+        s = m.state()
+        for n in range(3):
+            assert np.allclose(s["U"][n][:, 0], u[n], rtol=1e-12, atol=1e-14)
+        assert abs(s["lam"][0] - lam) <= 1e-12 * lam
+
+
+def test_stop_rule_tolerance_and_iteration_cap():
+    dims, R = (12, 11, 10), 3
+    T = random_tensor(dims, 121) * 0.05 + reconstruct(uniform_factors(dims, R, 122)).transpose(2, 1, 0)
+    init = uniform_factors(dims, R, 123)
+    free = O.cp_als(T, init, tol=-1.0, max_iters=60)
+    assert free["status"] == O.MAX_ITERS and free["iters"] == 60
+    h = free["fit_history"]
+    tol = float(np.sort(np.abs(np.diff(h)))[len(h) // 2])   # a tolerance this trajectory crosses midway
+    first = next(i for i in range(1, len(h)) if abs(h[i] - h[i - 1]) < tol) + 1   # 1-based iteration
+    stopped = O.cp_als(T, init, tol=tol, max_iters=60)
+    assert stopped["status"] == O.CONVERGED and stopped["iters"] == first
+    assert stopped["fit"] == h[first - 1]
+    # "two consecutive iterations": never stops at iteration 1, even with a huge tolerance
+    assert O.cp_als(T, init, tol=10.0, max_iters=60)["iters"] == 2
+    assert O.cp_als(T, init, tol=10.0, max_iters=1)["status"] == O.MAX_ITERS
+
+
+def test_singular_normal_equations_stop_the_model():
+    dims, R = (6, 5, 4), 2
+    T = random_tensor(dims, 131)
+    init = uniform_factors(dims, R, 132)
+    init[1][:, 1] = 0.0
+    init[2][:, 1] = 0.0
+    r = O.cp_als(T, init, tol=-1.0, max_iters=5)
+    assert r["status"] == O.NUMERICAL and r["iters"] == 0
+    assert np.array_equal(r["U"][0], init[0])
+
+
+# ------------------------------------------------------------------ queue (Alg. 3)
+
+def _read_schedules():
+    out = []
+    with open(os.path.join(GOLD, "queue_schedules.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = [p.strip() for p in line.split(";")]
+            ints = lambda s: [int(x) for x in s.split(",")]
+            out.append((ints(parts[0]), ints(parts[1]), int(parts[2]), int(parts[3]), ints(parts[4]), ints(parts[5])))
+    return out
+
+
+@pytest.mark.parametrize("case", _read_schedules())
+def test_queue_schedules_computed_by_hand(case):
+    ranks, mits, rstar, slots, widths, order = case
+    dims = (5, 4, 3)
+    T = random_tensor(dims, 141)
+    models = [dict(rank=r, init=uniform_factors(dims, r, 150 + k), tol=-1.0, max_iters=mi, flags=0, ls_alpha=1.0)
+              for k, (r, mi) in enumerate(zip(ranks, mits))]
+    out = O.cals(T, models, rstar, slots)
+    assert list(out["total_rank_log"]) == widths
+    assert list(out["retire_order"]) == order
+    assert out["rounds"] == len(widths)
+    assert list(out["iters"]) == mits
+
+
+def test_cals_results_do_not_depend_on_co_residents():
+    # "without numerically affecting any of the invocations": lock-step CALS == solo CP-ALS, bit for bit
+    dims = (9, 8, 7)
+    T = random_tensor(dims, 161) + reconstruct(uniform_factors(dims, 2, 162)).transpose(2, 1, 0)
+    ranks = [1, 2, 3, 2, 4, 1]
+    models = [dict(rank=r, init=uniform_factors(dims, r, 170 + k), tol=1e-4, max_iters=40, flags=0, ls_alpha=1.0)
+              for k, r in enumerate(ranks)]
+    a = O.cals(T, models, max_total_rank=sum(ranks))
+    b = O.cals(T, models, max_total_rank=5, max_slots=2)
+    for k, mdl in enumerate(models):
+        solo = O.cp_als(T, mdl["init"], tol=1e-4, max_iters=40)
+        for res in (a, b):
+            assert res["iters"][k] == solo["iters"] and res["status"][k] == solo["status"]
+            assert res["fit"][k] == solo["fit"]
+            for n in range(3):
+                assert np.array_equal(res["U"][k][n], solo["U"][n])
+    assert sorted(a["retire_order"]) == list(range(len(ranks)))
+    assert sorted(b["retire_order"]) == list(range(len(ranks)))
+    # with everything resident the retirement order is (iteration count, slot)
+    assert list(a["retire_order"]) == sorted(range(len(ranks)), key=lambda k: (a["iters"][k], k))
+    with pytest.raises(ValueError):
+        O.cals(T, models, max_total_rank=3)
+
+
+# ------------------------------------------------------------------ non-negativity (Sec. 5)
+
+def test_nnls_matches_lawson_hanson_library_and_kkt():
+    rng = np.random.default_rng(7)
+    for R in (1, 2, 3, 6, 12, 20):
+        for trial in range(6):
+            A = rng.standard_normal((R + 5, R))
+            b = rng.standard_normal(R + 5) + 0.3
+            H, m = A.T @ A, A.T @ b
+            rc, x, P = O.nnls_row(H, m)
+            assert rc == 0
+            want, _ = scipy.optimize.nnls(A, b)
+            assert np.allclose(x, want, rtol=1e-8, atol=1e-10)
+            w = m - H @ x
+            assert np.all(x >= 0)
+            assert np.all(np.abs(w[x > 0]) <= 1e-9 * max(1.0, np.abs(m).max()))
+            assert np.all(w[x == 0] <= 1e-9 * max(1.0, np.abs(m).max()))
+            assert P == sum(1 << j for j in range(R) if x[j] > 0)
+            # warm start from any set gives the same (unique) minimiser
+            for warm in (P, (1 << R) - 1, 1):
+                rc2, x2, _ = O.nnls_row(H, m, warm)
+                assert rc2 == 0 and np.allclose(x2, x, rtol=1e-8, atol=1e-10)
+
+
+def test_nnls_brute_force_over_supports():
+    rng = np.random.default_rng(8)
+    R = 5
+    for trial in range(10):
+        A = rng.standard_normal((R + 2, R))
+        b = rng.standard_normal(R + 2)
+        H, m = A.T @ A, A.T @ b
+        best, bestx = 0.0, np.zeros(R)
+        for k in range(1, R + 1):
+            for S in itertools.combinations(range(R), k):
+                S = list(S)
+                xs = np.linalg.solve(H[np.ix_(S, S)], m[S])
+                if np.all(xs >= 0):
+                    x = np.zeros(R)
+                    x[S] = xs
+                    f = 0.5 * x @ H @ x - m @ x
+                    if f < best:
+                        best, bestx = f, x
+        rc, x, _ = O.nnls_row(H, m)
+        assert rc == 0 and np.allclose(x, bestx, rtol=1e-8, atol=1e-10)
+
+
+def test_nonneg_als_equals_plain_als_when_solution_is_positive_and_stays_nonneg_otherwise():
+    dims, R = (10, 9, 8), 2
+    true = uniform_factors(dims, R, 181)
+    T = np.ascontiguousarray(reconstruct([t + 0.5 for t in true]).transpose(2, 1, 0))
+    init = uniform_factors(dims, R, 182)
+    near = [t + 0.5 + 0.05 * u for t, u in zip(true, init)]      # start close to the positive truth
+    a = O.cp_als(T, near, tol=-1.0, max_iters=8)
+    b = O.cp_als(T, near, tol=-1.0, max_iters=8, flags=O.FLAG_NONNEG)
+    assert min(u.min() for u in a["U"]) > 0
+    assert np.allclose(a["fit_history"], b["fit_history"], rtol=0, atol=1e-12)
+    for n in range(3):
+        assert np.allclose(a["U"][n], b["U"][n], rtol=1e-9, atol=1e-12)
+    # a signed tensor: constrained factors stay >= 0, error still never increases, fast error still exact
+    T2 = random_tensor(dims, 183, signed=True) + tview(T).transpose(2, 1, 0) * 0.3
+    T2 = np.ascontiguousarray(T2)
+    m = O.Model(T2, init, tol=-1.0, max_iters=30, flags=O.FLAG_NONNEG)
+    prev = None
+    for it in range(12):
+        m.iterate()
+        s = m.state()
+        assert min(u.min() for u in s["U"]) >= 0.0
+        e = float(((tview(T2) - reconstruct(s["U"], s["lam"])) ** 2).sum())
+        assert abs(e - s["err"]) <= 1e-11 * np.linalg.norm(T2) ** 2
+        if prev is not None:
+            assert s["err"] <= prev + 1e-10
+        prev = s["err"]
+    unc = O.cp_als(T2, init, tol=-1.0, max_iters=12)
+    assert min(u.min() for u in unc["U"]) < 0   # the constraint was active in this problem
+
+
+# ------------------------------------------------------------------ line search (Sec. 5)
+
+def test_line_search_accepts_only_improvements_and_error_stays_exact():
+    dims, R = (14, 12, 10), 3
+    # collinear truth => slow ALS convergence, where extrapolation is worth something
+    base = uniform_factors(dims, 1, 191)
+    true = [np.hstack([b + 0.15 * u[:, [r]] for r in range(R)]) for b, u in zip(base, uniform_factors(dims, R, 192))]
+    T = np.ascontiguousarray(reconstruct(true).transpose(2, 1, 0)) + 0.001 * random_tensor(dims, 193, signed=True)
+    init = uniform_factors(dims, R, 194)
+    m = O.Model(T, init, tol=-1.0, max_iters=200, flags=O.FLAG_LINESEARCH, alpha=1.3)
+    plain = O.Model(T, init, tol=-1.0, max_iters=200)
+    nT2 = np.linalg.norm(T) ** 2
+    prev, acc_prev = None, 0
+    for it in range(40):
+        m.iterate()
+        plain.iterate()
+        s = m.state()
+        e = float(((tview(T) - reconstruct(s["U"], s["lam"])) ** 2).sum())
+        assert abs(e - s["err"]) <= 1e-11 * nT2, it
+        if prev is not None:
+            assert s["err"] <= prev * (1 + 1e-12)
+        if it == 0:
+            assert s["ls_accepted"] == 0 and s["err"] == plain.state()["err"]   # nothing to extrapolate from yet
+        if s["ls_accepted"] > acc_prev:
+            assert np.array_equal(s["lam"], np.ones(R))          # accepted point carries lambda = 1
+        prev, acc_prev = s["err"], s["ls_accepted"]
+    assert acc_prev > 0
+    assert m.state()["err"] < plain.state()["err"]               # and it did help on this problem
+
+
+def test_line_search_with_alpha_one_changes_nothing_material():
+    dims, R = (8, 7, 6), 2
+    T = random_tensor(dims, 201)
+    init = uniform_factors(dims, R, 202)
+    a = O.cp_als(T, init, tol=-1.0, max_iters=15)
+    b = O.cp_als(T, init, tol=-1.0, max_iters=15, flags=O.FLAG_LINESEARCH, alpha=1.0)
+    assert np.allclose(a["fit_history"], b["fit_history"], rtol=0, atol=1e-13)

@@ -1,0 +1,125 @@
+"""Seeded generators: tensors in first-index-fastest order, and column-major starting points.
+
+Random numbers come from numpy's Philox counter-based generator, keyed by (seed, stream), so
+that any slab of a large tensor can be produced on its own and in any order.
+
+Memory convention: a tensor T of dims (I1, I2, I3) is returned as a C-contiguous numpy array
+of shape (I3, I2, I1), i.e. element (i1, i2, i3) sits at flat offset i1 + I1*(i2 + I2*i3).
+Factor matrices are returned Fortran-ordered with shape (I_n, R) (column-major, ld = I_n).
+"""
+from __future__ import annotations
+
+import math
+from concurrent.futures import ThreadPoolExecutor
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+from .configs import WorkloadConfig
+
+
+def _rng(seed: int, stream: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[int(seed), int(stream)]))
+
+
+def uniform_factors(dims: Sequence[int], rank: int, seed: int) -> List[np.ndarray]:
+    """Three Uniform[0,1) matrices (I_n x rank), column-major."""
+    out = []
+    for n, I in enumerate(dims):
+        g = _rng(seed, n)
+        out.append(np.asfortranarray(g.random((int(I), int(rank)))))
+    return out
+
+
+def random_tensor(dims: Sequence[int], seed: int, signed: bool = False) -> np.ndarray:
+    """A dense tensor of iid entries (Uniform[0,1), or standard normal when signed)."""
+    I1, I2, I3 = (int(d) for d in dims)
+    g = _rng(seed, 7)
+    return g.standard_normal((I3, I2, I1)) if signed else g.random((I3, I2, I1))
+
+
+def _collinear_factor(I: int, R: int, c: float, seed: int, stream: int) -> np.ndarray:
+    """I x R matrix with unit columns whose pairwise cosine is exactly c (up to rounding)."""
+    g = _rng(seed, stream)
+    Q, _ = np.linalg.qr(g.standard_normal((I, R)))
+    C = np.linalg.cholesky(c * np.ones((R, R)) + (1.0 - c) * np.eye(R))
+    return np.asfortranarray(Q @ C.T)
+
+
+def _eem_factors(dims: Sequence[int], R: int, seed: int) -> List[np.ndarray]:
+    """samples x emission x excitation: lognormal concentrations, Gaussian-peak spectra."""
+    I1, I2, I3 = (int(d) for d in dims)
+    g = _rng(seed, 0)
+    conc = np.exp(g.standard_normal((I1, R)))
+    em_c = g.uniform(0.15, 0.85, R) * I2
+    em_w = g.uniform(0.05, 0.15, R) * I2
+    ex_c = g.uniform(0.15, 0.85, R) * I3
+    ex_w = g.uniform(0.08, 0.20, R) * I3
+    x2 = np.arange(I2)[:, None]
+    x3 = np.arange(I3)[:, None]
+    em = np.exp(-0.5 * ((x2 - em_c[None, :]) / em_w[None, :]) ** 2)
+    ex = np.exp(-0.5 * ((x3 - ex_c[None, :]) / ex_w[None, :]) ** 2)
+    return [np.asfortranarray(conc), np.asfortranarray(em), np.asfortranarray(ex)]
+
+
+def true_factors(cfg: WorkloadConfig) -> List[np.ndarray]:
+    if cfg.kind == "uniform":
+        return uniform_factors(cfg.dims, cfg.true_rank, cfg.tensor_seed)
+    if cfg.kind == "eem":
+        return _eem_factors(cfg.dims, cfg.true_rank, cfg.tensor_seed)
+    if cfg.kind == "collinear":
+        return [_collinear_factor(int(I), cfg.true_rank, cfg.collinearity, cfg.tensor_seed, n)
+                for n, I in enumerate(cfg.dims)]
+    raise ValueError(cfg.kind)
+
+
+def _low_rank_norm_sq(F: Sequence[np.ndarray]) -> float:
+    G = np.ones((F[0].shape[1],) * 2)
+    for U in F:
+        G = G * (U.T @ U)
+    return float(G.sum())
+
+
+def make_tensor(cfg: WorkloadConfig, dims: Sequence[int] | None = None, threads: int = 8,
+                out: np.ndarray | None = None) -> np.ndarray:
+    """Low-rank tensor plus Gaussian noise of std eta * rms(noise-free tensor), slab by slab.
+
+    `dims` may shrink the configuration (same recipe, smaller tensor) for quick tests.
+    """
+    if dims is not None and tuple(dims) != tuple(cfg.dims):
+        cfg = WorkloadConfig(**{**cfg.__dict__, "dims": tuple(int(d) for d in dims)})
+    I1, I2, I3 = cfg.dims
+    A, B, C = true_factors(cfg)
+    sigma = cfg.noise * math.sqrt(_low_rank_norm_sq([A, B, C]) / (float(I1) * I2 * I3))
+    T = out if out is not None else np.empty((I3, I2, I1), dtype=np.float64)
+    assert T.shape == (I3, I2, I1) and T.dtype == np.float64 and T.flags.c_contiguous
+    At = np.ascontiguousarray(A.T)
+
+    def slab(i3: int) -> None:
+        S = T[i3]
+        np.matmul(B * C[i3][None, :], At, out=S)
+        if sigma > 0.0:
+            S += sigma * _rng(cfg.noise_seed, i3 + 16).standard_normal((I2, I1))
+        if cfg.clip_at_zero:
+            np.maximum(S, 0.0, out=S)
+
+    if I3 * I2 * I1 < (1 << 22) or threads <= 1:
+        for i3 in range(I3):
+            slab(i3)
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(slab, range(I3)))
+    return T
+
+
+def make_inits(dims: Sequence[int], ranks: Sequence[int], seeds: Sequence[int]) -> List[List[np.ndarray]]:
+    """Uniform[0,1) starting points, one (U1, U2, U3) triple per model."""
+    return [uniform_factors(dims, r, s) for r, s in zip(ranks, seeds)]
+
+
+def make_models(cfg: WorkloadConfig, dims: Sequence[int] | None = None) -> List[dict]:
+    """Model descriptors in enqueue order: rank, init, tol, max_iters, flags, ls_alpha."""
+    d = tuple(dims) if dims is not None else cfg.dims
+    inits = make_inits(d, cfg.ranks, cfg.init_seeds)
+    return [dict(model_id=m, rank=r, init=inits[m], tol=cfg.tol, max_iters=cfg.max_iters,
+                 flags=cfg.flags, ls_alpha=cfg.ls_alpha) for m, r in enumerate(cfg.ranks)]
