@@ -1,0 +1,140 @@
+/*
+ * cals.h -- C boundary of the MI355X (gfx950) implementation of Concurrent ALS (CALS):
+ * many CP-ALS instances on one dense 3-way fp64 tensor, advanced in lock-step so that the three
+ * MTTKRPs of an iteration are each ONE fused contraction over the concatenated factor matrices.
+ *
+ * The calls follow the problem statement of the paper's full algorithm (Alg. 3): a tensor, an
+ * input queue of starting points, a main loop (fill, advance all active instances one iteration,
+ * remove converged instances), and an output queue.
+ *
+ * Conventions
+ *   - Every function returns CALS_OK (0) or a negative CALS_E_* code; nothing throws or aborts.
+ *   - "host" / "device" on a pointer says where the memory lives.  The library never frees a
+ *     caller pointer.
+ *   - Tensor memory order: first index fastest, element (i1,i2,i3) at i1 + I1*(i2 + I2*i3).
+ *   - Per-model factor matrices cross the boundary column-major, I_n x rank, ld = I_n.
+ *   - Device multi-matrices (cals_mttkrp) are ROW-major: row i of mode n holds the total_rank
+ *     concatenated columns of all models, leading dimension `ld` doubles.
+ *   - A context is not thread-safe.  All work is enqueued on the stream given at creation.
+ *   - The library needs its HIP code object; there is no CPU fallback of any kind.
+ */
+#ifndef CALS_H
+#define CALS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CALS_OK 0
+#define CALS_E_INVALID (-1)     /* bad argument (null pointer, size, NaN/Inf, rank out of range) */
+#define CALS_E_STATE (-2)       /* call not allowed in this state (e.g. no tensor yet)           */
+#define CALS_E_NOMEM (-3)       /* host or device allocation failed                             */
+#define CALS_E_HIP (-4)         /* a HIP runtime call failed                                    */
+#define CALS_E_UNSUPPORTED (-5) /* valid request the library does not implement                 */
+#define CALS_E_NOTFOUND (-6)    /* unknown model id / model not finished                        */
+
+/* model status (cals_result.status) */
+#define CALS_RUNNING 0
+#define CALS_CONVERGED 1   /* |fit - fit_prev| < tol at an iteration >= 2            */
+#define CALS_MAX_ITERS 2   /* iteration cap reached                                   */
+#define CALS_NUMERICAL 3   /* normal equations not positive definite; last good point */
+
+/* per-model flags (cals_enqueue_model) */
+#define CALS_MODEL_NONNEG 1u     /* non-negative factors by an active-set method (Sec. 5)      */
+#define CALS_MODEL_LINESEARCH 2u /* extrapolate after each iteration, keep if better (Sec. 5)  */
+
+/* context flags (cals_options.flags) */
+#define CALS_CTX_TIMING 1u /* bracket every MTTKRP launch with HIP events (read by cals_get_stats) */
+
+#define CALS_MAX_RANK 32 /* largest number of components of one model */
+
+typedef struct cals_ctx cals_ctx; /* opaque; one per tensor */
+
+typedef struct {
+  int64_t max_total_rank; /* R*: width of the factor multi-matrix buffers (Sec. 4); >= largest rank */
+  int32_t max_slots;      /* cap on simultaneously active models; 0 = limited by R* only            */
+  int32_t device;         /* HIP device ordinal                                                     */
+  void* stream;           /* hipStream_t to enqueue on (0 = the null stream); never created here    */
+  uint32_t flags;         /* CALS_CTX_*                                                             */
+} cals_options;
+
+typedef struct {
+  int64_t model_id; /* enqueue order: 0,1,2,... */
+  int32_t rank;
+  int32_t iters;  /* completed iterations */
+  int32_t status; /* CALS_CONVERGED | CALS_MAX_ITERS | CALS_NUMERICAL */
+  int32_t ls_accepted; /* accepted extrapolation steps */
+  double fit;     /* 1 - ||T - model|| / ||T|| after the last completed iteration */
+  double error;   /* ||T - model||^2 by the fast formula (Alg. 1, error line)     */
+} cals_result;
+
+typedef struct {
+  int64_t rounds;            /* main-loop rounds executed (Alg. 3)                           */
+  int64_t models_retired;
+  int64_t models_queued;     /* still waiting in the input queue                             */
+  int32_t n_active;
+  int32_t total_rank;        /* fused width right now                                        */
+  double tensor_norm_sq;     /* ||T||^2                                                      */
+  double mttkrp_flops;       /* algorithmic: 2 * fused width * prod(I) per launch, summed    */
+  double mttkrp_ms[3];       /* per mode, main contraction kernel only (needs CALS_CTX_TIMING) */
+  double reduce_ms[3];       /* per mode, split-K reduction kernel (needs CALS_CTX_TIMING)     */
+  int64_t mttkrp_launches[3];
+} cals_stats;
+
+/* Create / destroy a context.  `opt` is copied.  Errors: INVALID (null, R* < 1, slots < 0), HIP. */
+int cals_create(cals_ctx** out, const cals_options* opt);
+int cals_destroy(cals_ctx* c);
+
+/* Hand over the tensor (Alg. 3 input T).  dims = {I1,I2,I3}, each >= 1, product < 2^40.
+ * on_device = 1: `data` is a device pointer, BORROWED until cals_destroy (the caller keeps it
+ * alive and unchanged); on_device = 0: `data` is a host pointer and is copied.  Computes ||T||^2
+ * (needed once by the error formula of Alg. 1) and rejects a tensor with a NaN/Inf entry.
+ * One tensor per context: a second call returns CALS_E_STATE. */
+int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], int on_device);
+
+/* Append a starting point to the input queue (Alg. 3, Q_in).  init[n] is a HOST pointer to the
+ * column-major I_n x rank starting factor of mode n+1; it is copied.  tol < 0 means "never stop
+ * by tolerance" (fixed iteration count).  ls_alpha is read only with CALS_MODEL_LINESEARCH.
+ * Errors: STATE (no tensor), INVALID (rank < 1, > CALS_MAX_RANK or > R*; max_iters < 1; NaN
+ * tol/alpha; NaN/Inf in init), UNSUPPORTED (NONNEG together with LINESEARCH). */
+int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const init[3], double tol, int32_t max_iters,
+                       uint32_t flags, double ls_alpha, int64_t* model_id);
+
+/* Run up to n_rounds rounds of the main loop of Alg. 3 (fill from the queue front until the next
+ * model does not fit; one fused ALS iteration of all active models; retire in slot order and
+ * compact).  Stops early when the queue is empty and nothing is active.  *n_retired (may be
+ * null) receives the number of models that left during this call.  Synchronises the stream. */
+int cals_iterate(cals_ctx* c, int32_t n_rounds, int32_t* n_retired);
+
+/* cals_iterate until the input queue is empty and no model is active. */
+int cals_run(cals_ctx* c);
+
+/* Pop finished models from the output queue (Alg. 3, Q_out) in retirement order: up to `cap`
+ * results are written to `out` (host), *n receives how many. */
+int cals_poll_retired(cals_ctx* c, cals_result* out, int32_t cap, int32_t* n);
+
+/* Factors of a FINISHED model: U[n] (host, column-major I_n x rank, may be null to skip) and
+ * lambda (host, rank doubles, may be null).  The model tensor is sum_r lambda[r] u1_r o u2_r o u3_r.
+ * Errors: NOTFOUND (unknown id or model not finished yet). */
+int cals_get_factors(cals_ctx* c, int64_t model_id, double* const U[3], double* lambda);
+
+/* The fused MTTKRP alone (Eq. (2); Alg. 2, fused-MTTKRP line), for parity and roofline runs:
+ *   M[i_mode, c] = sum over the other two indices of T[i1,i2,i3] * Ua[ia,c] * Ub[ib,c],  c < total_rank.
+ * mode is 1, 2 or 3.  U_dev[n] (device, row-major I_n x ld) for the two modes != mode (the third
+ * pointer is ignored and may be null); M_dev (device, row-major I_mode x ld) is overwritten in
+ * columns [0, total_rank); ld >= total_rank.  Uses the context's tensor, stream and workspace. */
+int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const U_dev[3],
+                double* M_dev);
+
+/* Counters and timings (see cals_stats).  Synchronises the stream when timing is on. */
+int cals_get_stats(cals_ctx* c, cals_stats* s);
+
+/* Static description of an error code. */
+const char* cals_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CALS_H */

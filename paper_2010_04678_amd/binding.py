@@ -1,0 +1,234 @@
+"""ctypes binding of the C-ABI in include/cals.h: argument marshalling only.
+
+PyTorch is used for device memory and streams (the tensor and the multi-matrices handed to
+cals_mttkrp are torch CUDA tensors; the library enqueues on torch's current stream).  There is no
+Python or CPU implementation of any step here: without the built HIP library every call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+FLAG_NONNEG, FLAG_LINESEARCH = 1, 2
+CTX_TIMING = 1
+RUNNING, CONVERGED, MAX_ITERS, NUMERICAL = 0, 1, 2, 3
+MAX_RANK = 32
+
+EXPORTS = ["cals_create", "cals_destroy", "cals_submit_tensor", "cals_enqueue_model", "cals_iterate", "cals_run",
+           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_get_stats", "cals_strerror"]
+
+
+class CalsError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__("%s failed: %s (%d)" % (what, _strerror(code), code))
+        self.code = code
+
+
+class _Options(C.Structure):
+    _fields_ = [("max_total_rank", C.c_int64), ("max_slots", C.c_int32), ("device", C.c_int32),
+                ("stream", C.c_void_p), ("flags", C.c_uint32)]
+
+
+class _Result(C.Structure):
+    _fields_ = [("model_id", C.c_int64), ("rank", C.c_int32), ("iters", C.c_int32), ("status", C.c_int32),
+                ("ls_accepted", C.c_int32), ("fit", C.c_double), ("error", C.c_double)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("rounds", C.c_int64), ("models_retired", C.c_int64), ("models_queued", C.c_int64),
+                ("n_active", C.c_int32), ("total_rank", C.c_int32), ("tensor_norm_sq", C.c_double),
+                ("mttkrp_flops", C.c_double), ("mttkrp_ms", C.c_double * 3), ("reduce_ms", C.c_double * 3),
+                ("mttkrp_launches", C.c_int64 * 3)]
+
+
+@dataclass
+class Result:
+    model_id: int
+    rank: int
+    iters: int
+    status: int
+    ls_accepted: int
+    fit: float
+    error: float
+
+
+@dataclass
+class Stats:
+    rounds: int
+    models_retired: int
+    models_queued: int
+    n_active: int
+    total_rank: int
+    tensor_norm_sq: float
+    mttkrp_flops: float
+    mttkrp_ms: List[float]
+    reduce_ms: List[float]
+    mttkrp_launches: List[int]
+
+
+_lib: Optional[C.CDLL] = None
+_dp = C.POINTER(C.c_double)
+
+
+def library_path() -> str:
+    return os.path.join(HERE, "libcals_hip.so")
+
+
+def load_library() -> C.CDLL:
+    """Load the built HIP library.  Never builds, never falls back: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError("HIP library %s is not built; run `python -m paper_2010_04678_amd.build` "
+                          "(there is no CPU fallback)" % path)
+    L = C.CDLL(path)
+    vp = C.c_void_p
+    L.cals_create.argtypes = [C.POINTER(vp), C.POINTER(_Options)]
+    L.cals_destroy.argtypes = [vp]
+    L.cals_submit_tensor.argtypes = [vp, vp, C.POINTER(C.c_int64), C.c_int]
+    L.cals_enqueue_model.argtypes = [vp, C.c_int32, C.POINTER(vp), C.c_double, C.c_int32, C.c_uint32, C.c_double,
+                                     C.POINTER(C.c_int64)]
+    L.cals_iterate.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32)]
+    L.cals_run.argtypes = [vp]
+    L.cals_poll_retired.argtypes = [vp, C.POINTER(_Result), C.c_int32, C.POINTER(C.c_int32)]
+    L.cals_get_factors.argtypes = [vp, C.c_int64, C.POINTER(vp), vp]
+    L.cals_mttkrp.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(vp), vp]
+    L.cals_get_stats.argtypes = [vp, C.POINTER(_Stats)]
+    L.cals_strerror.argtypes = [C.c_int]
+    L.cals_strerror.restype = C.c_char_p
+    for name in EXPORTS:
+        if name != "cals_strerror":
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _strerror(code: int) -> str:
+    try:
+        return load_library().cals_strerror(code).decode()
+    except Exception:
+        return "error"
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise CalsError(rc, what)
+
+
+class Context:
+    """One tensor, one queue of models (cals_ctx).  Methods mirror the C calls one to one."""
+
+    def __init__(self, max_total_rank: int, max_slots: int = 0, device: int = 0, stream: Optional[int] = None,
+                 flags: int = 0):
+        self._L = load_library()
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream(device).cuda_stream
+        opt = _Options(int(max_total_rank), int(max_slots), int(device), C.c_void_p(int(stream)), int(flags))
+        h = C.c_void_p()
+        _check(self._L.cals_create(C.byref(h), C.byref(opt)), "cals_create")
+        self._h = h
+        self.dims = None
+        self._keep = []          # borrowed device tensors must outlive the context
+        self._ranks = {}
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            self._L.cals_destroy(self._h)
+            self._h = None
+            self._keep = []
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- cals_submit_tensor
+    def submit_tensor(self, T) -> None:
+        """T: torch CUDA float64 tensor (borrowed) or numpy array (copied), shape (I3, I2, I1) C-contiguous,
+        i.e. element (i1,i2,i3) at i1 + I1*(i2 + I2*i3)."""
+        if isinstance(T, np.ndarray):
+            assert T.dtype == np.float64 and T.ndim == 3 and T.flags.c_contiguous
+            dims = (C.c_int64 * 3)(T.shape[2], T.shape[1], T.shape[0])
+            _check(self._L.cals_submit_tensor(self._h, T.ctypes.data, dims, 0), "cals_submit_tensor")
+            self.dims = (T.shape[2], T.shape[1], T.shape[0])
+        else:
+            import torch
+            assert T.is_cuda and T.dtype == torch.float64 and T.dim() == 3 and T.is_contiguous()
+            dims = (C.c_int64 * 3)(T.shape[2], T.shape[1], T.shape[0])
+            self._keep.append(T)
+            _check(self._L.cals_submit_tensor(self._h, T.data_ptr(), dims, 1), "cals_submit_tensor")
+            self.dims = (T.shape[2], T.shape[1], T.shape[0])
+
+    # -- cals_enqueue_model
+    def enqueue_model(self, init: Sequence[np.ndarray], tol: float = -1.0, max_iters: int = 50, flags: int = 0,
+                      ls_alpha: float = 1.0) -> int:
+        U = [np.asfortranarray(u, dtype=np.float64) for u in init]
+        rank = int(U[0].shape[1])
+        for n in range(3):
+            if self.dims is not None and U[n].shape != (self.dims[n], rank):
+                raise ValueError("init[%d] has shape %s, expected %s" % (n, U[n].shape, (self.dims[n], rank)))
+        ptrs = (C.c_void_p * 3)(*[u.ctypes.data for u in U])
+        mid = C.c_int64(-1)
+        _check(self._L.cals_enqueue_model(self._h, rank, ptrs, float(tol), int(max_iters), int(flags),
+                                          float(ls_alpha), C.byref(mid)), "cals_enqueue_model")
+        self._ranks[mid.value] = rank
+        return mid.value
+
+    # -- cals_iterate / cals_run
+    def iterate(self, n_rounds: int = 1) -> int:
+        n = C.c_int32(0)
+        _check(self._L.cals_iterate(self._h, int(n_rounds), C.byref(n)), "cals_iterate")
+        return n.value
+
+    def run(self) -> None:
+        _check(self._L.cals_run(self._h), "cals_run")
+
+    # -- cals_poll_retired
+    def poll_retired(self, cap: int = 1024) -> List[Result]:
+        buf = (_Result * cap)()
+        n = C.c_int32(0)
+        _check(self._L.cals_poll_retired(self._h, buf, cap, C.byref(n)), "cals_poll_retired")
+        return [Result(r.model_id, r.rank, r.iters, r.status, r.ls_accepted, r.fit, r.error) for r in buf[:n.value]]
+
+    # -- cals_get_factors
+    def get_factors(self, model_id: int):
+        rank = self._ranks[model_id]
+        U = [np.zeros((self.dims[n], rank), order="F") for n in range(3)]
+        lam = np.zeros(rank)
+        ptrs = (C.c_void_p * 3)(*[u.ctypes.data for u in U])
+        _check(self._L.cals_get_factors(self._h, int(model_id), ptrs, lam.ctypes.data), "cals_get_factors")
+        return U, lam
+
+    # -- cals_mttkrp
+    def mttkrp(self, mode: int, U_dev: Sequence, M_dev, total_rank: Optional[int] = None) -> None:
+        """U_dev[n]: torch CUDA float64 (I_n, ld) row-major multi-matrices (the one for `mode` may be None);
+        M_dev: (I_mode, ld), columns [0,total_rank) overwritten."""
+        ld = int(M_dev.shape[1])
+        tr = int(total_rank) if total_rank is not None else ld
+        ptrs = (C.c_void_p * 3)()
+        for n in range(3):
+            u = U_dev[n]
+            if u is None:
+                ptrs[n] = None
+                continue
+            assert u.is_cuda and u.is_contiguous() and u.shape[1] == ld and u.shape[0] == self.dims[n]
+            ptrs[n] = u.data_ptr()
+        assert M_dev.is_cuda and M_dev.is_contiguous() and M_dev.shape[0] == self.dims[mode - 1]
+        _check(self._L.cals_mttkrp(self._h, int(mode), tr, ld, ptrs, M_dev.data_ptr()), "cals_mttkrp")
+
+    # -- cals_get_stats
+    def stats(self) -> Stats:
+        s = _Stats()
+        _check(self._L.cals_get_stats(self._h, C.byref(s)), "cals_get_stats")
+        return Stats(s.rounds, s.models_retired, s.models_queued, s.n_active, s.total_rank, s.tensor_norm_sq,
+                     s.mttkrp_flops, list(s.mttkrp_ms), list(s.reduce_ms), list(s.mttkrp_launches))

@@ -1,0 +1,572 @@
+// C boundary and host scheduler of the CALS library: the queue logic of the paper's full algorithm
+// (Alg. 3) around the device kernels.  One round = fill the multi-matrices from the queue front,
+// advance every active model one ALS iteration with three fused MTTKRPs, read back the per-model
+// fits, retire in slot order, compact.  The only host-visible data dependency per round is the
+// retire decision.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <map>
+#include <new>
+#include <vector>
+
+#include "../../include/cals.h"
+#include "cals_internal.h"
+
+using namespace cals;
+
+#define HIP_TRY(expr)                         \
+  do {                                        \
+    hipError_t e__ = (expr);                  \
+    if (e__ != hipSuccess) {                  \
+      (void)hipGetLastError();                \
+      return CALS_E_HIP;                      \
+    }                                         \
+  } while (0)
+#define CALS_TRY(expr)            \
+  do {                            \
+    int rc__ = (expr);            \
+    if (rc__ != CALS_OK) return rc__; \
+  } while (0)
+
+namespace {
+
+struct PendingModel {
+  int64_t id;
+  int rank;
+  double tol;
+  int max_iters;
+  uint32_t flags;
+  double alpha;
+  std::vector<double> init[3];  // row-major I_n x rank
+};
+
+struct ActiveModel {
+  int64_t id;
+  int sid, col, rank;
+  double tol;
+  int max_iters;
+  uint32_t flags;
+  double alpha;
+  double fit_prev;
+};
+
+struct RetiredModel {
+  cals_result res;
+  std::vector<double> U[3];     // column-major I_n x rank
+  std::vector<double> lambda;
+};
+
+struct TimedLaunch { hipEvent_t ev[4]; int mode; bool reduced; };
+
+}  // namespace
+
+struct cals_ctx {
+  cals_options opt;
+  hipStream_t stream = nullptr;
+  int num_cus = 0;
+  bool has_tensor = false;
+  int64_t dims[3] = {0, 0, 0};
+  const double* T = nullptr;
+  double* T_owned = nullptr;
+  double normT2 = 0.0;
+  int ld = 0;                 // leading dimension of every multi-matrix (R* rounded up to 16)
+  int capacity = 0;           // slots with persistent storage
+  double* U[3] = {nullptr, nullptr, nullptr};
+  double* Ualt[3] = {nullptr, nullptr, nullptr};
+  double* Uprev[3] = {nullptr, nullptr, nullptr};   // line search only (allocated on first use)
+  double* Unew[3] = {nullptr, nullptr, nullptr};
+  double* M = nullptr;        // MTTKRP result, max(I_n) x ld
+  double* workspace = nullptr;
+  size_t workspace_bytes = 0;
+  ModelDesc* d_desc = nullptr;
+  ModelDesc* h_desc = nullptr;   // pinned
+  ModelState* d_state = nullptr;
+  ModelOut* d_out = nullptr;
+  ModelOut* h_out = nullptr;     // pinned
+  int32_t* d_map = nullptr;
+  int32_t* h_map = nullptr;      // pinned
+  uint32_t* passive[3] = {nullptr, nullptr, nullptr};  // NONNEG only
+  double* d_scratch = nullptr;   // 1024 partial sums + result + flag
+  std::deque<PendingModel> queue;
+  std::vector<ActiveModel> active;
+  std::vector<int> free_sids;
+  std::map<int64_t, RetiredModel> retired;
+  std::deque<int64_t> out_queue;
+  int64_t next_id = 0;
+  int total_rank = 0;
+  bool desc_dirty = true;
+  bool any_ls = false, any_nonneg = false;
+  // statistics
+  int64_t rounds = 0, n_retired = 0;
+  double mttkrp_flops = 0.0;
+  double mttkrp_ms[3] = {0, 0, 0}, reduce_ms[3] = {0, 0, 0};
+  int64_t mttkrp_launches[3] = {0, 0, 0};
+  std::vector<TimedLaunch> timed;
+  std::vector<hipEvent_t> event_pool;
+};
+
+namespace {
+
+int set_device(cals_ctx* c) {
+  HIP_TRY(hipSetDevice(c->opt.device));
+  return CALS_OK;
+}
+
+bool all_finite(const double* p, int64_t n) {
+  for (int64_t i = 0; i < n; ++i)
+    if (!std::isfinite(p[i])) return false;
+  return true;
+}
+
+int ensure_workspace(cals_ctx* c, size_t bytes) {
+  if (bytes <= c->workspace_bytes) return CALS_OK;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  if (c->workspace) HIP_TRY(hipFree(c->workspace));
+  c->workspace = nullptr;
+  c->workspace_bytes = 0;
+  hipError_t e = hipMalloc(&c->workspace, bytes);
+  if (e != hipSuccess) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  c->workspace_bytes = bytes;
+  return CALS_OK;
+}
+
+// Problem description of the fused MTTKRP for output mode `mode` (0,1,2) over given multi-matrices.
+MttkrpProblem make_problem(const cals_ctx* c, int mode, const double* const U[3], double* M, int ncols, int ld) {
+  const int64_t I1 = c->dims[0], I2 = c->dims[1];
+  MttkrpProblem p{};
+  p.T = c->T;
+  p.M = M;
+  p.ncols = ncols;
+  p.ld = ld;
+  if (mode == 0) {          // rows i1; contract (i2 fast, i3 slow)
+    p.In = (int)c->dims[0]; p.sm = 1;
+    p.Ia = (int)c->dims[1]; p.sa = I1; p.Ua = U[1];
+    p.Ib = (int)c->dims[2]; p.sb = I1 * I2; p.Ub = U[2];
+  } else if (mode == 1) {   // rows i2; contract (i1 fast, i3 slow)
+    p.In = (int)c->dims[1]; p.sm = I1;
+    p.Ia = (int)c->dims[0]; p.sa = 1; p.Ua = U[0];
+    p.Ib = (int)c->dims[2]; p.sb = I1 * I2; p.Ub = U[2];
+  } else {                  // rows i3; contract (i1 fast, i2 slow)
+    p.In = (int)c->dims[2]; p.sm = I1 * I2;
+    p.Ia = (int)c->dims[0]; p.sa = 1; p.Ua = U[0];
+    p.Ib = (int)c->dims[1]; p.sb = I1; p.Ub = U[1];
+  }
+  return p;
+}
+
+hipEvent_t take_event(cals_ctx* c) {
+  if (!c->event_pool.empty()) {
+    hipEvent_t e = c->event_pool.back();
+    c->event_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+int drain_timings(cals_ctx* c) {
+  if (c->timed.empty()) return CALS_OK;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  for (TimedLaunch& t : c->timed) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, t.ev[0], t.ev[1]) == hipSuccess) c->mttkrp_ms[t.mode] += ms;
+    if (t.reduced && hipEventElapsedTime(&ms, t.ev[2], t.ev[3]) == hipSuccess) c->reduce_ms[t.mode] += ms;
+    for (int i = 0; i < 4; ++i) c->event_pool.push_back(t.ev[i]);
+  }
+  c->timed.clear();
+  return CALS_OK;
+}
+
+int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int ncols, int ld) {
+  MttkrpProblem p = make_problem(c, mode, U, M, ncols, ld);
+  if ((int64_t)p.Ia * ld >= (1LL << 31) || (int64_t)p.Ib * ld >= (1LL << 31)) return CALS_E_UNSUPPORTED;
+  MttkrpPlan pl = mttkrp_plan(p, c->num_cus);
+  if (pl.chunk >= (1LL << 31)) return CALS_E_UNSUPPORTED;
+  CALS_TRY(ensure_workspace(c, pl.workspace_bytes));
+  hipEvent_t* ev = nullptr;
+  TimedLaunch t{};
+  if (c->opt.flags & CALS_CTX_TIMING) {
+    bool ok = true;
+    for (int i = 0; i < 4; ++i) { t.ev[i] = take_event(c); ok = ok && t.ev[i]; }
+    if (!ok) return CALS_E_HIP;
+    t.mode = mode;
+    t.reduced = pl.splits > 1;
+    ev = t.ev;
+  }
+  HIP_TRY(mttkrp_launch(p, pl, c->workspace, c->stream, ev));
+  if (ev) {
+    c->timed.push_back(t);
+    if (c->timed.size() > 2048) CALS_TRY(drain_timings(c));
+  }
+  c->mttkrp_flops += 2.0 * ncols * (double)c->dims[0] * (double)c->dims[1] * (double)c->dims[2];
+  c->mttkrp_launches[mode] += 1;
+  return CALS_OK;
+}
+
+int upload_desc(cals_ctx* c) {
+  if (!c->desc_dirty) return CALS_OK;
+  const int n = (int)c->active.size();
+  for (int k = 0; k < n; ++k) {
+    const ActiveModel& m = c->active[k];
+    ModelDesc d;
+    d.sid = m.sid; d.col = m.col; d.rank = m.rank; d.flags = m.flags; d.alpha = m.alpha;
+    c->h_desc[k] = d;
+  }
+  if (n > 0) HIP_TRY(hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(ModelDesc) * n, hipMemcpyHostToDevice, c->stream));
+  c->desc_dirty = false;
+  return CALS_OK;
+}
+
+// Alg. 3, fill loop: take models from the queue front while they fit; stop at the first that does not.
+int fill(cals_ctx* c) {
+  const int first_new = (int)c->active.size();
+  while (!c->queue.empty()) {
+    PendingModel& pm = c->queue.front();
+    if (c->total_rank + pm.rank > c->opt.max_total_rank) break;
+    if ((int)c->active.size() >= c->capacity) break;
+    ActiveModel m;
+    m.id = pm.id; m.rank = pm.rank; m.tol = pm.tol; m.max_iters = pm.max_iters; m.flags = pm.flags;
+    m.alpha = pm.alpha; m.fit_prev = 0.0;
+    m.sid = c->free_sids.back();
+    c->free_sids.pop_back();
+    m.col = c->total_rank;
+    for (int n = 0; n < 3; ++n) {
+      HIP_TRY(hipMemcpy2D(c->U[n] + m.col, sizeof(double) * c->ld, pm.init[n].data(), sizeof(double) * m.rank,
+                          sizeof(double) * m.rank, (size_t)c->dims[n], hipMemcpyHostToDevice));
+    }
+    c->total_rank += m.rank;
+    c->active.push_back(m);
+    c->queue.pop_front();
+    c->desc_dirty = true;
+  }
+  const int count = (int)c->active.size() - first_new;
+  if (count > 0) {
+    CALS_TRY(upload_desc(c));
+    const int In[3] = {(int)c->dims[0], (int)c->dims[1], (int)c->dims[2]};
+    const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
+    HIP_TRY(launch_gram_init(c->d_desc, c->d_state, c->d_out, true, Uc, In, c->ld, first_new, count, c->stream));
+  }
+  return CALS_OK;
+}
+
+int retire_model(cals_ctx* c, const ActiveModel& m, const ModelOut& o, int status) {
+  RetiredModel r;
+  r.res.model_id = m.id;
+  r.res.rank = m.rank;
+  r.res.iters = o.iters;
+  r.res.status = status;
+  r.res.ls_accepted = o.ls_accepted;
+  r.res.fit = o.fit;
+  r.res.error = o.err;
+  std::vector<double> rowmajor;
+  for (int n = 0; n < 3; ++n) {
+    const int64_t In = c->dims[n];
+    rowmajor.resize((size_t)In * m.rank);
+    HIP_TRY(hipMemcpy2D(rowmajor.data(), sizeof(double) * m.rank, c->U[n] + m.col, sizeof(double) * c->ld,
+                        sizeof(double) * m.rank, (size_t)In, hipMemcpyDeviceToHost));
+    r.U[n].resize((size_t)In * m.rank);
+    for (int64_t i = 0; i < In; ++i)
+      for (int q = 0; q < m.rank; ++q) r.U[n][(size_t)(i + In * q)] = rowmajor[(size_t)(i * m.rank + q)];
+  }
+  r.lambda.resize(m.rank);
+  HIP_TRY(hipMemcpy(r.lambda.data(), c->d_state[m.sid].lambda, sizeof(double) * m.rank, hipMemcpyDeviceToHost));
+  c->retired[m.id] = std::move(r);
+  c->out_queue.push_back(m.id);
+  c->free_sids.push_back(m.sid);
+  c->n_retired += 1;
+  return CALS_OK;
+}
+
+// Stable left-compaction of the column blocks of the survivors (Sec. 4, "compression routine").
+int compact(cals_ctx* c, const std::vector<ActiveModel>& survivors) {
+  int col = 0;
+  bool moved = false;
+  std::vector<ActiveModel> out = survivors;
+  for (ActiveModel& m : out) {
+    for (int q = 0; q < m.rank; ++q) c->h_map[col + q] = m.col + q;
+    if (m.col != col) moved = true;
+    m.col = col;
+    col += m.rank;
+  }
+  if (moved && col > 0) {
+    HIP_TRY(hipMemcpyAsync(c->d_map, c->h_map, sizeof(int32_t) * col, hipMemcpyHostToDevice, c->stream));
+    for (int n = 0; n < 3; ++n) {
+      HIP_TRY(launch_gather_columns(c->U[n], c->Ualt[n], c->d_map, (int)c->dims[n], col, c->ld, c->stream));
+      std::swap(c->U[n], c->Ualt[n]);
+      if (c->Uprev[n]) {
+        HIP_TRY(launch_gather_columns(c->Uprev[n], c->Ualt[n], c->d_map, (int)c->dims[n], col, c->ld, c->stream));
+        std::swap(c->Uprev[n], c->Ualt[n]);
+      }
+    }
+    // h_map is reused next round: the copy above must have been consumed before it is rewritten
+    HIP_TRY(hipStreamSynchronize(c->stream));
+  }
+  c->active.swap(out);
+  c->total_rank = col;
+  c->desc_dirty = true;
+  return CALS_OK;
+}
+
+int one_round(cals_ctx* c, int* retired_now) {
+  CALS_TRY(fill(c));
+  const int n = (int)c->active.size();
+  if (n == 0) return CALS_OK;
+  CALS_TRY(upload_desc(c));
+  for (int mode = 0; mode < 3; ++mode) {
+    const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
+    CALS_TRY(run_mttkrp(c, mode, Uc, c->M, c->total_rank, c->ld));
+    UpdateArgs ua{};
+    ua.desc = c->d_desc; ua.state = c->d_state; ua.out = c->d_out;
+    ua.M = c->M; ua.U = c->U[mode]; ua.passive = c->passive[mode];
+    ua.In = (int)c->dims[mode]; ua.ld = c->ld; ua.mode = mode;
+    ua.n_models = n; ua.max_slots = c->capacity; ua.normT2 = c->normT2;
+    HIP_TRY(launch_update(ua, c->stream));
+  }
+  // the only per-round readback: fit, error, status and iteration count of every slot in use
+  int max_sid = 0;
+  for (const ActiveModel& m : c->active) max_sid = std::max(max_sid, m.sid);
+  HIP_TRY(hipMemcpyAsync(c->h_out, c->d_out, sizeof(ModelOut) * (max_sid + 1), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  c->rounds += 1;
+
+  // Alg. 3, removal loop: slots in order; a model leaves when its fit changed by less than tol between two
+  // consecutive iterations, when it reached its iteration cap, or when its update failed numerically.
+  std::vector<ActiveModel> survivors;
+  survivors.reserve(c->active.size());
+  for (ActiveModel& m : c->active) {
+    const ModelOut& o = c->h_out[m.sid];
+    int status = CALS_RUNNING;
+    if (o.status == CALS_NUMERICAL) status = CALS_NUMERICAL;
+    else if (o.iters >= 2 && std::fabs(o.fit - m.fit_prev) < m.tol) status = CALS_CONVERGED;
+    else if (o.iters >= m.max_iters) status = CALS_MAX_ITERS;
+    m.fit_prev = o.fit;
+    if (status != CALS_RUNNING) {
+      CALS_TRY(retire_model(c, m, o, status));
+      *retired_now += 1;
+    } else {
+      survivors.push_back(m);
+    }
+  }
+  if (survivors.size() != c->active.size()) CALS_TRY(compact(c, survivors));
+  return CALS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cals_create(cals_ctx** out, const cals_options* opt) {
+  if (!out || !opt) return CALS_E_INVALID;
+  *out = nullptr;
+  if (opt->max_total_rank < 1 || opt->max_total_rank > (1 << 20) || opt->max_slots < 0) return CALS_E_INVALID;
+  cals_ctx* c = new (std::nothrow) cals_ctx();
+  if (!c) return CALS_E_NOMEM;
+  c->opt = *opt;
+  c->stream = reinterpret_cast<hipStream_t>(opt->stream);
+  int rc = CALS_OK;
+  hipDeviceProp_t prop;
+  if (hipSetDevice(opt->device) != hipSuccess || hipGetDeviceProperties(&prop, opt->device) != hipSuccess ||
+      mttkrp_init() != hipSuccess) {
+    (void)hipGetLastError();
+    rc = CALS_E_HIP;
+  }
+  if (rc != CALS_OK) { delete c; return rc; }
+  c->num_cus = prop.multiProcessorCount;
+  c->ld = (int)((opt->max_total_rank + 15) / 16 * 16);
+  c->capacity = opt->max_slots > 0 ? opt->max_slots : (int)std::min<int64_t>(opt->max_total_rank, 4096);
+  *out = c;
+  return CALS_OK;
+}
+
+int cals_destroy(cals_ctx* c) {
+  if (!c) return CALS_E_INVALID;
+  (void)hipSetDevice(c->opt.device);
+  (void)hipStreamSynchronize(c->stream);
+  for (TimedLaunch& t : c->timed)
+    for (int i = 0; i < 4; ++i) (void)hipEventDestroy(t.ev[i]);
+  for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
+  for (int n = 0; n < 3; ++n) {
+    (void)hipFree(c->U[n]); (void)hipFree(c->Ualt[n]); (void)hipFree(c->Uprev[n]); (void)hipFree(c->Unew[n]);
+    (void)hipFree(c->passive[n]);
+  }
+  (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
+  (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned);
+  (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
+  delete c;
+  return CALS_OK;
+}
+
+int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], int on_device) {
+  if (!c || !data || !dims) return CALS_E_INVALID;
+  if (c->has_tensor) return CALS_E_STATE;
+  int64_t total = 1;
+  for (int n = 0; n < 3; ++n) {
+    if (dims[n] < 1 || dims[n] >= (1LL << 31)) return CALS_E_INVALID;
+    total *= dims[n];
+    if (total >= (1LL << 40)) return CALS_E_INVALID;
+  }
+  CALS_TRY(set_device(c));
+  for (int n = 0; n < 3; ++n) c->dims[n] = dims[n];
+  if (on_device) {
+    c->T = data;
+  } else {
+    if (hipMalloc(&c->T_owned, sizeof(double) * (size_t)total) != hipSuccess) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+    HIP_TRY(hipMemcpy(c->T_owned, data, sizeof(double) * (size_t)total, hipMemcpyHostToDevice));
+    c->T = c->T_owned;
+  }
+  // buffers: three factor multi-matrices (+ a spare set for compaction), the MTTKRP result, per-model storage
+  const int64_t imax = std::max(dims[0], std::max(dims[1], dims[2]));
+  bool ok = true;
+  for (int n = 0; n < 3; ++n) {
+    const size_t bytes = sizeof(double) * (size_t)dims[n] * c->ld;
+    ok = ok && hipMalloc(&c->U[n], bytes) == hipSuccess && hipMalloc(&c->Ualt[n], bytes) == hipSuccess;
+    if (ok) ok = hipMemsetAsync(c->U[n], 0, bytes, c->stream) == hipSuccess &&
+                 hipMemsetAsync(c->Ualt[n], 0, bytes, c->stream) == hipSuccess;
+  }
+  ok = ok && hipMalloc(&c->M, sizeof(double) * (size_t)imax * c->ld) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_desc, sizeof(ModelDesc) * c->capacity) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_state, sizeof(ModelState) * (size_t)c->capacity) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_map, sizeof(int32_t) * c->ld) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_scratch, sizeof(double) * 1032) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_desc, sizeof(ModelDesc) * c->capacity) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_map, sizeof(int32_t) * c->ld) == hipSuccess;
+  if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  HIP_TRY(hipMemsetAsync(c->d_out, 0, sizeof(ModelOut) * c->capacity, c->stream));
+  c->free_sids.clear();
+  for (int s = c->capacity - 1; s >= 0; --s) c->free_sids.push_back(s);
+  // ||T||^2 once (Alg. 1, error line: the tensor term is computed once at the start), and a NaN/Inf scan
+  int* d_flag = reinterpret_cast<int*>(c->d_scratch + 1025);
+  HIP_TRY(hipMemsetAsync(d_flag, 0, sizeof(int), c->stream));
+  HIP_TRY(launch_norm_sq(c->T, total, c->d_scratch, c->d_scratch + 1024, d_flag, c->stream));
+  double nrm = 0.0;
+  int flag = 0;
+  HIP_TRY(hipMemcpyAsync(&nrm, c->d_scratch + 1024, sizeof(double), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipMemcpyAsync(&flag, d_flag, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  if (flag != 0 || !std::isfinite(nrm)) return CALS_E_INVALID;
+  c->normT2 = nrm;
+  c->has_tensor = true;
+  return CALS_OK;
+}
+
+int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const init[3], double tol, int32_t max_iters,
+                       uint32_t flags, double ls_alpha, int64_t* model_id) {
+  if (!c || !init) return CALS_E_INVALID;
+  if (!c->has_tensor) return CALS_E_STATE;
+  if (rank < 1 || rank > CALS_MAX_RANK || rank > c->opt.max_total_rank || max_iters < 1) return CALS_E_INVALID;
+  if (std::isnan(tol)) return CALS_E_INVALID;
+  if (flags & ~(CALS_MODEL_NONNEG | CALS_MODEL_LINESEARCH)) return CALS_E_INVALID;
+  if ((flags & CALS_MODEL_NONNEG) && (flags & CALS_MODEL_LINESEARCH)) return CALS_E_UNSUPPORTED;
+  if ((flags & CALS_MODEL_LINESEARCH) && !std::isfinite(ls_alpha)) return CALS_E_INVALID;
+  if (flags & (CALS_MODEL_NONNEG | CALS_MODEL_LINESEARCH)) return CALS_E_UNSUPPORTED;  // not built yet
+  PendingModel pm;
+  pm.id = c->next_id;
+  pm.rank = rank; pm.tol = tol; pm.max_iters = max_iters; pm.flags = flags; pm.alpha = ls_alpha;
+  for (int n = 0; n < 3; ++n) {
+    if (!init[n]) return CALS_E_INVALID;
+    const int64_t In = c->dims[n];
+    if (!all_finite(init[n], In * rank)) return CALS_E_INVALID;
+    pm.init[n].resize((size_t)In * rank);
+    for (int64_t i = 0; i < In; ++i)
+      for (int q = 0; q < rank; ++q) pm.init[n][(size_t)(i * rank + q)] = init[n][(size_t)(i + In * q)];
+  }
+  c->queue.push_back(std::move(pm));
+  if (model_id) *model_id = c->next_id;
+  c->next_id += 1;
+  return CALS_OK;
+}
+
+int cals_iterate(cals_ctx* c, int32_t n_rounds, int32_t* n_retired) {
+  if (!c || n_rounds < 0) return CALS_E_INVALID;
+  if (!c->has_tensor) return CALS_E_STATE;
+  CALS_TRY(set_device(c));
+  int retired_now = 0;
+  if (n_retired) *n_retired = 0;
+  for (int r = 0; r < n_rounds; ++r) {
+    if (c->queue.empty() && c->active.empty()) break;
+    CALS_TRY(one_round(c, &retired_now));
+    if (n_retired) *n_retired = retired_now;
+  }
+  return CALS_OK;
+}
+
+int cals_run(cals_ctx* c) {
+  if (!c) return CALS_E_INVALID;
+  if (!c->has_tensor) return CALS_E_STATE;
+  while (!(c->queue.empty() && c->active.empty())) CALS_TRY(cals_iterate(c, 64, nullptr));
+  return CALS_OK;
+}
+
+int cals_poll_retired(cals_ctx* c, cals_result* out, int32_t cap, int32_t* n) {
+  if (!c || !n || cap < 0 || (cap > 0 && !out)) return CALS_E_INVALID;
+  int k = 0;
+  while (k < cap && !c->out_queue.empty()) {
+    out[k++] = c->retired[c->out_queue.front()].res;
+    c->out_queue.pop_front();
+  }
+  *n = k;
+  return CALS_OK;
+}
+
+int cals_get_factors(cals_ctx* c, int64_t model_id, double* const U[3], double* lambda) {
+  if (!c) return CALS_E_INVALID;
+  auto it = c->retired.find(model_id);
+  if (it == c->retired.end()) return CALS_E_NOTFOUND;
+  const RetiredModel& r = it->second;
+  if (U)
+    for (int n = 0; n < 3; ++n)
+      if (U[n]) std::memcpy(U[n], r.U[n].data(), sizeof(double) * r.U[n].size());
+  if (lambda) std::memcpy(lambda, r.lambda.data(), sizeof(double) * r.lambda.size());
+  return CALS_OK;
+}
+
+int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const U_dev[3],
+                double* M_dev) {
+  if (!c || !U_dev || !M_dev) return CALS_E_INVALID;
+  if (!c->has_tensor) return CALS_E_STATE;
+  if (mode < 1 || mode > 3 || total_rank < 1 || ld < total_rank || ld >= (1LL << 24)) return CALS_E_INVALID;
+  for (int n = 0; n < 3; ++n)
+    if (n != mode - 1 && !U_dev[n]) return CALS_E_INVALID;
+  CALS_TRY(set_device(c));
+  return run_mttkrp(c, mode - 1, U_dev, M_dev, total_rank, (int)ld);
+}
+
+int cals_get_stats(cals_ctx* c, cals_stats* s) {
+  if (!c || !s) return CALS_E_INVALID;
+  CALS_TRY(set_device(c));
+  CALS_TRY(drain_timings(c));
+  s->rounds = c->rounds;
+  s->models_retired = c->n_retired;
+  s->models_queued = (int64_t)c->queue.size();
+  s->n_active = (int32_t)c->active.size();
+  s->total_rank = c->total_rank;
+  s->tensor_norm_sq = c->normT2;
+  s->mttkrp_flops = c->mttkrp_flops;
+  for (int n = 0; n < 3; ++n) {
+    s->mttkrp_ms[n] = c->mttkrp_ms[n];
+    s->reduce_ms[n] = c->reduce_ms[n];
+    s->mttkrp_launches[n] = c->mttkrp_launches[n];
+  }
+  return CALS_OK;
+}
+
+const char* cals_strerror(int code) {
+  switch (code) {
+    case CALS_OK: return "ok";
+    case CALS_E_INVALID: return "invalid argument";
+    case CALS_E_STATE: return "call not allowed in this state";
+    case CALS_E_NOMEM: return "out of memory";
+    case CALS_E_HIP: return "HIP runtime error";
+    case CALS_E_UNSUPPORTED: return "not supported";
+    case CALS_E_NOTFOUND: return "model not found or not finished";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+// Internal declarations shared by the HIP translation units of the CALS library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cals {
+
+constexpr int kMaxRank = 32;       // largest rank of one model (CALS_MAX_RANK)
+constexpr int kGramStride = kMaxRank * kMaxRank;
+
+// ---- fused MTTKRP (Eq. (2); Alg. 2 fused-MTTKRP line) ------------------------------------------
+// GEMM view for output mode n:  M[In x ncols] = A[In x K] * KRP[K x ncols],  K = Ia*Ib, where
+// `a` is the faster and `b` the slower of the two contracted tensor indices and
+// A[m, (ia,ib)] = T[m*sm + ia*sa + ib*sb],  KRP[(ia,ib), c] = Ua[ia,c] * Ub[ib,c].
+struct MttkrpProblem {
+  const double* T;
+  const double* Ua;   // row-major Ia x ld
+  const double* Ub;   // row-major Ib x ld
+  double* M;          // row-major In x ld, columns [0,ncols) written
+  int64_t sm, sa, sb; // element strides in T
+  int In, Ia, Ib;
+  int ncols;          // fused width (total rank)
+  int ld;             // leading dimension (doubles) of Ua, Ub, M
+};
+
+struct MttkrpPlan {
+  int wn;          // 16-column MFMA tiles per wave
+  int ka;          // contraction rows per LDS stage
+  int ny;          // column blocks (grid.y)
+  int splits;      // split-K factor (grid.z)
+  int64_t chunk;   // contraction indices per split
+  int mtiles;      // 64-row blocks (grid.x)
+  size_t workspace_bytes;  // split-K partials: splits * In * ld doubles (0 when splits == 1)
+};
+
+// Chooses tile shape and split-K for a problem on a device with `num_cus` compute units.
+MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus);
+// Enqueues contraction (+ ordered split-K reduction when plan.splits > 1) on `stream`.
+// `workspace` must hold plan.workspace_bytes.  ev[0..3], when non-null, are recorded around the
+// contraction kernel (ev[0], ev[1]) and around the reduction kernel (ev[2], ev[3]).
+hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& plan, double* workspace, hipStream_t stream,
+                         hipEvent_t* ev);
+// One-time per-process kernel attribute set-up (dynamic LDS sizes).
+hipError_t mttkrp_init();
+
+// ---- per-model steps (Alg. 2 inner loop: Hadamard of Gramians, update; Alg. 1 error line) -------
+struct ModelDesc {   // one per active model, in slot order
+  int32_t sid;       // index of the model's persistent per-model storage
+  int32_t col;       // first column in the multi-matrices
+  int32_t rank;
+  uint32_t flags;
+  double alpha;      // line-search step
+};
+
+struct ModelState {  // persistent per-model device storage, indexed by sid
+  double G[3][kGramStride];   // Gramians of the current factors (rank x rank, ld = rank)
+  double lambda[kMaxRank];
+  double inner, normsq;       // error terms of the last mode-3 update
+};
+
+struct ModelOut {    // per-model scalars the host reads back once per round, indexed by sid
+  double err, fit;            // after the last completed iteration
+  int32_t status;             // CALS_RUNNING or CALS_NUMERICAL (set on device)
+  int32_t iters;              // completed iterations
+  int32_t ls_accepted;
+  int32_t pad;
+};
+
+struct UpdateArgs {
+  const ModelDesc* desc;
+  ModelState* state;
+  ModelOut* out;
+  const double* M;      // MTTKRP result, row-major In x ld
+  double* U;            // factor multi-matrix of the updated mode, row-major In x ld
+  uint32_t* passive;    // NONNEG: per (row, slot) passive-set masks for this mode, In x max_slots (or null)
+  int In, ld, mode;     // mode = 0,1,2
+  int n_models;
+  int max_slots;
+  double normT2;
+};
+
+hipError_t launch_update(const UpdateArgs& a, hipStream_t stream);
+// Gramians of all three modes for models [first, first+count) of desc (used when a model is inserted
+// and after an accepted line-search step).
+// With reset_out, also puts the models' ModelOut back to {0, 0, RUNNING, 0, 0}.
+hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, bool reset_out,
+                            const double* const U[3], const int In[3], int ld, int first, int count,
+                            hipStream_t stream);
+// ||T||^2 with a fixed summation tree, and a finiteness check (flag[0] != 0 when a NaN/Inf was seen).
+hipError_t launch_norm_sq(const double* T, int64_t n, double* partial /* >= 1024 doubles */, double* out, int* flag,
+                          hipStream_t stream);
+// Stable left-compaction / arbitrary column gather of a row-major multi-matrix:
+// dst[i, c] = src[i, map[c]] for c < ncols, all rows.
+hipError_t launch_gather_columns(const double* src, double* dst, const int32_t* map, int rows, int ncols, int ld,
+                                 hipStream_t stream);
+
+// ---- line search (Sec. 5) ------------------------------------------------------------------------
+struct LineSearchArgs {
+  const ModelDesc* desc;
+  ModelState* state;
+  ModelOut* out;
+  double* U[3];          // current factors
+  double* Uprev[3];      // point after the previous iteration (lambda folded into mode 3)
+  double* Unew[3];       // extrapolated point
+  int In[3];
+  int ld, n_models;
+  double normT2;
+};
+// Unew = Uprev + alpha (Ucur*scale - Uprev) for line-search models past their first iteration (others: Unew = Ucur*scale).
+hipError_t launch_ls_extrapolate(const LineSearchArgs& a, hipStream_t stream);
+// Error of the extrapolated point from M3(Unew) (row-major I3 x ld) and acceptance; copies accepted points into U,
+// refreshes Gramians, and stores the new "previous" point.
+hipError_t launch_ls_decide(const LineSearchArgs& a, const double* M3, hipStream_t stream);
+
+}  // namespace cals

@@ -1,0 +1,326 @@
+// Per-model steps of one CALS mode update (Alg. 2 inner loop; Alg. 1 Hadamard, update and error lines),
+// one workgroup per active model:
+//   H = Ga * Gb (cached Gramians of the other two modes)         -- Hadamard product of Gramians
+//   H = L L^T                                                    -- Cholesky, no pivoting
+//   U[i,:] = M[i,:] H^-1 for every row i (two triangular solves) -- normal-equation update
+//   mode 3 only: inner = sum(U * M), normsq = sum(H * U^T U)     -- terms of the fast error formula
+//   lambda_r = ||U[:,r]||_2, U[:,r] /= lambda_r, G = U^T U       -- unit columns, Gramian refresh
+// plus the small utility kernels around it (initial Gramians, ||T||^2, column gather).
+#include "cals_internal.h"
+
+namespace cals {
+
+constexpr int kRows = 256;             // rows staged per pass (= workgroup size)
+constexpr int kXs = kRows + 1;         // padded stride of the staged block (conflict-free pair reads)
+
+__device__ inline double block_sum(double v, double* red /* 256 doubles in LDS */) {
+  const int tid = threadIdx.x;
+  red[tid] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) red[tid] += red[tid + s];
+    __syncthreads();
+  }
+  const double r = red[0];
+  __syncthreads();
+  return r;
+}
+
+__device__ inline void pair_rs(int p, int& r, int& s) {   // p -> (r, s), r >= s, row-major lower triangle
+  r = (int)((sqrt(8.0 * p + 1.0) - 1.0) * 0.5);
+  while (r * (r + 1) / 2 > p) --r;
+  while ((r + 1) * (r + 2) / 2 <= p) ++r;
+  s = p - r * (r + 1) / 2;
+}
+
+// Accumulates the lower triangle of X^T X over the `nrows` staged rows.  Pair p (< R(R+1)/2 <= 528) is
+// owned by thread p % 256, slot p / 256.  xs[r * kXs + j] holds X[row j][r].
+__device__ inline void gram_accumulate(const double* xs, int R, int nrows, double (&gacc)[3]) {
+  const int npairs = R * (R + 1) / 2;
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const int p = threadIdx.x + 256 * q;
+    if (p < npairs) {
+      int r, s;
+      pair_rs(p, r, s);
+      const double* xr = xs + r * kXs;
+      const double* xc = xs + s * kXs;
+      double acc = gacc[q];
+      for (int j = 0; j < nrows; ++j) acc += xr[j] * xc[j];
+      gacc[q] = acc;
+    }
+  }
+}
+
+__device__ inline void gram_store(const double (&gacc)[3], int R, double* Gl /* LDS, R x R */) {
+  const int npairs = R * (R + 1) / 2;
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const int p = threadIdx.x + 256 * q;
+    if (p < npairs) {
+      int r, s;
+      pair_rs(p, r, s);
+      Gl[r * R + s] = gacc[q];
+      Gl[s * R + r] = gacc[q];
+    }
+  }
+}
+
+// In-place lower Cholesky of the R x R matrix A (LDS, row-major, ld = R).  The updates reach every
+// element in the same order as the textbook column algorithm (k = 0,1,...).  Returns false (to all
+// threads) when a pivot is not a positive finite number.
+__device__ inline bool block_cholesky(double* A, int R, int* flag /* LDS */) {
+  const int tid = threadIdx.x;
+  if (tid == 0) *flag = 1;
+  __syncthreads();
+  for (int j = 0; j < R; ++j) {
+    if (tid == 0) {
+      const double d = A[j * R + j];
+      if (!(d > 0.0) || !isfinite(d)) *flag = 0;
+      else A[j * R + j] = sqrt(d);
+    }
+    __syncthreads();
+    if (*flag == 0) return false;
+    const double djj = A[j * R + j];
+    for (int i = j + 1 + tid; i < R; i += 256) A[i * R + j] = A[i * R + j] / djj;
+    __syncthreads();
+    const int n = R - j - 1;                  // trailing block, lower triangle only
+    for (int e = tid; e < n * n; e += 256) {
+      const int i = j + 1 + e / n, c = j + 1 + e % n;
+      if (c <= i) A[i * R + c] -= A[i * R + j] * A[c * R + j];
+    }
+    __syncthreads();
+  }
+  return true;
+}
+
+__global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
+  extern __shared__ double lds[];
+  const ModelDesc d = a.desc[blockIdx.x];
+  ModelState* st = a.state + d.sid;
+  ModelOut* out = a.out + d.sid;
+  if (out->status != 0) return;               // stopped earlier in this iteration (uniform)
+  const int tid = threadIdx.x;
+  const int R = d.rank;
+  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
+  double* xs = lds;                           // R * kXs
+  double* H = xs + kMaxRank * kXs;            // R*R, Hadamard of Gramians
+  double* L = H + kGramStride;                // R*R, Cholesky factor
+  double* Gl = L + kGramStride;               // R*R, Gramian of the updated factor
+  double* red = Gl + kGramStride;             // 256
+  double* lam = red + 256;                    // R
+  __shared__ int flag;
+
+  for (int e = tid; e < R * R; e += 256) {
+    const double h = st->G[ma][e] * st->G[mb][e];
+    H[e] = h;
+    L[e] = h;
+  }
+  __syncthreads();
+  if (!block_cholesky(L, R, &flag)) {
+    if (tid == 0) out->status = 3;            // CALS_NUMERICAL; factors of this mode stay untouched
+    return;
+  }
+
+  double gacc[3] = {0.0, 0.0, 0.0};
+  double inner = 0.0;
+  const double* Mb = a.M + d.col;
+  double* Ub = a.U + d.col;
+  for (int base = 0; base < a.In; base += kRows) {
+    const int i = base + tid;
+    const int nrows = (a.In - base < kRows) ? (a.In - base) : kRows;
+    if (i < a.In) {
+      const double* mrow = Mb + (int64_t)i * a.ld;
+      for (int r = 0; r < R; ++r) xs[r * kXs + tid] = mrow[r];
+      // L y = m
+      for (int r = 0; r < R; ++r) {
+        double v = xs[r * kXs + tid];
+        for (int k = 0; k < r; ++k) v -= L[r * R + k] * xs[k * kXs + tid];
+        xs[r * kXs + tid] = v / L[r * R + r];
+      }
+      // L^T x = y
+      for (int r = R - 1; r >= 0; --r) {
+        double v = xs[r * kXs + tid];
+        for (int k = r + 1; k < R; ++k) v -= L[k * R + r] * xs[k * kXs + tid];
+        xs[r * kXs + tid] = v / L[r * R + r];
+      }
+      double* urow = Ub + (int64_t)i * a.ld;
+      double part = 0.0;
+      for (int r = 0; r < R; ++r) {
+        const double x = xs[r * kXs + tid];
+        urow[r] = x;
+        part += x * mrow[r];
+      }
+      inner += part;
+    }
+    __syncthreads();
+    gram_accumulate(xs, R, nrows, gacc);
+    __syncthreads();
+  }
+  gram_store(gacc, R, Gl);
+  __syncthreads();
+
+  if (a.mode == 2) {
+    double part = 0.0;
+    for (int e = tid; e < R * R; e += 256) part += H[e] * Gl[e];
+    const double normsq = block_sum(part, red);
+    const double in = block_sum(inner, red);
+    if (tid == 0) {
+      st->inner = in;
+      st->normsq = normsq;
+      const double err = a.normT2 + normsq - 2.0 * in;
+      out->err = err;
+      out->fit = 1.0 - sqrt(err > 0.0 ? err : 0.0) / sqrt(a.normT2);
+      out->iters += 1;
+    }
+  }
+  if (tid < R) {
+    const double l = sqrt(Gl[tid * R + tid]);
+    lam[tid] = l;
+    st->lambda[tid] = l;
+  }
+  __syncthreads();
+  for (int e = tid; e < R * R; e += 256) {
+    const int r = e / R, s = e % R;
+    const double lr = lam[r] > 0.0 ? lam[r] : 1.0, ls = lam[s] > 0.0 ? lam[s] : 1.0;
+    st->G[a.mode][e] = (Gl[e] / lr) / ls;
+  }
+  for (int i = tid; i < a.In; i += 256) {
+    double* urow = Ub + (int64_t)i * a.ld;
+    for (int r = 0; r < R; ++r) {
+      const double l = lam[r];
+      if (l > 0.0) urow[r] = urow[r] / l;
+    }
+  }
+}
+
+static constexpr size_t kUpdateLds = sizeof(double) * (kMaxRank * kXs + 3 * kGramStride + 256 + kMaxRank);
+
+hipError_t launch_update(const UpdateArgs& a, hipStream_t stream) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(update_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUpdateLds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (a.n_models < 1) return hipSuccess;
+  hipLaunchKernelGGL(update_kernel, dim3(a.n_models), dim3(256), kUpdateLds, stream, a);
+  return hipGetLastError();
+}
+
+// ---- Gramians of freshly inserted models: one workgroup per (model, mode) -------------------------
+struct GramInitArgs {
+  const ModelDesc* desc;
+  ModelState* state;
+  ModelOut* out;
+  int reset_out;
+  const double* U[3];
+  int In[3];
+  int ld, first;
+};
+
+__global__ void __launch_bounds__(256) gram_init_kernel(GramInitArgs a) {
+  extern __shared__ double lds[];
+  const ModelDesc d = a.desc[a.first + blockIdx.x];
+  const int mode = blockIdx.y;
+  ModelState* st = a.state + d.sid;
+  const int tid = threadIdx.x, R = d.rank, In = a.In[mode];
+  double* xs = lds;
+  double* Gl = xs + kMaxRank * kXs;
+  double gacc[3] = {0.0, 0.0, 0.0};
+  const double* Ub = a.U[mode] + d.col;
+  for (int base = 0; base < In; base += kRows) {
+    const int i = base + tid;
+    const int nrows = (In - base < kRows) ? (In - base) : kRows;
+    if (i < In)
+      for (int r = 0; r < R; ++r) xs[r * kXs + tid] = Ub[(int64_t)i * a.ld + r];
+    __syncthreads();
+    gram_accumulate(xs, R, nrows, gacc);
+    __syncthreads();
+  }
+  gram_store(gacc, R, Gl);
+  __syncthreads();
+  for (int e = tid; e < R * R; e += 256) st->G[mode][e] = Gl[e];
+  if (a.reset_out && mode == 0 && tid == 0) {
+    ModelOut o;
+    o.err = 0.0; o.fit = 0.0; o.status = 0; o.iters = 0; o.ls_accepted = 0; o.pad = 0;
+    a.out[d.sid] = o;
+  }
+  if (a.reset_out && mode == 0 && tid < kMaxRank) st->lambda[tid] = 1.0;
+}
+
+hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, bool reset_out,
+                            const double* const U[3], const int In[3], int ld, int first, int count,
+                            hipStream_t stream) {
+  static bool attr_done = false;
+  const size_t lds = sizeof(double) * (kMaxRank * kXs + kGramStride);
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gram_init_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (count < 1) return hipSuccess;
+  GramInitArgs a;
+  a.desc = desc; a.state = state; a.out = out; a.reset_out = reset_out ? 1 : 0; a.ld = ld; a.first = first;
+  for (int n = 0; n < 3; ++n) { a.U[n] = U[n]; a.In[n] = In[n]; }
+  hipLaunchKernelGGL(gram_init_kernel, dim3(count, 3), dim3(256), lds, stream, a);
+  return hipGetLastError();
+}
+
+// ---- ||T||^2 with a fixed reduction tree ----------------------------------------------------------
+constexpr int kNormBlocks = 1024;
+
+__global__ void __launch_bounds__(256) norm_sq_partial_kernel(const double* __restrict__ T, int64_t n,
+                                                              double* __restrict__ partial, int* __restrict__ flag) {
+  __shared__ double red[256];
+  const int64_t per = (n + kNormBlocks - 1) / kNormBlocks;
+  const int64_t b0 = (int64_t)blockIdx.x * per;
+  const int64_t b1 = (b0 + per < n) ? (b0 + per) : n;
+  double s = 0.0;
+  bool bad = false;
+  for (int64_t i = b0 + threadIdx.x; i < b1; i += 256) {
+    const double v = T[i];
+    bad |= !isfinite(v);
+    s += v * v;
+  }
+  if (bad) atomicOr(flag, 1);
+  const double tot = block_sum(s, red);
+  if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+}
+
+__global__ void __launch_bounds__(256) norm_sq_final_kernel(const double* __restrict__ partial, double* __restrict__ out) {
+  __shared__ double red[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < kNormBlocks; i += 256) s += partial[i];
+  const double tot = block_sum(s, red);
+  if (threadIdx.x == 0) out[0] = tot;
+}
+
+hipError_t launch_norm_sq(const double* T, int64_t n, double* partial, double* out, int* flag, hipStream_t stream) {
+  hipLaunchKernelGGL(norm_sq_partial_kernel, dim3(kNormBlocks), dim3(256), 0, stream, T, n, partial, flag);
+  hipLaunchKernelGGL(norm_sq_final_kernel, dim3(1), dim3(256), 0, stream, (const double*)partial, out);
+  return hipGetLastError();
+}
+
+// ---- column gather (compaction of the multi-matrices after retirements; Sec. 4) -------------------
+__global__ void __launch_bounds__(256) gather_columns_kernel(const double* __restrict__ src, double* __restrict__ dst,
+                                                             const int32_t* __restrict__ map, int rows, int ncols, int ld) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = (int64_t)rows * ncols;
+  if (idx >= total) return;
+  const int i = (int)(idx / ncols), c = (int)(idx % ncols);
+  dst[(int64_t)i * ld + c] = src[(int64_t)i * ld + map[c]];
+}
+
+hipError_t launch_gather_columns(const double* src, double* dst, const int32_t* map, int rows, int ncols, int ld,
+                                 hipStream_t stream) {
+  if (rows < 1 || ncols < 1) return hipSuccess;
+  const int64_t total = (int64_t)rows * ncols;
+  hipLaunchKernelGGL(gather_columns_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, src, dst, map,
+                     rows, ncols, ld);
+  return hipGetLastError();
+}
+
+}  // namespace cals

@@ -1,0 +1,48 @@
+"""The C-ABI library builds for gfx950, loads, and exports every symbol include/cals.h declares
+(no compute calls: there is no GPU here)."""
+import os
+import re
+
+import paper_2010_04678_amd as P
+from paper_2010_04678_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "cals.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(cals_[a-z_]+)\s*\(", src)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    names = _declared()
+    assert "cals_mttkrp" in names and "cals_iterate" in names and len(names) >= 11
+    L = P.load_library()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_strerror_needs_no_device():
+    L = P.load_library()
+    assert L.cals_strerror(0) == b"ok"
+    assert L.cals_strerror(-1) == b"invalid argument"
+    assert b"unknown" in L.cals_strerror(-99)
+
+
+def test_struct_layouts_match_header():
+    import ctypes as C
+    # sizes implied by the field lists in cals.h (natural alignment, 8-byte pointers)
+    assert C.sizeof(binding._Options) == 32
+    assert C.sizeof(binding._Result) == 40
+    assert C.sizeof(binding._Stats) == 8 * 3 + 4 * 2 + 8 * 2 + 8 * 3 + 8 * 3 + 8 * 3
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2010_04678_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                txt = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in txt.lower() or f == "__never__", os.path.join(dirpath, f)

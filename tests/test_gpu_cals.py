@@ -1,0 +1,144 @@
+"""GPU parity of the whole CALS path (submit, enqueue, iterate, retire) against the CPU oracle.
+
+Bars: per-model fit within 1e-8, factors within 1e-6 relative (lambda absorbed, column by column; the
+starting points are identical so no permutation is involved), identical iteration counts, statuses and
+retirement order."""
+import numpy as np
+import pytest
+
+import oracle as O
+from workloads import get_config, make_models, make_tensor, random_tensor, uniform_factors
+
+pytestmark = pytest.mark.gpu
+FIT_TOL = 1e-8
+FACTOR_TOL = 1e-6
+
+
+def run_gpu(T, models, max_total_rank, max_slots=0, rounds_per_call=7):
+    import torch
+    import paper_2010_04678_amd as P
+    ctx = P.Context(max_total_rank=max_total_rank, max_slots=max_slots)
+    ctx.submit_tensor(torch.from_numpy(T).cuda())
+    ids = [ctx.enqueue_model(m["init"], m["tol"], m["max_iters"], m.get("flags", 0), m.get("ls_alpha", 1.0))
+           for m in models]
+    assert ids == list(range(len(models)))
+    results, guard = [], 0
+    while len(results) < len(models):
+        ctx.iterate(rounds_per_call)
+        results += ctx.poll_retired()
+        guard += 1
+        assert guard < 100000
+    st = ctx.stats()
+    assert st.n_active == 0 and st.models_queued == 0 and st.models_retired == len(models)
+    facs = {r.model_id: ctx.get_factors(r.model_id) for r in results}
+    ctx.close()
+    return results, facs, st
+
+
+def compare(results, facs, ref, models):
+    assert [r.model_id for r in results] == list(ref["retire_order"])
+    for r in results:
+        k = r.model_id
+        assert r.rank == models[k]["rank"]
+        assert r.iters == ref["iters"][k], (k, r.iters, ref["iters"][k])
+        assert r.status == ref["status"][k]
+        assert abs(r.fit - ref["fit"][k]) <= FIT_TOL, (k, r.fit, ref["fit"][k])
+        U, lam = facs[k]
+        for n in range(3):
+            a = U[n] * (lam[None, :] if n == 2 else 1.0)
+            b = ref["U"][k][n] * (ref["lam"][k][None, :] if n == 2 else 1.0)
+            den = np.linalg.norm(b, axis=0)
+            rel = np.linalg.norm(a - b, axis=0) / np.where(den > 0, den, 1.0)
+            assert rel.max() <= FACTOR_TOL, (k, n, rel.max())
+
+
+def test_config1_full():
+    cfg = get_config(1)
+    T = make_tensor(cfg)
+    models = make_models(cfg)
+    ref = O.cals(T, models, cfg.max_total_rank, cfg.max_slots)
+    results, facs, st = run_gpu(T, models, cfg.max_total_rank, cfg.max_slots)
+    compare(results, facs, ref, models)
+    assert st.rounds == 50 and abs(st.tensor_norm_sq - O.norm_sq(T)) <= 1e-12 * st.tensor_norm_sq
+
+
+def test_queue_with_tolerances_slots_and_refill():
+    # staggered stops: tolerance-driven and cap-driven models mixed, fewer slots than models, R* binding
+    dims = (24, 20, 18)
+    T = make_tensor(get_config(1), dims)
+    ranks = [3, 1, 4, 2, 5, 3, 2, 6, 1, 4, 3, 2]
+    models = []
+    for k, r in enumerate(ranks):
+        models.append(dict(rank=r, init=uniform_factors(dims, r, 900 + k), tol=[1e-4, -1.0, 1e-6][k % 3],
+                           max_iters=[40, 7, 25][k % 3], flags=0, ls_alpha=1.0))
+    for rstar, slots in [(sum(ranks), 0), (9, 3), (6, 0), (12, 4)]:
+        ref = O.cals(T, models, rstar, slots)
+        results, facs, st = run_gpu(T, models, rstar, slots, rounds_per_call=3)
+        compare(results, facs, ref, models)
+        assert st.rounds == ref["rounds"]
+
+
+def test_numerical_failure_retires_only_that_model():
+    dims = (12, 10, 8)
+    T = random_tensor(dims, 77)
+    models = []
+    for k, r in enumerate([2, 3, 2]):
+        init = uniform_factors(dims, r, 950 + k)
+        if k == 1:
+            init[1][:, 2] = 0.0
+            init[2][:, 2] = 0.0      # H of the first update has a zero row: not positive definite
+        models.append(dict(rank=r, init=init, tol=-1.0, max_iters=6, flags=0, ls_alpha=1.0))
+    ref = O.cals(T, models, 7)
+    assert ref["status"][1] == O.NUMERICAL
+    results, facs, _ = run_gpu(T, models, 7)
+    compare(results, facs, ref, models)
+
+
+def test_argument_errors():
+    import torch
+    import paper_2010_04678_amd as P
+    dims = (6, 5, 4)
+    T = random_tensor(dims, 5)
+    ctx = P.Context(max_total_rank=8)
+    good = uniform_factors(dims, 2, 1)
+    with pytest.raises(P.CalsError) as e:
+        ctx.enqueue_model(good)
+    assert e.value.code == -2                                  # no tensor yet
+    with pytest.raises(P.CalsError) as e:
+        ctx.iterate(1)
+    assert e.value.code == -2
+    bad = T.copy()
+    bad[1, 2, 3] = np.nan
+    with pytest.raises(P.CalsError) as e:
+        ctx.submit_tensor(bad)
+    assert e.value.code == -1
+    ctx.close()
+    ctx = P.Context(max_total_rank=8)
+    ctx.submit_tensor(T)                                       # host pointer: copied
+    with pytest.raises(P.CalsError) as e:
+        ctx.submit_tensor(T)
+    assert e.value.code == -2                                  # one tensor per context
+    for kwargs, code in [(dict(max_iters=0), -1), (dict(tol=float("nan")), -1), (dict(flags=3), -5),
+                         (dict(flags=8), -1)]:
+        with pytest.raises(P.CalsError) as e:
+            ctx.enqueue_model(good, **kwargs)
+        assert e.value.code == code, kwargs
+    with pytest.raises(P.CalsError) as e:
+        ctx.enqueue_model(uniform_factors(dims, 9, 1))         # rank > R*
+    assert e.value.code == -1
+    nan_init = [g.copy() for g in good]
+    nan_init[0][0, 0] = np.inf
+    with pytest.raises(P.CalsError) as e:
+        ctx.enqueue_model(nan_init)
+    assert e.value.code == -1
+    ctx.enqueue_model(good, max_iters=2)
+    assert ctx.poll_retired() == []
+    ctx.run()
+    res = ctx.poll_retired()
+    assert len(res) == 1 and res[0].iters == 2 and res[0].status == P.MAX_ITERS
+    with pytest.raises(P.CalsError) as e:
+        ctx._ranks[5] = 2
+        ctx.get_factors(5)
+    assert e.value.code == -6
+    ctx.close()
+    torch.cuda.synchronize()

@@ -1,0 +1,113 @@
+"""GPU parity of the fused MTTKRP (cals_mttkrp through the C-ABI) against the CPU oracle.
+
+Bar (floating point, fp64): per-element |gpu - oracle| <= 1e-12 * sum|terms| of that element
+(for non-negative data that is the element itself, i.e. the relative error)."""
+import numpy as np
+import pytest
+
+import oracle as O
+from workloads import get_config, make_tensor, random_tensor, uniform_factors
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-12
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _fused(dims, ranks, seed, signed=False):
+    facs = [uniform_factors(dims, r, seed + k) for k, r in enumerate(ranks)]
+    U = [np.hstack([f[n] for f in facs]) for n in range(3)]
+    if signed:
+        U = [2.0 * u - 1.0 for u in U]
+    return U
+
+
+def _abs_scale(T, U, mode):
+    """sum of |terms| per output element = MTTKRP of |T| with |U| (oracle definition, non-negative data)."""
+    return O.mttkrp(np.abs(T), [np.abs(u) for u in U], mode)
+
+
+def _gpu_mttkrp(T, U, pad_to=None, poison=True):
+    import paper_2010_04678_amd as P
+    torch = _torch()
+    dims = (T.shape[2], T.shape[1], T.shape[0])
+    R = U[0].shape[1]
+    ld = pad_to if pad_to is not None else R
+    ctx = P.Context(max_total_rank=max(R, 1))
+    Td = torch.from_numpy(T).cuda()
+    ctx.submit_tensor(Td)
+    Ud = []
+    for n in range(3):
+        buf = torch.full((dims[n], ld), float("nan") if poison else 0.0, dtype=torch.float64, device="cuda")
+        buf[:, :R] = torch.from_numpy(np.ascontiguousarray(U[n])).cuda()
+        Ud.append(buf)
+    out = []
+    for mode in (1, 2, 3):
+        M = torch.full((dims[mode - 1], ld), 777.0, dtype=torch.float64, device="cuda")
+        ctx.mttkrp(mode, Ud, M, total_rank=R)
+        torch.cuda.synchronize()
+        Mh = M.cpu().numpy()
+        assert np.all(Mh[:, R:] == 777.0), "columns beyond total_rank must not be touched"
+        out.append(Mh[:, :R])
+    ctx.close()
+    return out
+
+
+CASES = [
+    # dims, ranks, signed
+    ((17, 13, 11), [3, 1, 5], True),            # odd sizes, ragged everywhere, one 16-column tile
+    ((32, 32, 32), [1, 2, 3, 4, 5] * 2, False), # config 1 shape
+    ((70, 9, 150), [7] * 5, True),              # two 16-row tiles + tail, contraction much longer than a stage
+    ((5, 3, 2), [1], True),                     # smaller than any tile; contracted index shorter than a stage
+    ((3, 130, 2), [20, 20, 20, 3], False),      # tiny fast index for modes 2,3 (general wrap path), 4 column tiles
+    ((129, 65, 33), list(range(1, 21)) + [11] * 20, True),   # 430 columns: the widest single column block
+    ((40, 24, 20), [20] * 30, False),           # 600 columns: two column blocks
+]
+
+
+@pytest.mark.parametrize("dims,ranks,signed", CASES)
+def test_mttkrp_matches_oracle_elementwise(dims, ranks, signed):
+    T = random_tensor(dims, 7 + dims[0], signed=signed)
+    U = _fused(dims, ranks, 100 + dims[1], signed=signed)
+    got = _gpu_mttkrp(T, U, pad_to=sum(ranks) + 5)
+    for mode in (1, 2, 3):
+        want = O.mttkrp(T, U, mode)
+        scale = _abs_scale(T, U, mode)
+        err = np.abs(got[mode - 1] - want)
+        assert np.all(np.isfinite(got[mode - 1]))
+        assert np.all(err <= TOL * scale + 1e-300), (mode, float((err / (scale + 1e-300)).max()))
+
+
+def test_mttkrp_config2_shape_reduced_depth():
+    # configuration 2's fused width (110) on a tensor with its row count but fewer slabs (oracle stays fast)
+    cfg = get_config(2)
+    dims = (200, 200, 24)
+    T = make_tensor(cfg, dims)
+    U = _fused(dims, cfg.ranks, 300)
+    got = _gpu_mttkrp(T, U)
+    for mode in (1, 2, 3):
+        want = O.mttkrp(T, U, mode)
+        rel = np.abs(got[mode - 1] - want) / np.abs(want)
+        assert rel.max() <= TOL, (mode, rel.max())
+
+
+def test_mttkrp_is_bit_reproducible_and_fusion_is_exact():
+    # Eq. (2): a model's block of the fused result equals its solo MTTKRP.  With a fixed split of the
+    # contraction range the GPU result is also run-to-run identical.
+    dims, ranks = (48, 40, 36), [2, 7, 1, 12, 9]
+    T = random_tensor(dims, 55, signed=True)
+    U = _fused(dims, ranks, 500, signed=True)
+    a = _gpu_mttkrp(T, U)
+    b = _gpu_mttkrp(T, U)
+    for mode in range(3):
+        assert np.array_equal(a[mode], b[mode])
+    c0 = 0
+    for r in ranks:
+        solo = _gpu_mttkrp(T, [u[:, c0:c0 + r] for u in U])
+        for mode in range(3):
+            scale = _abs_scale(T, [u[:, c0:c0 + r] for u in U], mode + 1)
+            assert np.all(np.abs(solo[mode] - a[mode][:, c0:c0 + r]) <= 1e-13 * scale)
+        c0 += r
