@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the CALS hot path on one MI355X.
+
+A step is one round of the full algorithm (Alg. 3) over every model of the workload: three fused
+MTTKRPs, the per-model Gram/Hadamard/Cholesky/normalise/fit updates, the fit read-back and the retire
+decision; the last timed step retires all models (factor copy-out and bookkeeping included).  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg2|cfg1|cfg5shape|cfg3shape]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP64_MFMA_TFLOPS = 78.6      # MI355X dense fp64 matrix peak (256 CUs x 128 flop/clk x 2.4 GHz)
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain elementwise copy kernel of known size (counter calibration for rocprofv3 --pmc)")
+    return ap.parse_args()
+
+
+def workload(name: str):
+    from workloads import get_config
+    cid = {"cfg1": 1, "cfg2": 2, "cfg3shape": 3, "cfg4": 4, "cfg5shape": 5}[name]
+    return get_config(cid)
+
+
+def cpu_baseline(cfg, T: np.ndarray, models) -> dict:
+    """The oracle as it stands, timed on this host on a bounded sample: its fused MTTKRP of the workload's
+    full width, all three modes, on the first slabs of the same tensor (sized for roughly 10-30 s)."""
+    import oracle as O
+    I1, I2, I3 = cfg.dims
+    U = [np.hstack([m["init"][n] for m in models]) for n in range(3)]
+    R = U[0].shape[1]
+    # probe on a thin sample, then size the timed sample for ~15 s
+    s0 = max(1, min(I3, int(2e9 / (2.0 * R * I1 * I2)) or 1))
+    Ts = np.ascontiguousarray(T[:s0])
+    Us = [U[0], U[1], U[2][:s0]]
+    t = time.perf_counter()
+    O.mttkrp(Ts, Us, 1)
+    dt = time.perf_counter() - t
+    rate = 2.0 * R * I1 * I2 * s0 / max(dt, 1e-9)
+    slabs = int(max(1, min(I3, (15.0 * rate / 3.0) / (2.0 * R * I1 * I2))))
+    Ts = np.ascontiguousarray(T[:slabs])
+    Us = [U[0], U[1], U[2][:slabs]]
+    t = time.perf_counter()
+    for mode in (1, 2, 3):
+        O.mttkrp(Ts, Us, mode)
+    dt = time.perf_counter() - t
+    flops = 3 * 2.0 * R * I1 * I2 * slabs
+    return {"value": flops / dt * 1e-9, "unit": "GFLOP/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": "oracle fused MTTKRP, all 3 modes, width %d, first %d of %d slabs (i3) of the %s tensor, %.1f s"
+                      % (R, slabs, I3, cfg.name, dt)}
+
+
+def main() -> int:
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+    if args.calibrate_copy:
+        n = 1 << 28                                    # 2 GiB read + 2 GiB written per launch
+        a = torch.ones(n, dtype=torch.float64, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.add(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "read_bytes_per_launch": 8 * n, "write_bytes_per_launch": 8 * n,
+                          "launches": 3}))
+        return 0
+    import paper_2010_04678_amd as P
+    from workloads import make_models, make_tensor
+
+    cfg = workload(args.workload)
+    K, W = args.steps, args.warmup
+    I1, I2, I3 = cfg.dims
+    t_gen = time.perf_counter()
+    T = make_tensor(cfg, threads=min(16, os.cpu_count() or 8))
+    models = make_models(cfg)
+    # active set of the benchmark: the models that fit the buffers at once (all of them except for the queued cfg5)
+    active, tot = [], 0
+    for m in models:
+        if tot + m["rank"] > cfg.max_total_rank or (cfg.max_slots and len(active) >= cfg.max_slots):
+            break
+        active.append(m)
+        tot += m["rank"]
+    t_gen = time.perf_counter() - t_gen
+
+    dev = torch.device("cuda:0")
+    Td = torch.from_numpy(T).to(dev)
+    torch.cuda.synchronize()
+    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots, flags=P.CTX_TIMING)
+    ctx.submit_tensor(Td)
+    for m in active:
+        ctx.enqueue_model(m["init"], tol=-1.0, max_iters=W + K)   # plain ALS steps; nobody leaves before the last step
+    if W > 0:
+        ctx.iterate(W)
+    torch.cuda.synchronize()
+    s0 = ctx.stats()
+    t0 = time.perf_counter()
+    ctx.iterate(K)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    s1 = ctx.stats()
+    res = ctx.poll_retired()
+    assert len(res) == len(active) and all(r.iters == W + K for r in res), "every model must finish in the last step"
+    assert s1.rounds - s0.rounds == K
+
+    dt = t1 - t0
+    flops = s1.mttkrp_flops - s0.mttkrp_flops               # algorithmic: 2 * width * prod(I) per MTTKRP
+    assert abs(flops - 6.0 * tot * I1 * I2 * I3 * K) <= 1e-6 * flops
+    launches = sum(s1.mttkrp_launches) - sum(s0.mttkrp_launches)
+    kern_ms = sum(s1.mttkrp_ms) - sum(s0.mttkrp_ms)
+    per_mode_ms = [(s1.mttkrp_ms[n] - s0.mttkrp_ms[n]) / max(1, s1.mttkrp_launches[n] - s0.mttkrp_launches[n])
+                   for n in range(3)]
+    avg_ms = kern_ms / launches
+    flops_per_launch = 2.0 * tot * I1 * I2 * I3
+    bytes_per_launch = 8.0 * I1 * I2 * I3 + 8.0 * tot * (I1 + I2 + I3)   # tensor once + two factor panels + output
+    ai = flops_per_launch / bytes_per_launch
+    if ai >= PEAK_FP64_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        achieved = flops_per_launch / (avg_ms * 1e-3) * 1e-12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP64_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_FP64_MFMA_TFLOPS}
+    else:
+        achieved = bytes_per_launch / (avg_ms * 1e-3) * 1e-9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": achieved / PEAK_HBM_GBS}
+    roof["traffic"] = None
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tfile):
+        try:
+            roof["traffic"] = json.load(open(tfile)).get(cfg.name)
+        except Exception:
+            roof["traffic"] = None
+    roof["kernel"] = "mttkrp_kernel (fused MTTKRP contraction)"
+    roof["avg_launch_ms"] = avg_ms
+    roof["per_mode_ms"] = per_mode_ms
+
+    out = {
+        "metric": "fused MTTKRP fp64 GFLOP/s (% roofline); CP-ALS models completed/sec",
+        "value": flops / dt * 1e-9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": dt / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": cfg.name, "dims": list(cfg.dims), "models": len(active), "total_rank": tot,
+                   "iterations_timed": K},
+        "sweeps_per_s": K / dt,
+        "models_per_s": len(active) / dt,
+        "model_iterations_per_s": len(active) * K / dt,
+        "roofline": roof,
+        "setup_s": {"generate": t_gen},
+    }
+    ctx.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, T, active)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

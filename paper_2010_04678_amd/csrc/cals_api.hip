@@ -40,7 +40,7 @@ struct PendingModel {
   int max_iters;
   uint32_t flags;
   double alpha;
-  std::vector<double> init[3];  // row-major I_n x rank
+  std::vector<double> init[3];  // column-major I_n x rank, as given
 };
 
 struct ActiveModel {
@@ -90,6 +90,12 @@ struct cals_ctx {
   int32_t* h_map = nullptr;      // pinned
   uint32_t* passive[3] = {nullptr, nullptr, nullptr};  // NONNEG only
   double* d_scratch = nullptr;   // 1024 partial sums + result + flag
+  double* d_lambda = nullptr;    // kMaxRank column norms per sid
+  double* h_lambda = nullptr;    // pinned
+  double* d_stage = nullptr;     // (I1+I2+I3) x ld doubles: packed columns on their way in (fill) or out (retire)
+  double* h_stage = nullptr;     // pinned, same size
+  int32_t* d_rmap = nullptr;     // columns of the models being retired
+  int32_t* h_rmap = nullptr;     // pinned
   std::deque<PendingModel> queue;
   std::vector<ActiveModel> active;
   std::vector<int> free_sids;
@@ -222,62 +228,115 @@ int upload_desc(cals_ctx* c) {
 }
 
 // Alg. 3, fill loop: take models from the queue front while they fit; stop at the first that does not.
+// The new models' starting factors travel as ONE packed block per mode (pinned staging, one copy, one
+// scatter kernel) and land in the columns right after the current ones.
 int fill(cals_ctx* c) {
   const int first_new = (int)c->active.size();
-  while (!c->queue.empty()) {
-    PendingModel& pm = c->queue.front();
-    if (c->total_rank + pm.rank > c->opt.max_total_rank) break;
-    if ((int)c->active.size() >= c->capacity) break;
+  const int col0 = c->total_rank;
+  std::vector<const PendingModel*> fresh;
+  int newcols = 0;
+  size_t n_take = 0;
+  for (const PendingModel& pm : c->queue) {
+    if (col0 + newcols + pm.rank > c->opt.max_total_rank) break;
+    if ((int)c->active.size() + (int)fresh.size() >= c->capacity) break;
+    fresh.push_back(&pm);
+    newcols += pm.rank;
+    ++n_take;
+  }
+  if (fresh.empty()) return CALS_OK;
+  // pack: per mode a row-major I_n x newcols block
+  size_t off = 0;
+  size_t mode_off[3];
+  for (int n = 0; n < 3; ++n) {
+    const int64_t In = c->dims[n];
+    mode_off[n] = off;
+    double* blk = c->h_stage + off;
+    int cofs = 0;
+    for (const PendingModel* pm : fresh) {
+      const double* src = pm->init[n].data();
+      for (int q = 0; q < pm->rank; ++q)
+        for (int64_t i = 0; i < In; ++i) blk[(size_t)i * newcols + cofs + q] = src[(size_t)(i + In * q)];
+      cofs += pm->rank;
+    }
+    off += (size_t)In * newcols;
+  }
+  HIP_TRY(hipMemcpyAsync(c->d_stage, c->h_stage, sizeof(double) * off, hipMemcpyHostToDevice, c->stream));
+  for (int n = 0; n < 3; ++n)
+    HIP_TRY(launch_copy_block(c->d_stage + mode_off[n], newcols, c->U[n] + col0, c->ld, (int)c->dims[n], newcols,
+                              c->stream));
+  int col = col0;
+  for (const PendingModel* pm : fresh) {
     ActiveModel m;
-    m.id = pm.id; m.rank = pm.rank; m.tol = pm.tol; m.max_iters = pm.max_iters; m.flags = pm.flags;
-    m.alpha = pm.alpha; m.fit_prev = 0.0;
+    m.id = pm->id; m.rank = pm->rank; m.tol = pm->tol; m.max_iters = pm->max_iters; m.flags = pm->flags;
+    m.alpha = pm->alpha; m.fit_prev = 0.0;
     m.sid = c->free_sids.back();
     c->free_sids.pop_back();
-    m.col = c->total_rank;
-    for (int n = 0; n < 3; ++n) {
-      HIP_TRY(hipMemcpy2D(c->U[n] + m.col, sizeof(double) * c->ld, pm.init[n].data(), sizeof(double) * m.rank,
-                          sizeof(double) * m.rank, (size_t)c->dims[n], hipMemcpyHostToDevice));
-    }
-    c->total_rank += m.rank;
+    m.col = col;
+    col += m.rank;
     c->active.push_back(m);
-    c->queue.pop_front();
-    c->desc_dirty = true;
   }
-  const int count = (int)c->active.size() - first_new;
-  if (count > 0) {
-    CALS_TRY(upload_desc(c));
-    const int In[3] = {(int)c->dims[0], (int)c->dims[1], (int)c->dims[2]};
-    const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
-    HIP_TRY(launch_gram_init(c->d_desc, c->d_state, c->d_out, true, Uc, In, c->ld, first_new, count, c->stream));
-  }
+  c->total_rank = col;
+  c->desc_dirty = true;
+  CALS_TRY(upload_desc(c));
+  const int In[3] = {(int)c->dims[0], (int)c->dims[1], (int)c->dims[2]};
+  const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
+  HIP_TRY(launch_gram_init(c->d_desc, c->d_state, c->d_out, c->d_lambda, true, Uc, In, c->ld, first_new,
+                           (int)fresh.size(), c->stream));
+  // the staging buffer and the queue entries are free again once the copy has been consumed
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  for (size_t k = 0; k < n_take; ++k) c->queue.pop_front();
   return CALS_OK;
 }
 
-int retire_model(cals_ctx* c, const ActiveModel& m, const ModelOut& o, int status) {
-  RetiredModel r;
-  r.res.model_id = m.id;
-  r.res.rank = m.rank;
-  r.res.iters = o.iters;
-  r.res.status = status;
-  r.res.ls_accepted = o.ls_accepted;
-  r.res.fit = o.fit;
-  r.res.error = o.err;
-  std::vector<double> rowmajor;
-  for (int n = 0; n < 3; ++n) {
-    const int64_t In = c->dims[n];
-    rowmajor.resize((size_t)In * m.rank);
-    HIP_TRY(hipMemcpy2D(rowmajor.data(), sizeof(double) * m.rank, c->U[n] + m.col, sizeof(double) * c->ld,
-                        sizeof(double) * m.rank, (size_t)In, hipMemcpyDeviceToHost));
-    r.U[n].resize((size_t)In * m.rank);
-    for (int64_t i = 0; i < In; ++i)
-      for (int q = 0; q < m.rank; ++q) r.U[n][(size_t)(i + In * q)] = rowmajor[(size_t)(i * m.rank + q)];
+// Copies the factors and column norms of the models leaving this round to the host: one gather kernel and
+// one contiguous copy per mode, then a host-side unpack into per-model column-major matrices.
+int retire_models(cals_ctx* c, const std::vector<ActiveModel>& leaving, const std::vector<int>& statuses) {
+  int outcols = 0;
+  for (const ActiveModel& m : leaving) {
+    for (int q = 0; q < m.rank; ++q) c->h_rmap[outcols + q] = m.col + q;
+    outcols += m.rank;
   }
-  r.lambda.resize(m.rank);
-  HIP_TRY(hipMemcpy(r.lambda.data(), c->d_state[m.sid].lambda, sizeof(double) * m.rank, hipMemcpyDeviceToHost));
-  c->retired[m.id] = std::move(r);
-  c->out_queue.push_back(m.id);
-  c->free_sids.push_back(m.sid);
-  c->n_retired += 1;
+  HIP_TRY(hipMemcpyAsync(c->d_rmap, c->h_rmap, sizeof(int32_t) * outcols, hipMemcpyHostToDevice, c->stream));
+  size_t off = 0;
+  size_t mode_off[3];
+  for (int n = 0; n < 3; ++n) {
+    mode_off[n] = off;
+    HIP_TRY(launch_gather_block(c->U[n], c->ld, c->d_stage + off, outcols, c->d_rmap, (int)c->dims[n], outcols,
+                                c->stream));
+    off += (size_t)c->dims[n] * outcols;
+  }
+  HIP_TRY(hipMemcpyAsync(c->h_stage, c->d_stage, sizeof(double) * off, hipMemcpyDeviceToHost, c->stream));
+  int max_sid = 0;
+  for (const ActiveModel& m : leaving) max_sid = std::max(max_sid, m.sid);
+  HIP_TRY(hipMemcpyAsync(c->h_lambda, c->d_lambda, sizeof(double) * kMaxRank * (max_sid + 1), hipMemcpyDeviceToHost,
+                         c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  int cofs = 0;
+  for (size_t k = 0; k < leaving.size(); ++k) {
+    const ActiveModel& m = leaving[k];
+    const ModelOut& o = c->h_out[m.sid];
+    RetiredModel r;
+    r.res.model_id = m.id;
+    r.res.rank = m.rank;
+    r.res.iters = o.iters;
+    r.res.status = statuses[k];
+    r.res.ls_accepted = o.ls_accepted;
+    r.res.fit = o.fit;
+    r.res.error = o.err;
+    for (int n = 0; n < 3; ++n) {
+      const int64_t In = c->dims[n];
+      const double* blk = c->h_stage + mode_off[n];
+      r.U[n].resize((size_t)In * m.rank);
+      for (int q = 0; q < m.rank; ++q)
+        for (int64_t i = 0; i < In; ++i) r.U[n][(size_t)(i + In * q)] = blk[(size_t)i * outcols + cofs + q];
+    }
+    r.lambda.assign(c->h_lambda + (size_t)m.sid * kMaxRank, c->h_lambda + (size_t)m.sid * kMaxRank + m.rank);
+    cofs += m.rank;
+    c->retired[m.id] = std::move(r);
+    c->out_queue.push_back(m.id);
+    c->free_sids.push_back(m.sid);
+    c->n_retired += 1;
+  }
   return CALS_OK;
 }
 
@@ -320,7 +379,7 @@ int one_round(cals_ctx* c, int* retired_now) {
     const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
     CALS_TRY(run_mttkrp(c, mode, Uc, c->M, c->total_rank, c->ld));
     UpdateArgs ua{};
-    ua.desc = c->d_desc; ua.state = c->d_state; ua.out = c->d_out;
+    ua.desc = c->d_desc; ua.state = c->d_state; ua.out = c->d_out; ua.lambda = c->d_lambda;
     ua.M = c->M; ua.U = c->U[mode]; ua.passive = c->passive[mode];
     ua.In = (int)c->dims[mode]; ua.ld = c->ld; ua.mode = mode;
     ua.n_models = n; ua.max_slots = c->capacity; ua.normT2 = c->normT2;
@@ -335,7 +394,8 @@ int one_round(cals_ctx* c, int* retired_now) {
 
   // Alg. 3, removal loop: slots in order; a model leaves when its fit changed by less than tol between two
   // consecutive iterations, when it reached its iteration cap, or when its update failed numerically.
-  std::vector<ActiveModel> survivors;
+  std::vector<ActiveModel> survivors, leaving;
+  std::vector<int> statuses;
   survivors.reserve(c->active.size());
   for (ActiveModel& m : c->active) {
     const ModelOut& o = c->h_out[m.sid];
@@ -345,13 +405,17 @@ int one_round(cals_ctx* c, int* retired_now) {
     else if (o.iters >= m.max_iters) status = CALS_MAX_ITERS;
     m.fit_prev = o.fit;
     if (status != CALS_RUNNING) {
-      CALS_TRY(retire_model(c, m, o, status));
+      leaving.push_back(m);
+      statuses.push_back(status);
       *retired_now += 1;
     } else {
       survivors.push_back(m);
     }
   }
-  if (survivors.size() != c->active.size()) CALS_TRY(compact(c, survivors));
+  if (!leaving.empty()) {
+    CALS_TRY(retire_models(c, leaving, statuses));
+    CALS_TRY(compact(c, survivors));
+  }
   return CALS_OK;
 }
 
@@ -395,7 +459,9 @@ int cals_destroy(cals_ctx* c) {
   }
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned);
+  (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
+  (void)hipHostFree(c->h_lambda); (void)hipHostFree(c->h_stage); (void)hipHostFree(c->h_rmap);
   delete c;
   return CALS_OK;
 }
@@ -436,6 +502,13 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
   ok = ok && hipHostMalloc(&c->h_desc, sizeof(ModelDesc) * c->capacity) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_map, sizeof(int32_t) * c->ld) == hipSuccess;
+  const size_t stage_doubles = (size_t)(dims[0] + dims[1] + dims[2]) * c->ld;
+  ok = ok && hipMalloc(&c->d_lambda, sizeof(double) * kMaxRank * c->capacity) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_lambda, sizeof(double) * kMaxRank * c->capacity) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_stage, sizeof(double) * stage_doubles) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_stage, sizeof(double) * stage_doubles) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_rmap, sizeof(int32_t) * c->ld) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_rmap, sizeof(int32_t) * c->ld) == hipSuccess;
   if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
   HIP_TRY(hipMemsetAsync(c->d_out, 0, sizeof(ModelOut) * c->capacity, c->stream));
   c->free_sids.clear();
@@ -472,9 +545,7 @@ int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const init[3], d
     if (!init[n]) return CALS_E_INVALID;
     const int64_t In = c->dims[n];
     if (!all_finite(init[n], In * rank)) return CALS_E_INVALID;
-    pm.init[n].resize((size_t)In * rank);
-    for (int64_t i = 0; i < In; ++i)
-      for (int q = 0; q < rank; ++q) pm.init[n][(size_t)(i * rank + q)] = init[n][(size_t)(i + In * q)];
+    pm.init[n].assign(init[n], init[n] + (size_t)In * rank);
   }
   c->queue.push_back(std::move(pm));
   if (model_id) *model_id = c->next_id;

@@ -54,7 +54,6 @@ struct ModelDesc {   // one per active model, in slot order
 
 struct ModelState {  // persistent per-model device storage, indexed by sid
   double G[3][kGramStride];   // Gramians of the current factors (rank x rank, ld = rank)
-  double lambda[kMaxRank];
   double inner, normsq;       // error terms of the last mode-3 update
 };
 
@@ -70,6 +69,7 @@ struct UpdateArgs {
   const ModelDesc* desc;
   ModelState* state;
   ModelOut* out;
+  double* lambda;       // column norms, kMaxRank doubles per sid
   const double* M;      // MTTKRP result, row-major In x ld
   double* U;            // factor multi-matrix of the updated mode, row-major In x ld
   uint32_t* passive;    // NONNEG: per (row, slot) passive-set masks for this mode, In x max_slots (or null)
@@ -83,7 +83,7 @@ hipError_t launch_update(const UpdateArgs& a, hipStream_t stream);
 // Gramians of all three modes for models [first, first+count) of desc (used when a model is inserted
 // and after an accepted line-search step).
 // With reset_out, also puts the models' ModelOut back to {0, 0, RUNNING, 0, 0}.
-hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, bool reset_out,
+hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, double* lambda, bool reset_out,
                             const double* const U[3], const int In[3], int ld, int first, int count,
                             hipStream_t stream);
 // ||T||^2 with a fixed summation tree, and a finiteness check (flag[0] != 0 when a NaN/Inf was seen).
@@ -94,11 +94,19 @@ hipError_t launch_norm_sq(const double* T, int64_t n, double* partial /* >= 1024
 hipError_t launch_gather_columns(const double* src, double* dst, const int32_t* map, int rows, int ncols, int ld,
                                  hipStream_t stream);
 
+// Strided block copy on the device: dst[i*dst_ld + c] = src[i*src_ld + c], i < rows, c < cols.
+hipError_t launch_copy_block(const double* src, int64_t src_ld, double* dst, int64_t dst_ld, int rows, int cols,
+                             hipStream_t stream);
+// dst[i*dst_ld + c] = src[i*src_ld + map[c]] (gather with separate leading dimensions).
+hipError_t launch_gather_block(const double* src, int64_t src_ld, double* dst, int64_t dst_ld, const int32_t* map,
+                               int rows, int cols, hipStream_t stream);
+
 // ---- line search (Sec. 5) ------------------------------------------------------------------------
 struct LineSearchArgs {
   const ModelDesc* desc;
   ModelState* state;
   ModelOut* out;
+  double* lambda;
   double* U[3];          // current factors
   double* Uprev[3];      // point after the previous iteration (lambda folded into mode 3)
   double* Unew[3];       // extrapolated point

@@ -177,7 +177,7 @@ __global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
   if (tid < R) {
     const double l = sqrt(Gl[tid * R + tid]);
     lam[tid] = l;
-    st->lambda[tid] = l;
+    a.lambda[d.sid * kMaxRank + tid] = l;
   }
   __syncthreads();
   for (int e = tid; e < R * R; e += 256) {
@@ -214,6 +214,7 @@ struct GramInitArgs {
   const ModelDesc* desc;
   ModelState* state;
   ModelOut* out;
+  double* lambda;
   int reset_out;
   const double* U[3];
   int In[3];
@@ -247,10 +248,10 @@ __global__ void __launch_bounds__(256) gram_init_kernel(GramInitArgs a) {
     o.err = 0.0; o.fit = 0.0; o.status = 0; o.iters = 0; o.ls_accepted = 0; o.pad = 0;
     a.out[d.sid] = o;
   }
-  if (a.reset_out && mode == 0 && tid < kMaxRank) st->lambda[tid] = 1.0;
+  if (a.reset_out && mode == 0 && tid < kMaxRank) a.lambda[d.sid * kMaxRank + tid] = 1.0;
 }
 
-hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, bool reset_out,
+hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, double* lambda, bool reset_out,
                             const double* const U[3], const int In[3], int ld, int first, int count,
                             hipStream_t stream) {
   static bool attr_done = false;
@@ -263,7 +264,7 @@ hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* 
   }
   if (count < 1) return hipSuccess;
   GramInitArgs a;
-  a.desc = desc; a.state = state; a.out = out; a.reset_out = reset_out ? 1 : 0; a.ld = ld; a.first = first;
+  a.desc = desc; a.state = state; a.out = out; a.lambda = lambda; a.reset_out = reset_out ? 1 : 0; a.ld = ld; a.first = first;
   for (int n = 0; n < 3; ++n) { a.U[n] = U[n]; a.In[n] = In[n]; }
   hipLaunchKernelGGL(gram_init_kernel, dim3(count, 3), dim3(256), lds, stream, a);
   return hipGetLastError();
@@ -320,6 +321,29 @@ hipError_t launch_gather_columns(const double* src, double* dst, const int32_t* 
   const int64_t total = (int64_t)rows * ncols;
   hipLaunchKernelGGL(gather_columns_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, src, dst, map,
                      rows, ncols, ld);
+  return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) copy_block_kernel(const double* __restrict__ src, int64_t src_ld,
+                                                         double* __restrict__ dst, int64_t dst_ld,
+                                                         const int32_t* __restrict__ map, int rows, int cols) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)rows * cols) return;
+  const int i = (int)(idx / cols), c = (int)(idx % cols);
+  dst[(int64_t)i * dst_ld + c] = src[(int64_t)i * src_ld + (map ? map[c] : c)];
+}
+
+hipError_t launch_copy_block(const double* src, int64_t src_ld, double* dst, int64_t dst_ld, int rows, int cols,
+                             hipStream_t stream) {
+  return launch_gather_block(src, src_ld, dst, dst_ld, nullptr, rows, cols, stream);
+}
+
+hipError_t launch_gather_block(const double* src, int64_t src_ld, double* dst, int64_t dst_ld, const int32_t* map,
+                               int rows, int cols, hipStream_t stream) {
+  if (rows < 1 || cols < 1) return hipSuccess;
+  const int64_t total = (int64_t)rows * cols;
+  hipLaunchKernelGGL(copy_block_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, src, src_ld, dst,
+                     dst_ld, map, rows, cols);
   return hipGetLastError();
 }
 
