@@ -24,12 +24,13 @@ struct MttkrpProblem {
 };
 
 struct MttkrpPlan {
-  int wn;          // 16-column MFMA tiles per wave
+  int wm;          // 16-row MFMA tiles per wavefront
+  int wn;          // 16-column MFMA tiles per wavefront (all columns of the workgroup)
   int ka;          // contraction rows per LDS stage
   int ny;          // column blocks (grid.y)
   int splits;      // split-K factor (grid.z)
   int64_t chunk;   // contraction indices per split
-  int mtiles;      // 64-row blocks (grid.x)
+  int mtiles;      // row blocks of 64*wm rows
   size_t workspace_bytes;  // split-K partials: splits * In * ld doubles (0 when splits == 1)
 };
 

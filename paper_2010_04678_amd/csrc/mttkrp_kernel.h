@@ -1,0 +1,296 @@
+// Device code of the fused multi-model MTTKRP (Eq. (2) of the paper) for gfx950:
+//   M[m, c] = sum_{ia, ib} T[m, ia, ib] * (Ua[ia, c] * Ub[ib, c])      for every fused column c.
+//
+// One workgroup = 4 wavefronts; wavefront w owns WM 16-row MFMA tiles (rows m0 .. m0+16*WM) and ALL
+// 16*WN columns of the workgroup's column block; the WM*WN accumulator tiles (v_mfma_f64_16x16x4_f64,
+// 4 doubles per lane each) stay in registers over the workgroup's whole share of the contraction range.
+//
+// Measured on MI355X: an fp64 MFMA occupies its SIMD's issue port for all of its 64 cycles -- no other
+// instruction of any wavefront on that SIMD issues meanwhile.  Every non-MFMA instruction therefore costs
+// MFMA time, and the kernel is organised to need as few of them per MFMA as possible:
+//   - a wavefront holds WM row tiles, so one B fragment (one LDS read) feeds WM MFMAs;
+//   - the Khatri-Rao tile (KA x 16*WN) is produced once per workgroup in LDS (one fp64 multiply per
+//     element, a quarter of the rows per wavefront) and never exists in HBM; the row a wavefront produces
+//     is the same for all its lanes, so its address arithmetic runs on the scalar unit;
+//   - tensor fragments go from global memory straight into the MFMA register layout (lane l holds
+//     A[l%16][l/16]); one 64-bit offset serves all WM fragments of a k-step;
+//   - B fragments of k-step s+1 are read from LDS before the MFMAs of k-step s are issued, factor rows
+//     one k-step before they are multiplied, tensor fragments one stage ahead: no wait inside a k-step.
+// The LDS tile is double-buffered with one barrier per stage of KA contraction indices.
+#pragma once
+#include "cals_internal.h"
+
+namespace cals {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+struct MttkrpKernelArgs {
+  const double* T;
+  const double* Ua;
+  const double* Ub;
+  double* P;          // output: partials [split][In][ld], or M itself when there is one split
+  int64_t sm, sa, sb; // element strides of T: output row, fast contracted index, slow contracted index
+  int64_t K, chunk;   // contraction length Ia*Ib; indices per split (multiple of KA)
+  int64_t pstride;    // In * ld
+  int In, Ia, Ib;
+  int ncols, ld;
+  int mtiles, ny, splits;   // logical grid: row blocks, column blocks, splits
+};
+
+// How a contraction index k = ia + Ia*ib maps to a tensor offset ia*sa + ib*sb:
+//   kAffine : sb == Ia*sa, offset = k*sa (modes 1 and 3: no wrap bookkeeping at all)
+//   kWrap   : Ia >= KA, an index advanced by at most KA wraps at most once (mode 2)
+//   kGeneral: any Ia >= 1 (wrap loop; tiny tensors)
+//   kContig4: sa == 1, Ia % 4 == 0, Ia >= KA, 16-byte aligned rows (modes 2 and 3 of aligned tensors): a lane
+//             owns 4 CONSECUTIVE contraction indices per stage (two 16-byte loads, fully coalesced rows); MFMA
+//             k-step s then takes element s of every lane, i.e. tile row 4*lq + s instead of 4*s + lq.
+enum { kAffine = 0, kWrap = 1, kGeneral = 2, kContig4 = 3 };
+
+template <int WM, int WN, int KA, int MODE>
+__global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
+  constexpr int NC = 16 * WN;                 // columns of the LDS tile
+  constexpr int KS = KA / 4;                  // MFMA k-steps per stage = tile rows produced per wavefront
+  constexpr int CU = (NC + 63) / 64;          // 64-column chunks of a tile row
+  constexpr int TILE = KA * NC;               // doubles per LDS buffer
+  extern __shared__ double smem[];            // [2][KA][NC]
+
+  // ---- logical block coordinates.  Hardware hands consecutive workgroup ids to the 8 XCDs in turn; all
+  // workgroups of one split (same factor rows, and for ny > 1 the same tensor tile) are kept on one XCD
+  // so that they share its L2.
+  int bx, by, bz;
+  {
+    const int id = blockIdx.x;
+    const int xcd = id & 7, slot = id >> 3;
+    const int per_split = a.mtiles * a.ny;
+    bz = (slot / per_split) * 8 + xcd;
+    const int g = slot % per_split;
+    by = g % a.ny;
+    bx = g / a.ny;
+  }
+  if (bz >= a.splits) return;                 // uniform per workgroup
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15;                   // A: row within the tile / B,D: column within the tile
+  const int lq = lane >> 4;                   // A,B: k within the k-step / D: row group
+  const int m0 = bx * (64 * WM) + wave * (16 * WM);
+  const int n0 = by * NC;
+  const int64_t kb = (int64_t)bz * a.chunk;
+  const int64_t ke = (kb + a.chunk < a.K) ? (kb + a.chunk) : a.K;
+  const int nstage = (int)((ke - kb + KA - 1) / KA);
+  const int Ia = a.Ia;
+
+  double4_t acc[WM][WN];
+#pragma unroll
+  for (int t = 0; t < WM; ++t)
+#pragma unroll
+    for (int j = 0; j < WN; ++j) acc[t][j] = double4_t{0.0, 0.0, 0.0, 0.0};
+
+  // ---- tensor fragments: lane (li, lq) of row tile t reads T[Prow[t] + koff], koff = offset of its k.
+  // Rows past the end of the matrix are clamped to the last row (their results are never stored).
+  const double* Prow[WM];
+#pragma unroll
+  for (int t = 0; t < WM; ++t) {
+    const int r = m0 + 16 * t + li;
+    Prow[t] = a.T + (int64_t)(r < a.In ? r : a.In - 1) * a.sm;
+  }
+  int64_t koff;                               // ia*sa + ib*sb of this lane's current k
+  int a_ia = 0;                               // only tracked when the offset is not affine in k
+  int a_left;                                 // contraction indices left before ke, from this lane's k
+  {
+    const int64_t k = kb + (MODE == kContig4 ? 4 * lq : lq);
+    if (MODE == kAffine) {
+      koff = k * a.sa;
+    } else {
+      const int64_t ib = k / Ia;
+      a_ia = (int)(k - ib * Ia);
+      koff = (int64_t)a_ia * a.sa + ib * a.sb;
+    }
+    a_left = (int)(ke - k);                   // <= chunk < 2^31 (checked on the host)
+  }
+  const int64_t a_step = 4 * a.sa;
+  const int64_t a_wrap = a.sb - (int64_t)Ia * a.sa;
+
+  double areg0[KS][WM], areg1[KS][WM];
+
+  // Loads are unconditional from a clamped (always valid) offset and masked afterwards: no divergent
+  // control flow around them.
+  auto load_a_stage = [&](double (&dst)[KS][WM]) {
+    if (MODE == kContig4) {
+      static_assert(MODE != kContig4 || KA == 16, "a lane's run of 4 indices times 4 lane groups is one stage");
+      // all four indices of a lane are on the same side of ke (ke, kb and Ia are multiples of 4)
+      const bool ok = a_left > 0;
+      const int64_t off = ok ? koff : 0;
+#pragma unroll
+      for (int t = 0; t < WM; ++t) {
+        const double2 v01 = *reinterpret_cast<const double2*>(Prow[t] + off);
+        const double2 v23 = *reinterpret_cast<const double2*>(Prow[t] + off + 2);
+        dst[0][t] = ok ? v01.x : 0.0;
+        dst[1][t] = ok ? v01.y : 0.0;
+        dst[2][t] = ok ? v23.x : 0.0;
+        dst[3][t] = ok ? v23.y : 0.0;
+      }
+      a_left -= KA;
+      koff += KA;
+      a_ia += KA;
+      if (a_ia >= Ia) { a_ia -= Ia; koff += a_wrap; }
+      return;
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const bool ok = a_left > 0;
+      const int64_t off = ok ? koff : 0;
+#pragma unroll
+      for (int t = 0; t < WM; ++t) {
+        const double v = Prow[t][off];
+        dst[s][t] = ok ? v : 0.0;
+      }
+      a_left -= 4;
+      koff += a_step;
+      if (MODE == kWrap) {
+        a_ia += 4;
+        if (a_ia >= Ia) { a_ia -= Ia; koff += a_wrap; }
+      } else if (MODE == kGeneral) {
+        a_ia += 4;
+        while (a_ia >= Ia) { a_ia -= Ia; koff += a_wrap; }
+      }
+    }
+  };
+
+  // ---- Khatri-Rao tile production.  Wavefront w produces rows w, w+4, ... of the next stage's tile
+  // (one row per k-step): lane l covers columns l, l+64, ...  The row index is uniform over the
+  // wavefront, so (ia, ib) and the two row base pointers live in scalar registers.  Rows and columns
+  // outside the problem are clamped to valid ones rather than zeroed: such a row only meets zero tensor
+  // fragments (a_left <= 0), such a column only feeds output columns that are never stored.
+  int tcol[CU], gcol[CU];
+#pragma unroll
+  for (int u = 0; u < CU; ++u) {
+    const int tc = lane + 64 * u;
+    tcol[u] = tc < NC ? tc : NC - 1;          // surplus lanes repeat the last column (same value, same address)
+    const int gc = n0 + tcol[u];
+    gcol[u] = gc < a.ld ? gc : a.ld - 1;
+  }
+  int p_ia, p_ib;                             // (ia, ib) of the first index of the stage being produced (uniform)
+  {
+    const int64_t ib = kb / Ia;
+    p_ib = (int)ib;
+    p_ia = (int)(kb - ib * Ia);
+  }
+  double pua[2][CU], pub[2][CU];
+
+  auto fetch_row = [&](int x, double (&ua)[CU], double (&ub)[CU]) {
+    int ia = p_ia + wave + 4 * x, ib = p_ib;
+    if (MODE == kGeneral) {
+      while (ia >= Ia) { ia -= Ia; ib += 1; }
+    } else {
+      if (ia >= Ia) { ia -= Ia; ib += 1; }
+    }
+    ib = ib < a.Ib ? ib : a.Ib - 1;
+    const double* ra = a.Ua + (int64_t)ia * a.ld;
+    const double* rb = a.Ub + (int64_t)ib * a.ld;
+#pragma unroll
+    for (int u = 0; u < CU; ++u) {
+      ua[u] = ra[gcol[u]];
+      ub[u] = rb[gcol[u]];
+    }
+  };
+  auto commit_row = [&](double* tile, int x, const double (&ua)[CU], const double (&ub)[CU]) {
+#pragma unroll
+    for (int u = 0; u < CU; ++u) tile[(wave + 4 * x) * NC + tcol[u]] = ua[u] * ub[u];
+  };
+  auto advance_producer = [&]() {
+    p_ia += KA;
+    if (MODE == kGeneral) {
+      while (p_ia >= Ia) { p_ia -= Ia; p_ib += 1; }
+    } else {
+      if (p_ia >= Ia) { p_ia -= Ia; p_ib += 1; }
+    }
+  };
+
+  double breg[2][WN];
+  auto load_b = [&](const double* tile, int s, double (&b)[WN]) {
+    const double* brow = tile + (MODE == kContig4 ? 4 * lq + s : 4 * s + lq) * NC + li;
+#pragma unroll
+    for (int j = 0; j < WN; ++j) b[j] = brow[16 * j];
+  };
+
+  // One stage: MFMAs on (acur, tile `cur`); meanwhile the next tensor fragments are fetched and the
+  // next tile is produced into the other buffer.
+  auto run_stage = [&](const double (&acur)[KS][WM], double (&anext)[KS][WM], int cur) {
+    const double* tile = smem + cur * TILE;
+    double* next_tile = smem + (cur ^ 1) * TILE;
+    load_b(tile, 0, breg[0]);
+    fetch_row(0, pua[0], pub[0]);
+    load_a_stage(anext);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      if (s + 1 < KS) {
+        load_b(tile, s + 1, breg[(s + 1) & 1]);
+        fetch_row(s + 1, pua[(s + 1) & 1], pub[(s + 1) & 1]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int t = 0; t < WM; ++t)
+          acc[t][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(acur[s][t], breg[s & 1][j], acc[t][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      commit_row(next_tile, s, pua[s & 1], pub[s & 1]);
+    }
+    advance_producer();
+    __syncthreads();
+  };
+
+  // ---- prologue: tile 0 and fragment 0
+#pragma unroll
+  for (int x = 0; x < KS; ++x) {
+    fetch_row(x, pua[0], pub[0]);
+    commit_row(smem, x, pua[0], pub[0]);
+  }
+  advance_producer();
+  load_a_stage(areg0);
+  __syncthreads();
+
+  for (int st = 0; st < nstage; st += 2) {
+    run_stage(areg0, areg1, 0);
+    if (st + 1 < nstage) run_stage(areg1, areg0, 1);
+  }
+
+  // ---- epilogue: D[4*v + lq][li] of every tile -> P[split][row][col]
+  double* P = a.P + (int64_t)bz * a.pstride;
+#pragma unroll
+  for (int t = 0; t < WM; ++t) {
+    if (m0 + 16 * t < a.In) {
+#pragma unroll
+      for (int j = 0; j < WN; ++j) {
+        const int col = n0 + 16 * j + li;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int r = m0 + 16 * t + 4 * v + lq;
+          if (r < a.In && col < a.ncols) P[(int64_t)r * a.ld + col] = acc[t][j][v];
+        }
+      }
+    }
+  }
+}
+
+typedef void (*mttkrp_fn)(MttkrpKernelArgs);
+struct Variant {
+  int wm, wn, ka;
+  mttkrp_fn fn[4];    // indexed by kAffine / kWrap / kGeneral / kContig4
+};
+#define CALS_VARIANT(WM_, WN_, KA_)                                                                       \
+  {                                                                                                       \
+    WM_, WN_, KA_, {                                                                                      \
+      mttkrp_kernel<WM_, WN_, KA_, kAffine>, mttkrp_kernel<WM_, WN_, KA_, kWrap>,                         \
+          mttkrp_kernel<WM_, WN_, KA_, kGeneral>, mttkrp_kernel<WM_, WN_, KA_, kContig4>                  \
+    }                                                                                                     \
+  }
+
+// Variant tables, one translation unit per WM (compiled in parallel).
+const Variant* mttkrp_variants_wm1(int* n);
+const Variant* mttkrp_variants_wm2(int* n);
+const Variant* mttkrp_variants_wm4(int* n);
+
+}  // namespace cals
