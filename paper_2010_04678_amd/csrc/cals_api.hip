@@ -90,6 +90,7 @@ struct cals_ctx {
   int32_t* h_map = nullptr;      // pinned
   uint32_t* passive[3] = {nullptr, nullptr, nullptr};  // NONNEG only
   double* d_scratch = nullptr;   // 1024 partial sums + result + flag
+  double* d_zeros = nullptr;     // 8 zero doubles (what MTTKRP lanes past the end of a split load)
   double* d_lambda = nullptr;    // kMaxRank column norms per sid
   double* h_lambda = nullptr;    // pinned
   double* d_stage = nullptr;     // (I1+I2+I3) x ld doubles: packed columns on their way in (fill) or out (retire)
@@ -144,6 +145,7 @@ MttkrpProblem make_problem(const cals_ctx* c, int mode, const double* const U[3]
   const int64_t I1 = c->dims[0], I2 = c->dims[1];
   MttkrpProblem p{};
   p.T = c->T;
+  p.zeros = c->d_zeros;
   p.M = M;
   p.ncols = ncols;
   p.ld = ld;
@@ -189,7 +191,8 @@ int drain_timings(cals_ctx* c) {
 
 int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int ncols, int ld) {
   MttkrpProblem p = make_problem(c, mode, U, M, ncols, ld);
-  if ((int64_t)p.Ia * ld >= (1LL << 31) || (int64_t)p.Ib * ld >= (1LL << 31)) return CALS_E_UNSUPPORTED;
+  // factor matrices are addressed with 32-bit byte offsets
+  if ((int64_t)p.Ia * ld * 8 >= (1LL << 32) || (int64_t)p.Ib * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
   MttkrpPlan pl = mttkrp_plan(p, c->num_cus);
   if (pl.chunk >= (1LL << 31)) return CALS_E_UNSUPPORTED;
   CALS_TRY(ensure_workspace(c, pl.workspace_bytes));
@@ -459,7 +462,7 @@ int cals_destroy(cals_ctx* c) {
   }
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned);
-  (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
+  (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
   (void)hipHostFree(c->h_lambda); (void)hipHostFree(c->h_stage); (void)hipHostFree(c->h_rmap);
   delete c;
@@ -499,6 +502,8 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
   ok = ok && hipMalloc(&c->d_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
   ok = ok && hipMalloc(&c->d_map, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipMalloc(&c->d_scratch, sizeof(double) * 1032) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_zeros, sizeof(double) * 8) == hipSuccess;
+  ok = ok && hipMemsetAsync(c->d_zeros, 0, sizeof(double) * 8, c->stream) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_desc, sizeof(ModelDesc) * c->capacity) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_map, sizeof(int32_t) * c->ld) == hipSuccess;

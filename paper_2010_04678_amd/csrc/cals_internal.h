@@ -17,6 +17,7 @@ struct MttkrpProblem {
   const double* Ua;   // row-major Ia x ld
   const double* Ub;   // row-major Ib x ld
   double* M;          // row-major In x ld, columns [0,ncols) written
+  const double* zeros; // device buffer of at least 4 zero doubles, 16-byte aligned
   int64_t sm, sa, sb; // element strides in T
   int In, Ia, Ib;
   int ncols;          // fused width (total rank)

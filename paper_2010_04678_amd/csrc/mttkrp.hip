@@ -85,7 +85,7 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
   if (force_splits > 0) splits = force_splits;
   if (splits < 1) splits = 1;
   int64_t chunk = (K + splits - 1) / splits;
-  chunk = (chunk + pl.ka - 1) / pl.ka * pl.ka;
+  chunk = (chunk + 2 * pl.ka - 1) / (2 * pl.ka) * (2 * pl.ka);   // whole stage pairs
   splits = (K + chunk - 1) / chunk;
   pl.splits = (int)splits;
   pl.chunk = chunk;
@@ -101,8 +101,9 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   if ((int64_t)pl.ny * 16 * pl.wn < p.ncols || (int64_t)pl.mtiles * 64 * pl.wm < p.In) return hipErrorInvalidValue;
   if (pl.chunk % pl.ka != 0 || (int64_t)pl.splits * pl.chunk < (int64_t)p.Ia * p.Ib) return hipErrorInvalidValue;
   if (pl.splits > 1 && !workspace) return hipErrorInvalidValue;
+  if (!p.zeros || (reinterpret_cast<uintptr_t>(p.zeros) & 15)) return hipErrorInvalidValue;
   MttkrpKernelArgs a;
-  a.T = p.T; a.Ua = p.Ua; a.Ub = p.Ub;
+  a.T = p.T; a.Ua = p.Ua; a.Ub = p.Ub; a.zeros = p.zeros;
   a.P = (pl.splits > 1) ? workspace : p.M;
   a.sm = p.sm; a.sa = p.sa; a.sb = p.sb;
   a.K = (int64_t)p.Ia * p.Ib; a.chunk = pl.chunk;

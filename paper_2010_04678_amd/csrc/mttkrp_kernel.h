@@ -23,12 +23,23 @@
 namespace cals {
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
+typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
+
+// Factor rows are read through buffer descriptors: scalar base (the matrix), scalar offset (the row, uniform
+// over the wavefront) and a 32-bit per-lane offset (the column) -- no vector address arithmetic at all.
+__device__ inline __amdgpu_buffer_rsrc_t factor_rsrc(const double* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ inline double buffer_load_f64(__amdgpu_buffer_rsrc_t rsrc, unsigned lane_byte, unsigned row_byte) {
+  return __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_byte, (int)row_byte, 0));
+}
 
 struct MttkrpKernelArgs {
   const double* T;
   const double* Ua;
   const double* Ub;
   double* P;          // output: partials [split][In][ld], or M itself when there is one split
+  const double* zeros; // >= 4 zero doubles, 16-byte aligned: what a lane past the end of its split loads
   int64_t sm, sa, sb; // element strides of T: output row, fast contracted index, slow contracted index
   int64_t K, chunk;   // contraction length Ia*Ib; indices per split (multiple of KA)
   int64_t pstride;    // In * ld
@@ -114,22 +125,24 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 
   double areg0[KS][WM], areg1[KS][WM];
 
-  // Loads are unconditional from a clamped (always valid) offset and masked afterwards: no divergent
-  // control flow around them.
+  // Loads are unconditional; a lane past the end of the split reads from a zero buffer instead (pointer
+  // select: no divergent control flow, and nothing to patch once the value arrives, which would make the
+  // wavefront wait for the load right away).
+  const double* const zeros = a.zeros;
   auto load_a_stage = [&](double (&dst)[KS][WM]) {
     if (MODE == kContig4) {
       static_assert(MODE != kContig4 || KA == 16, "a lane's run of 4 indices times 4 lane groups is one stage");
       // all four indices of a lane are on the same side of ke (ke, kb and Ia are multiples of 4)
       const bool ok = a_left > 0;
-      const int64_t off = ok ? koff : 0;
 #pragma unroll
       for (int t = 0; t < WM; ++t) {
-        const double2 v01 = *reinterpret_cast<const double2*>(Prow[t] + off);
-        const double2 v23 = *reinterpret_cast<const double2*>(Prow[t] + off + 2);
-        dst[0][t] = ok ? v01.x : 0.0;
-        dst[1][t] = ok ? v01.y : 0.0;
-        dst[2][t] = ok ? v23.x : 0.0;
-        dst[3][t] = ok ? v23.y : 0.0;
+        const double* p = ok ? Prow[t] + koff : zeros;
+        const double2 v01 = *reinterpret_cast<const double2*>(p);
+        const double2 v23 = *reinterpret_cast<const double2*>(p + 2);
+        dst[0][t] = v01.x;
+        dst[1][t] = v01.y;
+        dst[2][t] = v23.x;
+        dst[3][t] = v23.y;
       }
       a_left -= KA;
       koff += KA;
@@ -140,11 +153,10 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       const bool ok = a_left > 0;
-      const int64_t off = ok ? koff : 0;
 #pragma unroll
       for (int t = 0; t < WM; ++t) {
-        const double v = Prow[t][off];
-        dst[s][t] = ok ? v : 0.0;
+        const double* p = ok ? Prow[t] + koff : zeros;
+        dst[s][t] = *p;
       }
       a_left -= 4;
       koff += a_step;
@@ -163,13 +175,14 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   // wavefront, so (ia, ib) and the two row base pointers live in scalar registers.  Rows and columns
   // outside the problem are clamped to valid ones rather than zeroed: such a row only meets zero tensor
   // fragments (a_left <= 0), such a column only feeds output columns that are never stored.
-  int tcol[CU], gcol[CU];
+  int tcol[CU];
+  unsigned gbyte[CU];                         // byte offset of the lane's column within a factor row
 #pragma unroll
   for (int u = 0; u < CU; ++u) {
     const int tc = lane + 64 * u;
     tcol[u] = tc < NC ? tc : NC - 1;          // surplus lanes repeat the last column (same value, same address)
     const int gc = n0 + tcol[u];
-    gcol[u] = gc < a.ld ? gc : a.ld - 1;
+    gbyte[u] = 8u * (unsigned)(gc < a.ld ? gc : a.ld - 1);
   }
   int p_ia, p_ib;                             // (ia, ib) of the first index of the stage being produced (uniform)
   {
@@ -178,6 +191,9 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
     p_ia = (int)(kb - ib * Ia);
   }
   double pua[2][CU], pub[2][CU];
+  const unsigned row_bytes = 8u * (unsigned)a.ld;
+  const __amdgpu_buffer_rsrc_t rsrc_a = factor_rsrc(a.Ua, row_bytes * (unsigned)Ia);   // < 2^32 (checked on the host)
+  const __amdgpu_buffer_rsrc_t rsrc_b = factor_rsrc(a.Ub, row_bytes * (unsigned)a.Ib);
 
   auto fetch_row = [&](int x, double (&ua)[CU], double (&ub)[CU]) {
     int ia = p_ia + wave + 4 * x, ib = p_ib;
@@ -187,12 +203,13 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
       if (ia >= Ia) { ia -= Ia; ib += 1; }
     }
     ib = ib < a.Ib ? ib : a.Ib - 1;
-    const double* ra = a.Ua + (int64_t)ia * a.ld;
-    const double* rb = a.Ub + (int64_t)ib * a.ld;
+    // uniform by construction; the explicit broadcast keeps them in scalar registers
+    const unsigned oa = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)ia * row_bytes));
+    const unsigned ob = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)ib * row_bytes));
 #pragma unroll
     for (int u = 0; u < CU; ++u) {
-      ua[u] = ra[gcol[u]];
-      ub[u] = rb[gcol[u]];
+      ua[u] = buffer_load_f64(rsrc_a, gbyte[u], oa);
+      ub[u] = buffer_load_f64(rsrc_b, gbyte[u], ob);
     }
   };
   auto commit_row = [&](double* tile, int x, const double (&ua)[CU], const double (&ub)[CU]) {
@@ -222,13 +239,16 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
     double* next_tile = smem + (cur ^ 1) * TILE;
     load_b(tile, 0, breg[0]);
     fetch_row(0, pua[0], pub[0]);
-    load_a_stage(anext);
+    if (KS == 1) load_a_stage(anext);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       if (s + 1 < KS) {
         load_b(tile, s + 1, breg[(s + 1) & 1]);
         fetch_row(s + 1, pua[(s + 1) & 1], pub[(s + 1) & 1]);
       }
+      // The tensor fragments of the next stage are requested in the second k-step: the memory counter
+      // retires in order, so the factor rows committed after k-steps 0 and 1 must not queue behind them.
+      if (KS > 1 && s == 1) load_a_stage(anext);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < WN; ++j)
@@ -252,9 +272,11 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   load_a_stage(areg0);
   __syncthreads();
 
+  // Stages run in pairs (the two register sets and LDS buffers alternate) with no branch in between, so the
+  // accumulators stay in place; a split with an odd stage count runs one extra stage on zero fragments.
   for (int st = 0; st < nstage; st += 2) {
     run_stage(areg0, areg1, 0);
-    if (st + 1 < nstage) run_stage(areg1, areg0, 1);
+    run_stage(areg1, areg0, 1);
   }
 
   // ---- epilogue: D[4*v + lq][li] of every tile -> P[split][row][col]
