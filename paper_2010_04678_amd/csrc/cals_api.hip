@@ -51,6 +51,7 @@ struct ActiveModel {
   uint32_t flags;
   double alpha;
   double fit_prev;
+  int iters;        // completed iterations as of the last read-back
 };
 
 struct RetiredModel {
@@ -97,6 +98,9 @@ struct cals_ctx {
   double* h_stage = nullptr;     // pinned, same size
   int32_t* d_rmap = nullptr;     // columns of the models being retired
   int32_t* h_rmap = nullptr;     // pinned
+  int32_t* d_colmodel = nullptr; // line search: slot position owning each column
+  int32_t* h_colmodel = nullptr; // pinned
+  int32_t* d_accept = nullptr;   // line search: per slot position, extrapolated point taken this round
   std::deque<PendingModel> queue;
   std::vector<ActiveModel> active;
   std::vector<int> free_sids;
@@ -216,6 +220,25 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int n
   return CALS_OK;
 }
 
+// Buffers only line search needs: the previous and the extrapolated point, column ownership, decisions.
+int ensure_ls_buffers(cals_ctx* c) {
+  if (c->d_colmodel) return CALS_OK;
+  HIP_TRY(hipSetDevice(c->opt.device));
+  bool ok = true;
+  for (int n = 0; n < 3; ++n) {
+    const size_t bytes = sizeof(double) * (size_t)c->dims[n] * c->ld;
+    ok = ok && hipMalloc(&c->Uprev[n], bytes) == hipSuccess && hipMalloc(&c->Unew[n], bytes) == hipSuccess;
+    if (ok) ok = hipMemsetAsync(c->Uprev[n], 0, bytes, c->stream) == hipSuccess &&
+                 hipMemsetAsync(c->Unew[n], 0, bytes, c->stream) == hipSuccess;
+  }
+  ok = ok && hipMalloc(&c->d_accept, sizeof(int32_t) * c->capacity) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
+  if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  c->desc_dirty = true;
+  return CALS_OK;
+}
+
 int upload_desc(cals_ctx* c) {
   if (!c->desc_dirty) return CALS_OK;
   const int n = (int)c->active.size();
@@ -226,6 +249,12 @@ int upload_desc(cals_ctx* c) {
     c->h_desc[k] = d;
   }
   if (n > 0) HIP_TRY(hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(ModelDesc) * n, hipMemcpyHostToDevice, c->stream));
+  if (c->d_colmodel && n > 0) {
+    for (int k = 0; k < n; ++k)
+      for (int q = 0; q < c->active[k].rank; ++q) c->h_colmodel[c->active[k].col + q] = k;
+    HIP_TRY(hipMemcpyAsync(c->d_colmodel, c->h_colmodel, sizeof(int32_t) * c->total_rank, hipMemcpyHostToDevice,
+                           c->stream));
+  }
   c->desc_dirty = false;
   return CALS_OK;
 }
@@ -271,7 +300,7 @@ int fill(cals_ctx* c) {
   for (const PendingModel* pm : fresh) {
     ActiveModel m;
     m.id = pm->id; m.rank = pm->rank; m.tol = pm->tol; m.max_iters = pm->max_iters; m.flags = pm->flags;
-    m.alpha = pm->alpha; m.fit_prev = 0.0;
+    m.alpha = pm->alpha; m.fit_prev = 0.0; m.iters = 0;
     m.sid = c->free_sids.back();
     c->free_sids.pop_back();
     m.col = col;
@@ -388,6 +417,29 @@ int one_round(cals_ctx* c, int* retired_now) {
     ua.n_models = n; ua.max_slots = c->capacity; ua.normT2 = c->normT2;
     HIP_TRY(launch_update(ua, c->stream));
   }
+  // line search (Sec. 5): extrapolate, one extra fused mode-3 MTTKRP at the extrapolated point, decide, apply
+  bool round_has_ls = false, ls_takes_part = false;
+  for (const ActiveModel& m : c->active)
+    if (m.flags & CALS_MODEL_LINESEARCH) {
+      round_has_ls = true;
+      if (m.iters + 1 >= 2) ls_takes_part = true;
+    }
+  if (round_has_ls) {
+    LineSearchArgs la{};
+    la.desc = c->d_desc; la.state = c->d_state; la.out = c->d_out; la.lambda = c->d_lambda;
+    la.colmodel = c->d_colmodel; la.accept = c->d_accept;
+    for (int k = 0; k < 3; ++k) {
+      la.U[k] = c->U[k]; la.Uprev[k] = c->Uprev[k]; la.Unew[k] = c->Unew[k]; la.In[k] = (int)c->dims[k];
+    }
+    la.M3 = c->M; la.ld = c->ld; la.n_models = n; la.ncols = c->total_rank; la.normT2 = c->normT2;
+    if (ls_takes_part) {
+      HIP_TRY(launch_ls_extrapolate(la, c->stream));
+      const double* Un[3] = {c->Unew[0], c->Unew[1], c->Unew[2]};
+      CALS_TRY(run_mttkrp(c, 2, Un, c->M, c->total_rank, c->ld));
+    }
+    HIP_TRY(launch_ls_decide(la, c->stream));
+    HIP_TRY(launch_ls_apply(la, c->stream));
+  }
   // the only per-round readback: fit, error, status and iteration count of every slot in use
   int max_sid = 0;
   for (const ActiveModel& m : c->active) max_sid = std::max(max_sid, m.sid);
@@ -407,6 +459,7 @@ int one_round(cals_ctx* c, int* retired_now) {
     else if (o.iters >= 2 && std::fabs(o.fit - m.fit_prev) < m.tol) status = CALS_CONVERGED;
     else if (o.iters >= m.max_iters) status = CALS_MAX_ITERS;
     m.fit_prev = o.fit;
+    m.iters = o.iters;
     if (status != CALS_RUNNING) {
       leaving.push_back(m);
       statuses.push_back(status);
@@ -462,6 +515,7 @@ int cals_destroy(cals_ctx* c) {
   }
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned);
+  (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
   (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
   (void)hipHostFree(c->h_lambda); (void)hipHostFree(c->h_stage); (void)hipHostFree(c->h_rmap);
@@ -542,7 +596,8 @@ int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const init[3], d
   if (flags & ~(CALS_MODEL_NONNEG | CALS_MODEL_LINESEARCH)) return CALS_E_INVALID;
   if ((flags & CALS_MODEL_NONNEG) && (flags & CALS_MODEL_LINESEARCH)) return CALS_E_UNSUPPORTED;
   if ((flags & CALS_MODEL_LINESEARCH) && !std::isfinite(ls_alpha)) return CALS_E_INVALID;
-  if (flags & (CALS_MODEL_NONNEG | CALS_MODEL_LINESEARCH)) return CALS_E_UNSUPPORTED;  // not built yet
+  if (flags & CALS_MODEL_NONNEG) return CALS_E_UNSUPPORTED;  // not built yet
+  if (flags & CALS_MODEL_LINESEARCH) CALS_TRY(ensure_ls_buffers(c));
   PendingModel pm;
   pm.id = c->next_id;
   pm.rank = rank; pm.tol = tol; pm.max_iters = max_iters; pm.flags = flags; pm.alpha = ls_alpha;

@@ -57,6 +57,8 @@ struct ModelDesc {   // one per active model, in slot order
 struct ModelState {  // persistent per-model device storage, indexed by sid
   double G[3][kGramStride];   // Gramians of the current factors (rank x rank, ld = rank)
   double inner, normsq;       // error terms of the last mode-3 update
+  double Gls[3][kGramStride]; // line search: Gramians of the extrapolated point
+  double inner_ls;            // line search: sum(A3_new * M3(A_new))
 };
 
 struct ModelOut {    // per-model scalars the host reads back once per round, indexed by sid
@@ -103,23 +105,30 @@ hipError_t launch_copy_block(const double* src, int64_t src_ld, double* dst, int
 hipError_t launch_gather_block(const double* src, int64_t src_ld, double* dst, int64_t dst_ld, const int32_t* map,
                                int rows, int cols, hipStream_t stream);
 
-// ---- line search (Sec. 5) ------------------------------------------------------------------------
+// ---- line search (Sec. 5, "Line search") -----------------------------------------------------------
+// A point is held with lambda folded into the mode-3 factor.  A model takes part in a round's line search when
+// it has the LINESEARCH flag, is still running and has completed at least two iterations.
 struct LineSearchArgs {
   const ModelDesc* desc;
   ModelState* state;
   ModelOut* out;
   double* lambda;
-  double* U[3];          // current factors
-  double* Uprev[3];      // point after the previous iteration (lambda folded into mode 3)
-  double* Unew[3];       // extrapolated point
+  const int32_t* colmodel; // slot position of the model that owns each column
+  int32_t* accept;         // per slot position: 1 when the extrapolated point was taken this round
+  double* U[3];            // current factors
+  double* Uprev[3];        // point after the previous iteration
+  double* Unew[3];         // extrapolated point
+  const double* M3;        // mode-3 MTTKRP at the extrapolated point, row-major I3 x ld
   int In[3];
-  int ld, n_models;
+  int ld, n_models, ncols;
   double normT2;
 };
-// Unew = Uprev + alpha (Ucur*scale - Uprev) for line-search models past their first iteration (others: Unew = Ucur*scale).
+// Unew = Uprev + alpha (A_cur - Uprev) for the models taking part, Unew = A_cur for all other columns.
 hipError_t launch_ls_extrapolate(const LineSearchArgs& a, hipStream_t stream);
-// Error of the extrapolated point from M3(Unew) (row-major I3 x ld) and acceptance; copies accepted points into U,
-// refreshes Gramians, and stores the new "previous" point.
-hipError_t launch_ls_decide(const LineSearchArgs& a, const double* M3, hipStream_t stream);
+// Gramians of the extrapolated point and sum(A3_new * M3); then e_new = ||T||^2 + sum(G1*G2*G3) - 2 inner and the
+// decision (strictly lower error wins): accepted models get err/fit/Gramians of the new point and lambda = 1.
+hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream);
+// U = Unew for accepted models; Uprev = the point kept (lambda folded into mode 3) for every line-search model.
+hipError_t launch_ls_apply(const LineSearchArgs& a, hipStream_t stream);
 
 }  // namespace cals

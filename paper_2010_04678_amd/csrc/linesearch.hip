@@ -1,0 +1,200 @@
+// Line search for CALS (Sec. 5 of the paper, "Line search"), applied to each model independently after a
+// round's three mode updates: P_new = P_prev + alpha (P_cur - P_prev); the extrapolated point replaces P_cur
+// only if its error is lower.  The error of P_new comes from the fast formula of Alg. 1 with ONE extra fused
+// mode-3 MTTKRP over the extrapolated multi-matrices, so the central fused operation is preserved.
+#include "cals_internal.h"
+
+namespace cals {
+
+constexpr int kRows = 256;
+constexpr int kXs = kRows + 1;
+
+__device__ inline bool ls_takes_part(const ModelDesc& d, const ModelOut& o) {
+  return (d.flags & 2u) && o.status == 0 && o.iters >= 2;
+}
+
+__device__ inline double ls_block_sum(double v, double* red) {
+  const int tid = threadIdx.x;
+  red[tid] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) red[tid] += red[tid + s];
+    __syncthreads();
+  }
+  const double r = red[0];
+  __syncthreads();
+  return r;
+}
+
+__global__ void __launch_bounds__(256) ls_extrapolate_kernel(LineSearchArgs a) {
+  const int mode = blockIdx.y;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)a.In[mode] * a.ncols) return;
+  const int i = (int)(idx / a.ncols), c = (int)(idx % a.ncols);
+  const ModelDesc d = a.desc[a.colmodel[c]];
+  const ModelOut o = a.out[d.sid];
+  const int64_t e = (int64_t)i * a.ld + c;
+  const double scale = (mode == 2) ? a.lambda[d.sid * kMaxRank + (c - d.col)] : 1.0;
+  const double cur = a.U[mode][e] * scale;
+  double v = cur;
+  if (ls_takes_part(d, o)) {
+    const double prev = a.Uprev[mode][e];
+    v = prev + d.alpha * (cur - prev);
+  }
+  a.Unew[mode][e] = v;
+}
+
+// grid (n_models, 3): Gramian of the extrapolated mode-`y` factor block; for mode 3 also sum(A3_new * M3).
+__global__ void __launch_bounds__(256) ls_gram_kernel(LineSearchArgs a) {
+  extern __shared__ double lds[];
+  const ModelDesc d = a.desc[blockIdx.x];
+  const ModelOut o = a.out[d.sid];
+  if (!ls_takes_part(d, o)) return;
+  const int mode = blockIdx.y, tid = threadIdx.x, R = d.rank, In = a.In[mode];
+  ModelState* st = a.state + d.sid;
+  double* xs = lds;                 // R x kXs staged rows
+  double* red = xs + kMaxRank * kXs;
+  const double* Ub = a.Unew[mode] + d.col;
+  const int npairs = R * (R + 1) / 2;
+  double gacc[3] = {0.0, 0.0, 0.0};
+  double inner = 0.0;
+  for (int base = 0; base < In; base += kRows) {
+    const int i = base + tid;
+    const int nrows = (In - base < kRows) ? (In - base) : kRows;
+    if (i < In) {
+      double part = 0.0;
+      for (int r = 0; r < R; ++r) {
+        const double x = Ub[(int64_t)i * a.ld + r];
+        xs[r * kXs + tid] = x;
+        if (mode == 2) part += x * a.M3[(int64_t)i * a.ld + d.col + r];
+      }
+      inner += part;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const int p = tid + 256 * q;
+      if (p < npairs) {
+        int r = (int)((sqrt(8.0 * p + 1.0) - 1.0) * 0.5);
+        while (r * (r + 1) / 2 > p) --r;
+        while ((r + 1) * (r + 2) / 2 <= p) ++r;
+        const int s = p - r * (r + 1) / 2;
+        double acc = gacc[q];
+        for (int j = 0; j < nrows; ++j) acc += xs[r * kXs + j] * xs[s * kXs + j];
+        gacc[q] = acc;
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const int p = tid + 256 * q;
+    if (p < npairs) {
+      int r = (int)((sqrt(8.0 * p + 1.0) - 1.0) * 0.5);
+      while (r * (r + 1) / 2 > p) --r;
+      while ((r + 1) * (r + 2) / 2 <= p) ++r;
+      const int s = p - r * (r + 1) / 2;
+      st->Gls[mode][r * R + s] = gacc[q];
+      st->Gls[mode][s * R + r] = gacc[q];
+    }
+  }
+  if (mode == 2) {
+    const double tot = ls_block_sum(inner, red);
+    if (tid == 0) st->inner_ls = tot;
+  }
+}
+
+// grid (n_models): error of the extrapolated point and the decision.
+__global__ void __launch_bounds__(256) ls_decide_kernel(LineSearchArgs a) {
+  __shared__ double red[256];
+  const ModelDesc d = a.desc[blockIdx.x];
+  ModelOut* o = a.out + d.sid;
+  const int tid = threadIdx.x;
+  if (!ls_takes_part(d, *o)) {
+    if (tid == 0) a.accept[blockIdx.x] = 0;
+    return;
+  }
+  ModelState* st = a.state + d.sid;
+  const int R = d.rank;
+  double part = 0.0;
+  for (int e = tid; e < R * R; e += 256) part += (st->Gls[0][e] * st->Gls[1][e]) * st->Gls[2][e];
+  const double normsq = ls_block_sum(part, red);
+  const double err = a.normT2 + normsq - 2.0 * st->inner_ls;
+  const bool take = err < o->err;             // uniform: every thread reads the same values
+  __syncthreads();
+  if (take) {
+    for (int e = tid; e < R * R; e += 256) {
+      st->G[0][e] = st->Gls[0][e];
+      st->G[1][e] = st->Gls[1][e];
+      st->G[2][e] = st->Gls[2][e];
+    }
+    if (tid < R) a.lambda[d.sid * kMaxRank + tid] = 1.0;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    a.accept[blockIdx.x] = take ? 1 : 0;
+    if (take) {
+      o->err = err;
+      o->fit = 1.0 - sqrt(err > 0.0 ? err : 0.0) / sqrt(a.normT2);
+      o->ls_accepted += 1;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) ls_apply_kernel(LineSearchArgs a) {
+  const int mode = blockIdx.y;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)a.In[mode] * a.ncols) return;
+  const int i = (int)(idx / a.ncols), c = (int)(idx % a.ncols);
+  const int k = a.colmodel[c];
+  const ModelDesc d = a.desc[k];
+  if (!(d.flags & 2u)) return;
+  const ModelOut o = a.out[d.sid];
+  if (o.status != 0) return;
+  const int64_t e = (int64_t)i * a.ld + c;
+  double v;
+  if (a.accept[k]) {
+    v = a.Unew[mode][e];
+    a.U[mode][e] = v;                          // lambda of an accepted point is 1
+  } else {
+    v = a.U[mode][e];
+    if (mode == 2) v *= a.lambda[d.sid * kMaxRank + (c - d.col)];
+  }
+  a.Uprev[mode][e] = v;
+}
+
+static dim3 elem_grid(const LineSearchArgs& a) {
+  int imax = a.In[0] > a.In[1] ? a.In[0] : a.In[1];
+  imax = imax > a.In[2] ? imax : a.In[2];
+  const int64_t total = (int64_t)imax * a.ncols;
+  return dim3((unsigned)((total + 255) / 256), 3);
+}
+
+hipError_t launch_ls_extrapolate(const LineSearchArgs& a, hipStream_t stream) {
+  if (a.n_models < 1 || a.ncols < 1) return hipSuccess;
+  hipLaunchKernelGGL(ls_extrapolate_kernel, elem_grid(a), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream) {
+  static bool attr_done = false;
+  const size_t lds = sizeof(double) * (kMaxRank * kXs + 256);
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ls_gram_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (a.n_models < 1) return hipSuccess;
+  hipLaunchKernelGGL(ls_gram_kernel, dim3(a.n_models, 3), dim3(256), lds, stream, a);
+  hipLaunchKernelGGL(ls_decide_kernel, dim3(a.n_models), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_ls_apply(const LineSearchArgs& a, hipStream_t stream) {
+  if (a.n_models < 1 || a.ncols < 1) return hipSuccess;
+  hipLaunchKernelGGL(ls_apply_kernel, elem_grid(a), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace cals

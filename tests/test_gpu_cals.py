@@ -142,3 +142,43 @@ def test_argument_errors():
     assert e.value.code == -6
     ctx.close()
     torch.cuda.synchronize()
+
+
+def _collinear_tensor(dims, R, seed):
+    base = uniform_factors(dims, 1, seed)
+    true = [np.hstack([b + 0.15 * u[:, [r]] for r in range(R)]) for b, u in zip(base, uniform_factors(dims, R, seed + 1))]
+    T = np.einsum("ir,jr,kr->kji", *true) + 0.001 * random_tensor(dims, seed + 2, signed=True)
+    return np.ascontiguousarray(T)
+
+
+def test_line_search_matches_oracle():
+    # Sec. 5 line search: same accepted steps, same trajectory as the oracle, alone and mixed with plain models
+    dims = (28, 24, 20)
+    T = _collinear_tensor(dims, 3, 1200)
+    models = []
+    for k, (r, ls) in enumerate([(3, True), (2, False), (4, True), (3, True), (1, True), (5, False), (2, True)]):
+        models.append(dict(rank=r, init=uniform_factors(dims, r, 1300 + k), tol=[-1.0, 1e-5, 1e-7][k % 3],
+                           max_iters=[30, 60, 45][k % 3], flags=O.FLAG_LINESEARCH if ls else 0,
+                           ls_alpha=[1.3, 1.2, 2.0][k % 3]))
+    for rstar, slots in [(20, 0), (8, 3)]:
+        ref = O.cals(T, models, rstar, slots)
+        results, facs, st = run_gpu(T, models, rstar, slots, rounds_per_call=4)
+        compare(results, facs, ref, models)
+        assert st.rounds == ref["rounds"]
+    # the extrapolation is actually exercised and agrees step for step
+    solo = O.cp_als(T, models[0]["init"], -1.0, 30, O.FLAG_LINESEARCH, 1.3)
+    got = [r for r in results if r.model_id == 0][0]
+    assert solo["ls_accepted"] > 0 and got.ls_accepted == solo["ls_accepted"]
+
+
+def test_config5_recipe_reduced():
+    # configuration 5's recipe (collinear factors, queue with slots, line search, tolerance stop) on a smaller tensor
+    cfg = get_config(5)
+    dims = (160, 40, 20)
+    T = make_tensor(cfg, dims)
+    models = make_models(cfg, dims)[::9][:14]
+    for m in models:
+        m["max_iters"] = 60
+    ref = O.cals(T, models, 40, 6)
+    results, facs, st = run_gpu(T, models, 40, 6, rounds_per_call=5)
+    compare(results, facs, ref, models)
