@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcals_hip.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["mttkrp_wm1.hip", "mttkrp_wm2.hip", "mttkrp_wm4.hip", "mttkrp.hip", "update.hip", "linesearch.hip", "cals_api.hip"]
+SOURCES = ["mttkrp_wm1.hip", "mttkrp_wm2.hip", "mttkrp_wm4.hip", "mttkrp.hip", "update.hip", "linesearch.hip", "nnls.hip", "cals_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

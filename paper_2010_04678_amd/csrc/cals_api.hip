@@ -101,6 +101,7 @@ struct cals_ctx {
   int32_t* d_colmodel = nullptr; // line search: slot position owning each column
   int32_t* h_colmodel = nullptr; // pinned
   int32_t* d_accept = nullptr;   // line search: per slot position, extrapolated point taken this round
+  int32_t* d_nnfail = nullptr;   // non-negativity: per slot position, failure flag of the current mode update
   std::deque<PendingModel> queue;
   std::vector<ActiveModel> active;
   std::vector<int> free_sids;
@@ -220,6 +221,22 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int n
   return CALS_OK;
 }
 
+// Buffers only the non-negative update needs: per (row, storage id) passive-set masks, failure flags.
+int ensure_nn_buffers(cals_ctx* c) {
+  if (c->d_nnfail) return CALS_OK;
+  HIP_TRY(hipSetDevice(c->opt.device));
+  bool ok = true;
+  for (int n = 0; n < 3; ++n) {
+    const size_t bytes = sizeof(uint32_t) * (size_t)c->dims[n] * c->capacity;
+    ok = ok && hipMalloc(&c->passive[n], bytes) == hipSuccess;
+    if (ok) ok = hipMemsetAsync(c->passive[n], 0, bytes, c->stream) == hipSuccess;
+  }
+  ok = ok && hipMalloc(&c->d_nnfail, sizeof(int32_t) * c->capacity) == hipSuccess;
+  if (ok) ok = hipMemsetAsync(c->d_nnfail, 0, sizeof(int32_t) * c->capacity, c->stream) == hipSuccess;
+  if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  return CALS_OK;
+}
+
 // Buffers only line search needs: the previous and the extrapolated point, column ownership, decisions.
 int ensure_ls_buffers(cals_ctx* c) {
   if (c->d_colmodel) return CALS_OK;
@@ -312,7 +329,7 @@ int fill(cals_ctx* c) {
   CALS_TRY(upload_desc(c));
   const int In[3] = {(int)c->dims[0], (int)c->dims[1], (int)c->dims[2]};
   const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
-  HIP_TRY(launch_gram_init(c->d_desc, c->d_state, c->d_out, c->d_lambda, true, Uc, In, c->ld, first_new,
+  HIP_TRY(launch_gram_init(c->d_desc, c->d_state, c->d_out, c->d_lambda, true, c->passive, c->capacity, Uc, In, c->ld, first_new,
                            (int)fresh.size(), c->stream));
   // the staging buffer and the queue entries are free again once the copy has been consumed
   HIP_TRY(hipStreamSynchronize(c->stream));
@@ -410,11 +427,21 @@ int one_round(cals_ctx* c, int* retired_now) {
   for (int mode = 0; mode < 3; ++mode) {
     const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
     CALS_TRY(run_mttkrp(c, mode, Uc, c->M, c->total_rank, c->ld));
+    bool round_has_nn = false;
+    for (const ActiveModel& m : c->active) round_has_nn = round_has_nn || (m.flags & CALS_MODEL_NONNEG);
+    if (round_has_nn) {
+      // rows of the NONNEG models, solved into the spare multi-matrix (free between compactions)
+      NnlsArgs na{};
+      na.desc = c->d_desc; na.state = c->d_state; na.out = c->d_out; na.M = c->M; na.X = c->Ualt[mode];
+      na.passive = c->passive[mode]; na.fail = c->d_nnfail;
+      na.In = (int)c->dims[mode]; na.ld = c->ld; na.mode = mode; na.n_models = n; na.capacity = c->capacity;
+      HIP_TRY(launch_nnls(na, c->stream));
+    }
     UpdateArgs ua{};
     ua.desc = c->d_desc; ua.state = c->d_state; ua.out = c->d_out; ua.lambda = c->d_lambda;
-    ua.M = c->M; ua.U = c->U[mode]; ua.passive = c->passive[mode];
+    ua.M = c->M; ua.U = c->U[mode]; ua.X = c->Ualt[mode]; ua.nn_fail = c->d_nnfail;
     ua.In = (int)c->dims[mode]; ua.ld = c->ld; ua.mode = mode;
-    ua.n_models = n; ua.max_slots = c->capacity; ua.normT2 = c->normT2;
+    ua.n_models = n; ua.normT2 = c->normT2;
     HIP_TRY(launch_update(ua, c->stream));
   }
   // line search (Sec. 5): extrapolate, one extra fused mode-3 MTTKRP at the extrapolated point, decide, apply
@@ -515,7 +542,7 @@ int cals_destroy(cals_ctx* c) {
   }
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned);
-  (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
+  (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
   (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
   (void)hipHostFree(c->h_lambda); (void)hipHostFree(c->h_stage); (void)hipHostFree(c->h_rmap);
@@ -596,7 +623,7 @@ int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const init[3], d
   if (flags & ~(CALS_MODEL_NONNEG | CALS_MODEL_LINESEARCH)) return CALS_E_INVALID;
   if ((flags & CALS_MODEL_NONNEG) && (flags & CALS_MODEL_LINESEARCH)) return CALS_E_UNSUPPORTED;
   if ((flags & CALS_MODEL_LINESEARCH) && !std::isfinite(ls_alpha)) return CALS_E_INVALID;
-  if (flags & CALS_MODEL_NONNEG) return CALS_E_UNSUPPORTED;  // not built yet
+  if (flags & CALS_MODEL_NONNEG) CALS_TRY(ensure_nn_buffers(c));
   if (flags & CALS_MODEL_LINESEARCH) CALS_TRY(ensure_ls_buffers(c));
   PendingModel pm;
   pm.id = c->next_id;

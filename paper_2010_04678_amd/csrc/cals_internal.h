@@ -76,10 +76,10 @@ struct UpdateArgs {
   double* lambda;       // column norms, kMaxRank doubles per sid
   const double* M;      // MTTKRP result, row-major In x ld
   double* U;            // factor multi-matrix of the updated mode, row-major In x ld
-  uint32_t* passive;    // NONNEG: per (row, slot) passive-set masks for this mode, In x max_slots (or null)
+  const double* X;      // NONNEG: rows already solved by the non-negative update (row-major In x ld), or null
+  int32_t* nn_fail;     // NONNEG: per slot position, set when a row's sub-block could not be factorised (reset here)
   int In, ld, mode;     // mode = 0,1,2
   int n_models;
-  int max_slots;
   double normT2;
 };
 
@@ -87,8 +87,9 @@ hipError_t launch_update(const UpdateArgs& a, hipStream_t stream);
 // Gramians of all three modes for models [first, first+count) of desc (used when a model is inserted
 // and after an accepted line-search step).
 // With reset_out, also puts the models' ModelOut back to {0, 0, RUNNING, 0, 0}.
+// passive[3] (may hold nulls): the NONNEG passive-set masks, cleared for the models' storage ids on reset.
 hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, double* lambda, bool reset_out,
-                            const double* const U[3], const int In[3], int ld, int first, int count,
+                            uint32_t* const passive[3], int capacity, const double* const U[3], const int In[3], int ld, int first, int count,
                             hipStream_t stream);
 // ||T||^2 with a fixed summation tree, and a finiteness check (flag[0] != 0 when a NaN/Inf was seen).
 hipError_t launch_norm_sq(const double* T, int64_t n, double* partial /* >= 1024 doubles */, double* out, int* flag,
@@ -104,6 +105,19 @@ hipError_t launch_copy_block(const double* src, int64_t src_ld, double* dst, int
 // dst[i*dst_ld + c] = src[i*src_ld + map[c]] (gather with separate leading dimensions).
 hipError_t launch_gather_block(const double* src, int64_t src_ld, double* dst, int64_t dst_ld, const int32_t* map,
                                int rows, int cols, hipStream_t stream);
+
+// ---- non-negative update (Sec. 5, "Non-negativity constraints") -------------------------------------
+struct NnlsArgs {
+  const ModelDesc* desc;
+  const ModelState* state;
+  const ModelOut* out;
+  const double* M;      // MTTKRP result, row-major In x ld
+  double* X;            // out: solved rows of the NONNEG models, row-major In x ld (other columns untouched)
+  uint32_t* passive;    // per (row, sid) passive-set masks of this mode, In x capacity; read (warm start) and written
+  int32_t* fail;        // per slot position; or-ed with 1 on failure
+  int In, ld, mode, n_models, capacity;
+};
+hipError_t launch_nnls(const NnlsArgs& a, hipStream_t stream);
 
 // ---- line search (Sec. 5, "Line search") -----------------------------------------------------------
 // A point is held with lambda folded into the mode-3 factor.  A model takes part in a round's line search when

@@ -117,7 +117,19 @@ __global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
     L[e] = h;
   }
   __syncthreads();
-  if (!block_cholesky(L, R, &flag)) {
+  // NONNEG models: the rows were solved by the non-negative update already (a.X); only its verdict is read
+  const bool nonneg = (d.flags & 1u) != 0;
+  if (nonneg) {
+    if (tid == 0) {
+      flag = a.nn_fail[blockIdx.x];
+      a.nn_fail[blockIdx.x] = 0;
+    }
+    __syncthreads();
+    if (flag != 0) {
+      if (tid == 0) out->status = 3;
+      return;
+    }
+  } else if (!block_cholesky(L, R, &flag)) {
     if (tid == 0) out->status = 3;            // CALS_NUMERICAL; factors of this mode stay untouched
     return;
   }
@@ -131,18 +143,23 @@ __global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
     const int nrows = (a.In - base < kRows) ? (a.In - base) : kRows;
     if (i < a.In) {
       const double* mrow = Mb + (int64_t)i * a.ld;
-      for (int r = 0; r < R; ++r) xs[r * kXs + tid] = mrow[r];
-      // L y = m
-      for (int r = 0; r < R; ++r) {
-        double v = xs[r * kXs + tid];
-        for (int k = 0; k < r; ++k) v -= L[r * R + k] * xs[k * kXs + tid];
-        xs[r * kXs + tid] = v / L[r * R + r];
-      }
-      // L^T x = y
-      for (int r = R - 1; r >= 0; --r) {
-        double v = xs[r * kXs + tid];
-        for (int k = r + 1; k < R; ++k) v -= L[k * R + r] * xs[k * kXs + tid];
-        xs[r * kXs + tid] = v / L[r * R + r];
+      if (nonneg) {
+        const double* xrow = a.X + (int64_t)i * a.ld + d.col;
+        for (int r = 0; r < R; ++r) xs[r * kXs + tid] = xrow[r];
+      } else {
+        for (int r = 0; r < R; ++r) xs[r * kXs + tid] = mrow[r];
+        // L y = m
+        for (int r = 0; r < R; ++r) {
+          double v = xs[r * kXs + tid];
+          for (int k = 0; k < r; ++k) v -= L[r * R + k] * xs[k * kXs + tid];
+          xs[r * kXs + tid] = v / L[r * R + r];
+        }
+        // L^T x = y
+        for (int r = R - 1; r >= 0; --r) {
+          double v = xs[r * kXs + tid];
+          for (int k = r + 1; k < R; ++k) v -= L[k * R + r] * xs[k * kXs + tid];
+          xs[r * kXs + tid] = v / L[r * R + r];
+        }
       }
       double* urow = Ub + (int64_t)i * a.ld;
       double part = 0.0;
@@ -215,6 +232,8 @@ struct GramInitArgs {
   ModelState* state;
   ModelOut* out;
   double* lambda;
+  uint32_t* passive[3];
+  int capacity;
   int reset_out;
   const double* U[3];
   int In[3];
@@ -249,10 +268,12 @@ __global__ void __launch_bounds__(256) gram_init_kernel(GramInitArgs a) {
     a.out[d.sid] = o;
   }
   if (a.reset_out && mode == 0 && tid < kMaxRank) a.lambda[d.sid * kMaxRank + tid] = 1.0;
+  if (a.reset_out && a.passive[mode])          // a fresh model starts with empty passive sets
+    for (int i = tid; i < In; i += 256) a.passive[mode][(int64_t)i * a.capacity + d.sid] = 0u;
 }
 
 hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, double* lambda, bool reset_out,
-                            const double* const U[3], const int In[3], int ld, int first, int count,
+                            uint32_t* const passive[3], int capacity, const double* const U[3], const int In[3], int ld, int first, int count,
                             hipStream_t stream) {
   static bool attr_done = false;
   const size_t lds = sizeof(double) * (kMaxRank * kXs + kGramStride);
@@ -265,7 +286,8 @@ hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* 
   if (count < 1) return hipSuccess;
   GramInitArgs a;
   a.desc = desc; a.state = state; a.out = out; a.lambda = lambda; a.reset_out = reset_out ? 1 : 0; a.ld = ld; a.first = first;
-  for (int n = 0; n < 3; ++n) { a.U[n] = U[n]; a.In[n] = In[n]; }
+  a.capacity = capacity;
+  for (int n = 0; n < 3; ++n) { a.U[n] = U[n]; a.In[n] = In[n]; a.passive[n] = passive ? passive[n] : nullptr; }
   hipLaunchKernelGGL(gram_init_kernel, dim3(count, 3), dim3(256), lds, stream, a);
   return hipGetLastError();
 }

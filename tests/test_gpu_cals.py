@@ -182,3 +182,38 @@ def test_config5_recipe_reduced():
     ref = O.cals(T, models, 40, 6)
     results, facs, st = run_gpu(T, models, 40, 6, rounds_per_call=5)
     compare(results, facs, ref, models)
+
+
+def test_nonneg_matches_oracle():
+    # Sec. 5 non-negativity: active-set update per row, warm-started; constraints active (signed data), mixed
+    # with unconstrained models, ranks on both sides of the row-block switch (20 / 21 / 28)
+    dims = (70, 33, 18)
+    T = np.ascontiguousarray(random_tensor(dims, 1400, signed=True) * 0.3 +
+                             np.einsum("ir,jr,kr->kji", *uniform_factors(dims, 4, 1401)))
+    models = []
+    for k, (r, nn) in enumerate([(3, True), (4, False), (6, True), (20, True), (21, True), (2, True), (28, True)]):
+        models.append(dict(rank=r, init=uniform_factors(dims, r, 1410 + k), tol=[-1.0, 1e-5][k % 2],
+                           max_iters=[12, 25][k % 2], flags=O.FLAG_NONNEG if nn else 0, ls_alpha=1.0))
+    for rstar, slots in [(sum(m["rank"] for m in models), 0), (30, 3)]:
+        ref = O.cals(T, models, rstar, slots)
+        results, facs, st = run_gpu(T, models, rstar, slots, rounds_per_call=4)
+        compare(results, facs, ref, models)
+        for r in results:
+            if models[r.model_id]["flags"]:
+                assert min(u.min() for u in facs[r.model_id][0]) >= 0.0
+    assert any((facs[r.model_id][0][0] == 0.0).any() for r in results if models[r.model_id]["flags"])
+
+
+def test_config3_recipe_reduced():
+    # configuration 3's recipe (fluorescence-shaped non-negative tensor, NONNEG models, tolerance stop), smaller
+    cfg = get_config(3)
+    dims = (60, 48, 16)
+    T = make_tensor(cfg, dims)
+    models = make_models(cfg, dims)[::4]          # ranks 1, 2, 3, 5, 6, 7, 9, ... 19
+    for m in models:
+        m["max_iters"] = 40
+        m["tol"] = 1e-6
+    R = sum(m["rank"] for m in models)
+    ref = O.cals(T, models, R, 0)
+    results, facs, st = run_gpu(T, models, R, 0, rounds_per_call=6)
+    compare(results, facs, ref, models)
