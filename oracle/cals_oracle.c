@@ -27,6 +27,8 @@
  *     H(n) is positive definite); a non-positive or non-finite pivot stops the model with
  *     status NUMERICAL, leaving the factors it had before the failing update.
  *   - every column of an updated factor is scaled to unit 2-norm, the norms kept in lambda.
+ *   - non-negativity: Lawson-Hanson active set on the normal equations per row; the passive set of the
+ *     previous iteration is a warm start that is dropped when its sub-block of H is not positive definite.
  *   - sums over the two contracted indices are nested: the inner sum runs over the lower-
  *     numbered contracted mode into a fresh accumulator, the outer sum adds those up.
  *
@@ -252,7 +254,9 @@ void oracle_mttkrp_element(const double* T, const int64_t* dims, int mode, const
 
 /* Minimise 1/2 x^T H x - m^T x subject to x >= 0.  `passive` is a bit mask of the variables
  * allowed to be non-zero: on entry the warm start (0 = none), on exit the final set.
- * Returns 0 on success, 1 if a sub-block of H could not be factorised. */
+ * A warm start is a hint: if its sub-block of H cannot be factorised (H may be only semi-definite, e.g. after a
+ * component has died) it is dropped and the search restarts from the empty set.
+ * Returns 0 on success, 1 if a sub-block reached by the search itself could not be factorised. */
 int oracle_nnls_row(const double* H, const double* m, int R, double* x, uint32_t* passive) {
   uint32_t P = *passive & ((R >= 32) ? 0xffffffffu : ((1u << R) - 1u));
   double h1 = 0.0;
@@ -264,6 +268,7 @@ int oracle_nnls_row(const double* H, const double* m, int R, double* x, uint32_t
   const double tau = 10.0 * DBL_EPSILON * h1 * (double)R;
   const int cap = 30 * R;
   int steps = 0;
+  int from_warm = (P != 0);   /* the passive set still derives from the warm start */
   double s[ORACLE_MAX_RANK], Hs[ORACLE_MAX_RANK * ORACLE_MAX_RANK], Ls[ORACLE_MAX_RANK * ORACLE_MAX_RANK];
   int idx[ORACLE_MAX_RANK];
   for (int j = 0; j < R; ++j) x[j] = 0.0;
@@ -276,7 +281,12 @@ int oracle_nnls_row(const double* H, const double* m, int R, double* x, uint32_t
         s[a] = m[idx[a]];
         for (int b = 0; b < np; ++b) Hs[a + np * b] = H[idx[a] + R * idx[b]];
       }
-      if (oracle_cholesky(Hs, np, Ls)) { *passive = P; return 1; }
+      if (oracle_cholesky(Hs, np, Ls)) {
+        if (!from_warm) { *passive = P; return 1; }
+        P = 0; from_warm = 0;
+        for (int j = 0; j < R; ++j) x[j] = 0.0;
+        break;
+      }
       oracle_cholesky_solve(Ls, np, s);
       int feasible = 1;
       for (int a = 0; a < np; ++a) if (!(s[a] > 0.0)) feasible = 0;
@@ -311,6 +321,7 @@ int oracle_nnls_row(const double* H, const double* m, int R, double* x, uint32_t
     }
     if (best < 0) break;
     P |= (1u << best);
+    from_warm = 0;
     if (++steps > cap) break;
   }
   *passive = P;

@@ -2,7 +2,7 @@
 // normal-equation solve of a NONNEG model is replaced, row by row, by
 //     minimise 1/2 x^T H x - m^T x   subject to x >= 0,
 // with an active-set (Lawson-Hanson) search on (H, m); the passive set a row ends with is kept for the next
-// iteration (warm start).  H and the MTTKRP are computed once per mode update, exactly as for plain ALS.
+// iteration (warm start; dropped if its sub-block of H is not positive definite).  H and the MTTKRP are computed once per mode update, exactly as for plain ALS.
 //
 // One lane per row, one wavefront per workgroup.  Every lane runs the textbook sequence (factorise the passive
 // sub-block of H, solve, step towards feasibility, gradient test) in the same order of operations as a scalar
@@ -59,6 +59,7 @@ __global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
   for (int r = 0; r < R; ++r) { MV(r) = mrow[r]; XV(r) = 0.0; }
   int steps = 0;
   bool bad = false;
+  bool from_warm = (P != 0);             // the passive set still derives from the warm start
   for (;;) {
     while (P) {
       // Cholesky of H restricted to the passive set (columns in ascending index order)
@@ -78,7 +79,15 @@ __global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
           LP(r, j) = v / dj;
         }
       }
-      if (bad) break;
+      if (bad) {
+        if (!from_warm) break;
+        // a warm start whose sub-block cannot be factorised is dropped: restart from the empty set
+        bad = false;
+        from_warm = false;
+        P = 0;
+        for (int r = 0; r < R; ++r) XV(r) = 0.0;
+        break;
+      }
       // solve (L L^T) s = m on the passive set
       for (int r = 0; r < R; ++r) {
         if (!(P & (1u << r))) continue;
@@ -128,6 +137,7 @@ __global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
     }
     if (best < 0) break;
     P |= (1u << best);
+    from_warm = false;
     if (++steps > cap) break;
   }
   if (bad) {

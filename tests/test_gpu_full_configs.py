@@ -1,0 +1,156 @@
+"""The five configurations at FULL size, in the launch configuration bench.py times (same R*, slots, flags).
+
+The oracle cannot run these whole in test time, so it checks what it can compute one by one: sampled MTTKRP
+elements (extended precision), sampled models run solo (models are numerically independent of their
+co-residents: the paper's "without numerically affecting any of the invocations"), and properties that hold
+at any size (retirement order replayed from the iteration counts, non-negativity, fit ranges)."""
+import numpy as np
+import pytest
+
+import oracle as O
+from workloads import get_config, make_models, make_tensor
+
+pytestmark = pytest.mark.gpu
+FIT_TOL, FACTOR_TOL, MTTKRP_TOL = 1e-8, 1e-6, 1e-12
+
+
+def gpu_run(T, models, cfg, keep=None):
+    import torch
+    import paper_2010_04678_amd as P
+    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots)
+    Td = torch.from_numpy(T).cuda()
+    ctx.submit_tensor(Td)
+    for m in models:
+        ctx.enqueue_model(m["init"], m["tol"], m["max_iters"], m["flags"], m["ls_alpha"])
+    ctx.run()
+    res = ctx.poll_retired(len(models) + 8)
+    assert len(res) == len(models)
+    facs = {k: ctx.get_factors(k) for k in (keep if keep is not None else range(len(models)))}
+    st = ctx.stats()
+    ctx.close()
+    del Td
+    torch.cuda.empty_cache()
+    return res, facs, st
+
+
+def check_models(res, facs, models, ref, sample):
+    """`ref` is the oracle's CALS on the sampled models only (indices into `sample`)."""
+    by_id = {r.model_id: r for r in res}
+    for j, k in enumerate(sample):
+        r = by_id[k]
+        assert r.iters == ref["iters"][j] and r.status == ref["status"][j], (k, r, ref["iters"][j], ref["status"][j])
+        assert abs(r.fit - ref["fit"][j]) <= FIT_TOL, (k, r.fit, ref["fit"][j])
+        U, lam = facs[k]
+        for n in range(3):
+            a = U[n] * (lam[None, :] if n == 2 else 1.0)
+            b = ref["U"][j][n] * (ref["lam"][j][None, :] if n == 2 else 1.0)
+            den = np.linalg.norm(b, axis=0)
+            rel = np.linalg.norm(a - b, axis=0) / np.where(den > 0, den, 1.0)
+            assert rel.max() <= FACTOR_TOL, (k, n, rel.max())
+
+
+def replay_queue(ranks, iters, rstar, slots):
+    """Retirement order implied by Alg. 3 when model k needs iters[k] iterations (host logic only)."""
+    active, nxt, rtot, order = [], 0, 0, []
+    left = list(iters)
+    while nxt < len(ranks) or active:
+        while nxt < len(ranks) and rtot + ranks[nxt] <= rstar and (slots == 0 or len(active) < slots):
+            active.append(nxt); rtot += ranks[nxt]; nxt += 1
+        keep = []
+        for k in active:
+            left[k] -= 1
+            if left[k] == 0:
+                order.append(k); rtot -= ranks[k]
+            else:
+                keep.append(k)
+        active = keep
+    return order
+
+
+def sampled_mttkrp_check(T, cfg, models, n_samples, seed):
+    import torch
+    import paper_2010_04678_amd as P
+    dims = cfg.dims
+    U = [np.hstack([m["init"][n] for m in models]) for n in range(3)]
+    R = U[0].shape[1]
+    ld = (R + 15) // 16 * 16
+    ctx = P.Context(max_total_rank=cfg.max_total_rank)
+    Td = torch.from_numpy(T).cuda()
+    ctx.submit_tensor(Td)
+    Ud = []
+    for n in range(3):
+        buf = torch.zeros((dims[n], ld), dtype=torch.float64, device="cuda")
+        buf[:, :R] = torch.from_numpy(np.ascontiguousarray(U[n])).cuda()
+        Ud.append(buf)
+    rng = np.random.default_rng(seed)
+    for mode in (1, 2, 3):
+        M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda")
+        ctx.mttkrp(mode, Ud, M, total_rank=R)
+        Mh = M.cpu().numpy()
+        rows = np.concatenate([[0, dims[mode - 1] - 1], rng.integers(0, dims[mode - 1], n_samples)])
+        cols = np.concatenate([[0, R - 1], rng.integers(0, R, n_samples)])
+        for i, c in zip(rows, cols):
+            want, scale = O.mttkrp_element(T, U, mode, int(i), int(c))
+            assert abs(Mh[i, c] - want) <= MTTKRP_TOL * scale, (mode, i, c, Mh[i, c], want)
+    ctx.close()
+    del Td, Ud
+    torch.cuda.empty_cache()
+
+
+def test_config2_full():
+    cfg = get_config(2)
+    T = make_tensor(cfg)
+    models = make_models(cfg)
+    # fused MTTKRP, every element, all three modes
+    sampled_mttkrp_check(T, cfg, models, 40, 21)
+    sample = [0, 4, 9, 13]
+    res, facs, st = gpu_run(T, models, cfg, keep=sample)
+    assert [r.model_id for r in res] == list(range(20)) and all(r.iters == 100 for r in res)
+    ref = O.cals(T, [models[k] for k in sample], cfg.max_total_rank, 0)
+    check_models(res, facs, models, ref, sample)
+
+
+def test_config4_full_mttkrp_and_two_iterations():
+    cfg = get_config(4)
+    T = make_tensor(cfg, threads=16)
+    models = make_models(cfg)
+    sampled_mttkrp_check(T, cfg, models, 30, 41)
+    for m in models:
+        m["max_iters"] = 2
+    sample = [0, 1]
+    res, facs, st = gpu_run(T, models, cfg, keep=sample)
+    assert [r.model_id for r in res] == list(range(40)) and all(r.iters == 2 for r in res)
+    assert all(0.0 < r.fit < 1.0 for r in res)
+    ref = O.cals(T, [models[k] for k in sample], cfg.max_total_rank, 0)
+    check_models(res, facs, models, ref, sample)
+
+
+def test_config3_full():
+    cfg = get_config(3)
+    T = make_tensor(cfg)
+    models = make_models(cfg)
+    sample = [0, 7, 16, 22]
+    res, facs, st = gpu_run(T, models, cfg, keep=sample + [59])
+    iters = {r.model_id: r.iters for r in res}
+    # everything is resident from round 1: the order is (iteration count, slot)
+    assert [r.model_id for r in res] == sorted(range(60), key=lambda k: (iters[k], k))
+    assert all(r.status in (O.CONVERGED, O.MAX_ITERS) for r in res)
+    assert min(u.min() for u in facs[59][0]) >= 0.0
+    ref = O.cals(T, [models[k] for k in sample], cfg.max_total_rank, 0)
+    check_models(res, facs, models, ref, sample)
+
+
+def test_config5_full():
+    cfg = get_config(5)
+    T = make_tensor(cfg)
+    models = make_models(cfg)
+    sample = [0, 3, 12, 25]
+    res, facs, st = gpu_run(T, models, cfg, keep=sample)
+    iters = [0] * len(models)
+    for r in res:
+        iters[r.model_id] = r.iters
+    # Alg. 3 at scale: the retirement order is the one the queue rules imply for these iteration counts
+    assert [r.model_id for r in res] == replay_queue(list(cfg.ranks), iters, cfg.max_total_rank, cfg.max_slots)
+    assert all(r.status in (O.CONVERGED, O.MAX_ITERS) for r in res)
+    ref = O.cals(T, [models[k] for k in sample], cfg.max_total_rank, cfg.max_slots)
+    check_models(res, facs, models, ref, sample)

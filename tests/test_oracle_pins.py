@@ -350,6 +350,31 @@ def test_nnls_matches_lawson_hanson_library_and_kkt():
                 assert rc2 == 0 and np.allclose(x2, x, rtol=1e-8, atol=1e-10)
 
 
+def test_nnls_semidefinite_normal_equations_and_unusable_warm_start():
+    # a dead component makes H only semi-definite (zero row and column): it must stay at zero, and a warm
+    # start that contains it (so that its sub-block cannot be factorised) is dropped, not fatal
+    rng = np.random.default_rng(9)
+    R = 6
+    A = rng.standard_normal((R + 4, R))
+    A[:, 2] = 0.0
+    b = rng.standard_normal(R + 4) + 0.5
+    H, m = A.T @ A, A.T @ b
+    want, _ = scipy.optimize.nnls(A, b)
+    for warm in (0, 0b000100, 0b111111, 0b000101):
+        rc, x, P = O.nnls_row(H, m, warm)
+        assert rc == 0 and x[2] == 0.0 and not (P >> 2) & 1
+        assert np.allclose(x, want, rtol=1e-8, atol=1e-10)
+    # two identical columns: no unique minimiser; the search itself reaches a singular block -> reported
+    A2 = rng.standard_normal((R + 4, R))
+    A2[:, 1] = A2[:, 0]
+    b2 = A2[:, 0] * 2.0 + 0.1
+    rc, x, P = O.nnls_row(A2.T @ A2, A2.T @ b2, 0)
+    assert rc in (0, 1)
+    if rc == 0:   # then it is A minimiser: same objective value as the library's
+        ref, _ = scipy.optimize.nnls(A2, b2)
+        assert np.all(x >= 0) and abs(np.linalg.norm(A2 @ x - b2) - np.linalg.norm(A2 @ ref - b2)) < 1e-9
+
+
 def test_nnls_brute_force_over_supports():
     rng = np.random.default_rng(8)
     R = 5
