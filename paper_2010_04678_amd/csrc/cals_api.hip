@@ -428,13 +428,18 @@ int one_round(cals_ctx* c, int* retired_now) {
     const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
     CALS_TRY(run_mttkrp(c, mode, Uc, c->M, c->total_rank, c->ld));
     bool round_has_nn = false;
-    for (const ActiveModel& m : c->active) round_has_nn = round_has_nn || (m.flags & CALS_MODEL_NONNEG);
+    int nn_max_rank = 1;
+    for (const ActiveModel& m : c->active)
+      if (m.flags & CALS_MODEL_NONNEG) {
+        round_has_nn = true;
+        nn_max_rank = std::max(nn_max_rank, m.rank);
+      }
     if (round_has_nn) {
       // rows of the NONNEG models, solved into the spare multi-matrix (free between compactions)
       NnlsArgs na{};
       na.desc = c->d_desc; na.state = c->d_state; na.out = c->d_out; na.M = c->M; na.X = c->Ualt[mode];
       na.passive = c->passive[mode]; na.fail = c->d_nnfail;
-      na.In = (int)c->dims[mode]; na.ld = c->ld; na.mode = mode; na.n_models = n; na.capacity = c->capacity;
+      na.In = (int)c->dims[mode]; na.ld = c->ld; na.mode = mode; na.n_models = n; na.capacity = c->capacity; na.max_rank = nn_max_rank;
       HIP_TRY(launch_nnls(na, c->stream));
     }
     UpdateArgs ua{};

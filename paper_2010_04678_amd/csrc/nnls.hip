@@ -15,7 +15,12 @@
 
 namespace cals {
 
-__device__ inline int nnls_rows_per_block(int R) { return R <= 20 ? 64 : (R <= 27 ? 32 : 16); }
+// Rows per workgroup: few, so that the per-lane LDS arrays stay small and several wavefronts share a CU (the
+// search is a chain of dependent LDS reads: it needs occupancy, not lanes).
+__host__ __device__ inline int nnls_rows_per_block(int R) { return R <= 24 ? 16 : 8; }
+__host__ __device__ inline size_t nnls_lds_doubles(int R) {
+  return (size_t)kGramStride + (size_t)(R * (R + 1) / 2 + 3 * R) * nnls_rows_per_block(R);
+}
 
 __global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
   extern __shared__ double lds[];
@@ -52,6 +57,9 @@ __global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
 #define XV(r) xv[(r) * RPB + lane]
 #define SV(r) sv[(r) * RPB + lane]
 #define MV(r) mv[(r) * RPB + lane]
+// loops over the members of a bit set in ascending order (the order a scalar implementation visits them)
+#define FOR_BITS(var, set) for (uint32_t var##_s = (set); var##_s; var##_s &= var##_s - 1) { const int var = __builtin_ctz(var##_s);
+#define END_BITS }
   const uint32_t full = (R >= 32) ? 0xffffffffu : ((1u << R) - 1u);
   uint32_t* pslot = a.passive + (int64_t)i * a.capacity + d.sid;
   uint32_t P = *pslot & full;
@@ -63,22 +71,20 @@ __global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
   for (;;) {
     while (P) {
       // Cholesky of H restricted to the passive set (columns in ascending index order)
-      for (int j = 0; j < R && !bad; ++j) {
-        if (!(P & (1u << j))) continue;
+      FOR_BITS(j, P)
+        const uint32_t below = P & ((1u << j) - 1u);
         double dj = H[j * R + j];
-        for (int k = 0; k < j; ++k)
-          if (P & (1u << k)) dj -= LP(j, k) * LP(j, k);
+        FOR_BITS(k, below) dj -= LP(j, k) * LP(j, k); END_BITS
         if (!(dj > 0.0) || !isfinite(dj)) { bad = true; break; }
         dj = sqrt(dj);
         LP(j, j) = dj;
-        for (int r = j + 1; r < R; ++r) {
-          if (!(P & (1u << r))) continue;
+        const uint32_t above = (j >= 31) ? 0u : (P & ~((2u << j) - 1u));
+        FOR_BITS(r, above)
           double v = H[r * R + j];
-          for (int k = 0; k < j; ++k)
-            if (P & (1u << k)) v -= LP(r, k) * LP(j, k);
+          FOR_BITS(k, below) v -= LP(r, k) * LP(j, k); END_BITS
           LP(r, j) = v / dj;
-        }
-      }
+        END_BITS
+      END_BITS
       if (bad) {
         if (!from_warm) break;
         // a warm start whose sub-block cannot be factorised is dropped: restart from the empty set
@@ -89,52 +95,49 @@ __global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
         break;
       }
       // solve (L L^T) s = m on the passive set
-      for (int r = 0; r < R; ++r) {
-        if (!(P & (1u << r))) continue;
+      FOR_BITS(r, P)
         double v = MV(r);
-        for (int k = 0; k < r; ++k)
-          if (P & (1u << k)) v -= LP(r, k) * SV(k);
+        FOR_BITS(k, P & ((1u << r) - 1u)) v -= LP(r, k) * SV(k); END_BITS
         SV(r) = v / LP(r, r);
-      }
+      END_BITS
       for (int r = R - 1; r >= 0; --r) {
         if (!(P & (1u << r))) continue;
         double v = SV(r);
-        for (int k = r + 1; k < R; ++k)
-          if (P & (1u << k)) v -= LP(k, r) * SV(k);
+        const uint32_t above = (r >= 31) ? 0u : (P & ~((2u << r) - 1u));
+        FOR_BITS(k, above) v -= LP(k, r) * SV(k); END_BITS
         SV(r) = v / LP(r, r);
       }
       bool feasible = true;
-      for (int r = 0; r < R; ++r)
-        if ((P & (1u << r)) && !(SV(r) > 0.0)) feasible = false;
+      FOR_BITS(r, P) if (!(SV(r) > 0.0)) feasible = false; END_BITS
       if (feasible) {
         for (int r = 0; r < R; ++r) XV(r) = (P & (1u << r)) ? SV(r) : 0.0;
         break;
       }
       double beta = 1.0;
-      for (int r = 0; r < R; ++r)
-        if ((P & (1u << r)) && !(SV(r) > 0.0)) {
+      FOR_BITS(r, P)
+        if (!(SV(r) > 0.0)) {
           const double xa = XV(r);
           const double q = xa / (xa - SV(r));
           if (q < beta) beta = q;
         }
-      for (int r = 0; r < R; ++r) {
-        if (!(P & (1u << r))) continue;
+      END_BITS
+      const uint32_t Pold = P;
+      FOR_BITS(r, Pold)
         const double xn = XV(r) + beta * (SV(r) - XV(r));
         if (!(xn > 0.0)) { XV(r) = 0.0; P &= ~(1u << r); }
         else XV(r) = xn;
-      }
+      END_BITS
       if (++steps > cap) break;
     }
     if (bad || steps > cap) break;
-    // gradient test: move the most violating variable into the passive set
+    // gradient test: move the most violating variable into the passive set (x is zero outside P)
     int best = -1;
     double wbest = tau;
-    for (int j = 0; j < R; ++j) {
-      if (P & (1u << j)) continue;
+    FOR_BITS(j, full & ~P)
       double w = MV(j);
-      for (int k = 0; k < R; ++k) w -= H[j * R + k] * XV(k);
+      FOR_BITS(k, P) w -= H[j * R + k] * XV(k); END_BITS
       if (w > wbest) { wbest = w; best = j; }
-    }
+    END_BITS
     if (best < 0) break;
     P |= (1u << best);
     from_warm = false;
@@ -151,20 +154,24 @@ __global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
 #undef XV
 #undef SV
 #undef MV
+#undef FOR_BITS
+#undef END_BITS
 }
 
 hipError_t launch_nnls(const NnlsArgs& a, hipStream_t stream) {
   static bool attr_done = false;
-  // worst case over the three row-block sizes: R = 20 with 64 rows
-  const size_t lds = sizeof(double) * (kGramStride + (size_t)(210 + 60) * 64 + 64);
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nnls_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)(sizeof(double) * nnls_lds_doubles(kMaxRank)));
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   if (a.n_models < 1) return hipSuccess;
-  hipLaunchKernelGGL(nnls_kernel, dim3(a.n_models, (a.In + 15) / 16), dim3(64), lds, stream, a);
+  const int rmax = a.max_rank < 1 ? 1 : (a.max_rank > kMaxRank ? kMaxRank : a.max_rank);
+  size_t doubles = 0;
+  for (int r = 1; r <= rmax; ++r) doubles = nnls_lds_doubles(r) > doubles ? nnls_lds_doubles(r) : doubles;
+  hipLaunchKernelGGL(nnls_kernel, dim3(a.n_models, (a.In + 7) / 8), dim3(64), sizeof(double) * doubles, stream, a);
   return hipGetLastError();
 }
 
