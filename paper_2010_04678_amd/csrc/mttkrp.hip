@@ -1,5 +1,6 @@
 // Host side of the fused multi-model MTTKRP (Eq. (2) of the paper): choice of tile shape and split of the
 // contraction range, kernel launch, and the ordered reduction of the split-K partials.
+#include <algorithm>
 #include <cstdlib>
 
 #include "mttkrp_kernel.h"
@@ -76,14 +77,23 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
   const int lds_fit = (int)(160 * 1024 / ((size_t)2 * pl.ka * 16 * pl.wn * sizeof(double)));
   if (per_cu > lds_fit) per_cu = lds_fit;
   per_cu = env_int("CALS_MTTKRP_PERCU", per_cu);
-  const int64_t target = (int64_t)num_cus * per_cu;
-  const int64_t base = (int64_t)pl.mtiles * pl.ny;
-  int64_t splits = (target + base - 1) / base;
-  const int64_t max_splits = (K + 4 * pl.ka - 1) / (4 * pl.ka);   // at least four stages per split
-  if (splits > max_splits) splits = max_splits;
+  // Split of the contraction range.  Workgroups run in waves of `slots` (one per resident position); the time
+  // of a launch is about waves x (stages per workgroup + fixed cost).  Splits are whole multiples of 8 when
+  // there are 8 or more, so that the XCD-pinned block order gives every XCD the same number of splits; with
+  // fewer splits the blocks of a split are spread over the XCDs instead.
+  const int64_t slots = (int64_t)num_cus * per_cu;
+  const int64_t per_split = (int64_t)pl.mtiles * pl.ny;
+  const int64_t max_splits = std::max<int64_t>(1, K / (4 * pl.ka));   // at least two stage pairs per split
   const int force_splits = env_int("CALS_MTTKRP_SPLITS", 0);
+  int64_t splits = 1;
+  double best_cost = 1e300;
+  for (int64_t cand = 1; cand <= std::min<int64_t>(max_splits, 4096); cand = (cand < 8) ? cand + 1 : cand + 8) {
+    const int64_t waves = (per_split * cand + slots - 1) / slots;
+    const int64_t pairs = (K + cand * 2 * pl.ka - 1) / (cand * 2 * pl.ka);
+    const double cost = (double)waves * (2.0 * pairs + 6.0) * (1.0 + 0.002 * cand);
+    if (cost < best_cost) { best_cost = cost; splits = cand; }
+  }
   if (force_splits > 0) splits = force_splits;
-  if (splits < 1) splits = 1;
   int64_t chunk = (K + splits - 1) / splits;
   chunk = (chunk + 2 * pl.ka - 1) / (2 * pl.ka) * (2 * pl.ka);   // whole stage pairs
   splits = (K + chunk - 1) / chunk;
@@ -111,6 +121,7 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   a.In = p.In; a.Ia = p.Ia; a.Ib = p.Ib;
   a.ncols = p.ncols; a.ld = p.ld;
   a.mtiles = pl.mtiles; a.ny = pl.ny; a.splits = pl.splits;
+  a.pinned = (pl.splits % 8 == 0) ? 1 : 0;
   int mode = (p.Ia < pl.ka) ? kGeneral : ((p.sb == (int64_t)p.Ia * p.sa) ? kAffine : kWrap);
   // rows contiguous along the contraction and 16-byte aligned: the coalesced 4-indices-per-lane path
   if (mode != kGeneral && p.sa == 1 && p.Ia % 4 == 0 && p.sm % 2 == 0 && p.sb % 2 == 0 && pl.ka == 16 &&
@@ -118,7 +129,7 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
     mode = kContig4;
   // 1-D grid, decoded in the kernel: 8 interleaved sequences (one per XCD) of whole splits
   const int64_t per_split = (int64_t)pl.mtiles * pl.ny;
-  const int64_t nblocks = per_split * 8 * ((pl.splits + 7) / 8);
+  const int64_t nblocks = per_split * pl.splits;
   if (nblocks >= (1LL << 31)) return hipErrorInvalidValue;
   if (ev) (void)hipEventRecord(ev[0], stream);
   hipLaunchKernelGGL(v->fn[mode], dim3((unsigned)nblocks), dim3(256), variant_lds_bytes(*v), stream, a);

@@ -46,6 +46,7 @@ struct MttkrpKernelArgs {
   int In, Ia, Ib;
   int ncols, ld;
   int mtiles, ny, splits;   // logical grid: row blocks, column blocks, splits
+  int pinned;               // splits is a multiple of 8: keep every split on one XCD
 };
 
 // How a contraction index k = ia + Ia*ib maps to a tensor offset ia*sa + ib*sb:
@@ -65,20 +66,25 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   constexpr int TILE = KA * NC;               // doubles per LDS buffer
   extern __shared__ double smem[];            // [2][KA][NC]
 
-  // ---- logical block coordinates.  Hardware hands consecutive workgroup ids to the 8 XCDs in turn; all
-  // workgroups of one split (same factor rows, and for ny > 1 the same tensor tile) are kept on one XCD
-  // so that they share its L2.
+  // ---- logical block coordinates.  Hardware hands consecutive workgroup ids to the 8 XCDs in turn.  With 8k
+  // splits all workgroups of one split (same factor rows, and for ny > 1 the same tensor tile) are kept on one
+  // XCD so that they share its L2; with fewer splits the workgroups of a split are spread over the XCDs.
   int bx, by, bz;
   {
     const int id = blockIdx.x;
-    const int xcd = id & 7, slot = id >> 3;
     const int per_split = a.mtiles * a.ny;
-    bz = (slot / per_split) * 8 + xcd;
-    const int g = slot % per_split;
+    int g;
+    if (a.pinned) {
+      const int xcd = id & 7, slot = id >> 3;
+      bz = (slot / per_split) * 8 + xcd;
+      g = slot % per_split;
+    } else {
+      bz = id / per_split;
+      g = id % per_split;
+    }
     by = g % a.ny;
     bx = g / a.ny;
   }
-  if (bz >= a.splits) return;                 // uniform per workgroup
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
