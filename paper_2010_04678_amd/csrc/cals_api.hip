@@ -54,6 +54,8 @@ struct ActiveModel {
   int iters;        // completed iterations as of the last read-back
 };
 
+struct Leaving { ActiveModel m; int status; int64_t round; int slot; };
+
 struct RetiredModel {
   cals_result res;
   std::vector<double> U[3];     // column-major I_n x rank
@@ -113,6 +115,7 @@ struct cals_ctx {
   bool any_ls = false, any_nonneg = false;
   // statistics
   int64_t rounds = 0, n_retired = 0;
+  int64_t rounds_unread = 0;     // rounds launched since the last read-back of the per-model records
   double mttkrp_flops = 0.0;
   double mttkrp_ms[3] = {0, 0, 0}, reduce_ms[3] = {0, 0, 0};
   int64_t mttkrp_launches[3] = {0, 0, 0};
@@ -419,7 +422,18 @@ int compact(cals_ctx* c, const std::vector<ActiveModel>& survivors) {
   return CALS_OK;
 }
 
-int one_round(cals_ctx* c, int* retired_now) {
+// A round's read-back can be postponed when no model can leave in it: nothing waits in the queue and every
+// active model runs a fixed number of iterations that it has not reached yet.  (A model whose update fails
+// numerically in such a round is noticed at the next read-back and then takes its place in the output queue
+// by the round in which it failed, so the order is the same as with a read-back every round.)
+bool round_may_retire(const cals_ctx* c) {
+  if (!c->queue.empty()) return true;
+  for (const ActiveModel& m : c->active)
+    if (!(m.tol < 0.0) || m.iters + c->rounds_unread + 1 >= m.max_iters) return true;
+  return false;
+}
+
+int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
   CALS_TRY(fill(c));
   const int n = (int)c->active.size();
   if (n == 0) return CALS_OK;
@@ -454,7 +468,7 @@ int one_round(cals_ctx* c, int* retired_now) {
   for (const ActiveModel& m : c->active)
     if (m.flags & CALS_MODEL_LINESEARCH) {
       round_has_ls = true;
-      if (m.iters + 1 >= 2) ls_takes_part = true;
+      if (m.iters + c->rounds_unread + 1 >= 2) ls_takes_part = true;
     }
   if (round_has_ls) {
     LineSearchArgs la{};
@@ -472,35 +486,52 @@ int one_round(cals_ctx* c, int* retired_now) {
     HIP_TRY(launch_ls_decide(la, c->stream));
     HIP_TRY(launch_ls_apply(la, c->stream));
   }
+  c->rounds += 1;
+  if (!last_of_call && !round_may_retire(c)) {
+    c->rounds_unread += 1;
+    return CALS_OK;
+  }
   // the only per-round readback: fit, error, status and iteration count of every slot in use
   int max_sid = 0;
   for (const ActiveModel& m : c->active) max_sid = std::max(max_sid, m.sid);
   HIP_TRY(hipMemcpyAsync(c->h_out, c->d_out, sizeof(ModelOut) * (max_sid + 1), hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(hipStreamSynchronize(c->stream));
-  c->rounds += 1;
+  const int64_t unread = c->rounds_unread;     // rounds before this one whose records were not read
+  c->rounds_unread = 0;
 
   // Alg. 3, removal loop: slots in order; a model leaves when its fit changed by less than tol between two
   // consecutive iterations, when it reached its iteration cap, or when its update failed numerically.
-  std::vector<ActiveModel> survivors, leaving;
-  std::vector<int> statuses;
+  std::vector<ActiveModel> survivors;
+  std::vector<Leaving> gone;
   survivors.reserve(c->active.size());
+  int slot = 0;
   for (ActiveModel& m : c->active) {
     const ModelOut& o = c->h_out[m.sid];
     int status = CALS_RUNNING;
-    if (o.status == CALS_NUMERICAL) status = CALS_NUMERICAL;
-    else if (o.iters >= 2 && std::fabs(o.fit - m.fit_prev) < m.tol) status = CALS_CONVERGED;
+    int64_t round = c->rounds;
+    if (o.status == CALS_NUMERICAL) {
+      status = CALS_NUMERICAL;
+      // it failed in the iteration after its last completed one; rounds since the previous read-back: unread + 1
+      round = c->rounds - (unread + 1) + (o.iters - m.iters) + 1;
+    } else if (o.iters >= 2 && std::fabs(o.fit - m.fit_prev) < m.tol) status = CALS_CONVERGED;
     else if (o.iters >= m.max_iters) status = CALS_MAX_ITERS;
     m.fit_prev = o.fit;
     m.iters = o.iters;
     if (status != CALS_RUNNING) {
-      leaving.push_back(m);
-      statuses.push_back(status);
+      gone.push_back(Leaving{m, status, round, slot});
       *retired_now += 1;
     } else {
       survivors.push_back(m);
     }
+    ++slot;
   }
-  if (!leaving.empty()) {
+  if (!gone.empty()) {
+    std::stable_sort(gone.begin(), gone.end(), [](const Leaving& x, const Leaving& y) {
+      return x.round != y.round ? x.round < y.round : x.slot < y.slot;
+    });
+    std::vector<ActiveModel> leaving;
+    std::vector<int> statuses;
+    for (const Leaving& g : gone) { leaving.push_back(g.m); statuses.push_back(g.status); }
     CALS_TRY(retire_models(c, leaving, statuses));
     CALS_TRY(compact(c, survivors));
   }
@@ -653,7 +684,7 @@ int cals_iterate(cals_ctx* c, int32_t n_rounds, int32_t* n_retired) {
   if (n_retired) *n_retired = 0;
   for (int r = 0; r < n_rounds; ++r) {
     if (c->queue.empty() && c->active.empty()) break;
-    CALS_TRY(one_round(c, &retired_now));
+    CALS_TRY(one_round(c, &retired_now, r + 1 == n_rounds));
     if (n_retired) *n_retired = retired_now;
   }
   return CALS_OK;
