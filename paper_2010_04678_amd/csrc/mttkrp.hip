@@ -48,8 +48,8 @@ hipError_t mttkrp_init() {
     int n = 0;
     const Variant* t = (wm == 1) ? mttkrp_variants_wm1(&n) : (wm == 2 ? mttkrp_variants_wm2(&n) : mttkrp_variants_wm4(&n));
     for (int i = 0; i < n; ++i)
-      for (int m = 0; m < 4; ++m) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(t[i].fn[m]),
+      for (int m = 0; m < 8; ++m) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(t[i].fn[m >> 1][m & 1]),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)variant_lds_bytes(t[i]));
         if (e != hipSuccess) return e;
       }
@@ -137,12 +137,15 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   if (mode != kGeneral && p.sa == 1 && p.Ia % 4 == 0 && p.sm % 2 == 0 && p.sb % 2 == 0 && pl.ka == 16 &&
       (reinterpret_cast<uintptr_t>(p.T) & 15) == 0 && env_int("CALS_MTTKRP_NOCONTIG", 0) == 0)
     mode = kContig4;
+  // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao tile production
+  const int pair = (p.ld % 2 == 0 && ((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub)) & 15) == 0 &&
+                    env_int("CALS_MTTKRP_NOPAIR", 0) == 0) ? 1 : 0;
   // 1-D grid, decoded in the kernel: 8 interleaved sequences (one per XCD) of whole splits
   const int64_t per_split = (int64_t)pl.mtiles * pl.ny;
   const int64_t nblocks = per_split * pl.splits;
   if (nblocks >= (1LL << 31)) return hipErrorInvalidValue;
   if (ev) (void)hipEventRecord(ev[0], stream);
-  hipLaunchKernelGGL(v->fn[mode], dim3((unsigned)nblocks), dim3(256), variant_lds_bytes(*v), stream, a);
+  hipLaunchKernelGGL(v->fn[mode][pair], dim3((unsigned)nblocks), dim3(256), variant_lds_bytes(*v), stream, a);
   if (ev) (void)hipEventRecord(ev[1], stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -14,8 +14,8 @@
 //     is the same for all its lanes, so its address arithmetic runs on the scalar unit;
 //   - tensor fragments go from global memory straight into the MFMA register layout (lane l holds
 //     A[l%16][l/16]); one 64-bit offset serves all WM fragments of a k-step;
-//   - B fragments of k-step s+1 are read from LDS before the MFMAs of k-step s are issued, factor rows
-//     one k-step before they are multiplied, tensor fragments one stage ahead: no wait inside a k-step.
+//   - B fragments of k-step s+1 are read from LDS before the MFMAs of k-step s are issued; factor rows and
+//     tensor fragments are requested a whole stage before they are used: no wait inside a k-step.
 // The LDS tile is double-buffered with one barrier per stage of KA contraction indices.
 #pragma once
 #include "cals_internal.h"
@@ -32,6 +32,9 @@ __device__ inline __amdgpu_buffer_rsrc_t factor_rsrc(const double* base, unsigne
 }
 __device__ inline double buffer_load_f64(__amdgpu_buffer_rsrc_t rsrc, unsigned lane_byte, unsigned row_byte) {
   return __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_byte, (int)row_byte, 0));
+}
+__device__ inline double2 buffer_load_f64x2(__amdgpu_buffer_rsrc_t rsrc, unsigned lane_byte, unsigned row_byte) {
+  return __builtin_bit_cast(double2, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_byte, (int)row_byte, 0));
 }
 
 struct MttkrpKernelArgs {
@@ -58,11 +61,12 @@ struct MttkrpKernelArgs {
 //             k-step s then takes element s of every lane, i.e. tile row 4*lq + s instead of 4*s + lq.
 enum { kAffine = 0, kWrap = 1, kGeneral = 2, kContig4 = 3 };
 
-template <int WM, int WN, int KA, int MODE>
+template <int WM, int WN, int KA, int MODE, bool PAIR>
 __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   constexpr int NC = 16 * WN;                 // columns of the LDS tile
   constexpr int KS = KA / 4;                  // MFMA k-steps per stage = tile rows produced per wavefront
-  constexpr int CU = (NC + 63) / 64;          // 64-column chunks of a tile row
+  constexpr int PW = PAIR ? 2 : 1;            // adjacent columns a lane produces (2: 16-byte loads and stores)
+  constexpr int CU = (NC / PW + 63) / 64;     // chunks of 64*PW columns of a tile row
   constexpr int TILE = KA * NC;               // doubles per LDS buffer
   extern __shared__ double smem[];            // [2][KA][NC]
 
@@ -185,23 +189,25 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   unsigned gbyte[CU];                         // byte offset of the lane's column within a factor row
 #pragma unroll
   for (int u = 0; u < CU; ++u) {
-    const int tc = lane + 64 * u;
-    tcol[u] = tc < NC ? tc : NC - 1;          // surplus lanes repeat the last column (same value, same address)
+    const int tc = PW * (lane + 64 * u);
+    tcol[u] = tc < NC ? tc : NC - PW;         // surplus lanes repeat the last columns (same value, same address)
     const int gc = n0 + tcol[u];
-    gbyte[u] = 8u * (unsigned)(gc < a.ld ? gc : a.ld - 1);
+    gbyte[u] = 8u * (unsigned)(gc <= a.ld - PW ? gc : a.ld - PW);   // PAIR: ld is even (checked on the host)
   }
-  int p_ia, p_ib;                             // (ia, ib) of the first index of the stage being produced (uniform)
+  int p_ia, p_ib;                             // (ia, ib) of the first index of the stage being FETCHED (uniform)
   {
     const int64_t ib = kb / Ia;
-    p_ib = (int)ib;
-    p_ia = (int)(kb - ib * Ia);
+    p_ib = __builtin_amdgcn_readfirstlane((int)ib);
+    p_ia = __builtin_amdgcn_readfirstlane((int)(kb - ib * Ia));
   }
-  double pua[2][CU], pub[2][CU];
+  // Factor rows are fetched a whole stage before they are multiplied (row x of the tile after next is requested
+  // right after row x of the next tile has been written), so that a miss in L2 never stalls the wavefront.
+  double pua[KS][CU][PW], pub[KS][CU][PW];
   const unsigned row_bytes = 8u * (unsigned)a.ld;
   const __amdgpu_buffer_rsrc_t rsrc_a = factor_rsrc(a.Ua, row_bytes * (unsigned)Ia);   // < 2^32 (checked on the host)
   const __amdgpu_buffer_rsrc_t rsrc_b = factor_rsrc(a.Ub, row_bytes * (unsigned)a.Ib);
 
-  auto fetch_row = [&](int x, double (&ua)[CU], double (&ub)[CU]) {
+  auto fetch_row = [&](int x, double (&ua)[CU][PW], double (&ub)[CU][PW]) {
     int ia = p_ia + wave + 4 * x, ib = p_ib;
     if (MODE == kGeneral) {
       while (ia >= Ia) { ia -= Ia; ib += 1; }
@@ -214,13 +220,26 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
     const unsigned ob = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)ib * row_bytes));
 #pragma unroll
     for (int u = 0; u < CU; ++u) {
-      ua[u] = buffer_load_f64(rsrc_a, gbyte[u], oa);
-      ub[u] = buffer_load_f64(rsrc_b, gbyte[u], ob);
+      if (PAIR) {
+        const double2 va = buffer_load_f64x2(rsrc_a, gbyte[u], oa);
+        const double2 vb = buffer_load_f64x2(rsrc_b, gbyte[u], ob);
+        ua[u][0] = va.x; ua[u][PW - 1] = va.y;
+        ub[u][0] = vb.x; ub[u][PW - 1] = vb.y;
+      } else {
+        ua[u][0] = buffer_load_f64(rsrc_a, gbyte[u], oa);
+        ub[u][0] = buffer_load_f64(rsrc_b, gbyte[u], ob);
+      }
     }
   };
-  auto commit_row = [&](double* tile, int x, const double (&ua)[CU], const double (&ub)[CU]) {
+  auto commit_row = [&](double* tile, int x, const double (&ua)[CU][PW], const double (&ub)[CU][PW]) {
 #pragma unroll
-    for (int u = 0; u < CU; ++u) tile[(wave + 4 * x) * NC + tcol[u]] = ua[u] * ub[u];
+    for (int u = 0; u < CU; ++u) {
+      double* dst = tile + (wave + 4 * x) * NC + tcol[u];
+      if (PAIR)
+        *reinterpret_cast<double2*>(dst) = double2{ua[u][0] * ub[u][0], ua[u][PW - 1] * ub[u][PW - 1]};
+      else
+        *dst = ua[u][0] * ub[u][0];
+    }
   };
   auto advance_producer = [&]() {
     p_ia += KA;
@@ -238,23 +257,16 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
     for (int j = 0; j < WN; ++j) b[j] = brow[16 * j];
   };
 
-  // One stage: MFMAs on (acur, tile `cur`); meanwhile the next tensor fragments are fetched and the
-  // next tile is produced into the other buffer.
+  // One stage: MFMAs on (acur, tile `cur`); meanwhile the tensor fragments of the next stage are fetched, the
+  // next tile is written into the other buffer and the factor rows of the tile after it are requested.
   auto run_stage = [&](const double (&acur)[KS][WM], double (&anext)[KS][WM], int cur) {
     const double* tile = smem + cur * TILE;
     double* next_tile = smem + (cur ^ 1) * TILE;
     load_b(tile, 0, breg[0]);
-    fetch_row(0, pua[0], pub[0]);
-    if (KS == 1) load_a_stage(anext);
+    load_a_stage(anext);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      if (s + 1 < KS) {
-        load_b(tile, s + 1, breg[(s + 1) & 1]);
-        fetch_row(s + 1, pua[(s + 1) & 1], pub[(s + 1) & 1]);
-      }
-      // The tensor fragments of the next stage are requested in the second k-step: the memory counter
-      // retires in order, so the factor rows committed after k-steps 0 and 1 must not queue behind them.
-      if (KS > 1 && s == 1) load_a_stage(anext);
+      if (s + 1 < KS) load_b(tile, s + 1, breg[(s + 1) & 1]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < WN; ++j)
@@ -262,18 +274,22 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
         for (int t = 0; t < WM; ++t)
           acc[t][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(acur[s][t], breg[s & 1][j], acc[t][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      commit_row(next_tile, s, pua[s & 1], pub[s & 1]);
+      commit_row(next_tile, s, pua[s], pub[s]);
+      fetch_row(s, pua[s], pub[s]);
     }
     advance_producer();
     __syncthreads();
   };
 
-  // ---- prologue: tile 0 and fragment 0
+  // ---- prologue: tile 0, the factor rows of tile 1 and fragment 0
 #pragma unroll
   for (int x = 0; x < KS; ++x) {
-    fetch_row(x, pua[0], pub[0]);
-    commit_row(smem, x, pua[0], pub[0]);
+    fetch_row(x, pua[x], pub[x]);
+    commit_row(smem, x, pua[x], pub[x]);
   }
+  advance_producer();
+#pragma unroll
+  for (int x = 0; x < KS; ++x) fetch_row(x, pua[x], pub[x]);
   advance_producer();
   load_a_stage(areg0);
   __syncthreads();
@@ -306,13 +322,15 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 typedef void (*mttkrp_fn)(MttkrpKernelArgs);
 struct Variant {
   int wm, wn, ka;
-  mttkrp_fn fn[4];    // indexed by kAffine / kWrap / kGeneral / kContig4
+  mttkrp_fn fn[4][2]; // indexed by kAffine / kWrap / kGeneral / kContig4, and by PAIR
 };
 #define CALS_VARIANT(WM_, WN_, KA_)                                                                       \
   {                                                                                                       \
     WM_, WN_, KA_, {                                                                                      \
-      mttkrp_kernel<WM_, WN_, KA_, kAffine>, mttkrp_kernel<WM_, WN_, KA_, kWrap>,                         \
-          mttkrp_kernel<WM_, WN_, KA_, kGeneral>, mttkrp_kernel<WM_, WN_, KA_, kContig4>                  \
+      {mttkrp_kernel<WM_, WN_, KA_, kAffine, false>, mttkrp_kernel<WM_, WN_, KA_, kAffine, true>},        \
+          {mttkrp_kernel<WM_, WN_, KA_, kWrap, false>, mttkrp_kernel<WM_, WN_, KA_, kWrap, true>},        \
+          {mttkrp_kernel<WM_, WN_, KA_, kGeneral, false>, mttkrp_kernel<WM_, WN_, KA_, kGeneral, true>},  \
+          {mttkrp_kernel<WM_, WN_, KA_, kContig4, false>, mttkrp_kernel<WM_, WN_, KA_, kContig4, true>}   \
     }                                                                                                     \
   }
 
