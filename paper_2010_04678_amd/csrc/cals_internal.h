@@ -24,12 +24,16 @@ struct MttkrpProblem {
   int ld;             // leading dimension (doubles) of Ua, Ub, M
 };
 
+struct MttkrpPart {  // one kernel launch: `ny` column blocks of `wn` 16-column tiles each, starting at column col0
+  int wn, ny, col0;
+};
+
 struct MttkrpPlan {
   int wm;          // 16-row MFMA tiles per wavefront
-  int wn;          // 16-column MFMA tiles per wavefront (all columns of the workgroup)
   int ka;          // contraction rows per LDS stage
-  int ny;          // column blocks (grid.y)
-  int splits;      // split-K factor (grid.z)
+  int nparts;      // launches: column blocks of unequal width run as separate launches (no padded tile columns)
+  MttkrpPart part[2];
+  int splits;      // split-K factor (same for all parts)
   int64_t chunk;   // contraction indices per split
   int mtiles;      // row blocks of 64*wm rows
   size_t workspace_bytes;  // split-K partials: splits * In * ld doubles (0 when splits == 1)

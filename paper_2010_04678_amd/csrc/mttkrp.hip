@@ -70,37 +70,53 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
   // tuning knobs (development aid): widest column block, row tiles per wavefront, forced split count
   int wn_max = env_int("CALS_MTTKRP_WNMAX", kMaxWn);
   wn_max = wn_max < 1 ? 1 : (wn_max > kMaxWn ? kMaxWn : wn_max);
-  pl.ny = (ntile16 + wn_max - 1) / wn_max;
-  pl.wn = (ntile16 + pl.ny - 1) / pl.ny;
+  // Column blocks: as few as the widest tile allows, widths as even as possible.  Blocks of the wider and of
+  // the narrower kind run as separate launches, each with the kernel of its own width, so no MFMA works on
+  // padding tile columns (the tensor is read once per column block either way).
+  const int ny = (ntile16 + wn_max - 1) / wn_max;
+  const int base = ntile16 / ny, rem = ntile16 % ny;
+  if (rem == 0) {
+    pl.nparts = 1;
+    pl.part[0] = MttkrpPart{base, ny, 0};
+  } else {
+    pl.nparts = 2;
+    pl.part[0] = MttkrpPart{base + 1, rem, 0};
+    pl.part[1] = MttkrpPart{base, ny - rem, rem * (base + 1) * 16};
+  }
+  const int wn_top = pl.part[0].wn;
   // row tiles per wavefront: as many as the accumulator budget (WM*WN <= 28 tiles) and the row count allow
-  int wm = (pl.wn <= 7 && p.In > 128) ? 4 : (p.In > 64 ? 2 : 1);
+  int wm = (wn_top <= 7 && p.In > 128) ? 4 : (p.In > 64 ? 2 : 1);
   wm = env_int("CALS_MTTKRP_WM", wm);
   if (wm != 1 && wm != 2 && wm != 4) wm = 2;
-  if (wm == 4 && pl.wn > 7) wm = 2;
+  if (wm == 4 && wn_top > 7) wm = 2;
   pl.wm = wm;
   pl.ka = 16;
   pl.mtiles = (p.In + 64 * wm - 1) / (64 * wm);
   const int64_t K = (int64_t)p.Ia * p.Ib;
   // resident workgroups per CU: bounded by registers (accumulators) and LDS
-  const int acc_tiles = wm * pl.wn;
+  const int acc_tiles = wm * wn_top;
   int per_cu = (acc_tiles >= 17) ? 1 : (acc_tiles >= 10 ? 2 : (acc_tiles >= 8 ? 3 : 4));
-  const int lds_fit = (int)(160 * 1024 / ((size_t)2 * pl.ka * 16 * pl.wn * sizeof(double)));
+  const int lds_fit = (int)(160 * 1024 / ((size_t)2 * pl.ka * 16 * wn_top * sizeof(double)));
   if (per_cu > lds_fit) per_cu = lds_fit;
   per_cu = env_int("CALS_MTTKRP_PERCU", per_cu);
   // Split of the contraction range.  Workgroups run in waves of `slots` (one per resident position); the time
-  // of a launch is about waves x (stages per workgroup + fixed cost).  Splits are whole multiples of 8 when
-  // there are 8 or more, so that the XCD-pinned block order gives every XCD the same number of splits; with
-  // fewer splits the blocks of a split are spread over the XCDs instead.
+  // of a launch is about waves x (stages per workgroup + fixed cost), a stage costing in proportion to the
+  // block width.  Splits are whole multiples of 8 when there are 8 or more, so that the XCD-pinned block order
+  // gives every XCD the same number of splits; with fewer splits the blocks of a split are spread over the
+  // XCDs instead.
   const int64_t slots = (int64_t)num_cus * per_cu;
-  const int64_t per_split = (int64_t)pl.mtiles * pl.ny;
   const int64_t max_splits = std::max<int64_t>(1, K / (4 * pl.ka));   // at least two stage pairs per split
   const int force_splits = env_int("CALS_MTTKRP_SPLITS", 0);
   int64_t splits = 1;
   double best_cost = 1e300;
   for (int64_t cand = 1; cand <= std::min<int64_t>(max_splits, 4096); cand = (cand < 8) ? cand + 1 : cand + 8) {
-    const int64_t waves = (per_split * cand + slots - 1) / slots;
     const int64_t pairs = (K + cand * 2 * pl.ka - 1) / (cand * 2 * pl.ka);
-    const double cost = (double)waves * (2.0 * pairs + 6.0) * (1.0 + 0.002 * cand);
+    double cost = 0.0;
+    for (int q = 0; q < pl.nparts; ++q) {
+      const int64_t waves = ((int64_t)pl.mtiles * pl.part[q].ny * cand + slots - 1) / slots;
+      cost += (double)waves * (2.0 * pairs * pl.part[q].wn / wn_top + 6.0);
+    }
+    cost *= 1.0 + 0.002 * cand;
     if (cost < best_cost) { best_cost = cost; splits = cand; }
   }
   if (force_splits > 0) splits = force_splits;
@@ -115,13 +131,19 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
 
 hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* workspace, hipStream_t stream,
                          hipEvent_t* ev) {
-  const Variant* v = find_variant(pl.wm, pl.wn);
-  if (!v || v->ka != pl.ka) return hipErrorInvalidValue;
+  if (pl.nparts < 1 || pl.nparts > 2) return hipErrorInvalidValue;
   if (p.ncols < 1 || p.ncols > p.ld || p.In < 1 || p.Ia < 1 || p.Ib < 1) return hipErrorInvalidValue;
-  if ((int64_t)pl.ny * 16 * pl.wn < p.ncols || (int64_t)pl.mtiles * 64 * pl.wm < p.In) return hipErrorInvalidValue;
+  if ((int64_t)pl.mtiles * 64 * pl.wm < p.In) return hipErrorInvalidValue;
   if (pl.chunk % pl.ka != 0 || (int64_t)pl.splits * pl.chunk < (int64_t)p.Ia * p.Ib) return hipErrorInvalidValue;
   if (pl.splits > 1 && !workspace) return hipErrorInvalidValue;
   if (!p.zeros || (reinterpret_cast<uintptr_t>(p.zeros) & 15)) return hipErrorInvalidValue;
+  // the parts tile the columns without gaps
+  int covered = 0;
+  for (int q = 0; q < pl.nparts; ++q) {
+    if (pl.part[q].col0 != covered || pl.part[q].wn < 1 || pl.part[q].ny < 1) return hipErrorInvalidValue;
+    covered += 16 * pl.part[q].wn * pl.part[q].ny;
+  }
+  if (covered < p.ncols) return hipErrorInvalidValue;
   MttkrpKernelArgs a;
   a.T = p.T; a.Ua = p.Ua; a.Ub = p.Ub; a.zeros = p.zeros;
   a.P = (pl.splits > 1) ? workspace : p.M;
@@ -130,7 +152,7 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   a.pstride = (int64_t)p.In * p.ld;
   a.In = p.In; a.Ia = p.Ia; a.Ib = p.Ib;
   a.ncols = p.ncols; a.ld = p.ld;
-  a.mtiles = pl.mtiles; a.ny = pl.ny; a.splits = pl.splits;
+  a.mtiles = pl.mtiles; a.splits = pl.splits;
   a.pinned = (pl.splits % 8 == 0) ? 1 : 0;
   int mode = (p.Ia < pl.ka) ? kGeneral : ((p.sb == (int64_t)p.Ia * p.sa) ? kAffine : kWrap);
   // rows contiguous along the contraction and 16-byte aligned: the coalesced 4-indices-per-lane path
@@ -140,15 +162,21 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao tile production
   const int pair = (p.ld % 2 == 0 && ((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub)) & 15) == 0 &&
                     env_int("CALS_MTTKRP_NOPAIR", 0) == 0) ? 1 : 0;
-  // 1-D grid, decoded in the kernel: 8 interleaved sequences (one per XCD) of whole splits
-  const int64_t per_split = (int64_t)pl.mtiles * pl.ny;
-  const int64_t nblocks = per_split * pl.splits;
-  if (nblocks >= (1LL << 31)) return hipErrorInvalidValue;
   if (ev) (void)hipEventRecord(ev[0], stream);
-  hipLaunchKernelGGL(v->fn[mode][pair], dim3((unsigned)nblocks), dim3(256), variant_lds_bytes(*v), stream, a);
+  for (int q = 0; q < pl.nparts; ++q) {
+    const Variant* v = find_variant(pl.wm, pl.part[q].wn);
+    if (!v || v->ka != pl.ka) return hipErrorInvalidValue;
+    a.ny = pl.part[q].ny;
+    a.col0 = pl.part[q].col0;
+    // 1-D grid, decoded in the kernel: 8 interleaved sequences (one per XCD) of whole splits
+    const int64_t nblocks = (int64_t)pl.mtiles * a.ny * pl.splits;
+    if (nblocks >= (1LL << 31)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(v->fn[mode][pair], dim3((unsigned)nblocks), dim3(256), variant_lds_bytes(*v), stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   if (ev) (void)hipEventRecord(ev[1], stream);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
   if (pl.splits > 1) {
     const int64_t n = a.pstride;
     if (ev) (void)hipEventRecord(ev[2], stream);

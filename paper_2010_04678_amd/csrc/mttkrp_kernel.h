@@ -49,6 +49,7 @@ struct MttkrpKernelArgs {
   int In, Ia, Ib;
   int ncols, ld;
   int mtiles, ny, splits;   // logical grid: row blocks, column blocks, splits
+  int col0;                 // first column of column block 0
   int pinned;               // splits is a multiple of 8: keep every split on one XCD
 };
 
@@ -96,7 +97,7 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   const int li = lane & 15;                   // A: row within the tile / B,D: column within the tile
   const int lq = lane >> 4;                   // A,B: k within the k-step / D: row group
   const int m0 = bx * (64 * WM) + wave * (16 * WM);
-  const int n0 = by * NC;
+  const int n0 = a.col0 + by * NC;
   const int64_t kb = (int64_t)bz * a.chunk;
   const int64_t ke = (kb + a.chunk < a.K) ? (kb + a.chunk) : a.K;
   const int nstage = (int)((ke - kb + KA - 1) / KA);
