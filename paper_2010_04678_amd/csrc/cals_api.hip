@@ -103,6 +103,7 @@ struct cals_ctx {
   int32_t* d_colmodel = nullptr; // line search: slot position owning each column
   int32_t* h_colmodel = nullptr; // pinned
   int32_t* d_accept = nullptr;   // line search: per slot position, extrapolated point taken this round
+  double* d_updpart = nullptr;   // update of tall modes: per (slot position, row block) partial sums
   int32_t* d_nnfail = nullptr;   // non-negativity: per slot position, failure flag of the current mode update
   std::deque<PendingModel> queue;
   std::vector<ActiveModel> active;
@@ -460,7 +461,7 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
     ua.desc = c->d_desc; ua.state = c->d_state; ua.out = c->d_out; ua.lambda = c->d_lambda;
     ua.M = c->M; ua.U = c->U[mode]; ua.X = c->Ualt[mode]; ua.nn_fail = c->d_nnfail;
     ua.In = (int)c->dims[mode]; ua.ld = c->ld; ua.mode = mode;
-    ua.n_models = n; ua.normT2 = c->normT2;
+    ua.n_models = n; ua.normT2 = c->normT2; ua.part = c->d_updpart;
     HIP_TRY(launch_update(ua, c->stream));
   }
   // line search (Sec. 5): extrapolate, one extra fused mode-3 MTTKRP at the extrapolated point, decide, apply
@@ -577,7 +578,7 @@ int cals_destroy(cals_ctx* c) {
     (void)hipFree(c->passive[n]);
   }
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
-  (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned);
+  (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart);
   (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
   (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
@@ -619,6 +620,8 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
   ok = ok && hipMalloc(&c->d_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
   ok = ok && hipMalloc(&c->d_map, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipMalloc(&c->d_scratch, sizeof(double) * 1032) == hipSuccess;
+  if (update_row_blocks((int)imax) > 1)
+    ok = ok && hipMalloc(&c->d_updpart, sizeof(double) * update_part_doubles((int)imax) * c->capacity) == hipSuccess;
   ok = ok && hipMalloc(&c->d_zeros, sizeof(double) * 8) == hipSuccess;
   ok = ok && hipMemsetAsync(c->d_zeros, 0, sizeof(double) * 8, c->stream) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_desc, sizeof(ModelDesc) * c->capacity) == hipSuccess;

@@ -85,7 +85,17 @@ struct UpdateArgs {
   int In, ld, mode;     // mode = 0,1,2
   int n_models;
   double normT2;
+  double* part;         // tall modes: per (slot position, row block) partial Gramian and inner product
+                        // (update_part_doubles(In) doubles per slot position); may be null when update_row_blocks(In) == 1
 };
+
+// Row blocks a mode of In rows is cut into for the update (1: one workgroup per model does everything).
+constexpr int kUpdatePartStride = 536;   // 528 lower-triangle pairs + the inner-product term, padded
+inline int update_row_blocks(int In) {
+  const int b = (In + 255) / 256;
+  return b < 1 ? 1 : (b > 32 ? 32 : b);
+}
+inline size_t update_part_doubles(int In) { return (size_t)update_row_blocks(In) * kUpdatePartStride; }
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t stream);
 // Gramians of all three modes for models [first, first+count) of desc (used when a model is inserted

@@ -1,5 +1,5 @@
 // Per-model steps of one CALS mode update (Alg. 2 inner loop; Alg. 1 Hadamard, update and error lines),
-// one workgroup per active model:
+// one workgroup per active model (modes of more than 256 rows: one per model and row block, two launches):
 //   H = Ga * Gb (cached Gramians of the other two modes)         -- Hadamard product of Gramians
 //   H = L L^T                                                    -- Cholesky, no pivoting
 //   U[i,:] = M[i,:] H^-1 for every row i (two triangular solves) -- normal-equation update
@@ -211,18 +211,190 @@ __global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
   }
 }
 
+// ---- tall modes: the same update cut into row blocks, two launches -------------------------------------
+// update_solve_kernel, grid (models, row blocks): every workgroup factorises H itself (identical results),
+// solves its rows and leaves its partial Gramian and inner product in a.part.  update_finish_kernel, same
+// grid: every workgroup adds the partials in block order (fixed order: reproducible), derives lambda and
+// scales its rows; row block 0 also writes the model's Gramian, lambda and error terms.
+__device__ inline int rows_per_block(int In, int nblk) { return ((In + nblk - 1) / nblk + kRows - 1) / kRows * kRows; }
+
+__global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
+  extern __shared__ double lds[];
+  const ModelDesc d = a.desc[blockIdx.x];
+  const ModelState* st = a.state + d.sid;
+  ModelOut* out = a.out + d.sid;
+  if (out->status != 0) return;               // stopped earlier in this iteration (uniform over the model's blocks:
+                                              // this launch only ever stores the value every block computes alike)
+  const int tid = threadIdx.x;
+  const int R = d.rank;
+  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
+  double* xs = lds;                           // R * kXs
+  double* L = xs + kMaxRank * kXs;            // R*R, Cholesky factor
+  double* red = L + kGramStride;              // 256
+  __shared__ int flag;
+
+  for (int e = tid; e < R * R; e += 256) L[e] = st->G[ma][e] * st->G[mb][e];
+  __syncthreads();
+  const bool nonneg = (d.flags & 1u) != 0;
+  bool failed;
+  if (nonneg) {
+    if (tid == 0) flag = a.nn_fail[blockIdx.x];   // cleared by update_finish_kernel
+    __syncthreads();
+    failed = flag != 0;
+  } else {
+    failed = !block_cholesky(L, R, &flag);
+  }
+  if (failed) {
+    if (tid == 0 && blockIdx.y == 0) out->status = 3;   // CALS_NUMERICAL; factors of this mode stay untouched
+    return;
+  }
+
+  const int nblk = gridDim.y;
+  const int rpb = rows_per_block(a.In, nblk);
+  const int r0 = blockIdx.y * rpb;
+  const int r1 = (r0 + rpb < a.In) ? (r0 + rpb) : a.In;
+  double gacc[3] = {0.0, 0.0, 0.0};
+  double inner = 0.0;
+  const double* Mb = a.M + d.col;
+  double* Ub = a.U + d.col;
+  for (int base = r0; base < r1; base += kRows) {
+    const int i = base + tid;
+    const int nrows = (r1 - base < kRows) ? (r1 - base) : kRows;
+    if (i < r1) {
+      const double* mrow = Mb + (int64_t)i * a.ld;
+      if (nonneg) {
+        const double* xrow = a.X + (int64_t)i * a.ld + d.col;
+        for (int r = 0; r < R; ++r) xs[r * kXs + tid] = xrow[r];
+      } else {
+        for (int r = 0; r < R; ++r) xs[r * kXs + tid] = mrow[r];
+        for (int r = 0; r < R; ++r) {          // L y = m
+          double v = xs[r * kXs + tid];
+          for (int k = 0; k < r; ++k) v -= L[r * R + k] * xs[k * kXs + tid];
+          xs[r * kXs + tid] = v / L[r * R + r];
+        }
+        for (int r = R - 1; r >= 0; --r) {     // L^T x = y
+          double v = xs[r * kXs + tid];
+          for (int k = r + 1; k < R; ++k) v -= L[k * R + r] * xs[k * kXs + tid];
+          xs[r * kXs + tid] = v / L[r * R + r];
+        }
+      }
+      double* urow = Ub + (int64_t)i * a.ld;
+      double part = 0.0;
+      for (int r = 0; r < R; ++r) {
+        const double x = xs[r * kXs + tid];
+        urow[r] = x;
+        part += x * mrow[r];
+      }
+      inner += part;
+    }
+    __syncthreads();
+    gram_accumulate(xs, R, nrows, gacc);
+    __syncthreads();
+  }
+  double* part = a.part + ((size_t)blockIdx.x * nblk + blockIdx.y) * kUpdatePartStride;
+  const int npairs = R * (R + 1) / 2;
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const int p = tid + 256 * q;
+    if (p < npairs) part[p] = gacc[q];
+  }
+  const double in = block_sum(inner, red);
+  if (tid == 0) part[528] = in;
+}
+
+__global__ void __launch_bounds__(256) update_finish_kernel(UpdateArgs a) {
+  extern __shared__ double lds[];
+  const ModelDesc d = a.desc[blockIdx.x];
+  ModelState* st = a.state + d.sid;
+  ModelOut* out = a.out + d.sid;
+  const int tid = threadIdx.x;
+  if ((d.flags & 1u) && blockIdx.y == 0 && tid == 0) a.nn_fail[blockIdx.x] = 0;
+  if (out->status != 0) return;               // this launch never changes a status
+  const int R = d.rank;
+  const int nblk = gridDim.y;
+  double* Gl = lds;                           // R*R, Gramian of the updated factor
+  double* red = Gl + kGramStride;             // 256
+  double* lam = red + 256;                    // R
+  const double* part = a.part + (size_t)blockIdx.x * nblk * kUpdatePartStride;
+  const int npairs = R * (R + 1) / 2;
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const int p = tid + 256 * q;
+    if (p < npairs) {
+      double g = 0.0;
+      for (int b = 0; b < nblk; ++b) g += part[(size_t)b * kUpdatePartStride + p];
+      int r, s;
+      pair_rs(p, r, s);
+      Gl[r * R + s] = g;
+      Gl[s * R + r] = g;
+    }
+  }
+  __syncthreads();
+  if (blockIdx.y == 0 && a.mode == 2) {
+    const int ma = 0, mb = 1;
+    double v = 0.0;
+    for (int e = tid; e < R * R; e += 256) v += (st->G[ma][e] * st->G[mb][e]) * Gl[e];
+    const double normsq = block_sum(v, red);
+    if (tid == 0) {
+      double in = 0.0;
+      for (int b = 0; b < nblk; ++b) in += part[(size_t)b * kUpdatePartStride + 528];
+      st->inner = in;
+      st->normsq = normsq;
+      const double err = a.normT2 + normsq - 2.0 * in;
+      out->err = err;
+      out->fit = 1.0 - sqrt(err > 0.0 ? err : 0.0) / sqrt(a.normT2);
+      out->iters += 1;
+    }
+  }
+  if (tid < R) {
+    const double l = sqrt(Gl[tid * R + tid]);
+    lam[tid] = l;
+    if (blockIdx.y == 0) a.lambda[d.sid * kMaxRank + tid] = l;
+  }
+  __syncthreads();
+  if (blockIdx.y == 0)
+    for (int e = tid; e < R * R; e += 256) {
+      const int r = e / R, s = e % R;
+      const double lr = lam[r] > 0.0 ? lam[r] : 1.0, ls = lam[s] > 0.0 ? lam[s] : 1.0;
+      st->G[a.mode][e] = (Gl[e] / lr) / ls;
+    }
+  const int rpb = rows_per_block(a.In, nblk);
+  const int r0 = blockIdx.y * rpb;
+  const int r1 = (r0 + rpb < a.In) ? (r0 + rpb) : a.In;
+  double* Ub = a.U + d.col;
+  for (int i = r0 + tid; i < r1; i += 256) {
+    double* urow = Ub + (int64_t)i * a.ld;
+    for (int r = 0; r < R; ++r) {
+      const double l = lam[r];
+      if (l > 0.0) urow[r] = urow[r] / l;
+    }
+  }
+}
+
 static constexpr size_t kUpdateLds = sizeof(double) * (kMaxRank * kXs + 3 * kGramStride + 256 + kMaxRank);
+static constexpr size_t kSolveLds = sizeof(double) * (kMaxRank * kXs + kGramStride + 256);
+static constexpr size_t kFinishLds = sizeof(double) * (kGramStride + 256 + kMaxRank);
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t stream) {
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(update_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUpdateLds);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(update_solve_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSolveLds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   if (a.n_models < 1) return hipSuccess;
-  hipLaunchKernelGGL(update_kernel, dim3(a.n_models), dim3(256), kUpdateLds, stream, a);
+  const int nblk = update_row_blocks(a.In);
+  if (nblk == 1) {
+    hipLaunchKernelGGL(update_kernel, dim3(a.n_models), dim3(256), kUpdateLds, stream, a);
+    return hipGetLastError();
+  }
+  if (!a.part) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(update_solve_kernel, dim3(a.n_models, nblk), dim3(256), kSolveLds, stream, a);
+  hipLaunchKernelGGL(update_finish_kernel, dim3(a.n_models, nblk), dim3(256), kFinishLds, stream, a);
   return hipGetLastError();
 }
 
