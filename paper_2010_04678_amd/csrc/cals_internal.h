@@ -130,7 +130,7 @@ struct NnlsArgs {
   uint32_t* passive;    // per (row, sid) passive-set masks of this mode, In x capacity; read (warm start) and written
   int32_t* fail;        // per slot position; or-ed with 1 on failure
   int In, ld, mode, n_models, capacity;
-  int max_rank;         // largest rank among the NONNEG models of this launch (sizes the LDS request)
+  int max_rank;         // largest rank among the NONNEG models of this launch
 };
 hipError_t launch_nnls(const NnlsArgs& a, hipStream_t stream);
 

@@ -2,176 +2,167 @@
 // normal-equation solve of a NONNEG model is replaced, row by row, by
 //     minimise 1/2 x^T H x - m^T x   subject to x >= 0,
 // with an active-set (Lawson-Hanson) search on (H, m); the passive set a row ends with is kept for the next
-// iteration (warm start; dropped if its sub-block of H is not positive definite).  H and the MTTKRP are computed once per mode update, exactly as for plain ALS.
+// iteration (warm start; dropped if its sub-block of H is not positive definite).  H and the MTTKRP are computed
+// once per mode update, exactly as for plain ALS.
 //
-// One lane per row, one wavefront per workgroup.  Every lane runs the textbook sequence (factorise the passive
-// sub-block of H, solve, step towards feasibility, gradient test) in the same order of operations as a scalar
-// implementation; loops run over the full index range with the lane's passive mask as predicate, so all lanes
-// read H at the same (broadcast) address.  Per-lane vectors and the packed Cholesky factor live in LDS,
-// element-major ([element][lane]), which is bank-conflict free.
+// One wavefront per row, lane r = component r.  The search is a chain of small dense solves; spreading a row
+// over the lanes turns each solve from O(R^3) dependent steps into O(R^2) register operations:
+//   - lane i keeps row i of H in registers (loaded once per model and wavefront) and, per solve, row i of the
+//     working matrix; the passive sub-system is solved by symmetric Gaussian elimination without pivoting
+//     (pivot j is broadcast from lane j with v_readlane, every lane below updates its own row and right-hand
+//     side) and column-oriented back-substitution.  A pivot that is not positive and finite is the same verdict
+//     as a failed Cholesky factorisation;
+//   - feasibility, the step length and the choice of the entering variable are wavefront votes and reductions;
+//     ties in the gradient test go to the lowest index, as in a scalar left-to-right scan;
+//   - all control flow is uniform over the wavefront, so no barrier and no LDS are needed.
 #include <cfloat>
+#include <cmath>
 
 #include "cals_internal.h"
 
 namespace cals {
 
-// Rows per workgroup: few, so that the per-lane LDS arrays stay small and several wavefronts share a CU (the
-// search is a chain of dependent LDS reads: it needs occupancy, not lanes).
-__host__ __device__ inline int nnls_rows_per_block(int R) { return R <= 24 ? 16 : 8; }
-__host__ __device__ inline size_t nnls_lds_doubles(int R) {
-  return (size_t)kGramStride + (size_t)(R * (R + 1) / 2 + 3 * R) * nnls_rows_per_block(R);
+__device__ inline double readlane_f64(double v, int src_lane /* wave-uniform */) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
+  return __hiloint2double(hi, lo);
+}
+__device__ inline double wave_max(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ inline double wave_min(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmin(v, __shfl_xor(v, o));
+  return v;
 }
 
-__global__ void __launch_bounds__(64) nnls_kernel(NnlsArgs a) {
-  extern __shared__ double lds[];
+constexpr int kNnlsRowsPerBlock = 16;   // 4 wavefronts x 4 rows
+
+// All rows [row0, row1) with stride 4 from row0 + wave, for one model of rank R <= RM.
+template <int RM>
+__device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d, int slot, int row0, int row1, int lane,
+                                          int wave) {
+  const int R = d.rank;
+  const ModelState* st = a.state + d.sid;
+  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
+  const bool live = lane < R;
+  double hrow[RM];                       // row `lane` of H = Ga * Gb (zero outside R x R)
+#pragma unroll
+  for (int k = 0; k < RM; ++k)
+    hrow[k] = (live && k < R) ? st->G[ma][lane * R + k] * st->G[mb][lane * R + k] : 0.0;
+  double cs = 0.0;                       // H is symmetric: row sums are column sums
+#pragma unroll
+  for (int k = 0; k < RM; ++k) cs += fabs(hrow[k]);
+  const double h1 = wave_max(cs);        // ||H||_1
+  const double tau = 10.0 * DBL_EPSILON * h1 * (double)R;
+  const int cap = 30 * R;
+  const uint32_t full = (R >= 32) ? 0xffffffffu : ((1u << R) - 1u);
+
+  for (int i = row0 + wave; i < row1; i += 4) {
+    uint32_t* pslot = a.passive + (int64_t)i * a.capacity + d.sid;
+    uint32_t P = (uint32_t)__builtin_amdgcn_readfirstlane((int)*pslot) & full;
+    const double m = live ? a.M[(int64_t)i * a.ld + d.col + lane] : 0.0;
+    double x = 0.0;                      // component `lane` of the iterate; zero outside the passive set
+    int steps = 0;
+    bool bad = false;
+    bool from_warm = (P != 0);           // the passive set still derives from the warm start
+    for (;;) {
+      while (P) {
+        // ---- solve H_PP s_P = m_P: elimination on the passive rows and columns, in ascending index order
+        double arow[RM];
+#pragma unroll
+        for (int k = 0; k < RM; ++k) arow[k] = hrow[k];
+        double b = m;
+        bool ok = true;
+#pragma unroll
+        for (int j = 0; j < RM; ++j) {
+          if (ok && ((P >> j) & 1u)) {         // P has no bits at or above R
+            const double dj = readlane_f64(arow[j], j);
+            if (!(dj > 0.0) || !isfinite(dj)) {
+              ok = false;
+            } else {
+              const double mult = (lane > j) ? arow[j] / dj : 0.0;
+              const double bj = readlane_f64(b, j);
+              b = fma(-mult, bj, b);
+#pragma unroll
+              for (int k = j + 1; k < RM; ++k) arow[k] = fma(-mult, readlane_f64(arow[k], j), arow[k]);
+            }
+          }
+        }
+        if (!ok) {
+          if (!from_warm) { bad = true; break; }
+          // a warm start whose sub-block cannot be factorised is dropped: restart from the empty set
+          from_warm = false;
+          P = 0;
+          x = 0.0;
+          break;
+        }
+        double s = 0.0;
+#pragma unroll
+        for (int k = RM - 1; k >= 0; --k) {
+          if ((P >> k) & 1u) {
+            const double sk = readlane_f64(b / arow[k], k);
+            s = (lane == k) ? sk : s;
+            b = (lane < k) ? fma(-arow[k], sk, b) : b;
+          }
+        }
+        // ---- feasible: take it; else step towards it until the first component reaches zero
+        const bool inP = live && ((P >> lane) & 1u);
+        const bool nonpos = inP && !(s > 0.0);
+        if (__ballot(nonpos) == 0) {
+          x = inP ? s : 0.0;
+          break;
+        }
+        const double beta = wave_min(nonpos ? x / (x - s) : 1.0);   // fmin drops the NaN of 0/0
+        const double xn = x + beta * (s - x);
+        const bool keep = inP && (xn > 0.0);
+        x = keep ? xn : 0.0;
+        P = (uint32_t)__ballot(keep);
+        if (++steps > cap) break;
+      }
+      if (bad || steps > cap) break;
+      // ---- gradient test: move the most violating variable into the passive set
+      double w = m;
+#pragma unroll
+      for (int k = 0; k < RM; ++k) w = fma(-hrow[k], readlane_f64(x, k), w);   // x and hrow are zero beyond R
+      const bool cand = live && !((P >> lane) & 1u) && (w > tau);
+      if (__ballot(cand) == 0) break;
+      const double wmax = wave_max(cand ? w : -INFINITY);
+      const unsigned long long winners = __ballot(cand && w == wmax);
+      P |= 1u << __builtin_ctzll(winners);
+      from_warm = false;
+      if (++steps > cap) break;
+    }
+    if (bad) {
+      if (lane == 0) atomicOr(a.fail + slot, 1);
+      continue;
+    }
+    if (lane == 0) *pslot = P;
+    if (live) a.X[(int64_t)i * a.ld + d.col + lane] = x;
+  }
+}
+
+__global__ void __launch_bounds__(256) nnls_kernel(NnlsArgs a) {
   const ModelDesc d = a.desc[blockIdx.x];
   if (!(d.flags & 1u)) return;
   if (a.out[d.sid].status != 0) return;
-  const int R = d.rank;
-  const int RPB = nnls_rows_per_block(R);
-  const int base = blockIdx.y * RPB;
-  if (base >= a.In) return;
-  const int lane = threadIdx.x;
-  const ModelState* st = a.state + d.sid;
-  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
-  const int npack = R * (R + 1) / 2;
-  double* H = lds;                       // R*R (symmetric), shared by the lanes
-  double* Lp = H + kGramStride;          // [npack][RPB]  packed lower Cholesky factor, indexed by original indices
-  double* xv = Lp + npack * RPB;         // [R][RPB]
-  double* sv = xv + R * RPB;             // [R][RPB]
-  double* mv = sv + R * RPB;             // [R][RPB]
-  for (int e = lane; e < R * R; e += 64) H[e] = st->G[ma][e] * st->G[mb][e];
-  __syncthreads();
-  double h1 = 0.0;                       // ||H||_1 (same for all lanes)
-  for (int j = 0; j < R; ++j) {
-    double cs = 0.0;
-    for (int i = 0; i < R; ++i) cs += fabs(H[i * R + j]);
-    if (cs > h1) h1 = cs;
-  }
-  const double tau = 10.0 * DBL_EPSILON * h1 * (double)R;
-  const int cap = 30 * R;
-  const int i = base + lane;
-  if (lane >= RPB || i >= a.In) return;  // no barrier below this point
-
-#define LP(r, c) Lp[((r) * ((r) + 1) / 2 + (c)) * RPB + lane]
-#define XV(r) xv[(r) * RPB + lane]
-#define SV(r) sv[(r) * RPB + lane]
-#define MV(r) mv[(r) * RPB + lane]
-// loops over the members of a bit set in ascending order (the order a scalar implementation visits them)
-#define FOR_BITS(var, set) for (uint32_t var##_s = (set); var##_s; var##_s &= var##_s - 1) { const int var = __builtin_ctz(var##_s);
-#define END_BITS }
-  const uint32_t full = (R >= 32) ? 0xffffffffu : ((1u << R) - 1u);
-  uint32_t* pslot = a.passive + (int64_t)i * a.capacity + d.sid;
-  uint32_t P = *pslot & full;
-  const double* mrow = a.M + (int64_t)i * a.ld + d.col;
-  for (int r = 0; r < R; ++r) { MV(r) = mrow[r]; XV(r) = 0.0; }
-  int steps = 0;
-  bool bad = false;
-  bool from_warm = (P != 0);             // the passive set still derives from the warm start
-  for (;;) {
-    while (P) {
-      // Cholesky of H restricted to the passive set (columns in ascending index order)
-      FOR_BITS(j, P)
-        const uint32_t below = P & ((1u << j) - 1u);
-        double dj = H[j * R + j];
-        FOR_BITS(k, below) dj -= LP(j, k) * LP(j, k); END_BITS
-        if (!(dj > 0.0) || !isfinite(dj)) { bad = true; break; }
-        dj = sqrt(dj);
-        LP(j, j) = dj;
-        const uint32_t above = (j >= 31) ? 0u : (P & ~((2u << j) - 1u));
-        FOR_BITS(r, above)
-          double v = H[r * R + j];
-          FOR_BITS(k, below) v -= LP(r, k) * LP(j, k); END_BITS
-          LP(r, j) = v / dj;
-        END_BITS
-      END_BITS
-      if (bad) {
-        if (!from_warm) break;
-        // a warm start whose sub-block cannot be factorised is dropped: restart from the empty set
-        bad = false;
-        from_warm = false;
-        P = 0;
-        for (int r = 0; r < R; ++r) XV(r) = 0.0;
-        break;
-      }
-      // solve (L L^T) s = m on the passive set
-      FOR_BITS(r, P)
-        double v = MV(r);
-        FOR_BITS(k, P & ((1u << r) - 1u)) v -= LP(r, k) * SV(k); END_BITS
-        SV(r) = v / LP(r, r);
-      END_BITS
-      for (int r = R - 1; r >= 0; --r) {
-        if (!(P & (1u << r))) continue;
-        double v = SV(r);
-        const uint32_t above = (r >= 31) ? 0u : (P & ~((2u << r) - 1u));
-        FOR_BITS(k, above) v -= LP(k, r) * SV(k); END_BITS
-        SV(r) = v / LP(r, r);
-      }
-      bool feasible = true;
-      FOR_BITS(r, P) if (!(SV(r) > 0.0)) feasible = false; END_BITS
-      if (feasible) {
-        for (int r = 0; r < R; ++r) XV(r) = (P & (1u << r)) ? SV(r) : 0.0;
-        break;
-      }
-      double beta = 1.0;
-      FOR_BITS(r, P)
-        if (!(SV(r) > 0.0)) {
-          const double xa = XV(r);
-          const double q = xa / (xa - SV(r));
-          if (q < beta) beta = q;
-        }
-      END_BITS
-      const uint32_t Pold = P;
-      FOR_BITS(r, Pold)
-        const double xn = XV(r) + beta * (SV(r) - XV(r));
-        if (!(xn > 0.0)) { XV(r) = 0.0; P &= ~(1u << r); }
-        else XV(r) = xn;
-      END_BITS
-      if (++steps > cap) break;
-    }
-    if (bad || steps > cap) break;
-    // gradient test: move the most violating variable into the passive set (x is zero outside P)
-    int best = -1;
-    double wbest = tau;
-    FOR_BITS(j, full & ~P)
-      double w = MV(j);
-      FOR_BITS(k, P) w -= H[j * R + k] * XV(k); END_BITS
-      if (w > wbest) { wbest = w; best = j; }
-    END_BITS
-    if (best < 0) break;
-    P |= (1u << best);
-    from_warm = false;
-    if (++steps > cap) break;
-  }
-  if (bad) {
-    atomicOr(a.fail + blockIdx.x, 1);
-    return;
-  }
-  *pslot = P;
-  double* xrow = a.X + (int64_t)i * a.ld + d.col;
-  for (int r = 0; r < R; ++r) xrow[r] = XV(r);
-#undef LP
-#undef XV
-#undef SV
-#undef MV
-#undef FOR_BITS
-#undef END_BITS
+  const int row0 = blockIdx.y * kNnlsRowsPerBlock;
+  if (row0 >= a.In) return;
+  const int row1 = (row0 + kNnlsRowsPerBlock < a.In) ? (row0 + kNnlsRowsPerBlock) : a.In;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (d.rank <= 8) nnls_rows<8>(a, d, blockIdx.x, row0, row1, lane, wave);
+  else if (d.rank <= 16) nnls_rows<16>(a, d, blockIdx.x, row0, row1, lane, wave);
+  else if (d.rank <= 24) nnls_rows<24>(a, d, blockIdx.x, row0, row1, lane, wave);
+  else nnls_rows<32>(a, d, blockIdx.x, row0, row1, lane, wave);
 }
 
 hipError_t launch_nnls(const NnlsArgs& a, hipStream_t stream) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nnls_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)(sizeof(double) * nnls_lds_doubles(kMaxRank)));
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  if (a.n_models < 1) return hipSuccess;
-  const int rmax = a.max_rank < 1 ? 1 : (a.max_rank > kMaxRank ? kMaxRank : a.max_rank);
-  size_t doubles = 0;
-  for (int r = 1; r <= rmax; ++r) doubles = nnls_lds_doubles(r) > doubles ? nnls_lds_doubles(r) : doubles;
-  hipLaunchKernelGGL(nnls_kernel, dim3(a.n_models, (a.In + 7) / 8), dim3(64), sizeof(double) * doubles, stream, a);
+  if (a.n_models < 1 || a.In < 1) return hipSuccess;
+  hipLaunchKernelGGL(nnls_kernel, dim3(a.n_models, (a.In + kNnlsRowsPerBlock - 1) / kNnlsRowsPerBlock), dim3(256), 0,
+                     stream, a);
   return hipGetLastError();
 }
 
