@@ -7,26 +7,38 @@
 
 namespace cals {
 
-// Adds the split-K partials in a fixed order (so results are bit-reproducible): the splits are cut into 4
-// consecutive groups, each group is summed in split order by its own quarter of the workgroup, and the four
-// group sums are added left to right.  64 elements per workgroup x 4 groups keeps many loads in flight even
-// when the output is small and the split count large.
+// Adds the split-K partials in a fixed order (so results are bit-reproducible): the splits are cut into 8
+// consecutive groups, each group is summed in split order by its own eighth of the workgroup, and the eight
+// group sums are added left to right.  32 elements per workgroup x 8 groups keeps many loads in flight and the
+// grid several times the CU count even when the output is small and the split count large.
+constexpr int kRedElems = 32, kRedGroups = 8;
+
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const double* __restrict__ P, double* __restrict__ M,
                                                             int64_t n_rows_ld, int ld, int ncols, int splits) {
-  __shared__ double part[4][64];
-  const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
-  const int64_t idx = (int64_t)blockIdx.x * 64 + e;
+  __shared__ double part[kRedGroups][kRedElems];
+  const int e = threadIdx.x % kRedElems, g = threadIdx.x / kRedElems;
+  const int64_t idx = (int64_t)blockIdx.x * kRedElems + e;
   const bool live = idx < n_rows_ld && (int)(idx % ld) < ncols;
-  const int per = (splits + 3) / 4;
+  const int per = (splits + kRedGroups - 1) / kRedGroups;
   const int z0 = g * per, z1 = (z0 + per < splits) ? (z0 + per) : splits;
   double s = 0.0;
   if (live) {
     const double* p = P + idx + (int64_t)z0 * n_rows_ld;
-    for (int z = z0; z < z1; ++z, p += n_rows_ld) s += *p;
+    int z = z0;
+    for (; z + 4 <= z1; z += 4, p += 4 * n_rows_ld) {      // four loads in flight; added in split order
+      const double v0 = p[0], v1 = p[n_rows_ld], v2 = p[2 * n_rows_ld], v3 = p[3 * n_rows_ld];
+      s = (((s + v0) + v1) + v2) + v3;
+    }
+    for (; z < z1; ++z, p += n_rows_ld) s += *p;
   }
   part[g][e] = s;
   __syncthreads();
-  if (g == 0 && live) M[idx] = ((part[0][e] + part[1][e]) + part[2][e]) + part[3][e];
+  if (g == 0 && live) {
+    double t = part[0][e];
+#pragma unroll
+    for (int q = 1; q < kRedGroups; ++q) t += part[q][e];
+    M[idx] = t;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -180,7 +192,7 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   if (pl.splits > 1) {
     const int64_t n = a.pstride;
     if (ev) (void)hipEventRecord(ev[2], stream);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + kRedElems - 1) / kRedElems)), dim3(256), 0, stream,
                        (const double*)workspace, p.M, n, p.ld, p.ncols, pl.splits);
     if (ev) (void)hipEventRecord(ev[3], stream);
     e = hipGetLastError();
