@@ -1,0 +1,91 @@
+"""Edge and degenerate cases of the CALS path on the GPU, each against the CPU oracle: empty queue, extreme ranks,
+a singleton dimension, total rank that fills R* exactly, a tall mode with the widest model (row-blocked update),
+and an all-zero tensor (every model fails numerically at once)."""
+import numpy as np
+import pytest
+
+import oracle as O
+from workloads import random_tensor, uniform_factors
+
+from test_gpu_cals import compare, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _model(dims, rank, seed, **kw):
+    m = dict(rank=rank, init=uniform_factors(dims, rank, seed), tol=-1.0, max_iters=5, flags=0, ls_alpha=1.0)
+    m.update(kw)
+    return m
+
+
+def _lowrank_tensor(dims, R, seed, noise=0.01):
+    A = uniform_factors(dims, R, seed)
+    T = np.einsum("ir,jr,kr->kji", *A)
+    return np.ascontiguousarray(T + noise * random_tensor(dims, seed + 1, signed=True) * np.sqrt((T ** 2).mean()))
+
+
+def test_empty_queue_is_a_no_op():
+    import paper_2010_04678_amd as P
+    ctx = P.Context(max_total_rank=16)
+    ctx.submit_tensor(random_tensor((4, 3, 2), 1))
+    assert ctx.iterate(3) == 0
+    ctx.run()
+    assert ctx.poll_retired() == []
+    st = ctx.stats()
+    assert st.rounds == 0 and st.n_active == 0 and st.models_queued == 0 and st.models_retired == 0
+    ctx.close()
+
+
+def test_rank_1_and_rank_32_side_by_side_fill_rstar_exactly():
+    # total rank 32 + 1 + 4 = 37 = R*: not a multiple of the 16-column tile; the widest model the library takes
+    dims = (40, 33, 21)
+    T = _lowrank_tensor(dims, 6, 11)
+    models = [_model(dims, 32, 1, max_iters=4), _model(dims, 1, 2), _model(dims, 4, 3, tol=1e-4, max_iters=40)]
+    ref = O.cals(T, models, 37, 0)
+    results, facs, st = run_gpu(T, models, 37)
+    compare(results, facs, ref, models)
+    assert max(ref["total_rank_log"]) == 37
+
+
+def test_head_of_line_blocking_when_next_model_does_not_fit():
+    # R* = 10: the rank-8 model blocks the queue although the rank-2 model behind it would fit (Alg. 3 fill rule)
+    dims = (12, 10, 8)
+    T = _lowrank_tensor(dims, 3, 21)
+    models = [_model(dims, 6, 1, max_iters=3), _model(dims, 8, 2, max_iters=2), _model(dims, 2, 3, max_iters=2)]
+    ref = O.cals(T, models, 10, 0)
+    results, facs, st = run_gpu(T, models, 10, rounds_per_call=1)
+    compare(results, facs, ref, models)
+    assert [r.model_id for r in results] == [0, 1, 2]
+    assert st.rounds == 3 + 2
+
+
+def test_singleton_dimension():
+    dims = (1, 9, 7)                                      # a matrix in disguise: mode-1 factors are 1 x R
+    T = random_tensor(dims, 3)
+    models = [_model(dims, 1, 1, max_iters=6), _model(dims, 1, 2, max_iters=6), _model(dims, 2, 5, max_iters=6)]
+    ref = O.cals(T, models, 8, 0)
+    results, facs, st = run_gpu(T, models, 8)
+    compare(results, facs, ref, models)
+
+
+def test_tall_mode_row_blocked_update_with_widest_model():
+    # 700 rows: the update of mode 1 runs as row blocks (two launches); 300 rows: two blocks with a ragged tail
+    dims = (700, 300, 3)
+    T = _lowrank_tensor(dims, 5, 31)
+    models = [_model(dims, 32, 1, max_iters=3), _model(dims, 3, 2, tol=1e-5, max_iters=30), _model(dims, 17, 4, max_iters=4)]
+    ref = O.cals(T, models, 64, 0)
+    results, facs, st = run_gpu(T, models, 64)
+    compare(results, facs, ref, models)
+
+
+def test_all_zero_tensor_fails_every_model_numerically():
+    import paper_2010_04678_amd as P
+    dims = (6, 5, 4)
+    T = np.zeros((4, 5, 6))
+    models = [_model(dims, 2, 1), _model(dims, 3, 2)]
+    ref = O.cals(T, models, 8, 0)
+    results, facs, st = run_gpu(T, models, 8)
+    assert [r.model_id for r in results] == list(ref["retire_order"]) == [0, 1]
+    for r in results:
+        assert r.status == P.NUMERICAL == ref["status"][r.model_id]
+        assert r.iters == ref["iters"][r.model_id] == 0

@@ -65,6 +65,8 @@ CASES = [
     ((3, 130, 2), [20, 20, 20, 3], False),      # tiny fast index for modes 2,3 (general wrap path), 4 column tiles
     ((129, 65, 33), list(range(1, 21)) + [11] * 20, True),   # 430 columns: the widest single column block
     ((40, 24, 20), [20] * 30, False),           # 600 columns: two column blocks
+    ((24, 20, 18), [20] * 21, True),            # 420 columns = 27 tiles: column blocks of 14 and 13 tiles, two launches
+    ((300, 7, 5), [5] * 3, False),              # odd leading dimension (one column per lane), four row tiles per wavefront
 ]
 
 
