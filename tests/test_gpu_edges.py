@@ -89,3 +89,17 @@ def test_all_zero_tensor_fails_every_model_numerically():
     for r in results:
         assert r.status == P.NUMERICAL == ref["status"][r.model_id]
         assert r.iters == ref["iters"][r.model_id] == 0
+
+
+def test_nonneg_ranks_at_the_kernel_width_boundaries():
+    # the non-negative update is compiled for widths 8, 16, 24 and 32: ranks on both sides of each, and 1 and 32
+    dims = (37, 29, 23)
+    T = np.ascontiguousarray(random_tensor(dims, 900, signed=True) * 0.25 +
+                             np.einsum("ir,jr,kr->kji", *uniform_factors(dims, 5, 901)))
+    models = [_model(dims, r, 910 + r, flags=O.FLAG_NONNEG, max_iters=6) for r in (1, 8, 9, 16, 17, 24, 25, 32)]
+    R = sum(m["rank"] for m in models)
+    ref = O.cals(T, models, R, 0)
+    results, facs, st = run_gpu(T, models, R, 0, rounds_per_call=2)
+    compare(results, facs, ref, models)
+    for r in results:
+        assert min(u.min() for u in facs[r.model_id][0]) >= 0.0
