@@ -11,6 +11,10 @@ resident in HBM before the timed region.  Prints ONE JSON line.
 `--workload cfgNjob` (N = 1..5) instead runs the configuration's whole job once as it is specified (queue, slots,
 tolerances, iteration caps, non-negativity, line search) and reports models completed per second; --steps and
 --warmup do not apply.  The default run appends the cfg5 job (the queue workload) under "jobs".
+
+`--workload sweepW1000` / `sweepW300` time the fused MTTKRP alone, all three modes, over fused widths 1..1024 on the
+cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1).  `--yardstick` prints the device's compute-unit
+count and clock and its practical peaks (back-to-back fp64 MFMA; streaming read of a 4 GiB buffer).
 """
 from __future__ import annotations
 
@@ -37,6 +41,7 @@ def parse():
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-jobs", action="store_true", help="skip the whole-job runs appended to the default line")
+    ap.add_argument("--yardstick", action="store_true", help="device properties and practical peaks (MFMA-only, read)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain elementwise copy kernel of known size (counter calibration for rocprofv3 --pmc)")
     return ap.parse_args()
@@ -75,6 +80,69 @@ def run_job(cid: int, T_dev=None) -> dict:
     return {"workload": cfg.name + "_job", "models": len(models), "seconds": dt, "models_per_s": len(models) / dt,
             "rounds": int(st.rounds), "ms_per_round": dt / max(1, st.rounds) * 1e3, "model_iterations": iters,
             "model_iterations_per_s": iters / dt, "mttkrp_gflops": st.mttkrp_flops / dt * 1e-9}
+
+
+SWEEP_WIDTHS = [1, 2, 4, 8, 16, 32, 64, 128, 256, 420, 512, 1024]
+
+
+def run_sweep(which: str, reps: int = 3) -> dict:
+    """Fused MTTKRP alone over fused widths (columns of random factors), all three modes, on an HBM-resident tensor."""
+    import torch
+    import paper_2010_04678_amd as P
+    from workloads import get_config, make_tensor
+    if which == "sweepW1000":
+        cfg = get_config(4)
+        T = torch.from_numpy(make_tensor(cfg, threads=min(16, os.cpu_count() or 8))).to("cuda:0")
+        dims = tuple(cfg.dims)
+    else:
+        dims = (300, 300, 300)
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(300)
+        T = torch.rand((300, 300, 300), dtype=torch.float64, device="cuda:0", generator=g)
+    I1, I2, I3 = dims
+    ctx = P.Context(max_total_rank=max(SWEEP_WIDTHS), flags=P.CTX_TIMING)
+    ctx.submit_tensor(T)
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(7)
+    rows = []
+    for R in SWEEP_WIDTHS:
+        ld = (R + 15) // 16 * 16
+        U = [torch.rand((d, ld), dtype=torch.float64, device="cuda:0", generator=g) for d in dims]
+        ms = []
+        for mode in (1, 2, 3):
+            M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda:0")
+            ctx.mttkrp(mode, U, M, total_rank=R)
+            torch.cuda.synchronize()
+            s0 = ctx.stats()
+            for _ in range(reps):
+                ctx.mttkrp(mode, U, M, total_rank=R)
+            s1 = ctx.stats()
+            ms.append(((s1.mttkrp_ms[mode - 1] - s0.mttkrp_ms[mode - 1]) / reps,
+                       (s1.reduce_ms[mode - 1] - s0.reduce_ms[mode - 1]) / reps))
+        flops = 2.0 * R * I1 * I2 * I3
+        nbytes = 8.0 * I1 * I2 * I3 + 8.0 * R * (I1 + I2 + I3)
+        rows.append({"width": R, "contraction_ms": [m[0] for m in ms], "reduce_ms": [m[1] for m in ms],
+                     "tflops": [flops / (m[0] * 1e-3) * 1e-12 for m in ms],
+                     "algorithmic_tb_per_s": [nbytes / (m[0] * 1e-3) * 1e-12 for m in ms]})
+    ctx.close()
+    return {"metric": "fused MTTKRP alone, widths 1..1024 (sweep W)", "workload": which, "dims": list(dims),
+            "reps": reps, "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "peak_hbm_gbs": PEAK_HBM_GBS, "rows": rows}
+
+
+def run_yardstick() -> dict:
+    import torch
+    import paper_2010_04678_amd as P
+    prop = torch.cuda.get_device_properties(0)
+    buf = torch.ones(1 << 29, dtype=torch.float64, device="cuda:0")      # 4 GiB
+    ctx = P.Context(max_total_rank=16)
+    out = {"yardstick": True, "device": prop.name, "gcn_arch": getattr(prop, "gcnArchName", ""),
+           "compute_units": int(ctx.yardstick(3)), "clock_mhz": ctx.yardstick(2),
+           "hbm_gib": prop.total_memory / 2 ** 30,
+           "mfma_f64_only_tflops": ctx.yardstick(0, reps=5),
+           "read_4gib_gb_per_s": ctx.yardstick(1, buf, reps=10),
+           "spec_mfma_f64_tflops": PEAK_FP64_MFMA_TFLOPS, "spec_hbm_gb_per_s": PEAK_HBM_GBS}
+    ctx.close()
+    return out
 
 
 def cpu_baseline(cfg, T: np.ndarray, models) -> dict:
@@ -124,6 +192,12 @@ def main() -> int:
     import paper_2010_04678_amd as P
     from workloads import make_models, make_tensor
 
+    if args.yardstick:
+        print(json.dumps(run_yardstick()))
+        return 0
+    if args.workload.startswith("sweepW"):
+        print(json.dumps(run_sweep(args.workload)))
+        return 0
     if args.workload.endswith("job"):
         job = run_job(int(args.workload[3]))
         print(json.dumps({"metric": "CP-ALS models completed/sec", "value": job["models_per_s"], "unit": "models/s",

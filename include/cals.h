@@ -131,6 +131,20 @@ int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const
 /* Counters and timings (see cals_stats).  Synchronises the stream when timing is on. */
 int cals_get_stats(cals_ctx* c, cals_stats* s);
 
+/* Practical peaks of the device the context runs on -- the yardsticks the MTTKRP rates are read against (the paper
+ * does the same with a plain GEMM, Sec. 6, "experimental setup").  kind CALS_YARDSTICK_MFMA: every SIMD issues
+ * back-to-back fp64 16x16x4 matrix instructions on register operands; *value = TFLOP/s.  kind CALS_YARDSTICK_READ:
+ * a streaming read-and-sum of `bytes` bytes (rounded down to 16; at least 1 MiB) of the caller's device buffer `buf`
+ * (pass the tensor); *value = GB/s.  Both run `reps` (1..100) timed launches after one warm-up on the context's stream
+ * and return the average.  Synchronises the stream.  Errors: INVALID (arguments), HIP.
+ * kinds CALS_YARDSTICK_CLOCK_MHZ and CALS_YARDSTICK_COMPUTE_UNITS return the device attributes the spec-sheet peaks
+ * are derived from (buf, bytes, reps ignored). */
+#define CALS_YARDSTICK_MFMA 0
+#define CALS_YARDSTICK_READ 1
+#define CALS_YARDSTICK_CLOCK_MHZ 2
+#define CALS_YARDSTICK_COMPUTE_UNITS 3
+int cals_yardstick(cals_ctx* c, int32_t kind, const void* buf, int64_t bytes, int32_t reps, double* value);
+
 /* Static description of an error code. */
 const char* cals_strerror(int code);
 

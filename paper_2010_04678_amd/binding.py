@@ -21,7 +21,7 @@ RUNNING, CONVERGED, MAX_ITERS, NUMERICAL = 0, 1, 2, 3
 MAX_RANK = 32
 
 EXPORTS = ["cals_create", "cals_destroy", "cals_submit_tensor", "cals_enqueue_model", "cals_iterate", "cals_run",
-           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_get_stats", "cals_strerror"]
+           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_get_stats", "cals_yardstick", "cals_strerror"]
 
 
 class CalsError(RuntimeError):
@@ -102,6 +102,7 @@ def load_library() -> C.CDLL:
     L.cals_get_factors.argtypes = [vp, C.c_int64, C.POINTER(vp), vp]
     L.cals_mttkrp.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(vp), vp]
     L.cals_get_stats.argtypes = [vp, C.POINTER(_Stats)]
+    L.cals_yardstick.argtypes = [vp, C.c_int32, vp, C.c_int64, C.c_int32, C.POINTER(C.c_double)]
     L.cals_strerror.argtypes = [C.c_int]
     L.cals_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -225,6 +226,15 @@ class Context:
             ptrs[n] = u.data_ptr()
         assert M_dev.is_cuda and M_dev.is_contiguous() and M_dev.shape[0] == self.dims[mode - 1]
         _check(self._L.cals_mttkrp(self._h, int(mode), tr, ld, ptrs, M_dev.data_ptr()), "cals_mttkrp")
+
+    # -- cals_yardstick
+    def yardstick(self, kind: int, buf=None, reps: int = 5) -> float:
+        """kind 0: fp64 MFMA issue rate (TFLOP/s); kind 1: streaming read of the CUDA tensor `buf` (GB/s)."""
+        v = C.c_double(0.0)
+        ptr = C.c_void_p(buf.data_ptr()) if buf is not None else None
+        nbytes = int(buf.numel() * buf.element_size()) if buf is not None else 0
+        _check(self._L.cals_yardstick(self._h, int(kind), ptr, C.c_int64(nbytes), int(reps), C.byref(v)), "cals_yardstick")
+        return v.value
 
     # -- cals_get_stats
     def stats(self) -> Stats:

@@ -14,7 +14,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcals_hip.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["mttkrp_wm1.hip", "mttkrp_wm2.hip", "mttkrp_wm4.hip", "mttkrp.hip", "update.hip", "linesearch.hip", "nnls.hip", "cals_api.hip"]
+SOURCES = ["mttkrp_wm1.hip", "mttkrp_wm2.hip", "mttkrp_wm4.hip", "mttkrp.hip", "update.hip", "linesearch.hip", "nnls.hip", "yardstick.hip", "cals_api.hip"]
+# yardstick.hip: its MFMA-only loop must keep the accumulators in place (VGPR form of the matrix instructions;
+# otherwise the compiler copies them between register files every iteration and the probe measures the copies)
+EXTRA_FLAGS = {"yardstick.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -39,7 +42,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
     def compile_one(src: str) -> str:
         obj = os.path.join(OBJDIR, src.replace(".hip", ".o"))
-        cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = ["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stderr))

@@ -93,6 +93,7 @@ struct cals_ctx {
   int32_t* h_map = nullptr;      // pinned
   uint32_t* passive[3] = {nullptr, nullptr, nullptr};  // NONNEG only
   double* d_scratch = nullptr;   // 1024 partial sums + result + flag
+  double* d_sink = nullptr;      // never-written target of the yardstick kernels
   double* d_zeros = nullptr;     // 8 zero doubles (what MTTKRP lanes past the end of a split load)
   double* d_lambda = nullptr;    // kMaxRank column norms per sid
   double* h_lambda = nullptr;    // pinned
@@ -580,6 +581,7 @@ int cals_destroy(cals_ctx* c) {
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart);
   (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
+  (void)hipFree(c->d_sink);
   (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
   (void)hipHostFree(c->h_lambda); (void)hipHostFree(c->h_stage); (void)hipHostFree(c->h_rmap);
@@ -750,6 +752,25 @@ int cals_get_stats(cals_ctx* c, cals_stats* s) {
     s->reduce_ms[n] = c->reduce_ms[n];
     s->mttkrp_launches[n] = c->mttkrp_launches[n];
   }
+  return CALS_OK;
+}
+
+int cals_yardstick(cals_ctx* c, int32_t kind, const void* buf, int64_t bytes, int32_t reps, double* value) {
+  if (!c || !value) return CALS_E_INVALID;
+  if (kind == CALS_YARDSTICK_CLOCK_MHZ || kind == CALS_YARDSTICK_COMPUTE_UNITS) {
+    int v = 0;
+    HIP_TRY(hipDeviceGetAttribute(&v, kind == CALS_YARDSTICK_CLOCK_MHZ ? hipDeviceAttributeClockRate
+                                                                         : hipDeviceAttributeMultiprocessorCount,
+                                  c->opt.device));
+    *value = (kind == CALS_YARDSTICK_CLOCK_MHZ) ? v * 1e-3 : (double)v;
+    return CALS_OK;
+  }
+  if (reps < 1 || reps > 100) return CALS_E_INVALID;
+  if (kind != CALS_YARDSTICK_MFMA && kind != CALS_YARDSTICK_READ) return CALS_E_INVALID;
+  if (kind == CALS_YARDSTICK_READ && (!buf || bytes < (1 << 20) || (reinterpret_cast<uintptr_t>(buf) & 15))) return CALS_E_INVALID;
+  CALS_TRY(set_device(c));
+  if (!c->d_sink && hipMalloc(&c->d_sink, sizeof(double) * 8) != hipSuccess) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  HIP_TRY(launch_yardstick(kind, buf, bytes, reps, c->num_cus, c->d_sink, c->stream, value));
   return CALS_OK;
 }
 

@@ -160,4 +160,8 @@ hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream);
 // U = Unew for accepted models; Uprev = the point kept (lambda folded into mode 3) for every line-search model.
 hipError_t launch_ls_apply(const LineSearchArgs& a, hipStream_t stream);
 
+// ---- practical-peak yardsticks (kind 0: fp64 MFMA issue rate in TFLOP/s, kind 1: streaming read in GB/s) ----
+hipError_t launch_yardstick(int kind, const void* buf, int64_t bytes, int reps, int num_cus, double* sink,
+                            hipStream_t stream, double* value);
+
 }  // namespace cals

@@ -10,7 +10,7 @@
 //   - lane i keeps row i of H in registers (loaded once per model and wavefront) and, per solve, row i of the
 //     working matrix; the passive sub-system is solved by symmetric Gaussian elimination without pivoting
 //     (pivot j is broadcast from lane j with v_readlane, every lane below updates its own row and right-hand
-//     side) and column-oriented back-substitution.  A pivot that is not positive and finite is the same verdict
+//     side) and column-oriented back-substitution.  A pivot that is not positive and finite is the same outcome
 //     as a failed Cholesky factorisation;
 //   - feasibility, the step length and the choice of the entering variable are wavefront votes and reductions;
 //     ties in the gradient test go to the lowest index, as in a scalar left-to-right scan;

@@ -117,7 +117,7 @@ __global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
     L[e] = h;
   }
   __syncthreads();
-  // NONNEG models: the rows were solved by the non-negative update already (a.X); only its verdict is read
+  // NONNEG models: the rows were solved by the non-negative update already (a.X); only its outcome is read
   const bool nonneg = (d.flags & 1u) != 0;
   if (nonneg) {
     if (tid == 0) {

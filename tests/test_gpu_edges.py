@@ -103,3 +103,18 @@ def test_nonneg_ranks_at_the_kernel_width_boundaries():
     compare(results, facs, ref, models)
     for r in results:
         assert min(u.min() for u in facs[r.model_id][0]) >= 0.0
+
+
+def test_yardsticks_return_plausible_rates():
+    import torch
+    import paper_2010_04678_amd as P
+    ctx = P.Context(max_total_rank=16)
+    assert ctx.yardstick(3) >= 1 and ctx.yardstick(2) > 100.0          # compute units, MHz
+    buf = torch.ones(1 << 24, dtype=torch.float64, device="cuda")      # 128 MiB
+    assert ctx.yardstick(1, buf, reps=2) > 100.0                       # GB/s
+    assert ctx.yardstick(0, reps=1) > 1.0                              # TFLOP/s
+    for bad in (dict(kind=7), dict(kind=1, buf=None), dict(kind=0, reps=0)):
+        with pytest.raises(P.CalsError) as e:
+            ctx.yardstick(bad.get("kind", 0), bad.get("buf"), bad.get("reps", 1))
+        assert e.value.code == -1
+    ctx.close()
