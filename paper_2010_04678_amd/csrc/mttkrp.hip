@@ -97,7 +97,18 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
   }
   const int wn_top = pl.part[0].wn;
   // row tiles per wavefront: as many as the accumulator budget (WM*WN <= 28 tiles) and the row count allow
-  int wm = (wn_top <= 7 && p.In > 128) ? 4 : (p.In > 64 ? 2 : 1);
+  // (more row tiles per wavefront = fewer instructions per MFMA, but rows are padded to 64*wm per workgroup:
+  // the choice minimises padded rows x a measured relative cost per MFMA of 1.0 / 1.08 / 1.25 for wm = 4 / 2 / 1)
+  int wm = 1;
+  {
+    double best = 1e300;
+    for (int cand : {4, 2, 1}) {
+      if (cand * wn_top > 28) continue;
+      const double padded = (double)((p.In + 64 * cand - 1) / (64 * cand)) * (64 * cand);
+      const double cost = padded * (cand == 4 ? 1.0 : (cand == 2 ? 1.08 : 1.25));
+      if (cost < best) { best = cost; wm = cand; }
+    }
+  }
   wm = env_int("CALS_MTTKRP_WM", wm);
   if (wm != 1 && wm != 2 && wm != 4) wm = 2;
   if (wm == 4 && wn_top > 7) wm = 2;
