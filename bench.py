@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-jobs", action="store_true", help="skip the whole-job runs appended to the default line")
+    ap.add_argument("--reuse", action="store_true",
+                    help="two-step sweeps (CALS_CTX_REUSE): modes 2 and 3 from the tensor contracted with the mode-1 factors")
     ap.add_argument("--yardstick", action="store_true", help="device properties and practical peaks (MFMA-only, read)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain elementwise copy kernel of known size (counter calibration for rocprofv3 --pmc)")
@@ -53,7 +55,7 @@ def workload(name: str):
     return get_config(cid)
 
 
-def run_job(cid: int, T_dev=None) -> dict:
+def run_job(cid: int, T_dev=None, reuse: bool = False) -> dict:
     """One whole job of configuration `cid`, as specified: every model enqueued with its own tolerance, iteration
     cap and flags; rounds until the queue and the slots are empty.  Tensor resident in HBM before the clock starts."""
     import torch
@@ -63,7 +65,7 @@ def run_job(cid: int, T_dev=None) -> dict:
     models = make_models(cfg)
     if T_dev is None:
         T_dev = torch.from_numpy(make_tensor(cfg, threads=min(16, os.cpu_count() or 8))).to("cuda:0")
-    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots)
+    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots, flags=P.CTX_REUSE if reuse else 0)
     ctx.submit_tensor(T_dev)
     for m in models:
         ctx.enqueue_model(m["init"], m["tol"], m["max_iters"], m["flags"], m["ls_alpha"])
@@ -77,7 +79,7 @@ def run_job(cid: int, T_dev=None) -> dict:
     assert len(res) == len(models)
     iters = sum(r.iters for r in res)
     ctx.close()
-    return {"workload": cfg.name + "_job", "models": len(models), "seconds": dt, "models_per_s": len(models) / dt,
+    return {"workload": cfg.name + "_job", "two_step_sweeps": bool(reuse), "models": len(models), "seconds": dt, "models_per_s": len(models) / dt,
             "rounds": int(st.rounds), "ms_per_round": dt / max(1, st.rounds) * 1e3, "model_iterations": iters,
             "model_iterations_per_s": iters / dt, "mttkrp_gflops": st.mttkrp_flops / dt * 1e-9}
 
@@ -199,7 +201,7 @@ def main() -> int:
         print(json.dumps(run_sweep(args.workload)))
         return 0
     if args.workload.endswith("job"):
-        job = run_job(int(args.workload[3]))
+        job = run_job(int(args.workload[3]), reuse=args.reuse)
         print(json.dumps({"metric": "CP-ALS models completed/sec", "value": job["models_per_s"], "unit": "models/s",
                           "n_gpus": 1, "steps": job["rounds"], "warmup": 0, "ms_per_step": job["ms_per_round"],
                           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
@@ -223,30 +225,37 @@ def main() -> int:
     dev = torch.device("cuda:0")
     Td = torch.from_numpy(T).to(dev)
     torch.cuda.synchronize()
-    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots, flags=P.CTX_TIMING)
-    ctx.submit_tensor(Td)
-    for m in active:
-        ctx.enqueue_model(m["init"], tol=-1.0, max_iters=W + K)   # plain ALS steps; nobody leaves before the last step
-    if W > 0:
-        ctx.iterate(W)
-    torch.cuda.synchronize()
-    s0 = ctx.stats()
-    t0 = time.perf_counter()
-    ctx.iterate(K)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    s1 = ctx.stats()
-    res = ctx.poll_retired()
-    assert len(res) == len(active) and all(r.iters == W + K for r in res), "every model must finish in the last step"
-    assert s1.rounds - s0.rounds == K
+    def timed_rounds(flags):
+        ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots, flags=flags)
+        ctx.submit_tensor(Td)
+        for m in active:
+            ctx.enqueue_model(m["init"], tol=-1.0, max_iters=W + K)   # plain ALS steps; nobody leaves before the last step
+        if W > 0:
+            ctx.iterate(W)
+        torch.cuda.synchronize()
+        s0 = ctx.stats()
+        t0 = time.perf_counter()
+        ctx.iterate(K)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        s1 = ctx.stats()
+        res = ctx.poll_retired()
+        assert len(res) == len(active) and all(r.iters == W + K for r in res), "every model must finish in the last step"
+        assert s1.rounds - s0.rounds == K
+        ctx.close()
+        return s0, s1, t0, t1
+
+    s0, s1, t0, t1 = timed_rounds(P.CTX_TIMING | (P.CTX_REUSE if args.reuse else 0))
 
     dt = t1 - t0
     flops = s1.mttkrp_flops - s0.mttkrp_flops               # algorithmic: 2 * width * prod(I) per MTTKRP
     assert abs(flops - 6.0 * tot * I1 * I2 * I3 * K) <= 1e-6 * flops
     launches = sum(s1.mttkrp_launches) - sum(s0.mttkrp_launches)
+    if args.reuse:
+        launches = 2 * K      # per round: the mode-1 MTTKRP and the first-step contraction, 2 * width * prod(I) flops each
     kern_ms = sum(s1.mttkrp_ms) - sum(s0.mttkrp_ms)
     per_mode_ms = [(s1.mttkrp_ms[n] - s0.mttkrp_ms[n]) / max(1, s1.mttkrp_launches[n] - s0.mttkrp_launches[n])
-                   for n in range(3)]
+                   for n in range(3)]   # with --reuse: [mode-1 MTTKRP, first-step contraction, 0]
     avg_ms = kern_ms / launches
     flops_per_launch = 2.0 * tot * I1 * I2 * I3
     bytes_per_launch = 8.0 * I1 * I2 * I3 + 8.0 * tot * (I1 + I2 + I3)   # tensor once + two factor panels + output
@@ -286,10 +295,17 @@ def main() -> int:
         "roofline": roof,
         "setup_s": {"generate": t_gen},
     }
-    ctx.close()
+    if args.reuse:
+        out["config"]["two_step_sweeps"] = True
+    if args.workload == "cfg4" and not args.no_jobs and not args.reuse:
+        # the same timed rounds with two-step sweeps (one pass over the tensor fewer per sweep); flops stay algorithmic
+        _, _, r0, r1 = timed_rounds(P.CTX_REUSE)
+        out["two_step_sweeps"] = {"ms_per_step": (r1 - r0) / K * 1e3, "sweeps_per_s": K / (r1 - r0),
+                                  "models_per_s": len(active) / (r1 - r0),
+                                  "effective_gflops": flops / (r1 - r0) * 1e-9}
     del Td
     if args.workload == "cfg4" and not args.no_jobs:
-        out["jobs"] = [run_job(5)]
+        out["jobs"] = [run_job(5, reuse=args.reuse)] + ([] if args.reuse else [run_job(5, reuse=True)])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, T, active)
     print(json.dumps(out))

@@ -47,6 +47,11 @@ extern "C" {
 
 /* context flags (cals_options.flags) */
 #define CALS_CTX_TIMING 1u /* bracket every MTTKRP launch with HIP events (read by cals_get_stats) */
+#define CALS_CTX_REUSE 2u  /* two-step sweeps: after the mode-1 update, contract the tensor once with the new
+                              mode-1 multi-matrix (Y[(i2,i3),c] = sum_i1 T * U1) and obtain the mode-2 and mode-3
+                              MTTKRPs from Y instead of from the tensor (partial-contraction reuse, the scheme of
+                              Phan et al. cited in Sec. 2; same results up to rounding order, one pass over the
+                              tensor fewer per sweep).  Costs a device buffer of I2*I3*ld doubles. */
 
 #define CALS_MAX_RANK 32 /* largest number of components of one model */
 
@@ -127,6 +132,15 @@ int cals_get_factors(cals_ctx* c, int64_t model_id, double* const U[3], double* 
  * columns [0, total_rank); ld >= total_rank.  Uses the context's tensor, stream and workspace. */
 int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const U_dev[3],
                 double* M_dev);
+
+/* The two MTTKRPs of a two-step sweep alone, for parity runs (needs CALS_CTX_REUSE): Y from U_dev[0], then
+ *   M2[i2,c] = sum_i3 Y[(i2,i3),c] * U3[i3,c]   and   M3[i3,c] = sum_i2 Y[(i2,i3),c] * U2[i2,c],   c < total_rank,
+ * which equal the mode-2 and mode-3 MTTKRPs of (U1, U2, U3).  All three U_dev[n] are device, row-major I_n x ld,
+ * ld <= the context's leading dimension (max_total_rank rounded up to 16); M2_dev (I2 x ld) and M3_dev (I3 x ld)
+ * are overwritten in columns [0, total_rank).  Errors: STATE (context without CALS_CTX_REUSE or no tensor),
+ * INVALID (arguments). */
+int cals_mttkrp_reuse(cals_ctx* c, int32_t total_rank, int64_t ld, const double* const U_dev[3], double* M2_dev,
+                      double* M3_dev);
 
 /* Counters and timings (see cals_stats).  Synchronises the stream when timing is on. */
 int cals_get_stats(cals_ctx* c, cals_stats* s);

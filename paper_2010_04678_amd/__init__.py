@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     load_library,
     FLAG_NONNEG,
     FLAG_LINESEARCH,
+    CTX_REUSE,
     CTX_TIMING,
     RUNNING,
     CONVERGED,

@@ -17,11 +17,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 FLAG_NONNEG, FLAG_LINESEARCH = 1, 2
 CTX_TIMING = 1
+CTX_REUSE = 2
 RUNNING, CONVERGED, MAX_ITERS, NUMERICAL = 0, 1, 2, 3
 MAX_RANK = 32
 
 EXPORTS = ["cals_create", "cals_destroy", "cals_submit_tensor", "cals_enqueue_model", "cals_iterate", "cals_run",
-           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_get_stats", "cals_yardstick", "cals_strerror"]
+           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_mttkrp_reuse", "cals_get_stats", "cals_yardstick",
+           "cals_strerror"]
 
 
 class CalsError(RuntimeError):
@@ -101,6 +103,7 @@ def load_library() -> C.CDLL:
     L.cals_poll_retired.argtypes = [vp, C.POINTER(_Result), C.c_int32, C.POINTER(C.c_int32)]
     L.cals_get_factors.argtypes = [vp, C.c_int64, C.POINTER(vp), vp]
     L.cals_mttkrp.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(vp), vp]
+    L.cals_mttkrp_reuse.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(vp), vp, vp]
     L.cals_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.cals_yardstick.argtypes = [vp, C.c_int32, vp, C.c_int64, C.c_int32, C.POINTER(C.c_double)]
     L.cals_strerror.argtypes = [C.c_int]
@@ -226,6 +229,20 @@ class Context:
             ptrs[n] = u.data_ptr()
         assert M_dev.is_cuda and M_dev.is_contiguous() and M_dev.shape[0] == self.dims[mode - 1]
         _check(self._L.cals_mttkrp(self._h, int(mode), tr, ld, ptrs, M_dev.data_ptr()), "cals_mttkrp")
+
+    # -- cals_mttkrp_reuse
+    def mttkrp_reuse(self, U_dev: Sequence, M2_dev, M3_dev, total_rank: Optional[int] = None) -> None:
+        """Mode-2 and mode-3 MTTKRPs through the contraction of the tensor with U_dev[0] (two-step sweep)."""
+        ld = int(M2_dev.shape[1])
+        tr = int(total_rank) if total_rank is not None else ld
+        ptrs = (C.c_void_p * 3)()
+        for n in range(3):
+            u = U_dev[n]
+            assert u.is_cuda and u.is_contiguous() and u.shape[1] == ld and u.shape[0] == self.dims[n]
+            ptrs[n] = u.data_ptr()
+        assert M2_dev.is_cuda and M2_dev.is_contiguous() and M2_dev.shape[0] == self.dims[1]
+        assert M3_dev.is_cuda and M3_dev.is_contiguous() and M3_dev.shape == (self.dims[2], ld)
+        _check(self._L.cals_mttkrp_reuse(self._h, tr, ld, ptrs, M2_dev.data_ptr(), M3_dev.data_ptr()), "cals_mttkrp_reuse")
 
     # -- cals_yardstick
     def yardstick(self, kind: int, buf=None, reps: int = 5) -> float:

@@ -93,6 +93,8 @@ struct cals_ctx {
   int32_t* h_map = nullptr;      // pinned
   uint32_t* passive[3] = {nullptr, nullptr, nullptr};  // NONNEG only
   double* d_scratch = nullptr;   // 1024 partial sums + result + flag
+  double* Y = nullptr;           // two-step sweeps: the tensor contracted with the mode-1 multi-matrix, (I2*I3) x ld
+  double* d_ones = nullptr;      // two-step sweeps: ld ones (the second "factor" of the first step)
   double* d_sink = nullptr;      // never-written target of the yardstick kernels
   double* d_zeros = nullptr;     // 8 zero doubles (what MTTKRP lanes past the end of a split load)
   double* d_lambda = nullptr;    // kMaxRank column norms per sid
@@ -221,6 +223,47 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int n
     c->timed.push_back(t);
     if (c->timed.size() > 2048) CALS_TRY(drain_timings(c));
   }
+  c->mttkrp_flops += 2.0 * ncols * (double)c->dims[0] * (double)c->dims[1] * (double)c->dims[2];
+  c->mttkrp_launches[mode] += 1;
+  return CALS_OK;
+}
+
+// First step of a two-step sweep: Y[(i2,i3), c] = sum_i1 T[i1,i2,i3] * U1[i1,c], i.e. the fused MTTKRP kernel on the
+// (I2*I3) x I1 unfolding with a single row of ones as the second factor.  Timed under mode index 1.
+int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld) {
+  const int64_t rows = c->dims[1] * c->dims[2];
+  if (rows >= (1LL << 31) || (int64_t)c->dims[0] * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
+  MttkrpProblem p{};
+  p.T = c->T; p.zeros = c->d_zeros; p.M = c->Y; p.ncols = ncols; p.ld = ld;
+  p.In = (int)rows; p.sm = c->dims[0];
+  p.Ia = (int)c->dims[0]; p.sa = 1; p.Ua = U1;
+  p.Ib = 1; p.sb = c->dims[0]; p.Ub = c->d_ones;
+  MttkrpPlan pl = mttkrp_plan(p, c->num_cus);
+  if (pl.chunk >= (1LL << 31)) return CALS_E_UNSUPPORTED;
+  CALS_TRY(ensure_workspace(c, pl.workspace_bytes));
+  hipEvent_t* ev = nullptr;
+  TimedLaunch t{};
+  if (c->opt.flags & CALS_CTX_TIMING) {
+    bool ok = true;
+    for (int i = 0; i < 4; ++i) { t.ev[i] = take_event(c); ok = ok && t.ev[i]; }
+    if (!ok) return CALS_E_HIP;
+    t.mode = 1;
+    t.reduced = pl.splits > 1;
+    ev = t.ev;
+  }
+  HIP_TRY(mttkrp_launch(p, pl, c->workspace, c->stream, ev));
+  if (ev) {
+    c->timed.push_back(t);
+    if (c->timed.size() > 2048) CALS_TRY(drain_timings(c));
+  }
+  return CALS_OK;
+}
+
+// Second step: the mode-2 (mode == 1) or mode-3 (mode == 2) MTTKRP from Y and the other remaining factor.
+int run_from_contraction(cals_ctx* c, int mode, const double* Uother, double* M, int ncols, int ld) {
+  const int I2 = (int)c->dims[1], I3 = (int)c->dims[2];
+  if (mode == 1) HIP_TRY(launch_ttv(c->Y, Uother, M, I2, I3, 1, I2, ld, ncols, c->stream));
+  else HIP_TRY(launch_ttv(c->Y, Uother, M, I3, I2, I2, 1, ld, ncols, c->stream));
   c->mttkrp_flops += 2.0 * ncols * (double)c->dims[0] * (double)c->dims[1] * (double)c->dims[2];
   c->mttkrp_launches[mode] += 1;
   return CALS_OK;
@@ -442,7 +485,13 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
   CALS_TRY(upload_desc(c));
   for (int mode = 0; mode < 3; ++mode) {
     const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
-    CALS_TRY(run_mttkrp(c, mode, Uc, c->M, c->total_rank, c->ld));
+    if (c->Y && mode > 0) {
+      // two-step sweep: modes 2 and 3 come from the tensor contracted with the mode-1 factors just updated
+      if (mode == 1) CALS_TRY(run_contract_mode1(c, c->U[0], c->total_rank, c->ld));
+      CALS_TRY(run_from_contraction(c, mode, mode == 1 ? c->U[2] : c->U[1], c->M, c->total_rank, c->ld));
+    } else {
+      CALS_TRY(run_mttkrp(c, mode, Uc, c->M, c->total_rank, c->ld));
+    }
     bool round_has_nn = false;
     int nn_max_rank = 1;
     for (const ActiveModel& m : c->active)
@@ -483,7 +532,12 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
     if (ls_takes_part) {
       HIP_TRY(launch_ls_extrapolate(la, c->stream));
       const double* Un[3] = {c->Unew[0], c->Unew[1], c->Unew[2]};
-      CALS_TRY(run_mttkrp(c, 2, Un, c->M, c->total_rank, c->ld));
+      if (c->Y) {
+        CALS_TRY(run_contract_mode1(c, c->Unew[0], c->total_rank, c->ld));
+        CALS_TRY(run_from_contraction(c, 2, c->Unew[1], c->M, c->total_rank, c->ld));
+      } else {
+        CALS_TRY(run_mttkrp(c, 2, Un, c->M, c->total_rank, c->ld));
+      }
     }
     HIP_TRY(launch_ls_decide(la, c->stream));
     HIP_TRY(launch_ls_apply(la, c->stream));
@@ -581,7 +635,7 @@ int cals_destroy(cals_ctx* c) {
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart);
   (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
-  (void)hipFree(c->d_sink);
+  (void)hipFree(c->d_sink); (void)hipFree(c->Y); (void)hipFree(c->d_ones);
   (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
   (void)hipHostFree(c->h_lambda); (void)hipHostFree(c->h_stage); (void)hipHostFree(c->h_rmap);
@@ -622,6 +676,11 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
   ok = ok && hipMalloc(&c->d_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
   ok = ok && hipMalloc(&c->d_map, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipMalloc(&c->d_scratch, sizeof(double) * 1032) == hipSuccess;
+  if ((c->opt.flags & CALS_CTX_REUSE) && dims[1] * dims[2] < (1LL << 31)) {
+    ok = ok && hipMalloc(&c->Y, sizeof(double) * (size_t)(dims[1] * dims[2]) * c->ld) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_ones, sizeof(double) * c->ld) == hipSuccess;
+    ok = ok && launch_fill(c->d_ones, c->ld, 1.0, c->stream) == hipSuccess;
+  }
   if (update_row_blocks((int)imax) > 1)
     ok = ok && hipMalloc(&c->d_updpart, sizeof(double) * update_part_doubles((int)imax) * c->capacity) == hipSuccess;
   ok = ok && hipMalloc(&c->d_zeros, sizeof(double) * 8) == hipSuccess;
@@ -734,6 +793,20 @@ int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const
     if (n != mode - 1 && !U_dev[n]) return CALS_E_INVALID;
   CALS_TRY(set_device(c));
   return run_mttkrp(c, mode - 1, U_dev, M_dev, total_rank, (int)ld);
+}
+
+int cals_mttkrp_reuse(cals_ctx* c, int32_t total_rank, int64_t ld, const double* const U_dev[3], double* M2_dev,
+                      double* M3_dev) {
+  if (!c || !U_dev || !M2_dev || !M3_dev) return CALS_E_INVALID;
+  if (!c->T || !c->Y) return CALS_E_STATE;
+  if (total_rank < 1 || ld < total_rank || ld > c->ld) return CALS_E_INVALID;
+  for (int n = 0; n < 3; ++n)
+    if (!U_dev[n]) return CALS_E_INVALID;
+  CALS_TRY(set_device(c));
+  CALS_TRY(run_contract_mode1(c, U_dev[0], total_rank, (int)ld));
+  CALS_TRY(run_from_contraction(c, 1, U_dev[2], M2_dev, total_rank, (int)ld));
+  CALS_TRY(run_from_contraction(c, 2, U_dev[1], M3_dev, total_rank, (int)ld));
+  return CALS_OK;
 }
 
 int cals_get_stats(cals_ctx* c, cals_stats* s) {

@@ -160,6 +160,12 @@ hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream);
 // U = Unew for accepted models; Uprev = the point kept (lambda folded into mode 3) for every line-search model.
 hipError_t launch_ls_apply(const LineSearchArgs& a, hipStream_t stream);
 
+// ---- two-step sweep: contraction of the intermediate Y with one factor ---------------------------------------
+// M[o, c] = sum_{s < ns} Y[(o*so + s*ss) * ld + c] * U[s * ld + c],  o < no, c < ncols (fixed summation order).
+hipError_t launch_ttv(const double* Y, const double* U, double* M, int no, int ns, int64_t so, int64_t ss, int ld,
+                      int ncols, hipStream_t stream);
+hipError_t launch_fill(double* p, int64_t n, double v, hipStream_t stream);
+
 // ---- practical-peak yardsticks (kind 0: fp64 MFMA issue rate in TFLOP/s, kind 1: streaming read in GB/s) ----
 hipError_t launch_yardstick(int kind, const void* buf, int64_t bytes, int reps, int num_cus, double* sink,
                             hipStream_t stream, double* value);

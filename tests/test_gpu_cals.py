@@ -14,10 +14,10 @@ FIT_TOL = 1e-8
 FACTOR_TOL = 1e-6
 
 
-def run_gpu(T, models, max_total_rank, max_slots=0, rounds_per_call=7):
+def run_gpu(T, models, max_total_rank, max_slots=0, rounds_per_call=7, ctx_flags=0):
     import torch
     import paper_2010_04678_amd as P
-    ctx = P.Context(max_total_rank=max_total_rank, max_slots=max_slots)
+    ctx = P.Context(max_total_rank=max_total_rank, max_slots=max_slots, flags=ctx_flags)
     ctx.submit_tensor(torch.from_numpy(T).cuda())
     ids = [ctx.enqueue_model(m["init"], m["tol"], m["max_iters"], m.get("flags", 0), m.get("ls_alpha", 1.0))
            for m in models]
@@ -216,4 +216,37 @@ def test_config3_recipe_reduced():
     R = sum(m["rank"] for m in models)
     ref = O.cals(T, models, R, 0)
     results, facs, st = run_gpu(T, models, R, 0, rounds_per_call=6)
+    compare(results, facs, ref, models)
+
+
+def test_two_step_sweeps_match_oracle():
+    # CALS_CTX_REUSE: modes 2 and 3 from the tensor contracted with the updated mode-1 factors.  Same bars as the
+    # plain path, on the queue workload (tolerances, slots, refill), with line search and with non-negativity.
+    import paper_2010_04678_amd as P
+    cfg = get_config(1)
+    T = make_tensor(cfg)
+    models = make_models(cfg)
+    ref = O.cals(T, models, cfg.max_total_rank, cfg.max_slots)
+    results, facs, st = run_gpu(T, models, cfg.max_total_rank, cfg.max_slots, ctx_flags=P.CTX_REUSE)
+    compare(results, facs, ref, models)
+
+    dims = (36, 30, 24)
+    T = _collinear_tensor(dims, 4, 2100)
+    models = []
+    for k, r in enumerate([2, 3, 4, 5, 6, 4, 3]):
+        models.append(dict(rank=r, init=uniform_factors(dims, r, 2110 + k), tol=[1e-6, 1e-5][k % 2], max_iters=60,
+                           flags=O.FLAG_LINESEARCH if k % 3 != 2 else 0, ls_alpha=1.2))
+    ref = O.cals(T, models, 12, 3)
+    results, facs, st = run_gpu(T, models, 12, 3, rounds_per_call=3, ctx_flags=P.CTX_REUSE)
+    compare(results, facs, ref, models)
+    assert sum(r.ls_accepted for r in results) > 0
+
+    dims = (70, 33, 18)
+    T = np.ascontiguousarray(random_tensor(dims, 1400, signed=True) * 0.3 +
+                             np.einsum("ir,jr,kr->kji", *uniform_factors(dims, 4, 1401)))
+    models = [dict(rank=r, init=uniform_factors(dims, r, 1410 + k), tol=-1.0, max_iters=10,
+                   flags=O.FLAG_NONNEG if k % 2 == 0 else 0, ls_alpha=1.0) for k, r in enumerate([3, 4, 9, 17, 2])]
+    R = sum(m["rank"] for m in models)
+    ref = O.cals(T, models, R, 0)
+    results, facs, st = run_gpu(T, models, R, 0, rounds_per_call=4, ctx_flags=P.CTX_REUSE)
     compare(results, facs, ref, models)

@@ -113,3 +113,47 @@ def test_mttkrp_is_bit_reproducible_and_fusion_is_exact():
             scale = _abs_scale(T, [u[:, c0:c0 + r] for u in U], mode + 1)
             assert np.all(np.abs(solo[mode] - a[mode][:, c0:c0 + r]) <= 1e-13 * scale)
         c0 += r
+
+
+def _gpu_mttkrp_reuse(T, U, pad_to=None):
+    """Mode-2 and mode-3 MTTKRPs through the two-step path (contraction with U1 first)."""
+    import paper_2010_04678_amd as P
+    torch = _torch()
+    dims = (T.shape[2], T.shape[1], T.shape[0])
+    R = U[0].shape[1]
+    ld = pad_to if pad_to is not None else R
+    ctx = P.Context(max_total_rank=max(ld, 1), flags=P.CTX_REUSE)
+    ctx.submit_tensor(torch.from_numpy(T).cuda())
+    Ud = []
+    for n in range(3):
+        buf = torch.full((dims[n], ld), float("nan"), dtype=torch.float64, device="cuda")
+        buf[:, :R] = torch.from_numpy(np.ascontiguousarray(U[n])).cuda()
+        Ud.append(buf)
+    M2 = torch.full((dims[1], ld), 777.0, dtype=torch.float64, device="cuda")
+    M3 = torch.full((dims[2], ld), 777.0, dtype=torch.float64, device="cuda")
+    ctx.mttkrp_reuse(Ud, M2, M3, total_rank=R)
+    torch.cuda.synchronize()
+    out = []
+    for M in (M2, M3):
+        Mh = M.cpu().numpy()
+        assert np.all(Mh[:, R:] == 777.0), "columns beyond total_rank must not be touched"
+        out.append(Mh[:, :R])
+    ctx.close()
+    return out
+
+
+@pytest.mark.parametrize("dims,ranks,signed", CASES)
+def test_two_step_mttkrp_matches_oracle_elementwise(dims, ranks, signed):
+    # the mode-2 and mode-3 results of the two-step path (tensor contracted with the mode-1 factors first) are the
+    # plain MTTKRPs: same bar, against the same definition
+    T = random_tensor(dims, 7 + dims[0], signed=signed)
+    U = _fused(dims, ranks, 100 + dims[1], signed=signed)
+    R = sum(ranks)
+    for pad in (R + 5, (R + 15) // 16 * 16):       # odd and 16-aligned leading dimension (one / two columns per lane)
+        got = _gpu_mttkrp_reuse(T, U, pad_to=pad)
+        for k, mode in enumerate((2, 3)):
+            want = O.mttkrp(T, U, mode)
+            scale = _abs_scale(T, U, mode)
+            err = np.abs(got[k] - want)
+            assert np.all(np.isfinite(got[k]))
+            assert np.all(err <= TOL * scale + 1e-300), (mode, pad, float((err / (scale + 1e-300)).max()))
