@@ -14,10 +14,10 @@ pytestmark = pytest.mark.gpu
 FIT_TOL, FACTOR_TOL, MTTKRP_TOL = 1e-8, 1e-6, 1e-12
 
 
-def gpu_run(T, models, cfg, keep=None):
+def gpu_run(T, models, cfg, keep=None, ctx_flags=0):
     import torch
     import paper_2010_04678_amd as P
-    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots)
+    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots, flags=ctx_flags)
     Td = torch.from_numpy(T).cuda()
     ctx.submit_tensor(Td)
     for m in models:
@@ -67,14 +67,15 @@ def replay_queue(ranks, iters, rstar, slots):
     return order
 
 
-def sampled_mttkrp_check(T, cfg, models, n_samples, seed):
+def sampled_mttkrp_check(T, cfg, models, n_samples, seed, two_step=False):
+    """two_step: modes 2 and 3 through the contraction with the mode-1 factors (cals_mttkrp_reuse)."""
     import torch
     import paper_2010_04678_amd as P
     dims = cfg.dims
     U = [np.hstack([m["init"][n] for m in models]) for n in range(3)]
     R = U[0].shape[1]
     ld = (R + 15) // 16 * 16
-    ctx = P.Context(max_total_rank=cfg.max_total_rank)
+    ctx = P.Context(max_total_rank=cfg.max_total_rank, flags=P.CTX_REUSE if two_step else 0)
     Td = torch.from_numpy(T).cuda()
     ctx.submit_tensor(Td)
     Ud = []
@@ -83,9 +84,15 @@ def sampled_mttkrp_check(T, cfg, models, n_samples, seed):
         buf[:, :R] = torch.from_numpy(np.ascontiguousarray(U[n])).cuda()
         Ud.append(buf)
     rng = np.random.default_rng(seed)
-    for mode in (1, 2, 3):
-        M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda")
-        ctx.mttkrp(mode, Ud, M, total_rank=R)
+    if two_step:
+        M23 = [torch.zeros((dims[n], ld), dtype=torch.float64, device="cuda") for n in (1, 2)]
+        ctx.mttkrp_reuse(Ud, M23[0], M23[1], total_rank=R)
+    for mode in ((2, 3) if two_step else (1, 2, 3)):
+        if two_step:
+            M = M23[mode - 2]
+        else:
+            M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda")
+            ctx.mttkrp(mode, Ud, M, total_rank=R)
         Mh = M.cpu().numpy()
         rows = np.concatenate([[0, dims[mode - 1] - 1], rng.integers(0, dims[mode - 1], n_samples)])
         cols = np.concatenate([[0, R - 1], rng.integers(0, R, n_samples)])
@@ -123,6 +130,12 @@ def test_config4_full_mttkrp_and_two_iterations():
     assert all(0.0 < r.fit < 1.0 for r in res)
     ref = O.cals(T, [models[k] for k in sample], cfg.max_total_rank, 0)
     check_models(res, facs, models, ref, sample)
+    # the same with two-step sweeps (3.5 GB intermediate at this size)
+    import paper_2010_04678_amd as P
+    sampled_mttkrp_check(T, cfg, models, 30, 43, two_step=True)
+    res, facs, st = gpu_run(T, models, cfg, keep=sample, ctx_flags=P.CTX_REUSE)
+    assert [r.model_id for r in res] == list(range(40)) and all(r.iters == 2 for r in res)
+    check_models(res, facs, models, ref, sample)
 
 
 def test_config3_full():
@@ -154,3 +167,8 @@ def test_config5_full():
     assert all(r.status in (O.CONVERGED, O.MAX_ITERS) for r in res)
     ref = O.cals(T, [models[k] for k in sample], cfg.max_total_rank, cfg.max_slots)
     check_models(res, facs, models, ref, sample)
+    # the same job with two-step sweeps (line-search MTTKRP included): same iteration counts, order and factors
+    import paper_2010_04678_amd as P
+    res2, facs2, st2 = gpu_run(T, models, cfg, keep=sample, ctx_flags=P.CTX_REUSE)
+    assert [(r.model_id, r.iters, r.status) for r in res2] == [(r.model_id, r.iters, r.status) for r in res]
+    check_models(res2, facs2, models, ref, sample)

@@ -75,6 +75,20 @@ def test_mttkrp_is_unfolding_times_explicit_krp():
         assert np.abs(got - want[mode - 1]).max() <= 1e-13 * scale * 50, mode
 
 
+def test_mttkrp_of_modes_2_and_3_factor_through_the_mode_1_contraction():
+    # the identity behind two-step sweeps (Sec. 2, partial-contraction reuse): with Y[i2,i3,c] = sum_i1 T U1,
+    # M2[i2,c] = sum_i3 Y U3 and M3[i3,c] = sum_i2 Y U2 are the plain MTTKRPs of the oracle
+    dims, R = (9, 7, 5), 4
+    T = random_tensor(dims, 31, signed=True)
+    U = signed_factors(dims, R, 32)
+    Y = np.einsum("ijk,ic->jkc", tview(T), U[0])
+    M2 = np.einsum("jkc,kc->jc", Y, U[2])
+    M3 = np.einsum("jkc,jc->kc", Y, U[1])
+    for mode, want in ((2, M2), (3, M3)):
+        got = O.mttkrp(T, U, mode)
+        assert np.abs(got - want).max() <= 1e-13 * np.abs(want).max() * 50, mode
+
+
 def test_fused_mttkrp_column_blocks_equal_solo_results_bitwise():
     # Eq. (1)/(2): the fused MTTKRP of concatenated factors is the concatenation of the solo MTTKRPs.
     dims, ranks = (9, 8, 7), [1, 3, 2, 5, 11]
