@@ -106,6 +106,7 @@ struct cals_ctx {
   int32_t* d_colmodel = nullptr; // line search: slot position owning each column
   int32_t* h_colmodel = nullptr; // pinned
   int32_t* d_accept = nullptr;   // line search: per slot position, extrapolated point taken this round
+  double* d_lspart = nullptr;    // line search: per (slot position, mode, row block) partial sums
   double* d_updpart = nullptr;   // update of tall modes: per (slot position, row block) partial sums
   int32_t* d_nnfail = nullptr;   // non-negativity: per slot position, failure flag of the current mode update
   std::deque<PendingModel> queue;
@@ -297,6 +298,10 @@ int ensure_ls_buffers(cals_ctx* c) {
                  hipMemsetAsync(c->Unew[n], 0, bytes, c->stream) == hipSuccess;
   }
   ok = ok && hipMalloc(&c->d_accept, sizeof(int32_t) * c->capacity) == hipSuccess;
+  {
+    const int64_t imax = std::max(c->dims[0], std::max(c->dims[1], c->dims[2]));
+    ok = ok && hipMalloc(&c->d_lspart, sizeof(double) * 3 * update_part_doubles((int)imax) * c->capacity) == hipSuccess;
+  }
   ok = ok && hipHostMalloc(&c->h_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipMalloc(&c->d_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
   if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
@@ -529,6 +534,8 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
       la.U[k] = c->U[k]; la.Uprev[k] = c->Uprev[k]; la.Unew[k] = c->Unew[k]; la.In[k] = (int)c->dims[k];
     }
     la.M3 = c->M; la.ld = c->ld; la.n_models = n; la.ncols = c->total_rank; la.normT2 = c->normT2;
+    la.part = c->d_lspart;
+    la.nblk = update_row_blocks((int)std::max(c->dims[0], std::max(c->dims[1], c->dims[2])));
     if (ls_takes_part) {
       HIP_TRY(launch_ls_extrapolate(la, c->stream));
       const double* Un[3] = {c->Unew[0], c->Unew[1], c->Unew[2]};
@@ -633,7 +640,7 @@ int cals_destroy(cals_ctx* c) {
     (void)hipFree(c->passive[n]);
   }
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
-  (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart);
+  (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart); (void)hipFree(c->d_lspart);
   (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
   (void)hipFree(c->d_sink); (void)hipFree(c->Y); (void)hipFree(c->d_ones);
   (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);

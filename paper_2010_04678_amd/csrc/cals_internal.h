@@ -148,6 +148,9 @@ struct LineSearchArgs {
   double* Uprev[3];        // point after the previous iteration
   double* Unew[3];         // extrapolated point
   const double* M3;        // mode-3 MTTKRP at the extrapolated point, row-major I3 x ld
+  double* part;            // per (slot position, mode, row block): partial Gramian and inner product of the
+                           // extrapolated point, kUpdatePartStride doubles each
+  int nblk;                // row blocks (update_row_blocks of the longest mode)
   int In[3];
   int ld, n_models, ncols;
   double normT2;

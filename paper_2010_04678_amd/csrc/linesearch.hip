@@ -44,24 +44,28 @@ __global__ void __launch_bounds__(256) ls_extrapolate_kernel(LineSearchArgs a) {
   a.Unew[mode][e] = v;
 }
 
-// grid (n_models, 3): Gramian of the extrapolated mode-`y` factor block; for mode 3 also sum(A3_new * M3).
+// grid (n_models, 3, row blocks): partial Gramian of the extrapolated mode-`y` factor block over the block's rows;
+// for mode 3 also the partial sum(A3_new * M3).  Partials go to a.part; ls_decide_kernel adds them in block order.
 __global__ void __launch_bounds__(256) ls_gram_kernel(LineSearchArgs a) {
   extern __shared__ double lds[];
   const ModelDesc d = a.desc[blockIdx.x];
   const ModelOut o = a.out[d.sid];
   if (!ls_takes_part(d, o)) return;
   const int mode = blockIdx.y, tid = threadIdx.x, R = d.rank, In = a.In[mode];
-  ModelState* st = a.state + d.sid;
+  const int nblk = gridDim.z;
+  const int rpb = ((In + nblk - 1) / nblk + kRows - 1) / kRows * kRows;
+  const int r0 = blockIdx.z * rpb;
+  const int r1 = (r0 + rpb < In) ? (r0 + rpb) : In;
   double* xs = lds;                 // R x kXs staged rows
   double* red = xs + kMaxRank * kXs;
   const double* Ub = a.Unew[mode] + d.col;
   const int npairs = R * (R + 1) / 2;
   double gacc[3] = {0.0, 0.0, 0.0};
   double inner = 0.0;
-  for (int base = 0; base < In; base += kRows) {
+  for (int base = r0; base < r1; base += kRows) {
     const int i = base + tid;
-    const int nrows = (In - base < kRows) ? (In - base) : kRows;
-    if (i < In) {
+    const int nrows = (r1 - base < kRows) ? (r1 - base) : kRows;
+    if (i < r1) {
       double part = 0.0;
       for (int r = 0; r < R; ++r) {
         const double x = Ub[(int64_t)i * a.ld + r];
@@ -86,21 +90,15 @@ __global__ void __launch_bounds__(256) ls_gram_kernel(LineSearchArgs a) {
     }
     __syncthreads();
   }
+  double* part = a.part + (((size_t)blockIdx.x * 3 + mode) * nblk + blockIdx.z) * kUpdatePartStride;
 #pragma unroll
   for (int q = 0; q < 3; ++q) {
     const int p = tid + 256 * q;
-    if (p < npairs) {
-      int r = (int)((sqrt(8.0 * p + 1.0) - 1.0) * 0.5);
-      while (r * (r + 1) / 2 > p) --r;
-      while ((r + 1) * (r + 2) / 2 <= p) ++r;
-      const int s = p - r * (r + 1) / 2;
-      st->Gls[mode][r * R + s] = gacc[q];
-      st->Gls[mode][s * R + r] = gacc[q];
-    }
+    if (p < npairs) part[p] = gacc[q];
   }
   if (mode == 2) {
     const double tot = ls_block_sum(inner, red);
-    if (tid == 0) st->inner_ls = tot;
+    if (tid == 0) part[528] = tot;
   }
 }
 
@@ -116,6 +114,28 @@ __global__ void __launch_bounds__(256) ls_decide_kernel(LineSearchArgs a) {
   }
   ModelState* st = a.state + d.sid;
   const int R = d.rank;
+  // Gramians of the extrapolated point: the row blocks' partials, added in block order
+  const int npairs = R * (R + 1) / 2;
+  for (int mode = 0; mode < 3; ++mode) {
+    const double* pm = a.part + ((size_t)blockIdx.x * 3 + mode) * a.nblk * kUpdatePartStride;
+    for (int p = tid; p < npairs; p += 256) {
+      double g = 0.0;
+      for (int b = 0; b < a.nblk; ++b) g += pm[(size_t)b * kUpdatePartStride + p];
+      int r = (int)((sqrt(8.0 * p + 1.0) - 1.0) * 0.5);
+      while (r * (r + 1) / 2 > p) --r;
+      while ((r + 1) * (r + 2) / 2 <= p) ++r;
+      const int c = p - r * (r + 1) / 2;
+      st->Gls[mode][r * R + c] = g;
+      st->Gls[mode][c * R + r] = g;
+    }
+  }
+  if (tid == 0) {
+    const double* pm = a.part + ((size_t)blockIdx.x * 3 + 2) * a.nblk * kUpdatePartStride;
+    double in = 0.0;
+    for (int b = 0; b < a.nblk; ++b) in += pm[(size_t)b * kUpdatePartStride + 528];
+    st->inner_ls = in;
+  }
+  __syncthreads();
   double part = 0.0;
   for (int e = tid; e < R * R; e += 256) part += (st->Gls[0][e] * st->Gls[1][e]) * st->Gls[2][e];
   const double normsq = ls_block_sum(part, red);
@@ -186,7 +206,8 @@ hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream) {
     attr_done = true;
   }
   if (a.n_models < 1) return hipSuccess;
-  hipLaunchKernelGGL(ls_gram_kernel, dim3(a.n_models, 3), dim3(256), lds, stream, a);
+  if (!a.part || a.nblk < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(ls_gram_kernel, dim3(a.n_models, 3, a.nblk), dim3(256), lds, stream, a);
   hipLaunchKernelGGL(ls_decide_kernel, dim3(a.n_models), dim3(256), 0, stream, a);
   return hipGetLastError();
 }

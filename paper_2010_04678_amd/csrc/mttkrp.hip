@@ -122,14 +122,18 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
   const int lds_fit = (int)(160 * 1024 / ((size_t)2 * pl.ka * 16 * wn_top * sizeof(double)));
   if (per_cu > lds_fit) per_cu = lds_fit;
   per_cu = env_int("CALS_MTTKRP_PERCU", per_cu);
-  // Split of the contraction range.  Workgroups run in waves of `slots` (one per resident position); the time
-  // of a launch is about waves x (stages per workgroup + fixed cost), a stage costing in proportion to the
-  // block width.  Splits are whole multiples of 8 when there are 8 or more, so that the XCD-pinned block order
-  // gives every XCD the same number of splits; with fewer splits the blocks of a split are spread over the
-  // XCDs instead.
+  // Split of the contraction range, by a cost model in microseconds.  Workgroups run in waves of `slots` (one per
+  // resident position); a launch takes about waves x (stages per workgroup + a fixed cost of 6 stages), a stage
+  // of a workgroup with t accumulator tiles per wavefront taking t x 4 MFMAs x 64 cycles at about 80 % MFMA
+  // utilisation.  More than one split adds the partials' way through memory: written once, read once by the
+  // reduction, plus the result (about 3 TB/s for these strided panels).  Splits are whole multiples of 8 when
+  // there are 8 or more, so that the XCD-pinned block order gives every XCD the same number of splits; with
+  // fewer splits the blocks of a split are spread over the XCDs instead.
   const int64_t slots = (int64_t)num_cus * per_cu;
   const int64_t max_splits = std::max<int64_t>(1, K / (4 * pl.ka));   // at least two stage pairs per split
   const int force_splits = env_int("CALS_MTTKRP_SPLITS", 0);
+  const double us_per_tile_stage = 4.0 * 64.0 / 2400.0 / 0.8;          // one accumulator tile, one stage (KA = 16)
+  const double panel_us = (double)p.In * p.ncols * 8.0 / 3.0e6;        // one In x ncols panel through memory
   int64_t splits = 1;
   double best_cost = 1e300;
   for (int64_t cand = 1; cand <= std::min<int64_t>(max_splits, 4096); cand = (cand < 8) ? cand + 1 : cand + 8) {
@@ -137,9 +141,9 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
     double cost = 0.0;
     for (int q = 0; q < pl.nparts; ++q) {
       const int64_t waves = ((int64_t)pl.mtiles * pl.part[q].ny * cand + slots - 1) / slots;
-      cost += (double)waves * (2.0 * pairs * pl.part[q].wn / wn_top + 6.0);
+      cost += (double)waves * (2.0 * pairs + 6.0) * us_per_tile_stage * wm * pl.part[q].wn;
     }
-    cost *= 1.0 + 0.002 * cand;
+    if (cand > 1) cost += (2.0 * cand + 1.0) * panel_us;
     if (cost < best_cost) { best_cost = cost; splits = cand; }
   }
   if (force_splits > 0) splits = force_splits;
