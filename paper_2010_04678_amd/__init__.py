@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     Context,
     Result,
     Stats,
+    cp_cals,
+    suggest_max_total_rank,
     library_path,
     load_library,
     FLAG_NONNEG,

@@ -259,3 +259,39 @@ class Context:
         _check(self._L.cals_get_stats(self._h, C.byref(s)), "cals_get_stats")
         return Stats(s.rounds, s.models_retired, s.models_queued, s.n_active, s.total_rank, s.tensor_norm_sq,
                      s.mttkrp_flops, list(s.mttkrp_ms), list(s.reduce_ms), list(s.mttkrp_launches))
+
+
+# ---- convenience driver in the spirit of the paper's cp_cals interface (Sec. 5, "interfaces") -----------------
+def suggest_max_total_rank(ranks: Sequence[int], plateau: int = 256) -> int:
+    """R* for a queue of models (Sec. 4, choice of the buffer size): the fused MTTKRP reaches its efficiency plateau
+    at a fused width of about `plateau` columns (measured: 128-256 on MI355X), and wider buffers only add memory and
+    iterations spent on models that could have been retired; so R* is the plateau width, but never more than all
+    models need together and never less than the widest model."""
+    ranks = [int(r) for r in ranks]
+    if not ranks or min(ranks) < 1:
+        raise ValueError("ranks must be positive")
+    return max(max(ranks), min(sum(ranks), int(plateau)))
+
+
+def cp_cals(T, inits: Sequence[Sequence[np.ndarray]], tol: float = 1e-4, max_iters: int = 50, nonneg: bool = False,
+            line_search: bool = False, ls_alpha: float = 1.2, max_total_rank: Optional[int] = None, max_slots: int = 0,
+            two_step: bool = False):
+    """Runs one CP-ALS model per entry of `inits` (three factor matrices I_n x R_k each) concurrently on the tensor T
+    (numpy (I3, I2, I1) C-contiguous, or a CUDA float64 torch tensor of that shape) and returns, in the order of
+    `inits`, a list of (Result, [U1, U2, U3], lambda).  Pure marshalling around the C calls."""
+    ranks = [int(u[0].shape[1]) for u in inits]
+    rstar = int(max_total_rank) if max_total_rank is not None else suggest_max_total_rank(ranks)
+    flags = (FLAG_NONNEG if nonneg else 0) | (FLAG_LINESEARCH if line_search else 0)
+    ctx = Context(max_total_rank=rstar, max_slots=max_slots, flags=CTX_REUSE if two_step else 0)
+    try:
+        ctx.submit_tensor(T)
+        ids = [ctx.enqueue_model(u, tol, max_iters, flags, ls_alpha) for u in inits]
+        ctx.run()
+        res = {r.model_id: r for r in ctx.poll_retired(len(ids) + 1)}
+        out = []
+        for k in ids:
+            U, lam = ctx.get_factors(k)
+            out.append((res[k], U, lam))
+        return out
+    finally:
+        ctx.close()

@@ -46,3 +46,13 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 txt = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in txt.lower() or f == "__never__", os.path.join(dirpath, f)
+
+
+def test_suggested_buffer_width():
+    # host logic only: plateau width, capped by the queue's total rank, never below the widest model
+    assert P.suggest_max_total_rank([3, 4, 5]) == 12
+    assert P.suggest_max_total_rank(list(range(1, 21)) * 10) == 256
+    assert P.suggest_max_total_rank([20] * 3, plateau=16) == 20
+    import pytest
+    with pytest.raises(ValueError):
+        P.suggest_max_total_rank([])

@@ -118,3 +118,22 @@ def test_yardsticks_return_plausible_rates():
             ctx.yardstick(bad.get("kind", 0), bad.get("buf"), bad.get("reps", 1))
         assert e.value.code == -1
     ctx.close()
+
+
+def test_cp_cals_driver_matches_per_model_oracle_runs():
+    # the convenience driver: every model equals its own plain CP-ALS (Alg. 1), whatever R* it picks
+    import paper_2010_04678_amd as P
+    dims = (30, 26, 22)
+    T = _lowrank_tensor(dims, 4, 77, noise=0.05)
+    inits = [uniform_factors(dims, r, 700 + k) for k, r in enumerate([2, 5, 3, 7, 4, 1, 6])]
+    for two_step in (False, True):
+        out = P.cp_cals(T, inits, tol=1e-5, max_iters=60, max_total_rank=12, two_step=two_step)
+        assert len(out) == len(inits)
+        for k, (res, U, lam) in enumerate(out):
+            ref = O.cp_als(T, inits[k], tol=1e-5, max_iters=60)
+            assert res.model_id == k and res.iters == ref["iters"] and res.status == ref["status"]
+            assert abs(res.fit - ref["fit"]) <= 1e-8
+            for n in range(3):
+                a = U[n] * (lam[None, :] if n == 2 else 1.0)
+                b = ref["U"][n] * (ref["lam"][None, :] if n == 2 else 1.0)
+                assert (np.linalg.norm(a - b, axis=0) / np.linalg.norm(b, axis=0)).max() <= 1e-6
