@@ -205,7 +205,8 @@ int drain_timings(cals_ctx* c) {
 int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int ncols, int ld) {
   MttkrpProblem p = make_problem(c, mode, U, M, ncols, ld);
   // factor matrices are addressed with 32-bit byte offsets
-  if ((int64_t)p.Ia * ld * 8 >= (1LL << 32) || (int64_t)p.Ib * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
+  // (with room for the rows a workgroup requests past the end of its range)
+  if ((int64_t)(p.Ia + 64) * ld * 8 >= (1LL << 32) || (int64_t)(p.Ib + 64) * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
   MttkrpPlan pl = mttkrp_plan(p, c->num_cus);
   if (pl.chunk >= (1LL << 31)) return CALS_E_UNSUPPORTED;
   CALS_TRY(ensure_workspace(c, pl.workspace_bytes));
@@ -233,7 +234,7 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int n
 // (I2*I3) x I1 unfolding with a single row of ones as the second factor.  Timed under mode index 1.
 int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld) {
   const int64_t rows = c->dims[1] * c->dims[2];
-  if (rows >= (1LL << 31) || (int64_t)c->dims[0] * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
+  if (rows >= (1LL << 31) || (int64_t)(c->dims[0] + 64) * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
   MttkrpProblem p{};
   p.T = c->T; p.zeros = c->d_zeros; p.M = c->Y; p.ncols = ncols; p.ld = ld;
   p.In = (int)rows; p.sm = c->dims[0];

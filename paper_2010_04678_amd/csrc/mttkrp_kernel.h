@@ -195,30 +195,28 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
     const int gc = n0 + tcol[u];
     gbyte[u] = 8u * (unsigned)(gc <= a.ld - PW ? gc : a.ld - PW);   // PAIR: ld is even (checked on the host)
   }
-  int p_ia, p_ib;                             // (ia, ib) of the first index of the stage being FETCHED (uniform)
-  {
-    const int64_t ib = kb / Ia;
-    p_ib = __builtin_amdgcn_readfirstlane((int)ib);
-    p_ia = __builtin_amdgcn_readfirstlane((int)(kb - ib * Ia));
-  }
   // Factor rows are fetched a whole stage before they are multiplied (row x of the tile after next is requested
   // right after row x of the next tile has been written), so that a miss in L2 never stalls the wavefront.
   double pua[KS][CU][PW], pub[KS][CU][PW];
   const unsigned row_bytes = 8u * (unsigned)a.ld;
   const __amdgpu_buffer_rsrc_t rsrc_a = factor_rsrc(a.Ua, row_bytes * (unsigned)Ia);   // < 2^32 (checked on the host)
   const __amdgpu_buffer_rsrc_t rsrc_b = factor_rsrc(a.Ub, row_bytes * (unsigned)a.Ib);
+  // Byte offsets of the factor rows (ia, ib) of this wavefront's row x of the tile to fetch next: uniform over
+  // the wavefront, kept in scalar registers and advanced by KA rows per fetch (one compare for the wrap of ia).
+  unsigned row_oa[KS], row_ob[KS];
+  const unsigned wrap_a = row_bytes * (unsigned)Ia;
+  const unsigned last_b = row_bytes * (unsigned)(a.Ib - 1);
+#pragma unroll
+  for (int x = 0; x < KS; ++x) {
+    const int64_t k = kb + wave + 4 * x;
+    const int64_t ib = k / Ia;
+    row_oa[x] = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)(k - ib * Ia) * row_bytes));
+    row_ob[x] = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)ib * row_bytes));   // < 2^32: ib <= Ib
+  }
 
   auto fetch_row = [&](int x, double (&ua)[CU][PW], double (&ub)[CU][PW]) {
-    int ia = p_ia + wave + 4 * x, ib = p_ib;
-    if (MODE == kGeneral) {
-      while (ia >= Ia) { ia -= Ia; ib += 1; }
-    } else {
-      if (ia >= Ia) { ia -= Ia; ib += 1; }
-    }
-    ib = ib < a.Ib ? ib : a.Ib - 1;
-    // uniform by construction; the explicit broadcast keeps them in scalar registers
-    const unsigned oa = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)ia * row_bytes));
-    const unsigned ob = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)ib * row_bytes));
+    const unsigned oa = row_oa[x];
+    const unsigned ob = row_ob[x] < last_b ? row_ob[x] : last_b;   // rows past the end of K: any valid row
 #pragma unroll
     for (int u = 0; u < CU; ++u) {
       if (PAIR) {
@@ -231,6 +229,13 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
         ub[u][0] = buffer_load_f64(rsrc_b, gbyte[u], ob);
       }
     }
+    // the same row of the following tile
+    row_oa[x] += (unsigned)KA * row_bytes;
+    if (MODE == kGeneral) {
+      while (row_oa[x] >= wrap_a) { row_oa[x] -= wrap_a; row_ob[x] += row_bytes; }
+    } else {
+      if (row_oa[x] >= wrap_a) { row_oa[x] -= wrap_a; row_ob[x] += row_bytes; }
+    }
   };
   auto commit_row = [&](double* tile, int x, const double (&ua)[CU][PW], const double (&ub)[CU][PW]) {
 #pragma unroll
@@ -242,15 +247,6 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
         *dst = ua[u][0] * ub[u][0];
     }
   };
-  auto advance_producer = [&]() {
-    p_ia += KA;
-    if (MODE == kGeneral) {
-      while (p_ia >= Ia) { p_ia -= Ia; p_ib += 1; }
-    } else {
-      if (p_ia >= Ia) { p_ia -= Ia; p_ib += 1; }
-    }
-  };
-
   double breg[2][WN];
   auto load_b = [&](const double* tile, int s, double (&b)[WN]) {
     const double* brow = tile + (MODE == kContig4 ? 4 * lq + s : 4 * s + lq) * NC + li;
@@ -278,7 +274,6 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
       commit_row(next_tile, s, pua[s], pub[s]);
       fetch_row(s, pua[s], pub[s]);
     }
-    advance_producer();
     __syncthreads();
   };
 
@@ -288,10 +283,8 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
     fetch_row(x, pua[x], pub[x]);
     commit_row(smem, x, pua[x], pub[x]);
   }
-  advance_producer();
 #pragma unroll
   for (int x = 0; x < KS; ++x) fetch_row(x, pua[x], pub[x]);
-  advance_producer();
   load_a_stage(areg0);
   __syncthreads();
 
