@@ -75,6 +75,7 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
 #pragma unroll
         for (int k = 0; k < RM; ++k) arow[k] = hrow[k];
         double b = m;
+        double rpiv[RM];                   // reciprocals of the pivots (uniform), reused by the back-substitution
         bool ok = true;
 #pragma unroll
         for (int j = 0; j < RM; ++j) {
@@ -83,7 +84,8 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
             if (!(dj > 0.0) || !isfinite(dj)) {
               ok = false;
             } else {
-              const double mult = (lane > j) ? arow[j] / dj : 0.0;
+              rpiv[j] = 1.0 / dj;
+              const double mult = (lane > j) ? arow[j] * rpiv[j] : 0.0;
               const double bj = readlane_f64(b, j);
               b = fma(-mult, bj, b);
 #pragma unroll
@@ -103,7 +105,7 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
 #pragma unroll
         for (int k = RM - 1; k >= 0; --k) {
           if ((P >> k) & 1u) {
-            const double sk = readlane_f64(b / arow[k], k);
+            const double sk = readlane_f64(b, k) * rpiv[k];
             s = (lane == k) ? sk : s;
             b = (lane < k) ? fma(-arow[k], sk, b) : b;
           }
