@@ -3,7 +3,18 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace cals {
+
+// True the first time it is called with the given flag word while a given device is current (kernel attributes
+// such as the dynamic LDS limit are per device); safe to call from several host threads.
+inline bool first_use_on_current_device(std::atomic<unsigned long long>& seen) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return true;
+  const unsigned long long bit = 1ull << dev;
+  return (seen.fetch_or(bit) & bit) == 0;
+}
 
 constexpr int kMaxRank = 32;       // largest rank of one model (CALS_MAX_RANK)
 constexpr int kGramStride = kMaxRank * kMaxRank;

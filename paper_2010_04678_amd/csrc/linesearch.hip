@@ -197,13 +197,12 @@ hipError_t launch_ls_extrapolate(const LineSearchArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream) {
-  static bool attr_done = false;
+  static std::atomic<unsigned long long> attr_seen{0};
   const size_t lds = sizeof(double) * (kMaxRank * kXs + 256);
-  if (!attr_done) {
+  if (first_use_on_current_device(attr_seen)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ls_gram_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_done = true;
   }
   if (a.n_models < 1) return hipSuccess;
   if (!a.part || a.nblk < 1) return hipErrorInvalidValue;

@@ -376,15 +376,14 @@ static constexpr size_t kSolveLds = sizeof(double) * (kMaxRank * kXs + kGramStri
 static constexpr size_t kFinishLds = sizeof(double) * (kGramStride + 256 + kMaxRank);
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t stream) {
-  static bool attr_done = false;
-  if (!attr_done) {
+  static std::atomic<unsigned long long> attr_seen{0};
+  if (first_use_on_current_device(attr_seen)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(update_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kUpdateLds);
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(update_solve_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSolveLds);
     if (e != hipSuccess) return e;
-    attr_done = true;
   }
   if (a.n_models < 1) return hipSuccess;
   const int nblk = update_row_blocks(a.In);
@@ -447,13 +446,12 @@ __global__ void __launch_bounds__(256) gram_init_kernel(GramInitArgs a) {
 hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, double* lambda, bool reset_out,
                             uint32_t* const passive[3], int capacity, const double* const U[3], const int In[3], int ld, int first, int count,
                             hipStream_t stream) {
-  static bool attr_done = false;
+  static std::atomic<unsigned long long> attr_seen{0};
   const size_t lds = sizeof(double) * (kMaxRank * kXs + kGramStride);
-  if (!attr_done) {
+  if (first_use_on_current_device(attr_seen)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gram_init_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_done = true;
   }
   if (count < 1) return hipSuccess;
   GramInitArgs a;
