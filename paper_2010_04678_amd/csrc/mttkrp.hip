@@ -60,7 +60,7 @@ hipError_t mttkrp_init() {
     int n = 0;
     const Variant* t = (wm == 1) ? mttkrp_variants_wm1(&n) : (wm == 2 ? mttkrp_variants_wm2(&n) : mttkrp_variants_wm4(&n));
     for (int i = 0; i < n; ++i)
-      for (int m = 0; m < 8; ++m) {
+      for (int m = 0; m < 10; ++m) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(t[i].fn[m >> 1][m & 1]),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)variant_lds_bytes(t[i]));
         if (e != hipSuccess) return e;
@@ -186,6 +186,10 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   if (mode != kGeneral && p.sa == 1 && p.Ia % 4 == 0 && p.sm % 2 == 0 && p.sb % 2 == 0 && pl.ka == 16 &&
       (reinterpret_cast<uintptr_t>(p.T) & 15) == 0 && env_int("CALS_MTTKRP_NOCONTIG", 0) == 0)
     mode = kContig4;
+  // rows contiguous in memory (mode 1), even row count, 16-byte aligned columns: two rows per 16-byte load
+  if (mode == kAffine && p.sm == 1 && pl.wm % 2 == 0 && p.In % 2 == 0 && p.sa % 2 == 0 && p.sb % 2 == 0 &&
+      (reinterpret_cast<uintptr_t>(p.T) & 15) == 0 && env_int("CALS_MTTKRP_NOROWPAIR", 0) == 0)
+    mode = kRowPair;
   // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao tile production
   const int pair = (p.ld % 2 == 0 && ((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub)) & 15) == 0 &&
                     env_int("CALS_MTTKRP_NOPAIR", 0) == 0) ? 1 : 0;

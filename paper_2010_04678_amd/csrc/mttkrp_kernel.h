@@ -60,7 +60,11 @@ struct MttkrpKernelArgs {
 //   kContig4: sa == 1, Ia % 4 == 0, Ia >= KA, 16-byte aligned rows (modes 2 and 3 of aligned tensors): a lane
 //             owns 4 CONSECUTIVE contraction indices per stage (two 16-byte loads, fully coalesced rows); MFMA
 //             k-step s then takes element s of every lane, i.e. tile row 4*lq + s instead of 4*s + lq.
-enum { kAffine = 0, kWrap = 1, kGeneral = 2, kContig4 = 3 };
+//   kRowPair: kAffine with sm == 1 (mode 1), an even row count and 16-byte aligned columns: a lane reads TWO
+//             adjacent rows with one 16-byte load and feeds them to two row tiles, so row tile 2p holds the even
+//             and row tile 2p+1 the odd rows of the wavefront's p-th group of 32 rows (needs WM even; kernels
+//             with odd WM treat it as kAffine and are never launched with it).
+enum { kAffine = 0, kWrap = 1, kGeneral = 2, kContig4 = 3, kRowPair = 4 };
 
 template <int WM, int WN, int KA, int MODE, bool PAIR>
 __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
@@ -102,6 +106,8 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   const int64_t ke = (kb + a.chunk < a.K) ? (kb + a.chunk) : a.K;
   const int nstage = (int)((ke - kb + KA - 1) / KA);
   const int Ia = a.Ia;
+  constexpr bool RP = (MODE == kRowPair) && (WM % 2 == 0);     // rows interleaved over pairs of row tiles
+  constexpr bool AFF = (MODE == kAffine) || (MODE == kRowPair);
 
   double4_t acc[WM][WN];
 #pragma unroll
@@ -114,15 +120,20 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   const double* Prow[WM];
 #pragma unroll
   for (int t = 0; t < WM; ++t) {
-    const int r = m0 + 16 * t + li;
-    Prow[t] = a.T + (int64_t)(r < a.In ? r : a.In - 1) * a.sm;
+    if (RP) {         // the even row of the lane's pair; only tiles 0, 2, ... load (In is even: the pair is in range)
+      const int r = m0 + 32 * (t / 2) + 2 * li;
+      Prow[t] = a.T + (int64_t)(r < a.In ? r : a.In - 2);
+    } else {
+      const int r = m0 + 16 * t + li;
+      Prow[t] = a.T + (int64_t)(r < a.In ? r : a.In - 1) * a.sm;
+    }
   }
   int64_t koff;                               // ia*sa + ib*sb of this lane's current k
   int a_ia = 0;                               // only tracked when the offset is not affine in k
   int a_left;                                 // contraction indices left before ke, from this lane's k
   {
     const int64_t k = kb + (MODE == kContig4 ? 4 * lq : lq);
-    if (MODE == kAffine) {
+    if (AFF) {
       koff = k * a.sa;
     } else {
       const int64_t ib = k / Ia;
@@ -167,7 +178,15 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 #pragma unroll
       for (int t = 0; t < WM; ++t) {
         const double* p = ok ? Prow[t] + koff : zeros;
-        dst[s][t] = *p;
+        if (RP) {
+          if (t % 2 == 0) {
+            const double2 v = *reinterpret_cast<const double2*>(p);
+            dst[s][t] = v.x;
+            dst[s][t + (WM > 1 ? 1 : 0)] = v.y;
+          }
+        } else {
+          dst[s][t] = *p;
+        }
       }
       a_left -= 4;
       koff += a_step;
@@ -299,13 +318,13 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   double* P = a.P + (int64_t)bz * a.pstride;
 #pragma unroll
   for (int t = 0; t < WM; ++t) {
-    if (m0 + 16 * t < a.In) {
+    if ((RP ? m0 + 32 * (t / 2) : m0 + 16 * t) < a.In) {
 #pragma unroll
       for (int j = 0; j < WN; ++j) {
         const int col = n0 + 16 * j + li;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const int r = m0 + 16 * t + 4 * v + lq;
+          const int r = RP ? m0 + 32 * (t / 2) + 2 * (4 * v + lq) + (t % 2) : m0 + 16 * t + 4 * v + lq;
           if (r < a.In && col < a.ncols) P[(int64_t)r * a.ld + col] = acc[t][j][v];
         }
       }
@@ -316,7 +335,7 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 typedef void (*mttkrp_fn)(MttkrpKernelArgs);
 struct Variant {
   int wm, wn, ka;
-  mttkrp_fn fn[4][2]; // indexed by kAffine / kWrap / kGeneral / kContig4, and by PAIR
+  mttkrp_fn fn[5][2]; // indexed by kAffine / kWrap / kGeneral / kContig4 / kRowPair, and by PAIR
 };
 #define CALS_VARIANT(WM_, WN_, KA_)                                                                       \
   {                                                                                                       \
@@ -324,7 +343,8 @@ struct Variant {
       {mttkrp_kernel<WM_, WN_, KA_, kAffine, false>, mttkrp_kernel<WM_, WN_, KA_, kAffine, true>},        \
           {mttkrp_kernel<WM_, WN_, KA_, kWrap, false>, mttkrp_kernel<WM_, WN_, KA_, kWrap, true>},        \
           {mttkrp_kernel<WM_, WN_, KA_, kGeneral, false>, mttkrp_kernel<WM_, WN_, KA_, kGeneral, true>},  \
-          {mttkrp_kernel<WM_, WN_, KA_, kContig4, false>, mttkrp_kernel<WM_, WN_, KA_, kContig4, true>}   \
+          {mttkrp_kernel<WM_, WN_, KA_, kContig4, false>, mttkrp_kernel<WM_, WN_, KA_, kContig4, true>},  \
+          {mttkrp_kernel<WM_, WN_, KA_, kRowPair, false>, mttkrp_kernel<WM_, WN_, KA_, kRowPair, true>}   \
     }                                                                                                     \
   }
 
