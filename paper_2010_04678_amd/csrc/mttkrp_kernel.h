@@ -266,40 +266,47 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
         *dst = ua[u][0] * ub[u][0];
     }
   };
-  // Narrow tiles (at most 32 columns, low total rank): the wavefront's four rows of a tile fit ONE 16-byte load per
-  // factor -- lane l covers row l / LPR and column pair l % LPR -- so a stage needs two loads, two multiplies and
-  // one LDS store per wavefront instead of four of each per row.  The row offsets are then per lane (vector).
-  constexpr bool PACK = PAIR && (NC <= 32) && (KS == 4);
-  constexpr int LPR = NC / 2;                 // lanes per tile row
-  unsigned pk_oa = 0, pk_ob = 0, pk_col = 0;
-  int pk_dst = 0;
-  double pk_ua[2] = {0.0, 0.0}, pk_ub[2] = {0.0, 0.0};
+  // Narrow tiles (at most 64 columns, low total rank): a 16-byte load per factor covers 64 / LPR tile rows -- lane
+  // l takes row l / LPR and column pair l % LPR -- so the wavefront's four rows of a tile take one load per factor
+  // (two for 64 columns), one multiply pair and one LDS store each, instead of one of each per row.  The row
+  // offsets are then per lane (vector registers).
+  constexpr bool PACK = PAIR && (NC <= 64) && (KS == 4);
+  constexpr int LPR = NC / 2;                        // lanes per tile row: 8, 16, 24 or 32
+  constexpr int RPI = (64 / (LPR > 0 ? LPR : 1)) >= 4 ? 4 : 2;   // whole rows of this wavefront per load instruction
+  constexpr int NIW = PACK ? KS / RPI : 1;           // load instructions per factor for the wavefront's four rows
+  unsigned pk_oa[NIW], pk_ob[NIW], pk_col = 0;
+  int pk_dst[NIW];
+  double pk_ua[NIW][2], pk_ub[NIW][2];
   if (PACK) {
-    const int xr = (lane / LPR < KS) ? lane / LPR : KS - 1;   // surplus lanes repeat the last row (same address, same value)
+    const int xl = (lane / LPR < RPI) ? lane / LPR : RPI - 1;   // surplus lanes repeat the last row (same address, same value)
     const int cp = lane % LPR;
     const int gc = n0 + 2 * cp;
     pk_col = 8u * (unsigned)(gc <= a.ld - 2 ? gc : a.ld - 2);
-    pk_dst = (wave + 4 * xr) * NC + 2 * cp;
-    const int64_t k = kb + wave + 4 * xr;
-    const int64_t ib = k / Ia;
-    pk_oa = (unsigned)(k - ib * Ia) * row_bytes;
-    pk_ob = (unsigned)ib * row_bytes;
+#pragma unroll
+    for (int i = 0; i < NIW; ++i) {
+      const int xr = i * RPI + xl;                   // which of the wavefront's rows: tile row wave + 4 * xr
+      pk_dst[i] = (wave + 4 * xr) * NC + 2 * cp;
+      const int64_t k = kb + wave + 4 * xr;
+      const int64_t ib = k / Ia;
+      pk_oa[i] = (unsigned)(k - ib * Ia) * row_bytes;
+      pk_ob[i] = (unsigned)ib * row_bytes;
+    }
   }
-  auto fetch_packed = [&]() {
-    const unsigned ob = pk_ob < last_b ? pk_ob : last_b;
-    const double2 va = buffer_load_f64x2(rsrc_a, pk_oa + pk_col, 0u);
+  auto fetch_packed = [&](int i) {
+    const unsigned ob = pk_ob[i] < last_b ? pk_ob[i] : last_b;
+    const double2 va = buffer_load_f64x2(rsrc_a, pk_oa[i] + pk_col, 0u);
     const double2 vb = buffer_load_f64x2(rsrc_b, ob + pk_col, 0u);
-    pk_ua[0] = va.x; pk_ua[1] = va.y;
-    pk_ub[0] = vb.x; pk_ub[1] = vb.y;
-    pk_oa += (unsigned)KA * row_bytes;
+    pk_ua[i][0] = va.x; pk_ua[i][1] = va.y;
+    pk_ub[i][0] = vb.x; pk_ub[i][1] = vb.y;
+    pk_oa[i] += (unsigned)KA * row_bytes;
     if (MODE == kGeneral) {
-      while (pk_oa >= wrap_a) { pk_oa -= wrap_a; pk_ob += row_bytes; }
+      while (pk_oa[i] >= wrap_a) { pk_oa[i] -= wrap_a; pk_ob[i] += row_bytes; }
     } else {
-      if (pk_oa >= wrap_a) { pk_oa -= wrap_a; pk_ob += row_bytes; }
+      if (pk_oa[i] >= wrap_a) { pk_oa[i] -= wrap_a; pk_ob[i] += row_bytes; }
     }
   };
-  auto commit_packed = [&](double* tile) {
-    *reinterpret_cast<double2*>(tile + pk_dst) = double2{pk_ua[0] * pk_ub[0], pk_ua[1] * pk_ub[1]};
+  auto commit_packed = [&](double* tile, int i) {
+    *reinterpret_cast<double2*>(tile + pk_dst[i]) = double2{pk_ua[i][0] * pk_ub[i][0], pk_ua[i][1] * pk_ub[i][1]};
   };
 
   double breg[2][WN];
@@ -327,9 +334,9 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
           acc[t][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(acur[s][t], breg[s & 1][j], acc[t][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       if (PACK) {
-        if (s == 0) {
-          commit_packed(next_tile);
-          fetch_packed();
+        if (s < NIW) {
+          commit_packed(next_tile, s);
+          fetch_packed(s);
         }
       } else {
         commit_row(next_tile, s, pua[s], pub[s]);
@@ -341,9 +348,13 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 
   // ---- prologue: tile 0, the factor rows of tile 1 and fragment 0
   if (PACK) {
-    fetch_packed();
-    commit_packed(smem);
-    fetch_packed();
+#pragma unroll
+    for (int i = 0; i < NIW; ++i) {
+      fetch_packed(i);
+      commit_packed(smem, i);
+    }
+#pragma unroll
+    for (int i = 0; i < NIW; ++i) fetch_packed(i);
   } else {
 #pragma unroll
     for (int x = 0; x < KS; ++x) {
