@@ -32,9 +32,10 @@
  *   - sums over the two contracted indices are nested: the inner sum runs over the lower-
  *     numbered contracted mode into a fresh accumulator, the outer sum adds those up.
  *
- * parity unpinned: the paper prints no worked numeric example (no factor, fit or error values),
- * so no number below is checked against a printed value; the routines are pinned by brute force,
- * identities, closed forms and library routines in the CPU test-suite instead.
+ * Pins: every routine below is pinned in the CPU test-suite by something other than itself -- brute force on
+ * tiny inputs, identities, closed forms, special cases that reduce to library routines (LAPACK Cholesky and
+ * least squares, scipy's Lawson-Hanson), hand-computed queue schedules.  The paper prints no worked numeric
+ * example (no factor, fit or error values), so none of the pins is a printed value.
  *
  * Build: gcc -O3 -fopenmp -fPIC -shared -o liboracle.so cals_oracle.c -lm
  */

@@ -56,3 +56,10 @@ def test_suggested_buffer_width():
     import pytest
     with pytest.raises(ValueError):
         P.suggest_max_total_rank([])
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
