@@ -16,6 +16,15 @@ inline bool first_use_on_current_device(std::atomic<unsigned long long>& seen) {
   return (seen.fetch_or(bit) & bit) == 0;
 }
 
+#if defined(__HIPCC__)
+// Broadcast of a double from one lane (wave-uniform index) to the whole wavefront through scalar registers.
+__device__ inline double readlane_f64(double v, int src_lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
+  return __hiloint2double(hi, lo);
+}
+#endif
+
 constexpr int kMaxRank = 32;       // largest rank of one model (CALS_MAX_RANK)
 constexpr int kGramStride = kMaxRank * kMaxRank;
 

@@ -94,12 +94,164 @@ __device__ inline bool block_cholesky(double* A, int R, int* flag /* LDS */) {
   return true;
 }
 
-__global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
-  extern __shared__ double lds[];
-  const ModelDesc d = a.desc[blockIdx.x];
+// ---- modes of at most 256 rows: one workgroup per model, one row per thread, everything in one pass ----------
+// The two latency chains of the update are kept out of LDS: the Cholesky factorisation runs in ONE wavefront with
+// row i of the working matrix in lane i's registers (pivot column broadcast through v_readlane; right-looking, so
+// every element sees its subtractions in the order of the textbook column algorithm), and a thread solves its row
+// with the right-hand side in registers (the factor is read from LDS at wave-uniform addresses, which do not depend
+// on the data: the dependent chain is the FMA latency only).  RM = rank rounded up to a multiple of 4; the factor
+// is stored RM x RM with zero padding and unit diagonal beyond the rank, so the unrolled loops need no guards.
+template <int RM>
+__device__ __forceinline__ bool wave_cholesky(const double* H, double* L, int R, int lane) {
+  double arow[RM];
+#pragma unroll
+  for (int k = 0; k < RM; ++k) arow[k] = (lane < R && k < R) ? H[lane * R + k] : 0.0;
+  bool ok = true;
+#pragma unroll
+  for (int j = 0; j < RM; ++j) {
+    if (ok && j < R) {
+      const double djj = readlane_f64(arow[j], j);
+      if (!(djj > 0.0) || !isfinite(djj)) {
+        ok = false;
+      } else {
+        const double ljj = sqrt(djj);
+        const double lcol = (lane > j) ? arow[j] / ljj : (lane == j ? ljj : 0.0);
+        if (lane >= j && lane < R) L[lane * RM + j] = lcol;
+#pragma unroll
+        for (int k = j + 1; k < RM; ++k) arow[k] = fma(-lcol, readlane_f64(lcol, k), arow[k]);
+      }
+    }
+  }
+  return ok;
+}
+
+__device__ inline double fast_block_sum(double v, double* red /* >= 4 doubles in LDS */) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+template <int RM>
+__device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDesc& d, int slot, double* lds, int* flag) {
   ModelState* st = a.state + d.sid;
   ModelOut* out = a.out + d.sid;
-  if (out->status != 0) return;               // stopped earlier in this iteration (uniform)
+  const int tid = threadIdx.x;
+  const int R = d.rank;
+  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
+  double* xs = lds;                           // R * kXs: the solved rows, staged for the Gramian
+  double* H = xs + kMaxRank * kXs;            // R*R, Hadamard of Gramians
+  double* L = H + kGramStride;                // RM*RM, Cholesky factor (zero padded, unit diagonal beyond R)
+  double* Gl = L + kGramStride;               // R*R, Gramian of the updated factor
+  double* red = Gl + kGramStride;             // 256
+  double* lam = red + 256;                    // R
+
+  for (int e = tid; e < R * R; e += 256) H[e] = st->G[ma][e] * st->G[mb][e];
+  for (int e = tid; e < RM * RM; e += 256) L[e] = (e / RM == e % RM && e / RM >= R) ? 1.0 : 0.0;
+  __syncthreads();
+  // NONNEG models: the rows were solved by the non-negative update already (a.X); only its outcome is read
+  const bool nonneg = (d.flags & 1u) != 0;
+  if (nonneg) {
+    if (tid == 0) {
+      *flag = a.nn_fail[slot] == 0;
+      a.nn_fail[slot] = 0;
+    }
+  } else if (tid < 64) {
+    const bool ok = wave_cholesky<RM>(H, L, R, tid);
+    if (tid == 0) *flag = ok;
+  }
+  __syncthreads();
+  if (*flag == 0) {
+    if (tid == 0) out->status = 3;            // CALS_NUMERICAL; factors of this mode stay untouched
+    return;
+  }
+
+  const int i = tid;
+  const bool live = i < a.In;
+  double x[RM];
+  double inner = 0.0;
+  if (live) {
+    const double* mrow = a.M + (int64_t)i * a.ld + d.col;
+    if (nonneg) {
+      const double* xrow = a.X + (int64_t)i * a.ld + d.col;
+#pragma unroll
+      for (int r = 0; r < RM; ++r) x[r] = (r < R) ? xrow[r] : 0.0;
+    } else {
+#pragma unroll
+      for (int r = 0; r < RM; ++r) x[r] = (r < R) ? mrow[r] : 0.0;
+#pragma unroll
+      for (int r = 0; r < RM; ++r) {          // L y = m
+        double v = x[r];
+#pragma unroll
+        for (int k = 0; k < r; ++k) v = fma(-L[r * RM + k], x[k], v);
+        x[r] = v / L[r * RM + r];
+        __builtin_amdgcn_sched_barrier(0);    // keeps the factor reads of later rows from being hoisted (registers)
+      }
+#pragma unroll
+      for (int r = RM - 1; r >= 0; --r) {     // L^T x = y
+        double v = x[r];
+#pragma unroll
+        for (int k = r + 1; k < RM; ++k) v = fma(-L[k * RM + r], x[k], v);
+        x[r] = v / L[r * RM + r];
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < RM; ++r)
+      if (r < R) {
+        xs[r * kXs + tid] = x[r];
+        inner = fma(x[r], mrow[r], inner);
+      }
+  }
+  __syncthreads();
+  double gacc[3] = {0.0, 0.0, 0.0};
+  gram_accumulate(xs, R, a.In, gacc);
+  gram_store(gacc, R, Gl);
+  __syncthreads();
+
+  if (a.mode == 2) {
+    double part = 0.0;
+    for (int e = tid; e < R * R; e += 256) part += H[e] * Gl[e];
+    const double normsq = fast_block_sum(part, red);
+    const double in = fast_block_sum(inner, red);
+    if (tid == 0) {
+      st->inner = in;
+      st->normsq = normsq;
+      const double err = a.normT2 + normsq - 2.0 * in;
+      out->err = err;
+      out->fit = 1.0 - sqrt(err > 0.0 ? err : 0.0) / sqrt(a.normT2);
+      out->iters += 1;
+    }
+  }
+  if (tid < R) {
+    const double l = sqrt(Gl[tid * R + tid]);
+    lam[tid] = l;
+    a.lambda[d.sid * kMaxRank + tid] = l;
+  }
+  __syncthreads();
+  for (int e = tid; e < R * R; e += 256) {
+    const int r = e / R, s = e % R;
+    const double lr = lam[r] > 0.0 ? lam[r] : 1.0, ls = lam[s] > 0.0 ? lam[s] : 1.0;
+    st->G[a.mode][e] = (Gl[e] / lr) / ls;
+  }
+  if (live) {
+    double* urow = a.U + (int64_t)i * a.ld + d.col;
+#pragma unroll
+    for (int r = 0; r < RM; ++r)
+      if (r < R) {
+        const double l = lam[r];
+        urow[r] = l > 0.0 ? x[r] / l : x[r];
+      }
+  }
+}
+
+// Ranks above 16: the same steps with the factor and the row vectors in LDS (the register arrays of the path above
+// would not fit next to each other for every rank in one kernel).
+__device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d, double* lds, int* flagp) {
+  ModelState* st = a.state + d.sid;
+  ModelOut* out = a.out + d.sid;
   const int tid = threadIdx.x;
   const int R = d.rank;
   const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
@@ -109,7 +261,7 @@ __global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
   double* Gl = L + kGramStride;               // R*R, Gramian of the updated factor
   double* red = Gl + kGramStride;             // 256
   double* lam = red + 256;                    // R
-  __shared__ int flag;
+  int& flag = *flagp;
 
   for (int e = tid; e < R * R; e += 256) {
     const double h = st->G[ma][e] * st->G[mb][e];
@@ -208,6 +360,20 @@ __global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
       const double l = lam[r];
       if (l > 0.0) urow[r] = urow[r] / l;
     }
+  }
+}
+
+__global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
+  extern __shared__ double lds[];
+  __shared__ int flag;
+  const ModelDesc d = a.desc[blockIdx.x];
+  if (a.out[d.sid].status != 0) return;       // stopped earlier in this iteration (uniform)
+  switch ((d.rank + 3) / 4) {
+    case 1: update_small<4>(a, d, blockIdx.x, lds, &flag); break;
+    case 2: update_small<8>(a, d, blockIdx.x, lds, &flag); break;
+    case 3: update_small<12>(a, d, blockIdx.x, lds, &flag); break;
+    case 4: update_small<16>(a, d, blockIdx.x, lds, &flag); break;
+    default: update_wide(a, d, lds, &flag); break;
   }
 }
 
