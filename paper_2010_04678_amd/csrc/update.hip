@@ -134,6 +134,58 @@ __device__ inline double fast_block_sum(double v, double* red /* >= 4 doubles in
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// Solves (L L^T) x = m for one row with x in registers; L is RM x RM in LDS, zero padded with unit diagonal.
+template <int RM>
+__device__ __forceinline__ void solve_row_in_registers(const double* L, double (&x)[RM]) {
+#pragma unroll
+  for (int r = 0; r < RM; ++r) {              // L y = m
+    double v = x[r];
+#pragma unroll
+    for (int k = 0; k < r; ++k) v = fma(-L[r * RM + k], x[k], v);
+    x[r] = v / L[r * RM + r];
+    __builtin_amdgcn_sched_barrier(0);        // keeps the factor reads of later rows from being hoisted (registers)
+  }
+#pragma unroll
+  for (int r = RM - 1; r >= 0; --r) {         // L^T x = y
+    double v = x[r];
+#pragma unroll
+    for (int k = r + 1; k < RM; ++k) v = fma(-L[k * RM + r], x[k], v);
+    x[r] = v / L[r * RM + r];
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Tall modes, ranks up to 16: the rows [r0, r1) of one model, 256 at a time -- solve in registers, store the
+// (not yet normalised) rows, stage them for the Gramian, accumulate Gramian and inner product.
+template <int RM>
+__device__ __forceinline__ void solve_rows_small(const UpdateArgs& a, const ModelDesc& d, const double* L, double* xs,
+                                                 bool nonneg, int r0, int r1, double (&gacc)[3], double& inner) {
+  const int tid = threadIdx.x, R = d.rank;
+  for (int base = r0; base < r1; base += kRows) {
+    const int i = base + tid;
+    const int nrows = (r1 - base < kRows) ? (r1 - base) : kRows;
+    if (i < r1) {
+      const double* mrow = a.M + (int64_t)i * a.ld + d.col;
+      const double* src = nonneg ? a.X + (int64_t)i * a.ld + d.col : mrow;
+      double x[RM];
+#pragma unroll
+      for (int r = 0; r < RM; ++r) x[r] = (r < R) ? src[r] : 0.0;
+      if (!nonneg) solve_row_in_registers<RM>(L, x);
+      double* urow = a.U + (int64_t)i * a.ld + d.col;
+#pragma unroll
+      for (int r = 0; r < RM; ++r)
+        if (r < R) {
+          xs[r * kXs + tid] = x[r];
+          urow[r] = x[r];
+          inner = fma(x[r], mrow[r], inner);
+        }
+    }
+    __syncthreads();
+    gram_accumulate(xs, R, nrows, gacc);
+    __syncthreads();
+  }
+}
+
 template <int RM>
 __device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDesc& d, int slot, double* lds, int* flag) {
   ModelState* st = a.state + d.sid;
@@ -181,22 +233,7 @@ __device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDes
     } else {
 #pragma unroll
       for (int r = 0; r < RM; ++r) x[r] = (r < R) ? mrow[r] : 0.0;
-#pragma unroll
-      for (int r = 0; r < RM; ++r) {          // L y = m
-        double v = x[r];
-#pragma unroll
-        for (int k = 0; k < r; ++k) v = fma(-L[r * RM + k], x[k], v);
-        x[r] = v / L[r * RM + r];
-        __builtin_amdgcn_sched_barrier(0);    // keeps the factor reads of later rows from being hoisted (registers)
-      }
-#pragma unroll
-      for (int r = RM - 1; r >= 0; --r) {     // L^T x = y
-        double v = x[r];
-#pragma unroll
-        for (int k = r + 1; k < RM; ++k) v = fma(-L[k * RM + r], x[k], v);
-        x[r] = v / L[r * RM + r];
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      solve_row_in_registers<RM>(L, x);
     }
 #pragma unroll
     for (int r = 0; r < RM; ++r)
@@ -395,11 +432,19 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
   const int R = d.rank;
   const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
   double* xs = lds;                           // R * kXs
-  double* L = xs + kMaxRank * kXs;            // R*R, Cholesky factor
+  double* L = xs + kMaxRank * kXs;            // Cholesky factor: R*R in place of H, or RM*RM padded (ranks <= 16)
   double* red = L + kGramStride;              // 256
+  double* H = red + 256;                      // R*R (ranks <= 16: the factorisation reads H and writes L)
   __shared__ int flag;
+  const bool small = R <= 16;
+  const int RMs = (R + 3) / 4 * 4;
 
-  for (int e = tid; e < R * R; e += 256) L[e] = st->G[ma][e] * st->G[mb][e];
+  if (small) {
+    for (int e = tid; e < R * R; e += 256) H[e] = st->G[ma][e] * st->G[mb][e];
+    for (int e = tid; e < RMs * RMs; e += 256) L[e] = (e / RMs == e % RMs && e / RMs >= R) ? 1.0 : 0.0;
+  } else {
+    for (int e = tid; e < R * R; e += 256) L[e] = st->G[ma][e] * st->G[mb][e];
+  }
   __syncthreads();
   const bool nonneg = (d.flags & 1u) != 0;
   bool failed;
@@ -407,6 +452,19 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
     if (tid == 0) flag = a.nn_fail[blockIdx.x];   // cleared by update_finish_kernel
     __syncthreads();
     failed = flag != 0;
+  } else if (small) {
+    if (tid < 64) {
+      bool ok;
+      switch (RMs) {
+        case 4: ok = wave_cholesky<4>(H, L, R, tid); break;
+        case 8: ok = wave_cholesky<8>(H, L, R, tid); break;
+        case 12: ok = wave_cholesky<12>(H, L, R, tid); break;
+        default: ok = wave_cholesky<16>(H, L, R, tid); break;
+      }
+      if (tid == 0) flag = ok;
+    }
+    __syncthreads();
+    failed = flag == 0;
   } else {
     failed = !block_cholesky(L, R, &flag);
   }
@@ -423,7 +481,15 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
   double inner = 0.0;
   const double* Mb = a.M + d.col;
   double* Ub = a.U + d.col;
-  for (int base = r0; base < r1; base += kRows) {
+  if (small) {
+    switch (RMs) {
+      case 4: solve_rows_small<4>(a, d, L, xs, nonneg, r0, r1, gacc, inner); break;
+      case 8: solve_rows_small<8>(a, d, L, xs, nonneg, r0, r1, gacc, inner); break;
+      case 12: solve_rows_small<12>(a, d, L, xs, nonneg, r0, r1, gacc, inner); break;
+      default: solve_rows_small<16>(a, d, L, xs, nonneg, r0, r1, gacc, inner); break;
+    }
+  }
+  for (int base = small ? r1 : r0; base < r1; base += kRows) {
     const int i = base + tid;
     const int nrows = (r1 - base < kRows) ? (r1 - base) : kRows;
     if (i < r1) {
@@ -538,7 +604,7 @@ __global__ void __launch_bounds__(256) update_finish_kernel(UpdateArgs a) {
 }
 
 static constexpr size_t kUpdateLds = sizeof(double) * (kMaxRank * kXs + 3 * kGramStride + 256 + kMaxRank);
-static constexpr size_t kSolveLds = sizeof(double) * (kMaxRank * kXs + kGramStride + 256);
+static constexpr size_t kSolveLds = sizeof(double) * (kMaxRank * kXs + 2 * kGramStride + 256);
 static constexpr size_t kFinishLds = sizeof(double) * (kGramStride + 256 + kMaxRank);
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t stream) {
