@@ -150,10 +150,16 @@ __global__ void __launch_bounds__(256) nnls_kernel(NnlsArgs a) {
   const int row1 = (row0 + kNnlsRowsPerBlock < a.In) ? (row0 + kNnlsRowsPerBlock) : a.In;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  if (d.rank <= 8) nnls_rows<8>(a, d, blockIdx.x, row0, row1, lane, wave);
-  else if (d.rank <= 16) nnls_rows<16>(a, d, blockIdx.x, row0, row1, lane, wave);
-  else if (d.rank <= 24) nnls_rows<24>(a, d, blockIdx.x, row0, row1, lane, wave);
-  else nnls_rows<32>(a, d, blockIdx.x, row0, row1, lane, wave);
+  switch ((d.rank + 3) / 4) {           // register arrays sized to the rank rounded up to a multiple of 4
+    case 1: nnls_rows<4>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+    case 2: nnls_rows<8>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+    case 3: nnls_rows<12>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+    case 4: nnls_rows<16>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+    case 5: nnls_rows<20>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+    case 6: nnls_rows<24>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+    case 7: nnls_rows<28>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+    default: nnls_rows<32>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+  }
 }
 
 hipError_t launch_nnls(const NnlsArgs& a, hipStream_t stream) {

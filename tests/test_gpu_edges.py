@@ -92,11 +92,11 @@ def test_all_zero_tensor_fails_every_model_numerically():
 
 
 def test_nonneg_ranks_at_the_kernel_width_boundaries():
-    # the non-negative update is compiled for widths 8, 16, 24 and 32: ranks on both sides of each, and 1 and 32
+    # the non-negative update is compiled for widths 4, 8, ..., 32: ranks on both sides of each boundary, and 1 and 32
     dims = (37, 29, 23)
     T = np.ascontiguousarray(random_tensor(dims, 900, signed=True) * 0.25 +
                              np.einsum("ir,jr,kr->kji", *uniform_factors(dims, 5, 901)))
-    models = [_model(dims, r, 910 + r, flags=O.FLAG_NONNEG, max_iters=6) for r in (1, 8, 9, 16, 17, 24, 25, 32)]
+    models = [_model(dims, r, 910 + r, flags=O.FLAG_NONNEG, max_iters=6) for r in (1, 4, 5, 8, 9, 12, 13, 16, 17, 20, 21, 24, 25, 28, 29, 32)]
     R = sum(m["rank"] for m in models)
     ref = O.cals(T, models, R, 0)
     results, facs, st = run_gpu(T, models, R, 0, rounds_per_call=2)
