@@ -157,3 +157,38 @@ def test_two_step_mttkrp_matches_oracle_elementwise(dims, ranks, signed):
             err = np.abs(got[k] - want)
             assert np.all(np.isfinite(got[k]))
             assert np.all(err <= TOL * scale + 1e-300), (mode, pad, float((err / (scale + 1e-300)).max()))
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        dims = tuple(int(rng.choice([1, 2, 3, 5, 8, 15, 16, 17, 31, 32, 33, 48, 64, 65, 96, 100, 127, 128, 130])) for _ in range(3))
+        if dims[0] * dims[1] * dims[2] > 600000:
+            dims = (dims[0], min(dims[1], 33), dims[2])
+        total = int(rng.choice([1, 2, 7, 15, 16, 17, 31, 32, 33, 47, 48, 49, 63, 64, 65, 100, 112, 113, 130, 224, 225]))
+        ranks, left = [], total
+        while left > 0:
+            r = int(min(left, rng.integers(1, 33)))
+            ranks.append(r)
+            left -= r
+        out.append((dims, ranks, bool(rng.integers(0, 2)), int(rng.integers(0, 3))))
+    return out
+
+
+@pytest.mark.parametrize("dims,ranks,signed,padkind", _random_cases(36, 2024))
+def test_mttkrp_seeded_random_shapes(dims, ranks, signed, padkind):
+    # shapes and widths around every tile, stage, pairing and packing boundary of the kernel (16-row and 16-column
+    # tiles, 4-/16-index stages, two-rows-per-load in mode 1, packed production up to 64 columns), plain and two-step
+    T = random_tensor(dims, 11 + sum(dims), signed=signed)
+    U = _fused(dims, ranks, 200 + dims[2], signed=signed)
+    R = sum(ranks)
+    pad = [R, R + 1, (R + 15) // 16 * 16][padkind]
+    got = _gpu_mttkrp(T, U, pad_to=pad)
+    got2 = _gpu_mttkrp_reuse(T, U, pad_to=pad)
+    for mode in (1, 2, 3):
+        want = O.mttkrp(T, U, mode)
+        scale = _abs_scale(T, U, mode)
+        assert np.all(np.abs(got[mode - 1] - want) <= TOL * scale + 1e-300), (mode, "plain")
+        if mode > 1:
+            assert np.all(np.abs(got2[mode - 2] - want) <= TOL * scale + 1e-300), (mode, "two-step")
