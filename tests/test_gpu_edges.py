@@ -137,3 +137,31 @@ def test_cp_cals_driver_matches_per_model_oracle_runs():
                 a = U[n] * (lam[None, :] if n == 2 else 1.0)
                 b = ref["U"][n] * (ref["lam"][None, :] if n == 2 else 1.0)
                 assert (np.linalg.norm(a - b, axis=0) / np.linalg.norm(b, axis=0)).max() <= 1e-6
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_seeded_random_queues_match_oracle(seed):
+    # random small jobs: dims, ranks, tolerances, iteration caps, R*, slot limits and a mix of plain, non-negative and
+    # line-search models; with and without two-step sweeps.  Same bars as everywhere (compare()).
+    import paper_2010_04678_amd as P
+    rng = np.random.default_rng(5000 + seed)
+    dims = tuple(int(rng.choice([3, 8, 17, 24, 33, 40])) for _ in range(3))
+    if seed % 5 == 4:
+        dims = (int(rng.choice([260, 300, 513])), dims[1], min(dims[2], 8))      # a tall mode: row-blocked update
+    T = _lowrank_tensor(dims, int(rng.integers(2, 6)), 6000 + seed, noise=0.05)
+    if seed % 3 == 1:
+        T = np.ascontiguousarray(np.abs(T))
+    models = []
+    for k in range(int(rng.integers(3, 12))):
+        r = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 20, 32], p=[.1, .1, .1, .1, .1, .1, .08, .08, .08, .06, .04, .04, .02]))
+        kind = int(rng.choice([0, 1, 2], p=[.5, .25, .25]))
+        models.append(dict(rank=r, init=uniform_factors(dims, r, 7000 + 100 * seed + k),
+                           tol=float(rng.choice([-1.0, 1e-3, 1e-5])), max_iters=int(rng.integers(2, 26)),
+                           flags=[0, O.FLAG_NONNEG, O.FLAG_LINESEARCH][kind], ls_alpha=float(rng.choice([1.1, 1.3, 2.0]))))
+    rmax = max(m["rank"] for m in models)
+    rstar = int(rng.integers(rmax, rmax + 40))
+    slots = int(rng.choice([0, 2, 3, 5]))
+    ref = O.cals(T, models, rstar, slots)
+    for flags in (0, P.CTX_REUSE):
+        results, facs, st = run_gpu(T, models, rstar, slots, rounds_per_call=int(rng.integers(1, 9)), ctx_flags=flags)
+        compare(results, facs, ref, models)
