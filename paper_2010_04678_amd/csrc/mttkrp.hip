@@ -134,14 +134,22 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
   const int force_splits = env_int("CALS_MTTKRP_SPLITS", 0);
   const double us_per_tile_stage = 4.0 * 64.0 / 2400.0 / 0.8;          // one accumulator tile, one stage (KA = 16)
   const double panel_us = (double)p.In * p.ncols * 8.0 / 3.0e6;        // one In x ncols panel through memory
+  // the tensor once per column block at the practical read rate, reached with two or more workgroups per CU
+  // (tensors of up to 1 GiB are largely served by the last-level cache: about twice the rate)
+  const double tensor_bytes = (double)p.In * (double)K * 8.0;
+  const double tensor_us = tensor_bytes / (tensor_bytes > 1073741824.0 ? 5.5e6 : 11.0e6);
   int64_t splits = 1;
   double best_cost = 1e300;
   for (int64_t cand = 1; cand <= std::min<int64_t>(max_splits, 4096); cand = (cand < 8) ? cand + 1 : cand + 8) {
     const int64_t pairs = (K + cand * 2 * pl.ka - 1) / (cand * 2 * pl.ka);
     double cost = 0.0;
     for (int q = 0; q < pl.nparts; ++q) {
-      const int64_t waves = ((int64_t)pl.mtiles * pl.part[q].ny * cand + slots - 1) / slots;
-      cost += (double)waves * (2.0 * pairs + 6.0) * us_per_tile_stage * wm * pl.part[q].wn;
+      const int64_t wgs = (int64_t)pl.mtiles * pl.part[q].ny * cand;
+      const int64_t waves = (wgs + slots - 1) / slots;
+      const double mfma_us = (double)waves * (2.0 * pairs + 6.0) * us_per_tile_stage * wm * pl.part[q].wn;
+      const double fill = wgs >= 2 * (int64_t)num_cus ? 1.0 : (double)(2 * num_cus) / (double)wgs;
+      const double hbm_us = tensor_us * pl.part[q].ny * fill;
+      cost += mfma_us > hbm_us ? mfma_us : hbm_us;
     }
     if (cand > 1) cost += (2.0 * cand + 1.0) * panel_us;
     if (cost < best_cost) { best_cost = cost; splits = cand; }
