@@ -284,7 +284,7 @@ __device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDes
   }
 }
 
-// Ranks above 16: the same steps with the factor and the row vectors in LDS (the register arrays of the path above
+// Ranks above 20: the same steps with the factor and the row vectors in LDS (the register arrays of the path above
 // would not fit next to each other for every rank in one kernel).
 __device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d, double* lds, int* flagp) {
   ModelState* st = a.state + d.sid;
@@ -410,6 +410,7 @@ __global__ void __launch_bounds__(256) update_kernel(UpdateArgs a) {
     case 2: update_small<8>(a, d, blockIdx.x, lds, &flag); break;
     case 3: update_small<12>(a, d, blockIdx.x, lds, &flag); break;
     case 4: update_small<16>(a, d, blockIdx.x, lds, &flag); break;
+    case 5: update_small<20>(a, d, blockIdx.x, lds, &flag); break;
     default: update_wide(a, d, lds, &flag); break;
   }
 }
