@@ -1,5 +1,7 @@
 /*
- * cals_oracle.c -- plain CPU reference ("oracle") for Concurrent ALS on a dense 3-way fp64 tensor.
+ * cals_oracle.c -- plain CPU reference ("oracle") for Concurrent ALS on a dense fp64 tensor of order 3
+ * (the routines without a suffix) or of any order from 3 to ORACLE_MAX_MODES (the routines ending in _nd; Alg. 1
+ * is stated for N modes).
  *
  * THIS IS TEST INFRASTRUCTURE.  It is the slow, obviously-correct statement of what the GPU
  * path must compute.  Only the test-suite, the smoke check and the benchmark's CPU-baseline
@@ -9,7 +11,8 @@
  *   - MTTKRP by its element-wise definition (Alg. 1, the MTTKRP line; Sec. 3.1):
  *       M(n)[i_n, r] = sum over the other two indices of T[i1,i2,i3] * (Ua[ia,r] * Ub[ib,r]).
  *     The fused multi-model MTTKRP of Eq. (2) is this same definition applied to the
- *     concatenated factor matrices, so one routine serves both.
+ *     concatenated factor matrices, so one routine serves both.  For N modes the product runs over
+ *     the N-1 other factor matrices and the sum over the N-1 other indices (the _nd routines).
  *   - Hadamard product of Gramians, the normal-equation update, and the fast error formula
  *     (Alg. 1, remaining lines), per model (Alg. 2: "instances are treated separately").
  *   - Queue handling of Alg. 3: fill from the queue front until the next model does not fit,
@@ -29,8 +32,11 @@
  *   - every column of an updated factor is scaled to unit 2-norm, the norms kept in lambda.
  *   - non-negativity: Lawson-Hanson active set on the normal equations per row; the passive set of the
  *     previous iteration is a warm start that is dropped when its sub-block of H is not positive definite.
- *   - sums over the two contracted indices are nested: the inner sum runs over the lower-
- *     numbered contracted mode into a fresh accumulator, the outer sum adds those up.
+ *   - order 3: sums over the two contracted indices are nested: the inner sum runs over the lower-
+ *     numbered contracted mode into a fresh accumulator, the outer sum adds those up.  Higher orders:
+ *     one running sum per output element over the contracted indices in memory order.
+ *   - for N modes the error terms come from the update of mode N, and line search folds lambda into
+ *     the factor of mode N (for N = 3 this is what the order-3 routines always did).
  *
  * Pins: every routine below is pinned in the CPU test-suite by something other than itself -- brute force on
  * tiny inputs, identities, closed forms, special cases that reduce to library routines (LAPACK Cholesky and
@@ -57,6 +63,7 @@
 #define ORACLE_FLAG_LINESEARCH 2u
 
 #define ORACLE_MAX_RANK 32
+#define ORACLE_MAX_MODES 6
 
 /* ------------------------------------------------------------------------------------------ */
 /* small dense helpers                                                                         */
@@ -79,6 +86,26 @@ double oracle_norm_sq(const double* T, const int64_t* dims) {
     for (int64_t i2 = 0; i2 < I2; ++i2) {
       double fibre = 0.0;
       const double* t = T + I1 * (i2 + I2 * i3);
+      for (int64_t i1 = 0; i1 < I1; ++i1) fibre += t[i1] * t[i1];
+      slab += fibre;
+    }
+    total += slab;
+  }
+  return total;
+}
+
+/* ||T||^2 of an order-N tensor: fibres along the first index, summed per value of the last index, then added up
+ * (for N = 3 the same order of additions as oracle_norm_sq). */
+double oracle_norm_sq_nd(const double* T, int N, const int64_t* dims) {
+  const int64_t I1 = dims[0], IN = dims[N - 1];
+  int64_t fibres = 1;
+  for (int n = 1; n < N - 1; ++n) fibres *= dims[n];
+  double total = 0.0;
+  for (int64_t s = 0; s < IN; ++s) {
+    double slab = 0.0;
+    for (int64_t f = 0; f < fibres; ++f) {
+      double fibre = 0.0;
+      const double* t = T + I1 * (f + fibres * s);
       for (int64_t i1 = 0; i1 < I1; ++i1) fibre += t[i1] * t[i1];
       slab += fibre;
     }
@@ -249,6 +276,86 @@ void oracle_mttkrp_element(const double* T, const int64_t* dims, int mode, const
   *abs_sum = (double)sa;
 }
 
+/* Order-N MTTKRP by its definition (Alg. 1, the MTTKRP line, for N modes; mode = 1..N):
+ *   M[i_mode, r] = sum over all other indices of T[i_1,...,i_N] * prod_{m != mode} U_m[i_m, r].
+ * The tensor is walked once in memory order (first index fastest); every element adds its term straight into the
+ * output element it belongs to, so each output element is one running sum over the contracted indices in memory
+ * order.  The product of factor entries is taken in increasing mode order.  Columns [c0, c0+nc); M is column-major
+ * with ld = I_mode and is written from its first column on. */
+static void mttkrp_columns_nd(const double* T, int N, const int64_t* dims, int mode, const double* const* U,
+                              int64_t c0, int nc, double* M) {
+  const int n = mode - 1;
+  const int64_t In = dims[n];
+  int64_t idx[ORACLE_MAX_MODES];
+  int64_t total = 1;
+  for (int m = 0; m < N; ++m) { idx[m] = 0; total *= dims[m]; }
+  for (int64_t e = 0; e < In * nc; ++e) M[e] = 0.0;
+  for (int64_t e = 0; e < total; ++e) {
+    const double tv = T[e];
+    for (int r = 0; r < nc; ++r) {
+      double k = 1.0;
+      int first = 1;
+      for (int m = 0; m < N; ++m) {
+        if (m == n) continue;
+        const double u = U[m][idx[m] + dims[m] * (c0 + r)];
+        k = first ? u : k * u;
+        first = 0;
+      }
+      M[idx[n] + In * r] += tv * k;
+    }
+    for (int m = 0; m < N; ++m) {             /* next index tuple, first index fastest */
+      if (++idx[m] < dims[m]) break;
+      idx[m] = 0;
+    }
+  }
+}
+
+/* Order-N MTTKRP for R columns (any R; fused or not), columns handed out to threads in blocks. */
+void oracle_mttkrp_nd(const double* T, int N, const int64_t* dims, int mode, int64_t R, const double* const* U,
+                      double* M) {
+  const int64_t In = dims[mode - 1];
+  const int blk = 8;
+  const int64_t nblk = (R + blk - 1) / blk;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t b = 0; b < nblk; ++b) {
+    const int64_t c0 = b * blk;
+    const int nc = (int)((R - c0 < blk) ? (R - c0) : blk);
+    mttkrp_columns_nd(T, N, dims, mode, U, c0, nc, M + In * c0);
+  }
+}
+
+/* One element of the order-N MTTKRP in extended precision, and the sum of the absolute values of its terms. */
+void oracle_mttkrp_element_nd(const double* T, int N, const int64_t* dims, int mode, const double* const* U,
+                              int64_t row, int64_t col, double* value, double* abs_sum) {
+  const int n = mode - 1;
+  int64_t idx[ORACLE_MAX_MODES], stride[ORACLE_MAX_MODES];
+  int64_t others = 1, s = 1;
+  for (int m = 0; m < N; ++m) { idx[m] = 0; stride[m] = s; s *= dims[m]; if (m != n) others *= dims[m]; }
+  idx[n] = row;
+  long double acc = 0.0L, aabs = 0.0L;
+  for (int64_t e = 0; e < others; ++e) {
+    int64_t off = 0;
+    double k = 1.0;
+    int first = 1;
+    for (int m = 0; m < N; ++m) {
+      off += idx[m] * stride[m];
+      if (m == n) continue;
+      const double u = U[m][idx[m] + dims[m] * col];
+      k = first ? u : k * u;
+      first = 0;
+    }
+    const long double term = (long double)T[off] * (long double)k;
+    acc += term; aabs += fabsl(term);
+    for (int m = 0; m < N; ++m) {
+      if (m == n) continue;
+      if (++idx[m] < dims[m]) break;
+      idx[m] = 0;
+    }
+  }
+  *value = (double)acc;
+  *abs_sum = (double)aabs;
+}
+
 /* ------------------------------------------------------------------------------------------ */
 /* Non-negative least squares on the normal equations, one row (Sec. 5, active-set method)     */
 /* ------------------------------------------------------------------------------------------ */
@@ -334,31 +441,32 @@ int oracle_nnls_row(const double* H, const double* m, int R, double* x, uint32_t
 /* ------------------------------------------------------------------------------------------ */
 
 typedef struct oracle_model {
-  int64_t I[3];
+  int N;                /* number of modes (3 for the routines without the _nd suffix) */
+  int64_t I[ORACLE_MAX_MODES];
   int R;
-  double* U[3];        /* current factors, column-major I_n x R */
-  double* M;           /* MTTKRP result, max(I_n) x R */
-  double* G[3];        /* Gramians of the current factors */
+  double* U[ORACLE_MAX_MODES];   /* current factors, column-major I_n x R */
+  double* M;                     /* MTTKRP result, max(I_n) x R */
+  double* G[ORACLE_MAX_MODES];   /* Gramians of the current factors */
   double lambda[ORACLE_MAX_RANK];
   double fit, fit_prev, err;
   double tol, alpha;
   int max_iters, iters, status;
   uint32_t flags;
-  uint32_t* passive[3]; /* NONNEG: per-row passive sets, kept between iterations */
-  double* Aprev[3];     /* LINESEARCH: the point after the previous iteration */
-  double* Anew[3];
+  uint32_t* passive[ORACLE_MAX_MODES]; /* NONNEG: per-row passive sets, kept between iterations */
+  double* Aprev[ORACLE_MAX_MODES];     /* LINESEARCH: the point after the previous iteration */
+  double* Anew[ORACLE_MAX_MODES];
   int ls_accepted;      /* number of accepted extrapolations */
   double* scratch;
 } oracle_model;
 
-oracle_model* oracle_model_create(const int64_t* dims, int R, const double* U1, const double* U2, const double* U3,
-                                  double tol, int max_iters, uint32_t flags, double alpha) {
-  if (R < 1 || R > ORACLE_MAX_RANK) return NULL;
+oracle_model* oracle_model_create_nd(int N, const int64_t* dims, int R, const double* const* init, double tol,
+                                     int max_iters, uint32_t flags, double alpha) {
+  if (R < 1 || R > ORACLE_MAX_RANK || N < 3 || N > ORACLE_MAX_MODES) return NULL;
   oracle_model* m = (oracle_model*)calloc(1, sizeof(oracle_model));
-  const double* init[3] = {U1, U2, U3};
   int64_t imax = 0;
+  m->N = N;
   m->R = R;
-  for (int n = 0; n < 3; ++n) {
+  for (int n = 0; n < N; ++n) {
     m->I[n] = dims[n];
     if (dims[n] > imax) imax = dims[n];
     m->U[n] = (double*)malloc(sizeof(double) * (size_t)(dims[n] * R));
@@ -379,15 +487,35 @@ oracle_model* oracle_model_create(const int64_t* dims, int R, const double* U1, 
   return m;
 }
 
+oracle_model* oracle_model_create(const int64_t* dims, int R, const double* U1, const double* U2, const double* U3,
+                                  double tol, int max_iters, uint32_t flags, double alpha) {
+  const double* init[3] = {U1, U2, U3};
+  return oracle_model_create_nd(3, dims, R, init, tol, max_iters, flags, alpha);
+}
+
 void oracle_model_destroy(oracle_model* m) {
   if (!m) return;
-  for (int n = 0; n < 3; ++n) { free(m->U[n]); free(m->G[n]); free(m->passive[n]); free(m->Aprev[n]); free(m->Anew[n]); }
+  for (int n = 0; n < m->N; ++n) { free(m->U[n]); free(m->G[n]); free(m->passive[n]); free(m->Aprev[n]); free(m->Anew[n]); }
   free(m->M); free(m->scratch); free(m);
 }
 
-static void single_mttkrp(const double* T, const oracle_model* m, int mode, const double* const U[3], double* M,
+/* MTTKRP of one model: order 3 by the nested sums of mttkrp_columns, higher orders by mttkrp_columns_nd. */
+static void single_mttkrp(const double* T, const oracle_model* m, int mode, const double* const* U, double* M,
                           double* scratch) {
-  mttkrp_columns(T, m->I, mode, U[0], U[1], U[2], 0, m->R, M, scratch);
+  if (m->N == 3) mttkrp_columns(T, m->I, mode, U[0], U[1], U[2], 0, m->R, M, scratch);
+  else mttkrp_columns_nd(T, m->N, m->I, mode, U, 0, m->R, M);
+}
+
+/* H = Hadamard product of the Gramians of all modes but n, multiplied up in increasing mode order
+ * (Alg. 1, Hadamard line). */
+static void hadamard_of_others(double* const* G, int N, int n, int R, double* H) {
+  int first = 1;
+  for (int k = 0; k < N; ++k) {
+    if (k == n) continue;
+    if (first) memcpy(H, G[k], sizeof(double) * (size_t)(R * R));
+    else oracle_hadamard(H, G[k], R, H);
+    first = 0;
+  }
 }
 
 /* e = ||T||^2 + normsq - 2 inner  ->  fit (Alg. 1, error line, with the corrected sign). */
@@ -395,21 +523,19 @@ static double fit_from_error(double err, double normT2) {
   return 1.0 - sqrt(err > 0.0 ? err : 0.0) / sqrt(normT2);
 }
 
-/* Advance one iteration (one update of all three modes, then error, fit and the stop test).
+/* Advance one iteration (one update of every mode, then error, fit and the stop test).
  * Returns the status after the iteration (RUNNING means "not stopped"). */
 int oracle_model_iterate(oracle_model* m, const double* T, double normT2) {
   if (m->status != ORACLE_RUNNING) return m->status;
-  const int R = m->R;
+  const int R = m->R, N = m->N, last = m->N - 1;
   double H[ORACLE_MAX_RANK * ORACLE_MAX_RANK], L[ORACLE_MAX_RANK * ORACLE_MAX_RANK];
   double Gt[ORACLE_MAX_RANK * ORACLE_MAX_RANK], row[ORACLE_MAX_RANK];
   double inner = 0.0, normsq = 0.0;
   m->iters += 1;
-  for (int n = 0; n < 3; ++n) {
-    const int a = (n == 0) ? 1 : 0, b = (n == 2) ? 1 : 2;
+  for (int n = 0; n < N; ++n) {
     const int64_t In = m->I[n];
-    const double* const Ucur[3] = {m->U[0], m->U[1], m->U[2]};
-    single_mttkrp(T, m, n + 1, Ucur, m->M, m->scratch);                    /* MTTKRP            */
-    oracle_hadamard(m->G[a], m->G[b], R, H);                               /* H = Ga * Gb       */
+    single_mttkrp(T, m, n + 1, (const double* const*)m->U, m->M, m->scratch); /* MTTKRP           */
+    hadamard_of_others(m->G, N, n, R, H);                                  /* H = * of Gramians */
     if (m->flags & ORACLE_FLAG_NONNEG) {                                   /* update, x >= 0    */
       double* Unew = m->scratch;
       int bad = 0;
@@ -430,13 +556,13 @@ int oracle_model_iterate(oracle_model* m, const double* T, double normT2) {
         for (int r = 0; r < R; ++r) m->U[n][i + In * r] = row[r];
       }
     }
-    if (n == 2) {                                                          /* error terms        */
+    if (n == last) {                                                       /* error terms        */
       for (int r = 0; r < R; ++r) {
         double col = 0.0;
-        for (int64_t i = 0; i < In; ++i) col += m->U[2][i + In * r] * m->M[i + In * r];
+        for (int64_t i = 0; i < In; ++i) col += m->U[last][i + In * r] * m->M[i + In * r];
         inner += col;
       }
-      oracle_gram(m->U[2], In, R, Gt);
+      oracle_gram(m->U[last], In, R, Gt);
       for (int e = 0; e < R * R; ++e) normsq += H[e] * Gt[e];
     }
     for (int r = 0; r < R; ++r) {                                          /* unit columns       */
@@ -454,13 +580,13 @@ int oracle_model_iterate(oracle_model* m, const double* T, double normT2) {
 
   if (m->flags & ORACLE_FLAG_LINESEARCH) {
     /* Sec. 5, line search: P_new = P_prev + alpha (P_cur - P_prev), kept only if its error is
-     * lower.  A point is represented with lambda folded into the mode-3 factor. */
-    const int64_t I3 = m->I[2];
+     * lower.  A point is represented with lambda folded into the factor of the last mode. */
+    const int64_t IN = m->I[last];
     if (m->iters >= 2) {
-      for (int n = 0; n < 3; ++n) {
+      for (int n = 0; n < N; ++n) {
         const int64_t In = m->I[n];
         for (int r = 0; r < R; ++r) {
-          const double scale = (n == 2) ? m->lambda[r] : 1.0;
+          const double scale = (n == last) ? m->lambda[r] : 1.0;
           for (int64_t i = 0; i < In; ++i) {
             const double cur = m->U[n][i + In * r] * scale;
             const double prev = m->Aprev[n][i + In * r];
@@ -468,35 +594,36 @@ int oracle_model_iterate(oracle_model* m, const double* T, double normT2) {
           }
         }
       }
-      const double* const Un[3] = {m->Anew[0], m->Anew[1], m->Anew[2]};
-      single_mttkrp(T, m, 3, Un, m->M, m->scratch);
+      single_mttkrp(T, m, N, (const double* const*)m->Anew, m->M, m->scratch);
       double inner2 = 0.0, normsq2 = 0.0;
       for (int r = 0; r < R; ++r) {
         double col = 0.0;
-        for (int64_t i = 0; i < I3; ++i) col += m->Anew[2][i + I3 * r] * m->M[i + I3 * r];
+        for (int64_t i = 0; i < IN; ++i) col += m->Anew[last][i + IN * r] * m->M[i + IN * r];
         inner2 += col;
       }
-      double G1[ORACLE_MAX_RANK * ORACLE_MAX_RANK], G2[ORACLE_MAX_RANK * ORACLE_MAX_RANK];
-      oracle_gram(m->Anew[0], m->I[0], R, G1);
-      oracle_gram(m->Anew[1], m->I[1], R, G2);
-      oracle_gram(m->Anew[2], m->I[2], R, Gt);
-      for (int e = 0; e < R * R; ++e) normsq2 += (G1[e] * G2[e]) * Gt[e];
+      double Gn[ORACLE_MAX_MODES][ORACLE_MAX_RANK * ORACLE_MAX_RANK];
+      for (int n = 0; n < N; ++n) oracle_gram(m->Anew[n], m->I[n], R, Gn[n]);
+      for (int e = 0; e < R * R; ++e) {
+        double h = Gn[0][e];
+        for (int n = 1; n < N; ++n) h = h * Gn[n][e];
+        normsq2 += h;
+      }
       const double err2 = normT2 + normsq2 - 2.0 * inner2;
       if (err2 < m->err) {
-        for (int n = 0; n < 3; ++n) memcpy(m->U[n], m->Anew[n], sizeof(double) * (size_t)(m->I[n] * R));
-        memcpy(m->G[0], G1, sizeof(double) * (size_t)(R * R));
-        memcpy(m->G[1], G2, sizeof(double) * (size_t)(R * R));
-        memcpy(m->G[2], Gt, sizeof(double) * (size_t)(R * R));
+        for (int n = 0; n < N; ++n) {
+          memcpy(m->U[n], m->Anew[n], sizeof(double) * (size_t)(m->I[n] * R));
+          memcpy(m->G[n], Gn[n], sizeof(double) * (size_t)(R * R));
+        }
         for (int r = 0; r < R; ++r) m->lambda[r] = 1.0;
         m->err = err2;
         m->fit = fit_from_error(err2, normT2);
         m->ls_accepted += 1;
       }
     }
-    for (int n = 0; n < 3; ++n) {
+    for (int n = 0; n < N; ++n) {
       const int64_t In = m->I[n];
       for (int r = 0; r < R; ++r) {
-        const double scale = (n == 2) ? m->lambda[r] : 1.0;
+        const double scale = (n == last) ? m->lambda[r] : 1.0;
         for (int64_t i = 0; i < In; ++i) m->Aprev[n][i + In * r] = m->U[n][i + In * r] * scale;
       }
     }
@@ -508,17 +635,24 @@ int oracle_model_iterate(oracle_model* m, const double* T, double normT2) {
   return m->status;
 }
 
-void oracle_model_get(const oracle_model* m, double* U1, double* U2, double* U3, double* lambda, double* fit,
-                      double* err, int* iters, int* status, int* ls_accepted) {
-  double* out[3] = {U1, U2, U3};
-  for (int n = 0; n < 3; ++n)
-    if (out[n]) memcpy(out[n], m->U[n], sizeof(double) * (size_t)(m->I[n] * m->R));
+/* out[n] (n < N; entries may be NULL) receive the factors. */
+void oracle_model_get_nd(const oracle_model* m, double* const* out, double* lambda, double* fit, double* err,
+                         int* iters, int* status, int* ls_accepted) {
+  if (out)
+    for (int n = 0; n < m->N; ++n)
+      if (out[n]) memcpy(out[n], m->U[n], sizeof(double) * (size_t)(m->I[n] * m->R));
   if (lambda) memcpy(lambda, m->lambda, sizeof(double) * (size_t)m->R);
   if (fit) *fit = m->fit;
   if (err) *err = m->err;
   if (iters) *iters = m->iters;
   if (status) *status = m->status;
   if (ls_accepted) *ls_accepted = m->ls_accepted;
+}
+
+void oracle_model_get(const oracle_model* m, double* U1, double* U2, double* U3, double* lambda, double* fit,
+                      double* err, int* iters, int* status, int* ls_accepted) {
+  double* out[3] = {U1, U2, U3};
+  oracle_model_get_nd(m, out, lambda, fit, err, iters, status, ls_accepted);
 }
 
 /* Plain CP-ALS (Alg. 1) for one starting point: iterate until it stops.  fit_history, when
@@ -541,22 +675,23 @@ int oracle_cp_als(const double* T, const int64_t* dims, double normT2, int R, do
 /* CALS, full algorithm (Alg. 3): queue in, lock-step iterations, queue out                    */
 /* ------------------------------------------------------------------------------------------ */
 
-/* Models are queued in index order 0..n_models-1.  inits[3*k + n] is model k's mode-(n+1)
- * starting factor; outs[3*k + n] receives its final factor (may be NULL).  A model fits if
+/* Models are queued in index order 0..n_models-1.  inits[N*k + n] is model k's mode-(n+1)
+ * starting factor; outs[N*k + n] receives its final factor (may be NULL).  A model fits if
  * the sum of active ranks plus its rank is at most max_total_rank and (max_slots == 0 or)
  * fewer than max_slots models are active.  retire_order receives the model indices in the
  * order they leave; total_rank_log (optional, one entry per round up to max_rounds) the
  * fused width of each round.  Returns the number of rounds, or -1 on a bad argument
  * (including a model that can never fit, which would block the queue for ever). */
-int64_t oracle_cals(const double* T, const int64_t* dims, int n_models, const int32_t* ranks,
-                    const double* const* inits, const double* tol, const int32_t* max_iters,
-                    const uint32_t* flags, const double* alpha, int64_t max_total_rank, int max_slots,
-                    double* const* outs, double* lambdas /* n_models x ORACLE_MAX_RANK */, double* fit, double* err,
-                    int32_t* iters, int32_t* status, int32_t* retire_order, int32_t* total_rank_log,
-                    int64_t max_rounds) {
+int64_t oracle_cals_nd(const double* T, int N, const int64_t* dims, int n_models, const int32_t* ranks,
+                       const double* const* inits, const double* tol, const int32_t* max_iters,
+                       const uint32_t* flags, const double* alpha, int64_t max_total_rank, int max_slots,
+                       double* const* outs, double* lambdas /* n_models x ORACLE_MAX_RANK */, double* fit, double* err,
+                       int32_t* iters, int32_t* status, int32_t* retire_order, int32_t* total_rank_log,
+                       int64_t max_rounds) {
+  if (N < 3 || N > ORACLE_MAX_MODES) return -1;
   for (int k = 0; k < n_models; ++k)
     if (ranks[k] < 1 || ranks[k] > ORACLE_MAX_RANK || ranks[k] > max_total_rank) return -1;
-  const double normT2 = oracle_norm_sq(T, dims);
+  const double normT2 = (N == 3) ? oracle_norm_sq(T, dims) : oracle_norm_sq_nd(T, N, dims);
   oracle_model** slot = (oracle_model**)calloc((size_t)(n_models > 0 ? n_models : 1), sizeof(oracle_model*));
   int* slot_id = (int*)calloc((size_t)(n_models > 0 ? n_models : 1), sizeof(int));
   int n_active = 0, next = 0, n_retired = 0;
@@ -566,8 +701,8 @@ int64_t oracle_cals(const double* T, const int64_t* dims, int n_models, const in
     while (next < n_models) {
       const int r = ranks[next];
       if (rtot + r > max_total_rank || (max_slots > 0 && n_active >= max_slots)) break;
-      slot[n_active] = oracle_model_create(dims, r, inits[3 * next], inits[3 * next + 1], inits[3 * next + 2],
-                                           tol[next], max_iters[next], flags[next], alpha[next]);
+      slot[n_active] = oracle_model_create_nd(N, dims, r, inits + (size_t)N * next, tol[next], max_iters[next],
+                                              flags[next], alpha[next]);
       slot_id[n_active] = next;
       n_active += 1; rtot += r; next += 1;
     }
@@ -581,9 +716,9 @@ int64_t oracle_cals(const double* T, const int64_t* dims, int n_models, const in
       oracle_model* m = slot[s];
       const int k = slot_id[s];
       if (m->status != ORACLE_RUNNING) {
-        oracle_model_get(m, outs ? outs[3 * k] : NULL, outs ? outs[3 * k + 1] : NULL, outs ? outs[3 * k + 2] : NULL,
-                         lambdas ? lambdas + (size_t)k * ORACLE_MAX_RANK : NULL, fit ? fit + k : NULL,
-                         err ? err + k : NULL, iters ? iters + k : NULL, status ? status + k : NULL, NULL);
+        oracle_model_get_nd(m, outs ? outs + (size_t)N * k : NULL,
+                            lambdas ? lambdas + (size_t)k * ORACLE_MAX_RANK : NULL, fit ? fit + k : NULL,
+                            err ? err + k : NULL, iters ? iters + k : NULL, status ? status + k : NULL, NULL);
         retire_order[n_retired++] = k;
         rtot -= m->R;
         oracle_model_destroy(m);
@@ -596,4 +731,14 @@ int64_t oracle_cals(const double* T, const int64_t* dims, int n_models, const in
   }
   free(slot); free(slot_id);
   return rounds;
+}
+
+int64_t oracle_cals(const double* T, const int64_t* dims, int n_models, const int32_t* ranks,
+                    const double* const* inits, const double* tol, const int32_t* max_iters,
+                    const uint32_t* flags, const double* alpha, int64_t max_total_rank, int max_slots,
+                    double* const* outs, double* lambdas /* n_models x ORACLE_MAX_RANK */, double* fit, double* err,
+                    int32_t* iters, int32_t* status, int32_t* retire_order, int32_t* total_rank_log,
+                    int64_t max_rounds) {
+  return oracle_cals_nd(T, 3, dims, n_models, ranks, inits, tol, max_iters, flags, alpha, max_total_rank, max_slots,
+                        outs, lambdas, fit, err, iters, status, retire_order, total_rank_log, max_rounds);
 }

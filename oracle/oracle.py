@@ -1,8 +1,9 @@
 """ctypes front-end of the C oracle (oracle/cals_oracle.c).  TEST INFRASTRUCTURE.
 
-All arrays are numpy float64.  Tensors are C-contiguous of shape (I3, I2, I1) (first index
-fastest in memory); factor matrices are (I_n, R), converted to column-major on the way in and
-returned Fortran-ordered.  Nothing here imports or calls the GPU package.
+All arrays are numpy float64.  Tensors are C-contiguous of shape (I_N, ..., I2, I1) (first index
+fastest in memory), N = 3 ... MAX_MODES; factor matrices are (I_n, R), converted to column-major on
+the way in and returned Fortran-ordered.  Order-3 tensors go to the C routines without a suffix,
+higher orders to the ones ending in _nd.  Nothing here imports or calls the GPU package.
 """
 from __future__ import annotations
 
@@ -16,8 +17,9 @@ from . import build as _build
 RUNNING, CONVERGED, MAX_ITERS, NUMERICAL = 0, 1, 2, 3
 FLAG_NONNEG, FLAG_LINESEARCH = 1, 2
 MAX_RANK = 32
+MAX_MODES = 6
 
-__all__ = ["RUNNING", "CONVERGED", "MAX_ITERS", "NUMERICAL", "FLAG_NONNEG", "FLAG_LINESEARCH", "MAX_RANK",
+__all__ = ["RUNNING", "CONVERGED", "MAX_ITERS", "NUMERICAL", "FLAG_NONNEG", "FLAG_LINESEARCH", "MAX_RANK", "MAX_MODES",
            "num_threads", "norm_sq", "gram", "hadamard", "cholesky", "cholesky_solve", "mttkrp", "mttkrp_element",
            "nnls_row", "Model", "cp_als", "cals"]
 
@@ -53,6 +55,17 @@ def lib() -> C.CDLL:
         L.oracle_cals.restype = C.c_int64
         L.oracle_cals.argtypes = [_dp, _i64p, C.c_int, _i32p, C.POINTER(_dp), _dp, _i32p, _u32p, _dp, C.c_int64,
                                   C.c_int, C.POINTER(_dp), _dp, _dp, _dp, _i32p, _i32p, _i32p, _i32p, C.c_int64]
+        _pp = C.POINTER(_dp)
+        L.oracle_norm_sq_nd.restype = C.c_double
+        L.oracle_norm_sq_nd.argtypes = [_dp, C.c_int, _i64p]
+        L.oracle_mttkrp_nd.argtypes = [_dp, C.c_int, _i64p, C.c_int, C.c_int64, _pp, _dp]
+        L.oracle_mttkrp_element_nd.argtypes = [_dp, C.c_int, _i64p, C.c_int, _pp, C.c_int64, C.c_int64, _dp, _dp]
+        L.oracle_model_create_nd.restype = C.c_void_p
+        L.oracle_model_create_nd.argtypes = [C.c_int, _i64p, C.c_int, _pp, C.c_double, C.c_int, C.c_uint32, C.c_double]
+        L.oracle_model_get_nd.argtypes = [C.c_void_p, _pp, _dp, _dp, _dp, _i32p, _i32p, _i32p]
+        L.oracle_cals_nd.restype = C.c_int64
+        L.oracle_cals_nd.argtypes = [_dp, C.c_int, _i64p, C.c_int, _i32p, _pp, _dp, _i32p, _u32p, _dp, C.c_int64,
+                                     C.c_int, _pp, _dp, _dp, _dp, _i32p, _i32p, _i32p, _i32p, C.c_int64]
         _lib = L
     return _lib
 
@@ -62,9 +75,13 @@ def _p(a: np.ndarray):
 
 
 def _tensor(T: np.ndarray):
-    assert T.dtype == np.float64 and T.ndim == 3 and T.flags.c_contiguous
-    dims = np.array([T.shape[2], T.shape[1], T.shape[0]], dtype=np.int64)
+    assert T.dtype == np.float64 and 3 <= T.ndim <= MAX_MODES and T.flags.c_contiguous
+    dims = np.array(T.shape[::-1], dtype=np.int64)
     return T, dims
+
+
+def _ptrs(mats):
+    return (_dp * len(mats))(*[_p(u) for u in mats])
 
 
 def _f(U: np.ndarray) -> np.ndarray:
@@ -77,6 +94,8 @@ def num_threads() -> int:
 
 def norm_sq(T: np.ndarray) -> float:
     T, dims = _tensor(T)
+    if T.ndim != 3:
+        return float(lib().oracle_norm_sq_nd(_p(T), T.ndim, dims.ctypes.data_as(_i64p)))
     return float(lib().oracle_norm_sq(_p(T), dims.ctypes.data_as(_i64p)))
 
 
@@ -109,13 +128,17 @@ def cholesky_solve(L: np.ndarray, b: np.ndarray) -> np.ndarray:
 
 
 def mttkrp(T: np.ndarray, U: Sequence[np.ndarray], mode: int) -> np.ndarray:
-    """Mode-`mode` (1..3) MTTKRP by definition; U are (I_n, R) with any common R (fused or not)."""
+    """Mode-`mode` (1..N) MTTKRP by definition; U are (I_n, R) with any common R (fused or not)."""
     T, dims = _tensor(T)
     Uf = [_f(u) for u in U]
     R = Uf[0].shape[1]
-    for n in range(3):
+    assert len(Uf) == T.ndim and 1 <= mode <= T.ndim
+    for n in range(T.ndim):
         assert Uf[n].shape == (dims[n], R)
     M = np.zeros((int(dims[mode - 1]), R), order="F")
+    if T.ndim != 3:
+        lib().oracle_mttkrp_nd(_p(T), T.ndim, dims.ctypes.data_as(_i64p), mode, R, _ptrs(Uf), _p(M))
+        return M
     lib().oracle_mttkrp(_p(T), dims.ctypes.data_as(_i64p), mode, R, _p(Uf[0]), _p(Uf[1]), _p(Uf[2]), _p(M))
     return M
 
@@ -125,6 +148,10 @@ def mttkrp_element(T: np.ndarray, U: Sequence[np.ndarray], mode: int, row: int, 
     T, dims = _tensor(T)
     Uf = [_f(u) for u in U]
     v, a = C.c_double(), C.c_double()
+    if T.ndim != 3:
+        lib().oracle_mttkrp_element_nd(_p(T), T.ndim, dims.ctypes.data_as(_i64p), mode, _ptrs(Uf), int(row), int(col),
+                                       C.byref(v), C.byref(a))
+        return v.value, a.value
     lib().oracle_mttkrp_element(_p(T), dims.ctypes.data_as(_i64p), mode, _p(Uf[0]), _p(Uf[1]), _p(Uf[2]),
                                 int(row), int(col), C.byref(v), C.byref(a))
     return v.value, a.value
@@ -148,8 +175,13 @@ class Model:
         self.R = int(init[0].shape[1])
         U = [_f(u) for u in init]
         self.normT2 = norm_sq(T) if normT2 is None else float(normT2)
-        self.h = lib().oracle_model_create(self.dims.ctypes.data_as(_i64p), self.R, _p(U[0]), _p(U[1]), _p(U[2]),
-                                           float(tol), int(max_iters), int(flags), float(alpha))
+        assert len(U) == self.T.ndim
+        if self.T.ndim != 3:
+            self.h = lib().oracle_model_create_nd(self.T.ndim, self.dims.ctypes.data_as(_i64p), self.R, _ptrs(U),
+                                                  float(tol), int(max_iters), int(flags), float(alpha))
+        else:
+            self.h = lib().oracle_model_create(self.dims.ctypes.data_as(_i64p), self.R, _p(U[0]), _p(U[1]), _p(U[2]),
+                                               float(tol), int(max_iters), int(flags), float(alpha))
         if not self.h:
             raise ValueError("rank out of range")
 
@@ -157,12 +189,16 @@ class Model:
         return int(lib().oracle_model_iterate(self.h, _p(self.T), self.normT2))
 
     def state(self) -> dict:
-        U = [np.zeros((int(self.dims[n]), self.R), order="F") for n in range(3)]
+        U = [np.zeros((int(self.dims[n]), self.R), order="F") for n in range(self.T.ndim)]
         lam = np.zeros(self.R)
         fit, err = C.c_double(), C.c_double()
         it, st, acc = C.c_int32(), C.c_int32(), C.c_int32()
-        lib().oracle_model_get(self.h, _p(U[0]), _p(U[1]), _p(U[2]), _p(lam), C.byref(fit), C.byref(err),
-                               C.byref(it), C.byref(st), C.byref(acc))
+        if self.T.ndim != 3:
+            lib().oracle_model_get_nd(self.h, _ptrs(U), _p(lam), C.byref(fit), C.byref(err), C.byref(it), C.byref(st),
+                                      C.byref(acc))
+        else:
+            lib().oracle_model_get(self.h, _p(U[0]), _p(U[1]), _p(U[2]), _p(lam), C.byref(fit), C.byref(err),
+                                   C.byref(it), C.byref(st), C.byref(acc))
         return dict(U=U, lam=lam, fit=fit.value, err=err.value, iters=it.value, status=st.value,
                     ls_accepted=acc.value)
 
@@ -199,9 +235,11 @@ def cals(T: np.ndarray, models: Sequence[dict], max_total_rank: int, max_slots: 
     flg = np.array([m.get("flags", 0) for m in models], dtype=np.uint32)
     alp = np.array([m.get("ls_alpha", 1.0) for m in models], dtype=np.float64)
     ins = [[_f(u) for u in m["init"]] for m in models]
-    outs = [[np.zeros((int(dims[k]), int(r)), order="F") for k in range(3)] for r in ranks]
-    in_ptrs = (_dp * (3 * n))(*[_p(u) for trip in ins for u in trip])
-    out_ptrs = (_dp * (3 * n))(*[_p(u) for trip in outs for u in trip])
+    N = T.ndim
+    outs = [[np.zeros((int(dims[k]), int(r)), order="F") for k in range(N)] for r in ranks]
+    assert all(len(trip) == N for trip in ins)
+    in_ptrs = (_dp * (N * n))(*[_p(u) for trip in ins for u in trip])
+    out_ptrs = (_dp * (N * n))(*[_p(u) for trip in outs for u in trip])
     lam = np.zeros((n, MAX_RANK))
     fit = np.zeros(n)
     err = np.zeros(n)
@@ -209,11 +247,13 @@ def cals(T: np.ndarray, models: Sequence[dict], max_total_rank: int, max_slots: 
     status = np.zeros(n, dtype=np.int32)
     order = np.full(n, -1, dtype=np.int32)
     rlog = np.zeros(max_rounds, dtype=np.int32)
-    rounds = lib().oracle_cals(_p(T), dims.ctypes.data_as(_i64p), n, ranks.ctypes.data_as(_i32p), in_ptrs, _p(tol),
-                               mit.ctypes.data_as(_i32p), flg.ctypes.data_as(_u32p), _p(alp), int(max_total_rank),
-                               int(max_slots), out_ptrs, _p(lam), _p(fit), _p(err), iters.ctypes.data_as(_i32p),
-                               status.ctypes.data_as(_i32p), order.ctypes.data_as(_i32p),
-                               rlog.ctypes.data_as(_i32p), int(max_rounds))
+    tail = (in_ptrs, _p(tol), mit.ctypes.data_as(_i32p), flg.ctypes.data_as(_u32p), _p(alp), int(max_total_rank),
+            int(max_slots), out_ptrs, _p(lam), _p(fit), _p(err), iters.ctypes.data_as(_i32p),
+            status.ctypes.data_as(_i32p), order.ctypes.data_as(_i32p), rlog.ctypes.data_as(_i32p), int(max_rounds))
+    if N != 3:
+        rounds = lib().oracle_cals_nd(_p(T), N, dims.ctypes.data_as(_i64p), n, ranks.ctypes.data_as(_i32p), *tail)
+    else:
+        rounds = lib().oracle_cals(_p(T), dims.ctypes.data_as(_i64p), n, ranks.ctypes.data_as(_i32p), *tail)
     if rounds < 0:
         raise ValueError("bad model list (rank out of range or larger than max_total_rank)")
     return dict(U=outs, lam=[lam[k, :ranks[k]].copy() for k in range(n)], fit=fit, err=err, iters=iters,

@@ -11,4 +11,5 @@ from .generators import (  # noqa: F401
     make_models,
     uniform_factors,
     random_tensor,
+    low_rank_tensor,
 )

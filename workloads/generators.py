@@ -4,7 +4,8 @@ Random numbers come from numpy's Philox counter-based generator, keyed by (seed,
 that any slab of a large tensor can be produced on its own and in any order.
 
 Memory convention: a tensor T of dims (I1, I2, I3) is returned as a C-contiguous numpy array
-of shape (I3, I2, I1), i.e. element (i1, i2, i3) sits at flat offset i1 + I1*(i2 + I2*i3).
+of shape (I3, I2, I1), i.e. element (i1, i2, i3) sits at flat offset i1 + I1*(i2 + I2*i3); tensors of
+higher order likewise (shape = dims reversed, first index fastest).
 Factor matrices are returned Fortran-ordered with shape (I_n, R) (column-major, ld = I_n).
 """
 from __future__ import annotations
@@ -23,7 +24,7 @@ def _rng(seed: int, stream: int = 0) -> np.random.Generator:
 
 
 def uniform_factors(dims: Sequence[int], rank: int, seed: int) -> List[np.ndarray]:
-    """Three Uniform[0,1) matrices (I_n x rank), column-major."""
+    """One Uniform[0,1) matrix (I_n x rank) per mode, column-major."""
     out = []
     for n, I in enumerate(dims):
         g = _rng(seed, n)
@@ -33,9 +34,23 @@ def uniform_factors(dims: Sequence[int], rank: int, seed: int) -> List[np.ndarra
 
 def random_tensor(dims: Sequence[int], seed: int, signed: bool = False) -> np.ndarray:
     """A dense tensor of iid entries (Uniform[0,1), or standard normal when signed)."""
-    I1, I2, I3 = (int(d) for d in dims)
+    shape = tuple(int(d) for d in dims)[::-1]
     g = _rng(seed, 7)
-    return g.standard_normal((I3, I2, I1)) if signed else g.random((I3, I2, I1))
+    return g.standard_normal(shape) if signed else g.random(shape)
+
+
+def low_rank_tensor(dims: Sequence[int], rank: int, seed: int, noise: float = 0.0) -> np.ndarray:
+    """Order-N tensor (N = len(dims)) = sum of `rank` outer products of Uniform[0,1) vectors, plus Gaussian
+    noise of std noise * rms(noise-free tensor).  Built mode by mode from the last index down."""
+    F = uniform_factors(dims, rank, seed)
+    acc = np.ascontiguousarray(F[-1])                    # (I_N, R)
+    for U in F[-2::-1]:                                  # prepend faster modes: (..., I_n, R)
+        acc = acc[..., None, :] * U
+    T = np.ascontiguousarray(acc.sum(axis=-1))
+    if noise > 0.0:
+        sigma = noise * math.sqrt(_low_rank_norm_sq(F) / float(T.size))
+        T += sigma * _rng(seed, 99).standard_normal(T.shape)
+    return T
 
 
 def _collinear_factor(I: int, R: int, c: float, seed: int, stream: int) -> np.ndarray:
