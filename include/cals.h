@@ -1,7 +1,8 @@
 /*
  * cals.h -- C boundary of the MI355X (gfx950) implementation of Concurrent ALS (CALS):
- * many CP-ALS instances on one dense 3-way fp64 tensor, advanced in lock-step so that the three
- * MTTKRPs of an iteration are each ONE fused contraction over the concatenated factor matrices.
+ * many CP-ALS instances on one dense fp64 tensor of order N = 3 (the paper's case) up to CALS_MAX_MODES,
+ * advanced in lock-step so that the N MTTKRPs of an iteration are each ONE fused contraction over the
+ * concatenated factor matrices.
  *
  * The calls follow the problem statement of the paper's full algorithm (Alg. 3): a tensor, an
  * input queue of starting points, a main loop (fill, advance all active instances one iteration,
@@ -11,7 +12,8 @@
  *   - Every function returns CALS_OK (0) or a negative CALS_E_* code; nothing throws or aborts.
  *   - "host" / "device" on a pointer says where the memory lives.  The library never frees a
  *     caller pointer.
- *   - Tensor memory order: first index fastest, element (i1,i2,i3) at i1 + I1*(i2 + I2*i3).
+ *   - Tensor memory order: first index fastest, element (i1,i2,i3) at i1 + I1*(i2 + I2*i3); order N likewise.
+ *   - Arrays indexed by mode (dims, init, U, U_dev) have one entry per mode of the tensor: N entries.
  *   - Per-model factor matrices cross the boundary column-major, I_n x rank, ld = I_n.
  *   - Device multi-matrices (cals_mttkrp) are ROW-major: row i of mode n holds the total_rank
  *     concatenated columns of all models, leading dimension `ld` doubles.
@@ -54,6 +56,7 @@ extern "C" {
                               tensor fewer per sweep).  Costs a device buffer of I2*I3*ld doubles. */
 
 #define CALS_MAX_RANK 32 /* largest number of components of one model */
+#define CALS_MAX_MODES 6 /* largest tensor order */
 
 typedef struct cals_ctx cals_ctx; /* opaque; one per tensor */
 
@@ -83,9 +86,9 @@ typedef struct {
   int32_t total_rank;        /* fused width right now                                        */
   double tensor_norm_sq;     /* ||T||^2                                                      */
   double mttkrp_flops;       /* algorithmic: 2 * fused width * prod(I) per launch, summed    */
-  double mttkrp_ms[3];       /* per mode, main contraction kernel only (needs CALS_CTX_TIMING) */
-  double reduce_ms[3];       /* per mode, split-K reduction kernel (needs CALS_CTX_TIMING)     */
-  int64_t mttkrp_launches[3];
+  double mttkrp_ms[CALS_MAX_MODES];  /* per mode, main contraction kernel only (needs CALS_CTX_TIMING) */
+  double reduce_ms[CALS_MAX_MODES];  /* per mode, split-K reduction kernel (needs CALS_CTX_TIMING)     */
+  int64_t mttkrp_launches[CALS_MAX_MODES];
 } cals_stats;
 
 /* Create / destroy a context.  `opt` is copied.  Errors: INVALID (null, R* < 1, slots < 0), HIP. */
@@ -99,12 +102,20 @@ int cals_destroy(cals_ctx* c);
  * One tensor per context: a second call returns CALS_E_STATE. */
 int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], int on_device);
 
+/* The same for a tensor of order ndims (Alg. 1 and Alg. 3 are stated for N modes): 3 <= ndims <= CALS_MAX_MODES,
+ * dims[0..ndims), first index fastest.  For output mode n the N-1 contracted modes form a fast and a slow run of
+ * consecutive modes; a run of more than one mode enters the fused contraction as the explicit Khatri-Rao product of
+ * its factor multi-matrices (device buffers of prod(run dims) x ld doubles, allocated here), so every product of
+ * the dims of such a run must stay below 2^31.  CALS_CTX_REUSE has no effect for ndims > 3.
+ * Errors as cals_submit_tensor; INVALID also for ndims out of range. */
+int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const int64_t* dims, int on_device);
+
 /* Append a starting point to the input queue (Alg. 3, Q_in).  init[n] is a HOST pointer to the
  * column-major I_n x rank starting factor of mode n+1; it is copied.  tol < 0 means "never stop
  * by tolerance" (fixed iteration count).  ls_alpha is read only with CALS_MODEL_LINESEARCH.
  * Errors: STATE (no tensor), INVALID (rank < 1, > CALS_MAX_RANK or > R*; max_iters < 1; NaN
  * tol/alpha; NaN/Inf in init), UNSUPPORTED (NONNEG together with LINESEARCH). */
-int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const init[3], double tol, int32_t max_iters,
+int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const* init, double tol, int32_t max_iters,
                        uint32_t flags, double ls_alpha, int64_t* model_id);
 
 /* Run up to n_rounds rounds of the main loop of Alg. 3 (fill from the queue front until the next
@@ -121,23 +132,25 @@ int cals_run(cals_ctx* c);
 int cals_poll_retired(cals_ctx* c, cals_result* out, int32_t cap, int32_t* n);
 
 /* Factors of a FINISHED model: U[n] (host, column-major I_n x rank, may be null to skip) and
- * lambda (host, rank doubles, may be null).  The model tensor is sum_r lambda[r] u1_r o u2_r o u3_r.
+ * lambda (host, rank doubles, may be null).  The model tensor is sum_r lambda[r] u1_r o u2_r o ... o uN_r.
  * Errors: NOTFOUND (unknown id or model not finished yet). */
-int cals_get_factors(cals_ctx* c, int64_t model_id, double* const U[3], double* lambda);
+int cals_get_factors(cals_ctx* c, int64_t model_id, double* const* U, double* lambda);
 
 /* The fused MTTKRP alone (Eq. (2); Alg. 2, fused-MTTKRP line), for parity and roofline runs:
- *   M[i_mode, c] = sum over the other two indices of T[i1,i2,i3] * Ua[ia,c] * Ub[ib,c],  c < total_rank.
- * mode is 1, 2 or 3.  U_dev[n] (device, row-major I_n x ld) for the two modes != mode (the third
- * pointer is ignored and may be null); M_dev (device, row-major I_mode x ld) is overwritten in
- * columns [0, total_rank); ld >= total_rank.  Uses the context's tensor, stream and workspace. */
-int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const U_dev[3],
+ *   M[i_mode, c] = sum over the other indices of T[i1,...,iN] * prod_{n != mode} U_n[i_n,c],  c < total_rank.
+ * mode is 1 .. N.  U_dev[n] (device, row-major I_n x ld) for the modes != mode (the pointer of `mode` itself
+ * is ignored and may be null); M_dev (device, row-major I_mode x ld) is overwritten in
+ * columns [0, total_rank); ld >= total_rank (for N > 3 also ld <= max_total_rank rounded up to 16, the width of
+ * the context's Khatri-Rao buffers).  Uses the context's tensor, stream and workspace. */
+int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const* U_dev,
                 double* M_dev);
 
 /* The two MTTKRPs of a two-step sweep alone, for parity runs (needs CALS_CTX_REUSE): Y from U_dev[0], then
  *   M2[i2,c] = sum_i3 Y[(i2,i3),c] * U3[i3,c]   and   M3[i3,c] = sum_i2 Y[(i2,i3),c] * U2[i2,c],   c < total_rank,
  * which equal the mode-2 and mode-3 MTTKRPs of (U1, U2, U3).  All three U_dev[n] are device, row-major I_n x ld,
  * ld <= the context's leading dimension (max_total_rank rounded up to 16); M2_dev (I2 x ld) and M3_dev (I3 x ld)
- * are overwritten in columns [0, total_rank).  Errors: STATE (context without CALS_CTX_REUSE or no tensor),
+ * are overwritten in columns [0, total_rank).  Order-3 tensors only.  Errors: STATE (context without CALS_CTX_REUSE,
+ * no tensor, or a tensor of higher order),
  * INVALID (arguments). */
 int cals_mttkrp_reuse(cals_ctx* c, int32_t total_rank, int64_t ld, const double* const U_dev[3], double* M2_dev,
                       double* M3_dev);

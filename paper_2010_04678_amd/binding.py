@@ -20,8 +20,9 @@ CTX_TIMING = 1
 CTX_REUSE = 2
 RUNNING, CONVERGED, MAX_ITERS, NUMERICAL = 0, 1, 2, 3
 MAX_RANK = 32
+MAX_MODES = 6
 
-EXPORTS = ["cals_create", "cals_destroy", "cals_submit_tensor", "cals_enqueue_model", "cals_iterate", "cals_run",
+EXPORTS = ["cals_create", "cals_destroy", "cals_submit_tensor", "cals_submit_tensor_nd", "cals_enqueue_model", "cals_iterate", "cals_run",
            "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_mttkrp_reuse", "cals_get_stats", "cals_yardstick",
            "cals_strerror"]
 
@@ -45,8 +46,8 @@ class _Result(C.Structure):
 class _Stats(C.Structure):
     _fields_ = [("rounds", C.c_int64), ("models_retired", C.c_int64), ("models_queued", C.c_int64),
                 ("n_active", C.c_int32), ("total_rank", C.c_int32), ("tensor_norm_sq", C.c_double),
-                ("mttkrp_flops", C.c_double), ("mttkrp_ms", C.c_double * 3), ("reduce_ms", C.c_double * 3),
-                ("mttkrp_launches", C.c_int64 * 3)]
+                ("mttkrp_flops", C.c_double), ("mttkrp_ms", C.c_double * MAX_MODES), ("reduce_ms", C.c_double * MAX_MODES),
+                ("mttkrp_launches", C.c_int64 * MAX_MODES)]
 
 
 @dataclass
@@ -96,6 +97,7 @@ def load_library() -> C.CDLL:
     L.cals_create.argtypes = [C.POINTER(vp), C.POINTER(_Options)]
     L.cals_destroy.argtypes = [vp]
     L.cals_submit_tensor.argtypes = [vp, vp, C.POINTER(C.c_int64), C.c_int]
+    L.cals_submit_tensor_nd.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_int64), C.c_int]
     L.cals_enqueue_model.argtypes = [vp, C.c_int32, C.POINTER(vp), C.c_double, C.c_int32, C.c_uint32, C.c_double,
                                      C.POINTER(C.c_int64)]
     L.cals_iterate.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32)]
@@ -158,30 +160,38 @@ class Context:
 
     # -- cals_submit_tensor
     def submit_tensor(self, T) -> None:
-        """T: torch CUDA float64 tensor (borrowed) or numpy array (copied), shape (I3, I2, I1) C-contiguous,
-        i.e. element (i1,i2,i3) at i1 + I1*(i2 + I2*i3)."""
+        """T: torch CUDA float64 tensor (borrowed) or numpy array (copied), shape (I_N, ..., I2, I1) C-contiguous,
+        i.e. first index fastest: element (i1,i2,i3) of an order-3 tensor at i1 + I1*(i2 + I2*i3).  Order 3 goes
+        through cals_submit_tensor, higher orders through cals_submit_tensor_nd."""
+        shape = tuple(int(d) for d in T.shape)
+        nd = len(shape)
+        dims = (C.c_int64 * nd)(*shape[::-1])
         if isinstance(T, np.ndarray):
-            assert T.dtype == np.float64 and T.ndim == 3 and T.flags.c_contiguous
-            dims = (C.c_int64 * 3)(T.shape[2], T.shape[1], T.shape[0])
-            _check(self._L.cals_submit_tensor(self._h, T.ctypes.data, dims, 0), "cals_submit_tensor")
-            self.dims = (T.shape[2], T.shape[1], T.shape[0])
+            assert T.dtype == np.float64 and T.flags.c_contiguous
+            ptr, on_device = T.ctypes.data, 0
         else:
             import torch
-            assert T.is_cuda and T.dtype == torch.float64 and T.dim() == 3 and T.is_contiguous()
-            dims = (C.c_int64 * 3)(T.shape[2], T.shape[1], T.shape[0])
+            assert T.is_cuda and T.dtype == torch.float64 and T.is_contiguous()
             self._keep.append(T)
-            _check(self._L.cals_submit_tensor(self._h, T.data_ptr(), dims, 1), "cals_submit_tensor")
-            self.dims = (T.shape[2], T.shape[1], T.shape[0])
+            ptr, on_device = T.data_ptr(), 1
+        if nd == 3:
+            _check(self._L.cals_submit_tensor(self._h, ptr, dims, on_device), "cals_submit_tensor")
+        else:
+            _check(self._L.cals_submit_tensor_nd(self._h, ptr, nd, dims, on_device), "cals_submit_tensor_nd")
+        self.dims = shape[::-1]
 
     # -- cals_enqueue_model
     def enqueue_model(self, init: Sequence[np.ndarray], tol: float = -1.0, max_iters: int = 50, flags: int = 0,
                       ls_alpha: float = 1.0) -> int:
         U = [np.asfortranarray(u, dtype=np.float64) for u in init]
         rank = int(U[0].shape[1])
-        for n in range(3):
-            if self.dims is not None and U[n].shape != (self.dims[n], rank):
-                raise ValueError("init[%d] has shape %s, expected %s" % (n, U[n].shape, (self.dims[n], rank)))
-        ptrs = (C.c_void_p * 3)(*[u.ctypes.data for u in U])
+        if self.dims is not None:           # without a tensor the library answers CALS_E_STATE itself
+            if len(U) != len(self.dims):
+                raise ValueError("init has %d matrices, the tensor %d modes" % (len(U), len(self.dims)))
+            for n in range(len(self.dims)):
+                if U[n].shape != (self.dims[n], rank):
+                    raise ValueError("init[%d] has shape %s, expected %s" % (n, U[n].shape, (self.dims[n], rank)))
+        ptrs = (C.c_void_p * len(U))(*[u.ctypes.data for u in U])
         mid = C.c_int64(-1)
         _check(self._L.cals_enqueue_model(self._h, rank, ptrs, float(tol), int(max_iters), int(flags),
                                           float(ls_alpha), C.byref(mid)), "cals_enqueue_model")
@@ -207,9 +217,9 @@ class Context:
     # -- cals_get_factors
     def get_factors(self, model_id: int):
         rank = self._ranks[model_id]
-        U = [np.zeros((self.dims[n], rank), order="F") for n in range(3)]
+        U = [np.zeros((self.dims[n], rank), order="F") for n in range(len(self.dims))]
         lam = np.zeros(rank)
-        ptrs = (C.c_void_p * 3)(*[u.ctypes.data for u in U])
+        ptrs = (C.c_void_p * len(U))(*[u.ctypes.data for u in U])
         _check(self._L.cals_get_factors(self._h, int(model_id), ptrs, lam.ctypes.data), "cals_get_factors")
         return U, lam
 
@@ -219,8 +229,8 @@ class Context:
         M_dev: (I_mode, ld), columns [0,total_rank) overwritten."""
         ld = int(M_dev.shape[1])
         tr = int(total_rank) if total_rank is not None else ld
-        ptrs = (C.c_void_p * 3)()
-        for n in range(3):
+        ptrs = (C.c_void_p * len(self.dims))()
+        for n in range(len(self.dims)):
             u = U_dev[n]
             if u is None:
                 ptrs[n] = None

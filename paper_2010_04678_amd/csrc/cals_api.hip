@@ -40,7 +40,7 @@ struct PendingModel {
   int max_iters;
   uint32_t flags;
   double alpha;
-  std::vector<double> init[3];  // column-major I_n x rank, as given
+  std::vector<double> init[kMaxModes];  // column-major I_n x rank, as given
 };
 
 struct ActiveModel {
@@ -58,7 +58,7 @@ struct Leaving { ActiveModel m; int status; int64_t round; int slot; };
 
 struct RetiredModel {
   cals_result res;
-  std::vector<double> U[3];     // column-major I_n x rank
+  std::vector<double> U[kMaxModes];     // column-major I_n x rank
   std::vector<double> lambda;
 };
 
@@ -71,16 +71,18 @@ struct cals_ctx {
   hipStream_t stream = nullptr;
   int num_cus = 0;
   bool has_tensor = false;
-  int64_t dims[3] = {0, 0, 0};
+  int nmodes = 0;             // tensor order N (3 .. kMaxModes)
+  int64_t dims[kMaxModes] = {0, 0, 0, 0, 0, 0};
   const double* T = nullptr;
   double* T_owned = nullptr;
   double normT2 = 0.0;
   int ld = 0;                 // leading dimension of every multi-matrix (R* rounded up to 16)
   int capacity = 0;           // slots with persistent storage
-  double* U[3] = {nullptr, nullptr, nullptr};
-  double* Ualt[3] = {nullptr, nullptr, nullptr};
-  double* Uprev[3] = {nullptr, nullptr, nullptr};   // line search only (allocated on first use)
-  double* Unew[3] = {nullptr, nullptr, nullptr};
+  double* U[kMaxModes] = {};
+  double* Ualt[kMaxModes] = {};
+  double* Uprev[kMaxModes] = {};   // line search only (allocated on first use)
+  double* Unew[kMaxModes] = {};
+  double* Kbuf[2] = {nullptr, nullptr};   // order > 3: explicit Khatri-Rao products of the fast and the slow run
   double* M = nullptr;        // MTTKRP result, max(I_n) x ld
   double* workspace = nullptr;
   size_t workspace_bytes = 0;
@@ -91,7 +93,7 @@ struct cals_ctx {
   ModelOut* h_out = nullptr;     // pinned
   int32_t* d_map = nullptr;
   int32_t* h_map = nullptr;      // pinned
-  uint32_t* passive[3] = {nullptr, nullptr, nullptr};  // NONNEG only
+  uint32_t* passive[kMaxModes] = {};  // NONNEG only
   double* d_scratch = nullptr;   // 1024 partial sums + result + flag
   double* Y = nullptr;           // two-step sweeps: the tensor contracted with the mode-1 multi-matrix, (I2*I3) x ld
   double* d_ones = nullptr;      // two-step sweeps: ld ones (the second "factor" of the first step)
@@ -99,7 +101,7 @@ struct cals_ctx {
   double* d_zeros = nullptr;     // 8 zero doubles (what MTTKRP lanes past the end of a split load)
   double* d_lambda = nullptr;    // kMaxRank column norms per sid
   double* h_lambda = nullptr;    // pinned
-  double* d_stage = nullptr;     // (I1+I2+I3) x ld doubles: packed columns on their way in (fill) or out (retire)
+  double* d_stage = nullptr;     // (I1+...+IN) x ld doubles: packed columns on their way in (fill) or out (retire)
   double* h_stage = nullptr;     // pinned, same size
   int32_t* d_rmap = nullptr;     // columns of the models being retired
   int32_t* h_rmap = nullptr;     // pinned
@@ -122,8 +124,8 @@ struct cals_ctx {
   int64_t rounds = 0, n_retired = 0;
   int64_t rounds_unread = 0;     // rounds launched since the last read-back of the per-model records
   double mttkrp_flops = 0.0;
-  double mttkrp_ms[3] = {0, 0, 0}, reduce_ms[3] = {0, 0, 0};
-  int64_t mttkrp_launches[3] = {0, 0, 0};
+  double mttkrp_ms[kMaxModes] = {}, reduce_ms[kMaxModes] = {};
+  int64_t mttkrp_launches[kMaxModes] = {};
   std::vector<TimedLaunch> timed;
   std::vector<hipEvent_t> event_pool;
 };
@@ -153,29 +155,75 @@ int ensure_workspace(cals_ctx* c, size_t bytes) {
   return CALS_OK;
 }
 
-// Problem description of the fused MTTKRP for output mode `mode` (0,1,2) over given multi-matrices.
-MttkrpProblem make_problem(const cals_ctx* c, int mode, const double* const U[3], double* M, int ncols, int ld) {
-  const int64_t I1 = c->dims[0], I2 = c->dims[1];
+// The contracted modes of output mode n, as a fast run A = [a0, a1) and a slow run B = [b0, b1) of consecutive
+// modes (first index fastest).  For an inner mode the runs are the modes before and after it; for the first and the
+// last mode the N-1 remaining modes are cut where the larger of the two run sizes is smallest (first such cut).
+// For N = 3 every run is a single mode.
+struct Runs { int a0, a1, b0, b1; int64_t Ia, Ib; };
+
+Runs contraction_runs(const cals_ctx* c, int n) {
+  const int N = c->nmodes;
+  Runs r{};
+  if (n > 0 && n < N - 1) {
+    r.a0 = 0; r.a1 = n; r.b0 = n + 1; r.b1 = N;
+  } else {
+    const int lo = (n == 0) ? 1 : 0, hi = (n == 0) ? N : N - 1;
+    int best_k = lo + 1;
+    double best = 1e300;
+    for (int k = lo + 1; k < hi; ++k) {
+      double pa = 1.0, pb = 1.0;
+      for (int m = lo; m < k; ++m) pa *= (double)c->dims[m];
+      for (int m = k; m < hi; ++m) pb *= (double)c->dims[m];
+      const double worst = pa > pb ? pa : pb;
+      if (worst < best) { best = worst; best_k = k; }
+    }
+    r.a0 = lo; r.a1 = best_k; r.b0 = best_k; r.b1 = hi;
+  }
+  r.Ia = 1; r.Ib = 1;
+  for (int m = r.a0; m < r.a1; ++m) r.Ia *= c->dims[m];
+  for (int m = r.b0; m < r.b1; ++m) r.Ib *= c->dims[m];
+  return r;
+}
+
+int64_t mode_stride(const cals_ctx* c, int m) {
+  int64_t s = 1;
+  for (int k = 0; k < m; ++k) s *= c->dims[k];
+  return s;
+}
+
+// One contracted run as the kernel's factor operand: the factor multi-matrix itself for a run of one mode, else the
+// explicit Khatri-Rao product of the run's multi-matrices, formed in `kbuf` (rows in memory order of the run).
+int run_operand(cals_ctx* c, int m0, int m1, int64_t rows, const double* const* U, double* kbuf, int ncols, int ld,
+                const double** out) {
+  if (m1 - m0 == 1) { *out = U[m0]; return CALS_OK; }
+  if (!kbuf || ld > c->ld) return CALS_E_INVALID;
+  KrpArgs k{};
+  k.nrun = m1 - m0;
+  for (int q = 0; q < k.nrun; ++q) { k.U[q] = U[m0 + q]; k.In[q] = (int)c->dims[m0 + q]; }
+  k.K = kbuf; k.rows = rows; k.ld = ld; k.ncols = ncols;
+  HIP_TRY(launch_krp(k, c->stream));
+  *out = kbuf;
+  return CALS_OK;
+}
+
+// Problem description of the fused MTTKRP for output mode `mode` (0-based) over given multi-matrices.  Enqueues the
+// Khatri-Rao products of runs of more than one mode (tensors of order above 3).
+int make_problem(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld, MttkrpProblem* out) {
+  const Runs r = contraction_runs(c, mode);
+  if (r.Ia >= (1LL << 31) || r.Ib >= (1LL << 31)) return CALS_E_UNSUPPORTED;
   MttkrpProblem p{};
   p.T = c->T;
   p.zeros = c->d_zeros;
   p.M = M;
   p.ncols = ncols;
   p.ld = ld;
-  if (mode == 0) {          // rows i1; contract (i2 fast, i3 slow)
-    p.In = (int)c->dims[0]; p.sm = 1;
-    p.Ia = (int)c->dims[1]; p.sa = I1; p.Ua = U[1];
-    p.Ib = (int)c->dims[2]; p.sb = I1 * I2; p.Ub = U[2];
-  } else if (mode == 1) {   // rows i2; contract (i1 fast, i3 slow)
-    p.In = (int)c->dims[1]; p.sm = I1;
-    p.Ia = (int)c->dims[0]; p.sa = 1; p.Ua = U[0];
-    p.Ib = (int)c->dims[2]; p.sb = I1 * I2; p.Ub = U[2];
-  } else {                  // rows i3; contract (i1 fast, i2 slow)
-    p.In = (int)c->dims[2]; p.sm = I1 * I2;
-    p.Ia = (int)c->dims[0]; p.sa = 1; p.Ua = U[0];
-    p.Ib = (int)c->dims[1]; p.sb = I1; p.Ub = U[1];
-  }
-  return p;
+  p.In = (int)c->dims[mode]; p.sm = mode_stride(c, mode);
+  p.Ia = (int)r.Ia; p.sa = mode_stride(c, r.a0);
+  p.Ib = (int)r.Ib; p.sb = mode_stride(c, r.b0);
+  CALS_TRY(run_operand(c, r.a0, r.a1, r.Ia, U, c->Kbuf[0], ncols, ld, &p.Ua));
+  CALS_TRY(run_operand(c, r.b0, r.b1, r.Ib, U, c->Kbuf[1], ncols, ld, &p.Ub));
+  *out = p;
+  return CALS_OK;
 }
 
 hipEvent_t take_event(cals_ctx* c) {
@@ -202,8 +250,9 @@ int drain_timings(cals_ctx* c) {
   return CALS_OK;
 }
 
-int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int ncols, int ld) {
-  MttkrpProblem p = make_problem(c, mode, U, M, ncols, ld);
+int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld) {
+  MttkrpProblem p{};
+  CALS_TRY(make_problem(c, mode, U, M, ncols, ld, &p));
   // factor matrices are addressed with 32-bit byte offsets
   // (with room for the rows a workgroup requests past the end of its range)
   if ((int64_t)(p.Ia + 64) * ld * 8 >= (1LL << 32) || (int64_t)(p.Ib + 64) * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
@@ -225,7 +274,9 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const U[3], double* M, int n
     c->timed.push_back(t);
     if (c->timed.size() > 2048) CALS_TRY(drain_timings(c));
   }
-  c->mttkrp_flops += 2.0 * ncols * (double)c->dims[0] * (double)c->dims[1] * (double)c->dims[2];
+  double elems = 1.0;
+  for (int n = 0; n < c->nmodes; ++n) elems *= (double)c->dims[n];
+  c->mttkrp_flops += 2.0 * ncols * elems;
   c->mttkrp_launches[mode] += 1;
   return CALS_OK;
 }
@@ -276,7 +327,7 @@ int ensure_nn_buffers(cals_ctx* c) {
   if (c->d_nnfail) return CALS_OK;
   HIP_TRY(hipSetDevice(c->opt.device));
   bool ok = true;
-  for (int n = 0; n < 3; ++n) {
+  for (int n = 0; n < c->nmodes; ++n) {
     const size_t bytes = sizeof(uint32_t) * (size_t)c->dims[n] * c->capacity;
     ok = ok && hipMalloc(&c->passive[n], bytes) == hipSuccess;
     if (ok) ok = hipMemsetAsync(c->passive[n], 0, bytes, c->stream) == hipSuccess;
@@ -292,7 +343,7 @@ int ensure_ls_buffers(cals_ctx* c) {
   if (c->d_colmodel) return CALS_OK;
   HIP_TRY(hipSetDevice(c->opt.device));
   bool ok = true;
-  for (int n = 0; n < 3; ++n) {
+  for (int n = 0; n < c->nmodes; ++n) {
     const size_t bytes = sizeof(double) * (size_t)c->dims[n] * c->ld;
     ok = ok && hipMalloc(&c->Uprev[n], bytes) == hipSuccess && hipMalloc(&c->Unew[n], bytes) == hipSuccess;
     if (ok) ok = hipMemsetAsync(c->Uprev[n], 0, bytes, c->stream) == hipSuccess &&
@@ -300,8 +351,8 @@ int ensure_ls_buffers(cals_ctx* c) {
   }
   ok = ok && hipMalloc(&c->d_accept, sizeof(int32_t) * c->capacity) == hipSuccess;
   {
-    const int64_t imax = std::max(c->dims[0], std::max(c->dims[1], c->dims[2]));
-    ok = ok && hipMalloc(&c->d_lspart, sizeof(double) * 3 * update_part_doubles((int)imax) * c->capacity) == hipSuccess;
+    const int64_t imax = *std::max_element(c->dims, c->dims + c->nmodes);
+    ok = ok && hipMalloc(&c->d_lspart, sizeof(double) * c->nmodes * update_part_doubles((int)imax) * c->capacity) == hipSuccess;
   }
   ok = ok && hipHostMalloc(&c->h_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipMalloc(&c->d_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
@@ -349,8 +400,8 @@ int fill(cals_ctx* c) {
   if (fresh.empty()) return CALS_OK;
   // pack: per mode a row-major I_n x newcols block
   size_t off = 0;
-  size_t mode_off[3];
-  for (int n = 0; n < 3; ++n) {
+  size_t mode_off[kMaxModes];
+  for (int n = 0; n < c->nmodes; ++n) {
     const int64_t In = c->dims[n];
     mode_off[n] = off;
     double* blk = c->h_stage + off;
@@ -364,7 +415,7 @@ int fill(cals_ctx* c) {
     off += (size_t)In * newcols;
   }
   HIP_TRY(hipMemcpyAsync(c->d_stage, c->h_stage, sizeof(double) * off, hipMemcpyHostToDevice, c->stream));
-  for (int n = 0; n < 3; ++n)
+  for (int n = 0; n < c->nmodes; ++n)
     HIP_TRY(launch_copy_block(c->d_stage + mode_off[n], newcols, c->U[n] + col0, c->ld, (int)c->dims[n], newcols,
                               c->stream));
   int col = col0;
@@ -381,10 +432,10 @@ int fill(cals_ctx* c) {
   c->total_rank = col;
   c->desc_dirty = true;
   CALS_TRY(upload_desc(c));
-  const int In[3] = {(int)c->dims[0], (int)c->dims[1], (int)c->dims[2]};
-  const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
-  HIP_TRY(launch_gram_init(c->d_desc, c->d_state, c->d_out, c->d_lambda, true, c->passive, c->capacity, Uc, In, c->ld, first_new,
-                           (int)fresh.size(), c->stream));
+  int In[kMaxModes];
+  for (int n = 0; n < c->nmodes; ++n) In[n] = (int)c->dims[n];
+  HIP_TRY(launch_gram_init(c->d_desc, c->d_state, c->d_out, c->d_lambda, true, c->passive, c->capacity, c->U, In,
+                           c->nmodes, c->ld, first_new, (int)fresh.size(), c->stream));
   // the staging buffer and the queue entries are free again once the copy has been consumed
   HIP_TRY(hipStreamSynchronize(c->stream));
   for (size_t k = 0; k < n_take; ++k) c->queue.pop_front();
@@ -401,8 +452,8 @@ int retire_models(cals_ctx* c, const std::vector<ActiveModel>& leaving, const st
   }
   HIP_TRY(hipMemcpyAsync(c->d_rmap, c->h_rmap, sizeof(int32_t) * outcols, hipMemcpyHostToDevice, c->stream));
   size_t off = 0;
-  size_t mode_off[3];
-  for (int n = 0; n < 3; ++n) {
+  size_t mode_off[kMaxModes];
+  for (int n = 0; n < c->nmodes; ++n) {
     mode_off[n] = off;
     HIP_TRY(launch_gather_block(c->U[n], c->ld, c->d_stage + off, outcols, c->d_rmap, (int)c->dims[n], outcols,
                                 c->stream));
@@ -426,7 +477,7 @@ int retire_models(cals_ctx* c, const std::vector<ActiveModel>& leaving, const st
     r.res.ls_accepted = o.ls_accepted;
     r.res.fit = o.fit;
     r.res.error = o.err;
-    for (int n = 0; n < 3; ++n) {
+    for (int n = 0; n < c->nmodes; ++n) {
       const int64_t In = c->dims[n];
       const double* blk = c->h_stage + mode_off[n];
       r.U[n].resize((size_t)In * m.rank);
@@ -456,7 +507,7 @@ int compact(cals_ctx* c, const std::vector<ActiveModel>& survivors) {
   }
   if (moved && col > 0) {
     HIP_TRY(hipMemcpyAsync(c->d_map, c->h_map, sizeof(int32_t) * col, hipMemcpyHostToDevice, c->stream));
-    for (int n = 0; n < 3; ++n) {
+    for (int n = 0; n < c->nmodes; ++n) {
       HIP_TRY(launch_gather_columns(c->U[n], c->Ualt[n], c->d_map, (int)c->dims[n], col, c->ld, c->stream));
       std::swap(c->U[n], c->Ualt[n]);
       if (c->Uprev[n]) {
@@ -489,14 +540,14 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
   const int n = (int)c->active.size();
   if (n == 0) return CALS_OK;
   CALS_TRY(upload_desc(c));
-  for (int mode = 0; mode < 3; ++mode) {
-    const double* Uc[3] = {c->U[0], c->U[1], c->U[2]};
+  const int N = c->nmodes;
+  for (int mode = 0; mode < N; ++mode) {
     if (c->Y && mode > 0) {
       // two-step sweep: modes 2 and 3 come from the tensor contracted with the mode-1 factors just updated
       if (mode == 1) CALS_TRY(run_contract_mode1(c, c->U[0], c->total_rank, c->ld));
       CALS_TRY(run_from_contraction(c, mode, mode == 1 ? c->U[2] : c->U[1], c->M, c->total_rank, c->ld));
     } else {
-      CALS_TRY(run_mttkrp(c, mode, Uc, c->M, c->total_rank, c->ld));
+      CALS_TRY(run_mttkrp(c, mode, c->U, c->M, c->total_rank, c->ld));
     }
     bool round_has_nn = false;
     int nn_max_rank = 1;
@@ -510,17 +561,17 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
       NnlsArgs na{};
       na.desc = c->d_desc; na.state = c->d_state; na.out = c->d_out; na.M = c->M; na.X = c->Ualt[mode];
       na.passive = c->passive[mode]; na.fail = c->d_nnfail;
-      na.In = (int)c->dims[mode]; na.ld = c->ld; na.mode = mode; na.n_models = n; na.capacity = c->capacity; na.max_rank = nn_max_rank;
+      na.In = (int)c->dims[mode]; na.ld = c->ld; na.mode = mode; na.nmodes = N; na.n_models = n; na.capacity = c->capacity; na.max_rank = nn_max_rank;
       HIP_TRY(launch_nnls(na, c->stream));
     }
     UpdateArgs ua{};
     ua.desc = c->d_desc; ua.state = c->d_state; ua.out = c->d_out; ua.lambda = c->d_lambda;
     ua.M = c->M; ua.U = c->U[mode]; ua.X = c->Ualt[mode]; ua.nn_fail = c->d_nnfail;
-    ua.In = (int)c->dims[mode]; ua.ld = c->ld; ua.mode = mode;
+    ua.In = (int)c->dims[mode]; ua.ld = c->ld; ua.mode = mode; ua.nmodes = N;
     ua.n_models = n; ua.normT2 = c->normT2; ua.part = c->d_updpart;
     HIP_TRY(launch_update(ua, c->stream));
   }
-  // line search (Sec. 5): extrapolate, one extra fused mode-3 MTTKRP at the extrapolated point, decide, apply
+  // line search (Sec. 5): extrapolate, one extra fused MTTKRP of the last mode at the extrapolated point, decide, apply
   bool round_has_ls = false, ls_takes_part = false;
   for (const ActiveModel& m : c->active)
     if (m.flags & CALS_MODEL_LINESEARCH) {
@@ -531,20 +582,20 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
     LineSearchArgs la{};
     la.desc = c->d_desc; la.state = c->d_state; la.out = c->d_out; la.lambda = c->d_lambda;
     la.colmodel = c->d_colmodel; la.accept = c->d_accept;
-    for (int k = 0; k < 3; ++k) {
+    la.nmodes = N;
+    for (int k = 0; k < N; ++k) {
       la.U[k] = c->U[k]; la.Uprev[k] = c->Uprev[k]; la.Unew[k] = c->Unew[k]; la.In[k] = (int)c->dims[k];
     }
     la.M3 = c->M; la.ld = c->ld; la.n_models = n; la.ncols = c->total_rank; la.normT2 = c->normT2;
     la.part = c->d_lspart;
-    la.nblk = update_row_blocks((int)std::max(c->dims[0], std::max(c->dims[1], c->dims[2])));
+    la.nblk = update_row_blocks((int)*std::max_element(c->dims, c->dims + N));
     if (ls_takes_part) {
       HIP_TRY(launch_ls_extrapolate(la, c->stream));
-      const double* Un[3] = {c->Unew[0], c->Unew[1], c->Unew[2]};
       if (c->Y) {
         CALS_TRY(run_contract_mode1(c, c->Unew[0], c->total_rank, c->ld));
         CALS_TRY(run_from_contraction(c, 2, c->Unew[1], c->M, c->total_rank, c->ld));
       } else {
-        CALS_TRY(run_mttkrp(c, 2, Un, c->M, c->total_rank, c->ld));
+        CALS_TRY(run_mttkrp(c, N - 1, c->Unew, c->M, c->total_rank, c->ld));
       }
     }
     HIP_TRY(launch_ls_decide(la, c->stream));
@@ -636,10 +687,11 @@ int cals_destroy(cals_ctx* c) {
   for (TimedLaunch& t : c->timed)
     for (int i = 0; i < 4; ++i) (void)hipEventDestroy(t.ev[i]);
   for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
-  for (int n = 0; n < 3; ++n) {
+  for (int n = 0; n < kMaxModes; ++n) {
     (void)hipFree(c->U[n]); (void)hipFree(c->Ualt[n]); (void)hipFree(c->Uprev[n]); (void)hipFree(c->Unew[n]);
     (void)hipFree(c->passive[n]);
   }
+  (void)hipFree(c->Kbuf[0]); (void)hipFree(c->Kbuf[1]);
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart); (void)hipFree(c->d_lspart);
   (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
@@ -652,16 +704,22 @@ int cals_destroy(cals_ctx* c) {
 }
 
 int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], int on_device) {
+  return cals_submit_tensor_nd(c, data, 3, dims, on_device);
+}
+
+int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const int64_t* dims, int on_device) {
   if (!c || !data || !dims) return CALS_E_INVALID;
+  if (ndims < 3 || ndims > CALS_MAX_MODES) return CALS_E_INVALID;
   if (c->has_tensor) return CALS_E_STATE;
   int64_t total = 1;
-  for (int n = 0; n < 3; ++n) {
+  for (int n = 0; n < ndims; ++n) {
     if (dims[n] < 1 || dims[n] >= (1LL << 31)) return CALS_E_INVALID;
     total *= dims[n];
     if (total >= (1LL << 40)) return CALS_E_INVALID;
   }
   CALS_TRY(set_device(c));
-  for (int n = 0; n < 3; ++n) c->dims[n] = dims[n];
+  c->nmodes = ndims;
+  for (int n = 0; n < ndims; ++n) c->dims[n] = dims[n];
   if (on_device) {
     c->T = data;
   } else {
@@ -670,9 +728,9 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
     c->T = c->T_owned;
   }
   // buffers: three factor multi-matrices (+ a spare set for compaction), the MTTKRP result, per-model storage
-  const int64_t imax = std::max(dims[0], std::max(dims[1], dims[2]));
+  const int64_t imax = *std::max_element(dims, dims + ndims);
   bool ok = true;
-  for (int n = 0; n < 3; ++n) {
+  for (int n = 0; n < ndims; ++n) {
     const size_t bytes = sizeof(double) * (size_t)dims[n] * c->ld;
     ok = ok && hipMalloc(&c->U[n], bytes) == hipSuccess && hipMalloc(&c->Ualt[n], bytes) == hipSuccess;
     if (ok) ok = hipMemsetAsync(c->U[n], 0, bytes, c->stream) == hipSuccess &&
@@ -684,7 +742,22 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
   ok = ok && hipMalloc(&c->d_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
   ok = ok && hipMalloc(&c->d_map, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipMalloc(&c->d_scratch, sizeof(double) * 1032) == hipSuccess;
-  if ((c->opt.flags & CALS_CTX_REUSE) && dims[1] * dims[2] < (1LL << 31)) {
+  // order above 3: room for the explicit Khatri-Rao products of the contracted runs (largest over the modes)
+  {
+    int64_t need[2] = {0, 0};
+    for (int n = 0; n < ndims; ++n) {
+      const Runs r = contraction_runs(c, n);
+      if (r.a1 - r.a0 > 1) need[0] = std::max(need[0], r.Ia);
+      if (r.b1 - r.b0 > 1) need[1] = std::max(need[1], r.Ib);
+    }
+    for (int q = 0; q < 2; ++q)
+      if (need[q] > 0) {
+        const size_t bytes = sizeof(double) * (size_t)need[q] * c->ld;
+        ok = ok && hipMalloc(&c->Kbuf[q], bytes) == hipSuccess;
+        if (ok) ok = hipMemsetAsync(c->Kbuf[q], 0, bytes, c->stream) == hipSuccess;
+      }
+  }
+  if ((c->opt.flags & CALS_CTX_REUSE) && ndims == 3 && dims[1] * dims[2] < (1LL << 31)) {
     ok = ok && hipMalloc(&c->Y, sizeof(double) * (size_t)(dims[1] * dims[2]) * c->ld) == hipSuccess;
     ok = ok && hipMalloc(&c->d_ones, sizeof(double) * c->ld) == hipSuccess;
     ok = ok && launch_fill(c->d_ones, c->ld, 1.0, c->stream) == hipSuccess;
@@ -696,7 +769,9 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
   ok = ok && hipHostMalloc(&c->h_desc, sizeof(ModelDesc) * c->capacity) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_out, sizeof(ModelOut) * c->capacity) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_map, sizeof(int32_t) * c->ld) == hipSuccess;
-  const size_t stage_doubles = (size_t)(dims[0] + dims[1] + dims[2]) * c->ld;
+  int64_t dim_sum = 0;
+  for (int n = 0; n < ndims; ++n) dim_sum += dims[n];
+  const size_t stage_doubles = (size_t)dim_sum * c->ld;
   ok = ok && hipMalloc(&c->d_lambda, sizeof(double) * kMaxRank * c->capacity) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_lambda, sizeof(double) * kMaxRank * c->capacity) == hipSuccess;
   ok = ok && hipMalloc(&c->d_stage, sizeof(double) * stage_doubles) == hipSuccess;
@@ -722,7 +797,7 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
   return CALS_OK;
 }
 
-int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const init[3], double tol, int32_t max_iters,
+int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const* init, double tol, int32_t max_iters,
                        uint32_t flags, double ls_alpha, int64_t* model_id) {
   if (!c || !init) return CALS_E_INVALID;
   if (!c->has_tensor) return CALS_E_STATE;
@@ -736,7 +811,7 @@ int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const init[3], d
   PendingModel pm;
   pm.id = c->next_id;
   pm.rank = rank; pm.tol = tol; pm.max_iters = max_iters; pm.flags = flags; pm.alpha = ls_alpha;
-  for (int n = 0; n < 3; ++n) {
+  for (int n = 0; n < c->nmodes; ++n) {
     if (!init[n]) return CALS_E_INVALID;
     const int64_t In = c->dims[n];
     if (!all_finite(init[n], In * rank)) return CALS_E_INVALID;
@@ -780,24 +855,25 @@ int cals_poll_retired(cals_ctx* c, cals_result* out, int32_t cap, int32_t* n) {
   return CALS_OK;
 }
 
-int cals_get_factors(cals_ctx* c, int64_t model_id, double* const U[3], double* lambda) {
+int cals_get_factors(cals_ctx* c, int64_t model_id, double* const* U, double* lambda) {
   if (!c) return CALS_E_INVALID;
   auto it = c->retired.find(model_id);
   if (it == c->retired.end()) return CALS_E_NOTFOUND;
   const RetiredModel& r = it->second;
   if (U)
-    for (int n = 0; n < 3; ++n)
+    for (int n = 0; n < c->nmodes; ++n)
       if (U[n]) std::memcpy(U[n], r.U[n].data(), sizeof(double) * r.U[n].size());
   if (lambda) std::memcpy(lambda, r.lambda.data(), sizeof(double) * r.lambda.size());
   return CALS_OK;
 }
 
-int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const U_dev[3],
+int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const* U_dev,
                 double* M_dev) {
   if (!c || !U_dev || !M_dev) return CALS_E_INVALID;
   if (!c->has_tensor) return CALS_E_STATE;
-  if (mode < 1 || mode > 3 || total_rank < 1 || ld < total_rank || ld >= (1LL << 24)) return CALS_E_INVALID;
-  for (int n = 0; n < 3; ++n)
+  if (mode < 1 || mode > c->nmodes || total_rank < 1 || ld < total_rank || ld >= (1LL << 24)) return CALS_E_INVALID;
+  if (c->nmodes > 3 && ld > c->ld) return CALS_E_INVALID;
+  for (int n = 0; n < c->nmodes; ++n)
     if (n != mode - 1 && !U_dev[n]) return CALS_E_INVALID;
   CALS_TRY(set_device(c));
   return run_mttkrp(c, mode - 1, U_dev, M_dev, total_rank, (int)ld);
@@ -828,7 +904,7 @@ int cals_get_stats(cals_ctx* c, cals_stats* s) {
   s->total_rank = c->total_rank;
   s->tensor_norm_sq = c->normT2;
   s->mttkrp_flops = c->mttkrp_flops;
-  for (int n = 0; n < 3; ++n) {
+  for (int n = 0; n < CALS_MAX_MODES; ++n) {
     s->mttkrp_ms[n] = c->mttkrp_ms[n];
     s->reduce_ms[n] = c->reduce_ms[n];
     s->mttkrp_launches[n] = c->mttkrp_launches[n];

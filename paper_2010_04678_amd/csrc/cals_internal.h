@@ -26,6 +26,7 @@ __device__ inline double readlane_f64(double v, int src_lane) {
 #endif
 
 constexpr int kMaxRank = 32;       // largest rank of one model (CALS_MAX_RANK)
+constexpr int kMaxModes = 6;       // largest tensor order (CALS_MAX_MODES)
 constexpr int kGramStride = kMaxRank * kMaxRank;
 
 // ---- fused MTTKRP (Eq. (2); Alg. 2 fused-MTTKRP line) ------------------------------------------
@@ -79,11 +80,23 @@ struct ModelDesc {   // one per active model, in slot order
 };
 
 struct ModelState {  // persistent per-model device storage, indexed by sid
-  double G[3][kGramStride];   // Gramians of the current factors (rank x rank, ld = rank)
-  double inner, normsq;       // error terms of the last mode-3 update
-  double Gls[3][kGramStride]; // line search: Gramians of the extrapolated point
-  double inner_ls;            // line search: sum(A3_new * M3(A_new))
+  double G[kMaxModes][kGramStride];   // Gramians of the current factors (rank x rank, ld = rank)
+  double inner, normsq;               // error terms of the last update of the last mode
+  double Gls[kMaxModes][kGramStride]; // line search: Gramians of the extrapolated point
+  double inner_ls;                    // line search: sum(A_N,new * M_N(A_new))
 };
+
+#if defined(__HIPCC__)
+// Element e of the Hadamard product of the Gramians of all modes but `mode`, multiplied up in increasing mode
+// order (Alg. 1, Hadamard line).
+__device__ inline double hadamard_of_others(const ModelState* st, int nmodes, int mode, int e) {
+  int k = (mode == 0) ? 1 : 0;
+  double h = st->G[k][e];
+  for (++k; k < nmodes; ++k)
+    if (k != mode) h *= st->G[k][e];
+  return h;
+}
+#endif
 
 struct ModelOut {    // per-model scalars the host reads back once per round, indexed by sid
   double err, fit;            // after the last completed iteration
@@ -102,7 +115,8 @@ struct UpdateArgs {
   double* U;            // factor multi-matrix of the updated mode, row-major In x ld
   const double* X;      // NONNEG: rows already solved by the non-negative update (row-major In x ld), or null
   int32_t* nn_fail;     // NONNEG: per slot position, set when a row's sub-block could not be factorised (reset here)
-  int In, ld, mode;     // mode = 0,1,2
+  int In, ld, mode;     // mode = 0 .. nmodes-1
+  int nmodes;           // tensor order
   int n_models;
   double normT2;
   double* part;         // tall modes: per (slot position, row block) partial Gramian and inner product
@@ -118,13 +132,12 @@ inline int update_row_blocks(int In) {
 inline size_t update_part_doubles(int In) { return (size_t)update_row_blocks(In) * kUpdatePartStride; }
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t stream);
-// Gramians of all three modes for models [first, first+count) of desc (used when a model is inserted
-// and after an accepted line-search step).
+// Gramians of all `nmodes` modes for models [first, first+count) of desc (used when a model is inserted).
 // With reset_out, also puts the models' ModelOut back to {0, 0, RUNNING, 0, 0}.
-// passive[3] (may hold nulls): the NONNEG passive-set masks, cleared for the models' storage ids on reset.
+// passive[nmodes] (may hold nulls): the NONNEG passive-set masks, cleared for the models' storage ids on reset.
 hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, double* lambda, bool reset_out,
-                            uint32_t* const passive[3], int capacity, const double* const U[3], const int In[3], int ld, int first, int count,
-                            hipStream_t stream);
+                            uint32_t* const* passive, int capacity, const double* const* U, const int* In, int nmodes,
+                            int ld, int first, int count, hipStream_t stream);
 // ||T||^2 with a fixed summation tree, and a finiteness check (flag[0] != 0 when a NaN/Inf was seen).
 hipError_t launch_norm_sq(const double* T, int64_t n, double* partial /* >= 1024 doubles */, double* out, int* flag,
                           hipStream_t stream);
@@ -150,12 +163,13 @@ struct NnlsArgs {
   uint32_t* passive;    // per (row, sid) passive-set masks of this mode, In x capacity; read (warm start) and written
   int32_t* fail;        // per slot position; or-ed with 1 on failure
   int In, ld, mode, n_models, capacity;
+  int nmodes;           // tensor order
   int max_rank;         // largest rank among the NONNEG models of this launch
 };
 hipError_t launch_nnls(const NnlsArgs& a, hipStream_t stream);
 
 // ---- line search (Sec. 5, "Line search") -----------------------------------------------------------
-// A point is held with lambda folded into the mode-3 factor.  A model takes part in a round's line search when
+// A point is held with lambda folded into the factor of the last mode.  A model takes part in a round's line search when
 // it has the LINESEARCH flag, is still running and has completed at least two iterations.
 struct LineSearchArgs {
   const ModelDesc* desc;
@@ -164,23 +178,24 @@ struct LineSearchArgs {
   double* lambda;
   const int32_t* colmodel; // slot position of the model that owns each column
   int32_t* accept;         // per slot position: 1 when the extrapolated point was taken this round
-  double* U[3];            // current factors
-  double* Uprev[3];        // point after the previous iteration
-  double* Unew[3];         // extrapolated point
-  const double* M3;        // mode-3 MTTKRP at the extrapolated point, row-major I3 x ld
+  double* U[kMaxModes];     // current factors
+  double* Uprev[kMaxModes]; // point after the previous iteration
+  double* Unew[kMaxModes];  // extrapolated point
+  const double* M3;        // MTTKRP of the last mode at the extrapolated point, row-major I_N x ld
   double* part;            // per (slot position, mode, row block): partial Gramian and inner product of the
                            // extrapolated point, kUpdatePartStride doubles each
   int nblk;                // row blocks (update_row_blocks of the longest mode)
-  int In[3];
+  int In[kMaxModes];
+  int nmodes;              // tensor order
   int ld, n_models, ncols;
   double normT2;
 };
 // Unew = Uprev + alpha (A_cur - Uprev) for the models taking part, Unew = A_cur for all other columns.
 hipError_t launch_ls_extrapolate(const LineSearchArgs& a, hipStream_t stream);
-// Gramians of the extrapolated point and sum(A3_new * M3); then e_new = ||T||^2 + sum(G1*G2*G3) - 2 inner and the
+// Gramians of the extrapolated point and sum(A_N,new * M_N); then e_new = ||T||^2 + sum(G1*...*GN) - 2 inner and the
 // decision (strictly lower error wins): accepted models get err/fit/Gramians of the new point and lambda = 1.
 hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream);
-// U = Unew for accepted models; Uprev = the point kept (lambda folded into mode 3) for every line-search model.
+// U = Unew for accepted models; Uprev = the point kept (lambda folded into the last mode) for every line-search model.
 hipError_t launch_ls_apply(const LineSearchArgs& a, hipStream_t stream);
 
 // ---- two-step sweep: contraction of the intermediate Y with one factor ---------------------------------------
@@ -188,6 +203,19 @@ hipError_t launch_ls_apply(const LineSearchArgs& a, hipStream_t stream);
 hipError_t launch_ttv(const double* Y, const double* U, double* M, int no, int ns, int64_t so, int64_t ss, int ld,
                       int ncols, hipStream_t stream);
 hipError_t launch_fill(double* p, int64_t n, double v, hipStream_t stream);
+
+// ---- tensors of order above 3: explicit Khatri-Rao product of a run of consecutive modes ----------------------
+// K[row, c] = prod_{q < nrun} U[q][i_q * ld + c],  row = i_0 + In[0] * (i_1 + In[1] * (...)),  c < ncols; K and the
+// U[q] are row-major with leading dimension ld.  The product is taken in increasing q.
+struct KrpArgs {
+  const double* U[kMaxModes];
+  int In[kMaxModes];
+  int nrun;
+  double* K;
+  int64_t rows;
+  int ld, ncols;
+};
+hipError_t launch_krp(const KrpArgs& a, hipStream_t stream);
 
 // ---- practical-peak yardsticks (kind 0: fp64 MFMA issue rate in TFLOP/s, kind 1: streaming read in GB/s) ----
 hipError_t launch_yardstick(int kind, const void* buf, int64_t bytes, int reps, int num_cus, double* sink,

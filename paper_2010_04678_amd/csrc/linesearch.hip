@@ -1,7 +1,7 @@
 // Line search for CALS (Sec. 5 of the paper, "Line search"), applied to each model independently after a
-// round's three mode updates: P_new = P_prev + alpha (P_cur - P_prev); the extrapolated point replaces P_cur
+// round's mode updates: P_new = P_prev + alpha (P_cur - P_prev); the extrapolated point replaces P_cur
 // only if its error is lower.  The error of P_new comes from the fast formula of Alg. 1 with ONE extra fused
-// mode-3 MTTKRP over the extrapolated multi-matrices, so the central fused operation is preserved.
+// MTTKRP of the last mode over the extrapolated multi-matrices, so the central fused operation is preserved.
 #include "cals_internal.h"
 
 namespace cals {
@@ -34,7 +34,7 @@ __global__ void __launch_bounds__(256) ls_extrapolate_kernel(LineSearchArgs a) {
   const ModelDesc d = a.desc[a.colmodel[c]];
   const ModelOut o = a.out[d.sid];
   const int64_t e = (int64_t)i * a.ld + c;
-  const double scale = (mode == 2) ? a.lambda[d.sid * kMaxRank + (c - d.col)] : 1.0;
+  const double scale = (mode == a.nmodes - 1) ? a.lambda[d.sid * kMaxRank + (c - d.col)] : 1.0;
   const double cur = a.U[mode][e] * scale;
   double v = cur;
   if (ls_takes_part(d, o)) {
@@ -44,8 +44,8 @@ __global__ void __launch_bounds__(256) ls_extrapolate_kernel(LineSearchArgs a) {
   a.Unew[mode][e] = v;
 }
 
-// grid (n_models, 3, row blocks): partial Gramian of the extrapolated mode-`y` factor block over the block's rows;
-// for mode 3 also the partial sum(A3_new * M3).  Partials go to a.part; ls_decide_kernel adds them in block order.
+// grid (n_models, modes, row blocks): partial Gramian of the extrapolated mode-`y` factor block over the block's rows;
+// for the last mode also the partial sum(A_new * M).  Partials go to a.part; ls_decide_kernel adds them in block order.
 __global__ void __launch_bounds__(256) ls_gram_kernel(LineSearchArgs a) {
   extern __shared__ double lds[];
   const ModelDesc d = a.desc[blockIdx.x];
@@ -70,7 +70,7 @@ __global__ void __launch_bounds__(256) ls_gram_kernel(LineSearchArgs a) {
       for (int r = 0; r < R; ++r) {
         const double x = Ub[(int64_t)i * a.ld + r];
         xs[r * kXs + tid] = x;
-        if (mode == 2) part += x * a.M3[(int64_t)i * a.ld + d.col + r];
+        if (mode == a.nmodes - 1) part += x * a.M3[(int64_t)i * a.ld + d.col + r];
       }
       inner += part;
     }
@@ -90,13 +90,13 @@ __global__ void __launch_bounds__(256) ls_gram_kernel(LineSearchArgs a) {
     }
     __syncthreads();
   }
-  double* part = a.part + (((size_t)blockIdx.x * 3 + mode) * nblk + blockIdx.z) * kUpdatePartStride;
+  double* part = a.part + (((size_t)blockIdx.x * a.nmodes + mode) * nblk + blockIdx.z) * kUpdatePartStride;
 #pragma unroll
   for (int q = 0; q < 3; ++q) {
     const int p = tid + 256 * q;
     if (p < npairs) part[p] = gacc[q];
   }
-  if (mode == 2) {
+  if (mode == a.nmodes - 1) {
     const double tot = ls_block_sum(inner, red);
     if (tid == 0) part[528] = tot;
   }
@@ -116,8 +116,8 @@ __global__ void __launch_bounds__(256) ls_decide_kernel(LineSearchArgs a) {
   const int R = d.rank;
   // Gramians of the extrapolated point: the row blocks' partials, added in block order
   const int npairs = R * (R + 1) / 2;
-  for (int mode = 0; mode < 3; ++mode) {
-    const double* pm = a.part + ((size_t)blockIdx.x * 3 + mode) * a.nblk * kUpdatePartStride;
+  for (int mode = 0; mode < a.nmodes; ++mode) {
+    const double* pm = a.part + ((size_t)blockIdx.x * a.nmodes + mode) * a.nblk * kUpdatePartStride;
     for (int p = tid; p < npairs; p += 256) {
       double g = 0.0;
       for (int b = 0; b < a.nblk; ++b) g += pm[(size_t)b * kUpdatePartStride + p];
@@ -130,24 +130,25 @@ __global__ void __launch_bounds__(256) ls_decide_kernel(LineSearchArgs a) {
     }
   }
   if (tid == 0) {
-    const double* pm = a.part + ((size_t)blockIdx.x * 3 + 2) * a.nblk * kUpdatePartStride;
+    const double* pm = a.part + ((size_t)blockIdx.x * a.nmodes + (a.nmodes - 1)) * a.nblk * kUpdatePartStride;
     double in = 0.0;
     for (int b = 0; b < a.nblk; ++b) in += pm[(size_t)b * kUpdatePartStride + 528];
     st->inner_ls = in;
   }
   __syncthreads();
   double part = 0.0;
-  for (int e = tid; e < R * R; e += 256) part += (st->Gls[0][e] * st->Gls[1][e]) * st->Gls[2][e];
+  for (int e = tid; e < R * R; e += 256) {
+    double h = st->Gls[0][e];
+    for (int k = 1; k < a.nmodes; ++k) h *= st->Gls[k][e];
+    part += h;
+  }
   const double normsq = ls_block_sum(part, red);
   const double err = a.normT2 + normsq - 2.0 * st->inner_ls;
   const bool take = err < o->err;             // uniform: every thread reads the same values
   __syncthreads();
   if (take) {
-    for (int e = tid; e < R * R; e += 256) {
-      st->G[0][e] = st->Gls[0][e];
-      st->G[1][e] = st->Gls[1][e];
-      st->G[2][e] = st->Gls[2][e];
-    }
+    for (int k = 0; k < a.nmodes; ++k)
+      for (int e = tid; e < R * R; e += 256) st->G[k][e] = st->Gls[k][e];
     if (tid < R) a.lambda[d.sid * kMaxRank + tid] = 1.0;
   }
   __syncthreads();
@@ -178,16 +179,16 @@ __global__ void __launch_bounds__(256) ls_apply_kernel(LineSearchArgs a) {
     a.U[mode][e] = v;                          // lambda of an accepted point is 1
   } else {
     v = a.U[mode][e];
-    if (mode == 2) v *= a.lambda[d.sid * kMaxRank + (c - d.col)];
+    if (mode == a.nmodes - 1) v *= a.lambda[d.sid * kMaxRank + (c - d.col)];
   }
   a.Uprev[mode][e] = v;
 }
 
 static dim3 elem_grid(const LineSearchArgs& a) {
-  int imax = a.In[0] > a.In[1] ? a.In[0] : a.In[1];
-  imax = imax > a.In[2] ? imax : a.In[2];
+  int imax = a.In[0];
+  for (int k = 1; k < a.nmodes; ++k) imax = imax > a.In[k] ? imax : a.In[k];
   const int64_t total = (int64_t)imax * a.ncols;
-  return dim3((unsigned)((total + 255) / 256), 3);
+  return dim3((unsigned)((total + 255) / 256), a.nmodes);
 }
 
 hipError_t launch_ls_extrapolate(const LineSearchArgs& a, hipStream_t stream) {
@@ -205,8 +206,8 @@ hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
   }
   if (a.n_models < 1) return hipSuccess;
-  if (!a.part || a.nblk < 1) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(ls_gram_kernel, dim3(a.n_models, 3, a.nblk), dim3(256), lds, stream, a);
+  if (!a.part || a.nblk < 1 || a.nmodes < 1 || a.nmodes > kMaxModes) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(ls_gram_kernel, dim3(a.n_models, a.nmodes, a.nblk), dim3(256), lds, stream, a);
   hipLaunchKernelGGL(ls_decide_kernel, dim3(a.n_models), dim3(256), 0, stream, a);
   return hipGetLastError();
 }

@@ -41,12 +41,11 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
                                           int wave) {
   const int R = d.rank;
   const ModelState* st = a.state + d.sid;
-  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
   const bool live = lane < R;
   double hrow[RM];                       // row `lane` of H = Ga * Gb (zero outside R x R)
 #pragma unroll
   for (int k = 0; k < RM; ++k)
-    hrow[k] = (live && k < R) ? st->G[ma][lane * R + k] * st->G[mb][lane * R + k] : 0.0;
+    hrow[k] = (live && k < R) ? hadamard_of_others(st, a.nmodes, a.mode, lane * R + k) : 0.0;
   double cs = 0.0;                       // H is symmetric: row sums are column sums
 #pragma unroll
   for (int k = 0; k < RM; ++k) cs += fabs(hrow[k]);

@@ -1,9 +1,9 @@
 // Per-model steps of one CALS mode update (Alg. 2 inner loop; Alg. 1 Hadamard, update and error lines),
 // one workgroup per active model (modes of more than 256 rows: one per model and row block, two launches):
-//   H = Ga * Gb (cached Gramians of the other two modes)         -- Hadamard product of Gramians
+//   H = product of the cached Gramians of all other modes        -- Hadamard product of Gramians
 //   H = L L^T                                                    -- Cholesky, no pivoting
 //   U[i,:] = M[i,:] H^-1 for every row i (two triangular solves) -- normal-equation update
-//   mode 3 only: inner = sum(U * M), normsq = sum(H * U^T U)     -- terms of the fast error formula
+//   last mode only: inner = sum(U * M), normsq = sum(H * U^T U)  -- terms of the fast error formula
 //   lambda_r = ||U[:,r]||_2, U[:,r] /= lambda_r, G = U^T U       -- unit columns, Gramian refresh
 // plus the small utility kernels around it (initial Gramians, ||T||^2, column gather).
 #include "cals_internal.h"
@@ -192,7 +192,6 @@ __device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDes
   ModelOut* out = a.out + d.sid;
   const int tid = threadIdx.x;
   const int R = d.rank;
-  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
   double* xs = lds;                           // R * kXs: the solved rows, staged for the Gramian
   double* H = xs + kMaxRank * kXs;            // R*R, Hadamard of Gramians
   double* L = H + kGramStride;                // RM*RM, Cholesky factor (zero padded, unit diagonal beyond R)
@@ -200,7 +199,7 @@ __device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDes
   double* red = Gl + kGramStride;             // 256
   double* lam = red + 256;                    // R
 
-  for (int e = tid; e < R * R; e += 256) H[e] = st->G[ma][e] * st->G[mb][e];
+  for (int e = tid; e < R * R; e += 256) H[e] = hadamard_of_others(st, a.nmodes, a.mode, e);
   for (int e = tid; e < RM * RM; e += 256) L[e] = (e / RM == e % RM && e / RM >= R) ? 1.0 : 0.0;
   __syncthreads();
   // NONNEG models: the rows were solved by the non-negative update already (a.X); only its outcome is read
@@ -248,7 +247,7 @@ __device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDes
   gram_store(gacc, R, Gl);
   __syncthreads();
 
-  if (a.mode == 2) {
+  if (a.mode == a.nmodes - 1) {
     double part = 0.0;
     for (int e = tid; e < R * R; e += 256) part += H[e] * Gl[e];
     const double normsq = fast_block_sum(part, red);
@@ -291,7 +290,6 @@ __device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d
   ModelOut* out = a.out + d.sid;
   const int tid = threadIdx.x;
   const int R = d.rank;
-  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
   double* xs = lds;                           // R * kXs
   double* H = xs + kMaxRank * kXs;            // R*R, Hadamard of Gramians
   double* L = H + kGramStride;                // R*R, Cholesky factor
@@ -301,7 +299,7 @@ __device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d
   int& flag = *flagp;
 
   for (int e = tid; e < R * R; e += 256) {
-    const double h = st->G[ma][e] * st->G[mb][e];
+    const double h = hadamard_of_others(st, a.nmodes, a.mode, e);
     H[e] = h;
     L[e] = h;
   }
@@ -366,7 +364,7 @@ __device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d
   gram_store(gacc, R, Gl);
   __syncthreads();
 
-  if (a.mode == 2) {
+  if (a.mode == a.nmodes - 1) {
     double part = 0.0;
     for (int e = tid; e < R * R; e += 256) part += H[e] * Gl[e];
     const double normsq = block_sum(part, red);
@@ -431,7 +429,6 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
                                               // this launch only ever stores the value every block computes alike)
   const int tid = threadIdx.x;
   const int R = d.rank;
-  const int ma = (a.mode == 0) ? 1 : 0, mb = (a.mode == 2) ? 1 : 2;
   double* xs = lds;                           // R * kXs
   double* L = xs + kMaxRank * kXs;            // Cholesky factor: R*R in place of H, or RM*RM padded (ranks <= 16)
   double* red = L + kGramStride;              // 256
@@ -441,10 +438,10 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
   const int RMs = (R + 3) / 4 * 4;
 
   if (small) {
-    for (int e = tid; e < R * R; e += 256) H[e] = st->G[ma][e] * st->G[mb][e];
+    for (int e = tid; e < R * R; e += 256) H[e] = hadamard_of_others(st, a.nmodes, a.mode, e);
     for (int e = tid; e < RMs * RMs; e += 256) L[e] = (e / RMs == e % RMs && e / RMs >= R) ? 1.0 : 0.0;
   } else {
-    for (int e = tid; e < R * R; e += 256) L[e] = st->G[ma][e] * st->G[mb][e];
+    for (int e = tid; e < R * R; e += 256) L[e] = hadamard_of_others(st, a.nmodes, a.mode, e);
   }
   __syncthreads();
   const bool nonneg = (d.flags & 1u) != 0;
@@ -563,10 +560,9 @@ __global__ void __launch_bounds__(256) update_finish_kernel(UpdateArgs a) {
     }
   }
   __syncthreads();
-  if (blockIdx.y == 0 && a.mode == 2) {
-    const int ma = 0, mb = 1;
+  if (blockIdx.y == 0 && a.mode == a.nmodes - 1) {
     double v = 0.0;
-    for (int e = tid; e < R * R; e += 256) v += (st->G[ma][e] * st->G[mb][e]) * Gl[e];
+    for (int e = tid; e < R * R; e += 256) v += (hadamard_of_others(st, a.nmodes, a.mode, e)) * Gl[e];
     const double normsq = block_sum(v, red);
     if (tid == 0) {
       double in = 0.0;
@@ -636,11 +632,11 @@ struct GramInitArgs {
   ModelState* state;
   ModelOut* out;
   double* lambda;
-  uint32_t* passive[3];
+  uint32_t* passive[kMaxModes];
   int capacity;
   int reset_out;
-  const double* U[3];
-  int In[3];
+  const double* U[kMaxModes];
+  int In[kMaxModes];
   int ld, first;
 };
 
@@ -677,8 +673,8 @@ __global__ void __launch_bounds__(256) gram_init_kernel(GramInitArgs a) {
 }
 
 hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* out, double* lambda, bool reset_out,
-                            uint32_t* const passive[3], int capacity, const double* const U[3], const int In[3], int ld, int first, int count,
-                            hipStream_t stream) {
+                            uint32_t* const* passive, int capacity, const double* const* U, const int* In, int nmodes,
+                            int ld, int first, int count, hipStream_t stream) {
   static std::atomic<unsigned long long> attr_seen{0};
   const size_t lds = sizeof(double) * (kMaxRank * kXs + kGramStride);
   if (first_use_on_current_device(attr_seen)) {
@@ -687,11 +683,12 @@ hipError_t launch_gram_init(const ModelDesc* desc, ModelState* state, ModelOut* 
     if (e != hipSuccess) return e;
   }
   if (count < 1) return hipSuccess;
-  GramInitArgs a;
+  if (nmodes < 1 || nmodes > kMaxModes) return hipErrorInvalidValue;
+  GramInitArgs a{};
   a.desc = desc; a.state = state; a.out = out; a.lambda = lambda; a.reset_out = reset_out ? 1 : 0; a.ld = ld; a.first = first;
   a.capacity = capacity;
-  for (int n = 0; n < 3; ++n) { a.U[n] = U[n]; a.In[n] = In[n]; a.passive[n] = passive ? passive[n] : nullptr; }
-  hipLaunchKernelGGL(gram_init_kernel, dim3(count, 3), dim3(256), lds, stream, a);
+  for (int n = 0; n < nmodes; ++n) { a.U[n] = U[n]; a.In[n] = In[n]; a.passive[n] = passive ? passive[n] : nullptr; }
+  hipLaunchKernelGGL(gram_init_kernel, dim3(count, nmodes), dim3(256), lds, stream, a);
   return hipGetLastError();
 }
 

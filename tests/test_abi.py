@@ -36,7 +36,8 @@ def test_struct_layouts_match_header():
     # sizes implied by the field lists in cals.h (natural alignment, 8-byte pointers)
     assert C.sizeof(binding._Options) == 32
     assert C.sizeof(binding._Result) == 40
-    assert C.sizeof(binding._Stats) == 8 * 3 + 4 * 2 + 8 * 2 + 8 * 3 + 8 * 3 + 8 * 3
+    assert binding.MAX_MODES == 6      # CALS_MAX_MODES
+    assert C.sizeof(binding._Stats) == 8 * 3 + 4 * 2 + 8 * 2 + 3 * 8 * binding.MAX_MODES
 
 
 def test_product_package_does_not_import_the_oracle():

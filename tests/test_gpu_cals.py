@@ -44,9 +44,10 @@ def compare(results, facs, ref, models):
         assert r.status == ref["status"][k]
         assert abs(r.fit - ref["fit"][k]) <= FIT_TOL, (k, r.fit, ref["fit"][k])
         U, lam = facs[k]
-        for n in range(3):
-            a = U[n] * (lam[None, :] if n == 2 else 1.0)
-            b = ref["U"][k][n] * (ref["lam"][k][None, :] if n == 2 else 1.0)
+        last = len(U) - 1
+        for n in range(len(U)):
+            a = U[n] * (lam[None, :] if n == last else 1.0)
+            b = ref["U"][k][n] * (ref["lam"][k][None, :] if n == last else 1.0)
             den = np.linalg.norm(b, axis=0)
             rel = np.linalg.norm(a - b, axis=0) / np.where(den > 0, den, 1.0)
             assert rel.max() <= FACTOR_TOL, (k, n, rel.max())

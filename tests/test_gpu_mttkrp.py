@@ -19,7 +19,7 @@ def _torch():
 
 def _fused(dims, ranks, seed, signed=False):
     facs = [uniform_factors(dims, r, seed + k) for k, r in enumerate(ranks)]
-    U = [np.hstack([f[n] for f in facs]) for n in range(3)]
+    U = [np.hstack([f[n] for f in facs]) for n in range(len(dims))]
     if signed:
         U = [2.0 * u - 1.0 for u in U]
     return U
@@ -33,19 +33,19 @@ def _abs_scale(T, U, mode):
 def _gpu_mttkrp(T, U, pad_to=None, poison=True):
     import paper_2010_04678_amd as P
     torch = _torch()
-    dims = (T.shape[2], T.shape[1], T.shape[0])
+    dims = tuple(T.shape[::-1])
     R = U[0].shape[1]
     ld = pad_to if pad_to is not None else R
-    ctx = P.Context(max_total_rank=max(R, 1))
+    ctx = P.Context(max_total_rank=max(ld, 1) if T.ndim > 3 else max(R, 1))
     Td = torch.from_numpy(T).cuda()
     ctx.submit_tensor(Td)
     Ud = []
-    for n in range(3):
+    for n in range(T.ndim):
         buf = torch.full((dims[n], ld), float("nan") if poison else 0.0, dtype=torch.float64, device="cuda")
         buf[:, :R] = torch.from_numpy(np.ascontiguousarray(U[n])).cuda()
         Ud.append(buf)
     out = []
-    for mode in (1, 2, 3):
+    for mode in range(1, T.ndim + 1):
         M = torch.full((dims[mode - 1], ld), 777.0, dtype=torch.float64, device="cuda")
         ctx.mttkrp(mode, Ud, M, total_rank=R)
         torch.cuda.synchronize()
