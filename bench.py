@@ -15,6 +15,10 @@ tolerances, iteration caps, non-negativity, line search) and reports models comp
 `--workload sweepW1000` / `sweepW300` time the fused MTTKRP alone, all three modes, over fused widths 1..1024 on the
 cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1).  `--yardstick` prints the device's compute-unit
 count and clock and its practical peaks (back-to-back fp64 MFMA; streaming read of a 4 GiB buffer).
+
+`--workload order4` / `order5` time the path on a tensor of order 4 (180^4) / 5 (60^5), 8.4 and 6.2 GB: the fused
+MTTKRP alone per mode at several widths (contraction kernel by events, and the whole call including the explicit
+partial Khatri-Rao products), and timed rounds of the 40-model, width-420 mix of cfg4.
 """
 from __future__ import annotations
 
@@ -131,6 +135,84 @@ def run_sweep(which: str, reps: int = 3) -> dict:
             "reps": reps, "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "peak_hbm_gbs": PEAK_HBM_GBS, "rows": rows}
 
 
+ORDER_N = {"order4": (180,) * 4, "order5": (60,) * 5}
+
+
+def run_order_n(which: str, steps: int, warmup: int, reps: int = 3) -> dict:
+    """Tensors of order above 3: rank-15 Uniform[0,1) factors plus 1 % Gaussian noise, generated on the device
+    (seeded); models as in cfg4 (ranks 1..20 twice, Uniform[0,1) starting points)."""
+    import torch
+    import paper_2010_04678_amd as P
+    from workloads import get_config, uniform_factors
+    dims = ORDER_N[which]
+    N = len(dims)
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(1000 + N)
+    F = [torch.rand((d, 15), dtype=torch.float64, device=dev, generator=g) for d in dims]
+    K = F[-1]
+    for U in F[-2:0:-1]:                                     # Khatri-Rao product of modes N..2, mode 2 fastest
+        K = (K[:, None, :] * U[None, :, :]).reshape(-1, 15)
+    T = (K @ F[0].T).reshape(tuple(dims[::-1]))
+    del K
+    sigma = 0.01 * float(T.pow(2).mean().sqrt())
+    step = max(1, T.shape[0] // 8)
+    for i in range(0, T.shape[0], step):                     # noise slab by slab: no second tensor-sized buffer
+        T[i:i + step].add_(sigma * torch.randn(T[i:i + step].shape, dtype=torch.float64, device=dev, generator=g))
+    elems = float(np.prod(dims))
+    cfg = get_config(4)
+    ranks = list(cfg.ranks)
+    rstar = sum(ranks)
+    ctx = P.Context(max_total_rank=rstar, flags=P.CTX_TIMING)
+    ctx.submit_tensor(T)
+    rows = []
+    for R in (16, 128, 256, rstar):
+        ld = (R + 15) // 16 * 16
+        U = [torch.rand((d, ld), dtype=torch.float64, device=dev, generator=g) for d in dims]
+        kern, call = [], []
+        for mode in range(1, N + 1):
+            M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device=dev)
+            ctx.mttkrp(mode, U, M, total_rank=R)
+            torch.cuda.synchronize()
+            s0 = ctx.stats()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                ctx.mttkrp(mode, U, M, total_rank=R)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            s1 = ctx.stats()
+            kern.append((s1.mttkrp_ms[mode - 1] - s0.mttkrp_ms[mode - 1] + s1.reduce_ms[mode - 1] - s0.reduce_ms[mode - 1]) / reps)
+            call.append((t1 - t0) / reps * 1e3)
+        flops = 2.0 * R * elems
+        nbytes = 8.0 * elems
+        rows.append({"width": R, "kernel_ms": kern, "call_ms": call,
+                     "kernel_tflops": [flops / (m * 1e-3) * 1e-12 for m in kern],
+                     "call_tflops": [flops / (m * 1e-3) * 1e-12 for m in call],
+                     "tensor_tb_per_s": [nbytes / (m * 1e-3) * 1e-12 for m in call]})
+    ctx.close()
+    # timed rounds of the whole path
+    ctx = P.Context(max_total_rank=rstar)
+    ctx.submit_tensor(T)
+    for k, r in enumerate(ranks):
+        ctx.enqueue_model(uniform_factors(dims, r, cfg.init_seeds[k]), tol=-1.0, max_iters=warmup + steps)
+    ctx.iterate(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.iterate(steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    res = ctx.poll_retired()
+    assert len(res) == len(ranks) and all(r.iters == warmup + steps for r in res)
+    ctx.close()
+    flops = 2.0 * N * rstar * elems * steps
+    return {"metric": "fused MTTKRP fp64 GFLOP/s on an order-%d tensor; whole rounds" % N, "value": flops / dt * 1e-9,
+            "unit": "GFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": which, "dims": list(dims), "models": len(ranks), "total_rank": rstar},
+            "models_per_s": len(ranks) / dt, "fits": [round(r.fit, 6) for r in res[:4]],
+            "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "mttkrp_alone": rows}
+
+
 def run_yardstick() -> dict:
     import torch
     import paper_2010_04678_amd as P
@@ -199,6 +281,9 @@ def main() -> int:
         return 0
     if args.workload.startswith("sweepW"):
         print(json.dumps(run_sweep(args.workload)))
+        return 0
+    if args.workload in ORDER_N:
+        print(json.dumps(run_order_n(args.workload, min(args.steps, 10), args.warmup)))
         return 0
     if args.workload.endswith("job"):
         job = run_job(int(args.workload[3]), reuse=args.reuse)

@@ -109,35 +109,45 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
       if (cost < best) { best = cost; wm = cand; }
     }
   }
+  const int64_t K = (int64_t)p.Ia * p.Ib;
+  // the tensor once per column block at the practical read rate (tensors of up to 1 GiB are largely served by the
+  // last-level cache: about twice the rate)
+  const double tensor_bytes = (double)p.In * (double)K * 8.0;
+  const double tensor_us = tensor_bytes / (tensor_bytes > 1073741824.0 ? 5.5e6 : 11.0e6);
+  // Bandwidth-bound launches (few columns): four row tiles per wavefront keep four times the tensor loads in flight
+  // per wavefront and allow 16-byte loads along contiguous rows, which outweighs the padding of the row count to
+  // 256 as long as the MFMA work on the padded rows stays well below the time the tensor takes to stream.
+  if (wm != 4 && wn_top <= 7) {
+    const double padded4 = (double)((p.In + 255) / 256) * 256.0;
+    const double mfma4_us = 2.0 * padded4 * (double)K * 16.0 * ntile16 / (78.6e6 * 0.8);
+    if (mfma4_us < 0.6 * tensor_us * ny) wm = 4;
+  }
   wm = env_int("CALS_MTTKRP_WM", wm);
   if (wm != 1 && wm != 2 && wm != 4) wm = 2;
   if (wm == 4 && wn_top > 7) wm = 2;
   pl.wm = wm;
   pl.ka = 16;
   pl.mtiles = (p.In + 64 * wm - 1) / (64 * wm);
-  const int64_t K = (int64_t)p.Ia * p.Ib;
   // resident workgroups per CU: bounded by registers (accumulators) and LDS
   const int acc_tiles = wm * wn_top;
   int per_cu = (acc_tiles >= 17) ? 1 : (acc_tiles >= 10 ? 2 : (acc_tiles >= 8 ? 3 : 4));
   const int lds_fit = (int)(160 * 1024 / ((size_t)2 * pl.ka * 16 * wn_top * sizeof(double)));
   if (per_cu > lds_fit) per_cu = lds_fit;
   per_cu = env_int("CALS_MTTKRP_PERCU", per_cu);
-  // Split of the contraction range, by a cost model in microseconds.  Workgroups run in waves of `slots` (one per
-  // resident position); a launch takes about waves x (stages per workgroup + a fixed cost of 6 stages), a stage
-  // of a workgroup with t accumulator tiles per wavefront taking t x 4 MFMAs x 64 cycles at about 80 % MFMA
-  // utilisation.  More than one split adds the partials' way through memory: written once, read once by the
-  // reduction, plus the result (about 3 TB/s for these strided panels).  Splits are whole multiples of 8 when
+  // Split of the contraction range, by a cost model in microseconds.  A stage of a workgroup with t accumulator
+  // tiles per wavefront takes t x 4 MFMAs x 64 cycles at about 80 % MFMA utilisation, plus a fixed cost of about 6
+  // stages per workgroup.  More than one split adds the partials' way through memory: written once, read once by
+  // the reduction, plus the result (about 3 TB/s for these strided panels).  Splits are whole multiples of 8 when
   // there are 8 or more, so that the XCD-pinned block order gives every XCD the same number of splits; with
   // fewer splits the blocks of a split are spread over the XCDs instead.
-  const int64_t slots = (int64_t)num_cus * per_cu;
   const int64_t max_splits = std::max<int64_t>(1, K / (4 * pl.ka));   // at least two stage pairs per split
   const int force_splits = env_int("CALS_MTTKRP_SPLITS", 0);
   const double us_per_tile_stage = 4.0 * 64.0 / 2400.0 / 0.8;          // one accumulator tile, one stage (KA = 16)
   const double panel_us = (double)p.In * p.ncols * 8.0 / 3.0e6;        // one In x ncols panel through memory
-  // the tensor once per column block at the practical read rate, reached with two or more workgroups per CU
-  // (tensors of up to 1 GiB are largely served by the last-level cache: about twice the rate)
-  const double tensor_bytes = (double)p.In * (double)K * 8.0;
-  const double tensor_us = tensor_bytes / (tensor_bytes > 1073741824.0 ? 5.5e6 : 11.0e6);
+  // the practical read rate needs enough loads in flight: two workgroups per CU with four row tiles per wavefront,
+  // three with two, four with one; and the workgroups share the bandwidth, so a launch lasts about as long as the
+  // CU with the most of them
+  const int64_t wgs_for_rate = (int64_t)num_cus * (wm == 4 ? 2 : (wm == 2 ? 3 : 4));
   int64_t splits = 1;
   double best_cost = 1e300;
   for (int64_t cand = 1; cand <= std::min<int64_t>(max_splits, 4096); cand = (cand < 8) ? cand + 1 : cand + 8) {
@@ -145,9 +155,18 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
     double cost = 0.0;
     for (int q = 0; q < pl.nparts; ++q) {
       const int64_t wgs = (int64_t)pl.mtiles * pl.part[q].ny * cand;
-      const int64_t waves = (wgs + slots - 1) / slots;
-      const double mfma_us = (double)waves * (2.0 * pairs + 6.0) * us_per_tile_stage * wm * pl.part[q].wn;
-      const double fill = wgs >= 2 * (int64_t)num_cus ? 1.0 : (double)(2 * num_cus) / (double)wgs;
+      // The workgroups of a CU share its MFMA pipes whether they are resident together or one after the other, so
+      // the busiest CU sets the time; co-residents hide each other's fixed cost and, for small tiles, each other's
+      // non-MFMA instructions (measured: one / two / three resident workgroups of up to 9 accumulator tiles reach
+      // 0.87 / 0.96 / 1 of the three-resident rate, of 10 to 16 tiles 0.92 / 1).
+      const int64_t on_cu = (wgs + num_cus - 1) / num_cus;
+      const int resident = (int)std::min<int64_t>(per_cu, on_cu);
+      const double overlap = acc_tiles >= 17 ? 1.0
+                             : (acc_tiles >= 10 ? (resident >= 2 ? 1.0 : 0.92)
+                                                : (resident >= 3 ? 1.0 : (resident == 2 ? 0.96 : 0.87)));
+      const double mfma_us = (double)on_cu * (2.0 * pairs + 6.0 / resident) * us_per_tile_stage * wm * pl.part[q].wn / overlap;
+      double fill = wgs >= wgs_for_rate ? 1.0 : (double)wgs_for_rate / (double)wgs;
+      fill *= (double)((wgs + num_cus - 1) / num_cus * num_cus) / (double)wgs;
       const double hbm_us = tensor_us * pl.part[q].ny * fill;
       cost += mfma_us > hbm_us ? mfma_us : hbm_us;
     }
