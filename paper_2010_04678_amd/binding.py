@@ -286,9 +286,10 @@ def suggest_max_total_rank(ranks: Sequence[int], plateau: int = 256) -> int:
 def cp_cals(T, inits: Sequence[Sequence[np.ndarray]], tol: float = 1e-4, max_iters: int = 50, nonneg: bool = False,
             line_search: bool = False, ls_alpha: float = 1.2, max_total_rank: Optional[int] = None, max_slots: int = 0,
             two_step: bool = False):
-    """Runs one CP-ALS model per entry of `inits` (three factor matrices I_n x R_k each) concurrently on the tensor T
-    (numpy (I3, I2, I1) C-contiguous, or a CUDA float64 torch tensor of that shape) and returns, in the order of
-    `inits`, a list of (Result, [U1, U2, U3], lambda).  Pure marshalling around the C calls."""
+    """Runs one CP-ALS model per entry of `inits` (one factor matrix I_n x R_k per mode) concurrently on the tensor T
+    (numpy (I_N, ..., I2, I1) C-contiguous, or a CUDA float64 torch tensor of that shape; N = 3 .. MAX_MODES) and
+    returns, in the order of `inits`, a list of (Result, [U1, ..., UN], lambda).  Pure marshalling around the C calls
+    (two_step applies to order-3 tensors only)."""
     ranks = [int(u[0].shape[1]) for u in inits]
     rstar = int(max_total_rank) if max_total_rank is not None else suggest_max_total_rank(ranks)
     flags = (FLAG_NONNEG if nonneg else 0) | (FLAG_LINESEARCH if line_search else 0)
