@@ -114,7 +114,8 @@ int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const 
  * column-major I_n x rank starting factor of mode n+1; it is copied.  tol < 0 means "never stop
  * by tolerance" (fixed iteration count).  ls_alpha is read only with CALS_MODEL_LINESEARCH.
  * Errors: STATE (no tensor), INVALID (rank < 1, > CALS_MAX_RANK or > R*; max_iters < 1; NaN
- * tol/alpha; NaN/Inf in init), UNSUPPORTED (NONNEG together with LINESEARCH). */
+ * tol/alpha; NaN/Inf in init).  NONNEG and LINESEARCH may be combined: the extrapolated point is then clipped
+ * at zero before its error is evaluated. */
 int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const* init, double tol, int32_t max_iters,
                        uint32_t flags, double ls_alpha, int64_t* model_id);
 

@@ -30,6 +30,8 @@
  *     H(n) is positive definite); a non-positive or non-finite pivot stops the model with
  *     status NUMERICAL, leaving the factors it had before the failing update.
  *   - every column of an updated factor is scaled to unit 2-norm, the norms kept in lambda.
+ *   - non-negativity together with line search (the paper describes each alone): the extrapolated point is
+ *     clipped at zero entry by entry before its error is evaluated, so every point a NONNEG model visits is feasible.
  *   - non-negativity: Lawson-Hanson active set on the normal equations per row; the passive set of the
  *     previous iteration is a warm start that is dropped when its sub-block of H is not positive definite.
  *   - order 3: sums over the two contracted indices are nested: the inner sum runs over the lower-
@@ -590,7 +592,10 @@ int oracle_model_iterate(oracle_model* m, const double* T, double normT2) {
           for (int64_t i = 0; i < In; ++i) {
             const double cur = m->U[n][i + In * r] * scale;
             const double prev = m->Aprev[n][i + In * r];
-            m->Anew[n][i + In * r] = prev + m->alpha * (cur - prev);
+            double v = prev + m->alpha * (cur - prev);
+            /* NONNEG models: the extrapolated point is projected back onto the feasible set */
+            if ((m->flags & ORACLE_FLAG_NONNEG) && !(v > 0.0)) v = 0.0;
+            m->Anew[n][i + In * r] = v;
           }
         }
       }

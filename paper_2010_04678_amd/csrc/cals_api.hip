@@ -804,7 +804,6 @@ int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const* init, dou
   if (rank < 1 || rank > CALS_MAX_RANK || rank > c->opt.max_total_rank || max_iters < 1) return CALS_E_INVALID;
   if (std::isnan(tol)) return CALS_E_INVALID;
   if (flags & ~(CALS_MODEL_NONNEG | CALS_MODEL_LINESEARCH)) return CALS_E_INVALID;
-  if ((flags & CALS_MODEL_NONNEG) && (flags & CALS_MODEL_LINESEARCH)) return CALS_E_UNSUPPORTED;
   if ((flags & CALS_MODEL_LINESEARCH) && !std::isfinite(ls_alpha)) return CALS_E_INVALID;
   if (flags & CALS_MODEL_NONNEG) CALS_TRY(ensure_nn_buffers(c));
   if (flags & CALS_MODEL_LINESEARCH) CALS_TRY(ensure_ls_buffers(c));

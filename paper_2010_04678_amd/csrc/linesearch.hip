@@ -40,6 +40,7 @@ __global__ void __launch_bounds__(256) ls_extrapolate_kernel(LineSearchArgs a) {
   if (ls_takes_part(d, o)) {
     const double prev = a.Uprev[mode][e];
     v = prev + d.alpha * (cur - prev);
+    if ((d.flags & 1u) && !(v > 0.0)) v = 0.0;   // NONNEG models: projected back onto the feasible set
   }
   a.Unew[mode][e] = v;
 }

@@ -119,8 +119,8 @@ def test_argument_errors():
     with pytest.raises(P.CalsError) as e:
         ctx.submit_tensor(T)
     assert e.value.code == -2                                  # one tensor per context
-    for kwargs, code in [(dict(max_iters=0), -1), (dict(tol=float("nan")), -1), (dict(flags=3), -5),
-                         (dict(flags=8), -1)]:
+    for kwargs, code in [(dict(max_iters=0), -1), (dict(tol=float("nan")), -1), (dict(flags=8), -1),
+                         (dict(flags=2, ls_alpha=float("inf")), -1)]:
         with pytest.raises(P.CalsError) as e:
             ctx.enqueue_model(good, **kwargs)
         assert e.value.code == code, kwargs
@@ -203,6 +203,34 @@ def test_nonneg_matches_oracle():
             if models[r.model_id]["flags"]:
                 assert min(u.min() for u in facs[r.model_id][0]) >= 0.0
     assert any((facs[r.model_id][0][0] == 0.0).any() for r in results if models[r.model_id]["flags"])
+
+
+def test_nonneg_with_line_search_matches_oracle():
+    # both extensions on one model: the extrapolated point is clipped at zero before it is judged.  Large steps
+    # (entries cross zero, some steps rejected), a tall mode (row-blocked kernels), other kinds of models alongside,
+    # with and without two-step sweeps.
+    import paper_2010_04678_amd as P
+    both = O.FLAG_NONNEG | O.FLAG_LINESEARCH
+    for dims, seed in [((40, 24, 18), 1500), ((300, 12, 9), 1520)]:
+        base = uniform_factors(dims, 1, seed)
+        true = [np.hstack([b + 0.2 * u[:, [r]] for r in range(4)]) for b, u in zip(base, uniform_factors(dims, 4, seed + 1))]
+        T = np.ascontiguousarray(np.einsum("ir,jr,kr->kji", *true) + 0.05 * random_tensor(dims, seed + 2, signed=True))
+        models = []
+        for k, (r, fl, al) in enumerate([(3, both, 2.5), (4, both, 1.3), (2, O.FLAG_NONNEG, 1.0), (5, both, 4.0),
+                                         (3, O.FLAG_LINESEARCH, 1.3), (17, both, 1.6), (4, 0, 1.0)]):
+            models.append(dict(rank=r, init=uniform_factors(dims, r, seed + 10 + k), tol=[-1.0, 1e-6][k % 2],
+                               max_iters=[14, 40][k % 2], flags=fl, ls_alpha=al))
+        ref = O.cals(T, models, 24, 4)
+        for ctx_flags in (0, P.CTX_REUSE):
+            results, facs, st = run_gpu(T, models, 24, 4, rounds_per_call=3, ctx_flags=ctx_flags)
+            compare(results, facs, ref, models)
+            acc = 0
+            for r in results:
+                if models[r.model_id]["flags"] == both:
+                    assert min(u.min() for u in facs[r.model_id][0]) >= 0.0
+                    assert r.ls_accepted <= r.iters - 1
+                    acc += r.ls_accepted
+            assert acc > 0
 
 
 def test_config3_recipe_reduced():

@@ -480,6 +480,73 @@ def test_line_search_with_alpha_one_changes_nothing_material():
     assert np.allclose(a["fit_history"], b["fit_history"], rtol=0, atol=1e-13)
 
 
+
+# ------------------------------------------------------------------ non-negativity with line search together
+
+def _nn_ls_problem():
+    dims, R = (12, 10, 9), 3
+    base = uniform_factors(dims, 1, 401)
+    true = [np.hstack([b + 0.2 * u[:, [r]] for r in range(R)]) for b, u in zip(base, uniform_factors(dims, R, 402))]
+    T = np.ascontiguousarray(reconstruct(true).transpose(2, 1, 0)) + 0.05 * random_tensor(dims, 403, signed=True)
+    return dims, R, T, uniform_factors(dims, R, 404)
+
+
+def test_nonneg_line_search_visits_only_feasible_points_and_keeps_the_error_exact():
+    dims, R, T, init = _nn_ls_problem()
+    both = O.FLAG_NONNEG | O.FLAG_LINESEARCH
+    m = O.Model(T, init, tol=-1.0, max_iters=100, flags=both, alpha=1.6)
+    nT2 = np.linalg.norm(T) ** 2
+    prev = None
+    for it in range(40):
+        m.iterate()
+        s = m.state()
+        assert min(u.min() for u in s["U"]) >= 0.0 and s["lam"].min() >= 0.0
+        e = float(((tview(T) - reconstruct(s["U"], s["lam"])) ** 2).sum())
+        assert abs(e - s["err"]) <= 1e-11 * nT2, it
+        if prev is not None:
+            assert s["err"] <= prev * (1 + 1e-12) + 1e-12 * nT2
+        prev = s["err"]
+    assert m.state()["ls_accepted"] > 0
+    # alpha = 1: the "extrapolated" point is the current one, never strictly better: the NONNEG run, unchanged
+    a = O.cp_als(T, init, tol=-1.0, max_iters=15, flags=O.FLAG_NONNEG)
+    b = O.cp_als(T, init, tol=-1.0, max_iters=15, flags=both, alpha=1.0)
+    assert np.allclose(a["fit_history"], b["fit_history"], rtol=0, atol=1e-13)
+
+
+def test_nonneg_line_search_steps_replayed_by_hand_with_clipping():
+    # every iteration of a NONNEG+LINESEARCH model rebuilt from a NONNEG-only iteration and numpy: from the point
+    # kept so far (lambda folded into mode 3) a fresh NONNEG model gives the ALS point; the candidate is
+    # max(0, P_prev + alpha (P_als - P_prev)) entry by entry, taken iff its explicit residual is smaller
+    dims, R, T, init = _nn_ls_problem()
+    alpha = 2.5                                   # far enough for some entries to cross zero
+    err = lambda P: float(((tview(T) - reconstruct(P)) ** 2).sum())
+    point = lambda st: [st["U"][0], st["U"][1], st["U"][2] * st["lam"]]
+    m = O.Model(T, init, tol=-1.0, max_iters=60, flags=O.FLAG_NONNEG | O.FLAG_LINESEARCH, alpha=alpha)
+    m.iterate()
+    assert m.state()["ls_accepted"] == 0          # nothing to extrapolate from after the first iteration
+    taken_clipped = rejected = 0
+    for it in range(2, 14):
+        before = m.state()
+        P_prev = point(before)
+        fresh = O.Model(T, P_prev, tol=-1.0, max_iters=5, flags=O.FLAG_NONNEG)
+        fresh.iterate()
+        P_als = point(fresh.state())
+        raw = [a + alpha * (b - a) for a, b in zip(P_prev, P_als)]
+        cand = [np.maximum(x, 0.0) for x in raw]
+        e_als, e_cand = err(P_als), err(cand)
+        m.iterate()
+        after = m.state()
+        take = e_cand < e_als
+        assert after["ls_accepted"] - before["ls_accepted"] == int(take), it
+        want = cand if take else P_als
+        for n in range(3):
+            assert np.allclose(point(after)[n], want[n], rtol=1e-9, atol=1e-11), (it, n)
+        assert abs(after["err"] - (e_cand if take else e_als)) <= 1e-11 * np.linalg.norm(T) ** 2
+        taken_clipped += int(take and min(x.min() for x in raw) < 0.0)
+        rejected += int(not take)
+    assert taken_clipped > 0 and rejected > 0     # both branches, and the projection mattered in an accepted step
+
+
 # ------------------------------------------------------------------ order-N tensors (Alg. 1 for N modes)
 
 def nview(T):
