@@ -26,9 +26,11 @@
  *     used here: e = ||T||^2 + sum(H(N) * U(N)^T U(N)) - 2 sum(U(N) * M(N)).
  *   - fit F = 1 - sqrt(max(e,0)) / ||T||; a model stops when it >= 2 and |F - F_prev| < tol,
  *     or when it == max_iters.
- *   - the update uses a Cholesky factorisation of H(n) (identical to the pseudo-inverse when
- *     H(n) is positive definite); a non-positive or non-finite pivot stops the model with
- *     status NUMERICAL, leaving the factors it had before the failing update.
+ *   - the update is U(n) = M(n) H(n)^+ (Alg. 1, update line).  While H(n) is numerically positive definite --
+ *     every Cholesky pivot above ORACLE_RANK_TOL times its diagonal entry -- the pseudo-inverse is the inverse and
+ *     is applied through the Cholesky factor.  Otherwise H(n)^+ = V diag(1/l_i : l_i > ORACLE_RANK_TOL * l_max) V^T
+ *     from the symmetric eigen-decomposition (cyclic Jacobi).  A non-finite H(n), or one without a positive
+ *     eigenvalue, stops the model with status NUMERICAL, leaving the factors it had before the failing update.
  *   - every column of an updated factor is scaled to unit 2-norm, the norms kept in lambda.
  *   - non-negativity together with line search (the paper describes each alone): the extrapolated point is
  *     clipped at zero entry by entry before its error is evaluated, so every point a NONNEG model visits is feasible.
@@ -66,6 +68,7 @@
 
 #define ORACLE_MAX_RANK 32
 #define ORACLE_MAX_MODES 6
+#define ORACLE_RANK_TOL 1e-12   /* relative size below which a pivot or an eigenvalue counts as zero */
 
 /* ------------------------------------------------------------------------------------------ */
 /* small dense helpers                                                                         */
@@ -147,6 +150,93 @@ int oracle_cholesky(const double* H, int R, double* L) {
       L[i + R * j] = v / d;
     }
   }
+  return 0;
+}
+
+/* The same factorisation for the plain update: H counts as (numerically) positive definite only if every pivot
+ * exceeds ORACLE_RANK_TOL times the diagonal entry it started from.  Returns 0, or 1 when it does not. */
+int oracle_cholesky_definite(const double* H, int R, double* L) {
+  for (int e = 0; e < R * R; ++e) L[e] = 0.0;
+  for (int j = 0; j < R; ++j) {
+    double d = H[j + R * j];
+    for (int k = 0; k < j; ++k) d -= L[j + R * k] * L[j + R * k];
+    if (!(d > ORACLE_RANK_TOL * H[j + R * j]) || !isfinite(d)) return 1;
+    d = sqrt(d);
+    L[j + R * j] = d;
+    for (int i = j + 1; i < R; ++i) {
+      double v = H[i + R * j];
+      for (int k = 0; k < j; ++k) v -= L[i + R * k] * L[j + R * k];
+      L[i + R * j] = v / d;
+    }
+  }
+  return 0;
+}
+
+/* Eigen-decomposition of the symmetric R x R matrix A by cyclic Jacobi rotations (rows p < q in order, sweep after
+ * sweep until the off-diagonal part is negligible).  On exit the diagonal of A holds the eigenvalues and the
+ * columns of V the eigenvectors (both column-major). */
+static void jacobi_eigen(double* A, int R, double* V) {
+  for (int e = 0; e < R * R; ++e) V[e] = 0.0;
+  for (int i = 0; i < R; ++i) V[i + R * i] = 1.0;
+  for (int sweep = 0; sweep < 100; ++sweep) {
+    double off = 0.0, all = 0.0;
+    for (int q = 0; q < R; ++q)
+      for (int p = 0; p < R; ++p) {
+        all += A[p + R * q] * A[p + R * q];
+        if (p != q) off += A[p + R * q] * A[p + R * q];
+      }
+    if (!(off > 1e-34 * all)) break;
+    for (int p = 0; p < R - 1; ++p)
+      for (int q = p + 1; q < R; ++q) {
+        const double apq = A[p + R * q];
+        if (apq == 0.0) continue;
+        /* rotation angle that annihilates A[p,q]: t = tan, the smaller root of t^2 + 2 tau t - 1 = 0 */
+        const double tau = (A[q + R * q] - A[p + R * p]) / (2.0 * apq);
+        const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+        const double c = 1.0 / sqrt(1.0 + t * t), sn = t * c;
+        for (int k = 0; k < R; ++k) {          /* A <- A J (columns p, q) */
+          const double akp = A[k + R * p], akq = A[k + R * q];
+          A[k + R * p] = c * akp - sn * akq;
+          A[k + R * q] = sn * akp + c * akq;
+        }
+        for (int k = 0; k < R; ++k) {          /* A <- J^T A (rows p, q) */
+          const double apk = A[p + R * k], aqk = A[q + R * k];
+          A[p + R * k] = c * apk - sn * aqk;
+          A[q + R * k] = sn * apk + c * aqk;
+        }
+        for (int k = 0; k < R; ++k) {          /* V <- V J */
+          const double vkp = V[k + R * p], vkq = V[k + R * q];
+          V[k + R * p] = c * vkp - sn * vkq;
+          V[k + R * q] = sn * vkp + c * vkq;
+        }
+      }
+  }
+}
+
+/* Pseudo-inverse of the symmetric positive semi-definite R x R matrix H: P = sum over the eigenpairs with
+ * l_i > ORACLE_RANK_TOL * l_max of v_i v_i^T / l_i.  *rank receives the number of eigenvalues kept.
+ * Returns 0, or 1 when H has a non-finite entry or no positive eigenvalue. */
+int oracle_pinv_sym(const double* H, int R, double* P, int* rank) {
+  double A[ORACLE_MAX_RANK * ORACLE_MAX_RANK], V[ORACLE_MAX_RANK * ORACLE_MAX_RANK];
+  if (rank) *rank = 0;
+  for (int e = 0; e < R * R; ++e) {
+    if (!isfinite(H[e])) return 1;
+    A[e] = H[e];
+  }
+  jacobi_eigen(A, R, V);
+  double lmax = 0.0;
+  for (int i = 0; i < R; ++i) if (A[i + R * i] > lmax) lmax = A[i + R * i];
+  if (!(lmax > 0.0)) return 1;
+  for (int e = 0; e < R * R; ++e) P[e] = 0.0;
+  int kept = 0;
+  for (int i = 0; i < R; ++i) {
+    const double l = A[i + R * i];
+    if (!(l > ORACLE_RANK_TOL * lmax)) continue;
+    kept += 1;
+    for (int c = 0; c < R; ++c)
+      for (int r = 0; r < R; ++r) P[r + R * c] += V[r + R * i] * V[c + R * i] / l;
+  }
+  if (rank) *rank = kept;
   return 0;
 }
 
@@ -550,12 +640,22 @@ int oracle_model_iterate(oracle_model* m, const double* T, double normT2) {
       }
       if (bad) { m->status = ORACLE_NUMERICAL; m->iters -= 1; return m->status; }
       memcpy(m->U[n], Unew, sizeof(double) * (size_t)(In * R));
-    } else {                                                               /* update, U = M H^-1 */
-      if (oracle_cholesky(H, R, L)) { m->status = ORACLE_NUMERICAL; m->iters -= 1; return m->status; }
+    } else if (!oracle_cholesky_definite(H, R, L)) {                       /* update, U = M H^-1 */
       for (int64_t i = 0; i < In; ++i) {
         for (int r = 0; r < R; ++r) row[r] = m->M[i + In * r];
         oracle_cholesky_solve(L, R, row);
         for (int r = 0; r < R; ++r) m->U[n][i + In * r] = row[r];
+      }
+    } else {                                                               /* rank-deficient: U = M H^+ */
+      double* P = L;
+      if (oracle_pinv_sym(H, R, P, NULL)) { m->status = ORACLE_NUMERICAL; m->iters -= 1; return m->status; }
+      for (int64_t i = 0; i < In; ++i) {
+        for (int r = 0; r < R; ++r) row[r] = m->M[i + In * r];
+        for (int c = 0; c < R; ++c) {
+          double v = 0.0;
+          for (int k = 0; k < R; ++k) v += row[k] * P[k + R * c];
+          m->U[n][i + In * c] = v;
+        }
       }
     }
     if (n == last) {                                                       /* error terms        */

@@ -18,9 +18,10 @@ RUNNING, CONVERGED, MAX_ITERS, NUMERICAL = 0, 1, 2, 3
 FLAG_NONNEG, FLAG_LINESEARCH = 1, 2
 MAX_RANK = 32
 MAX_MODES = 6
+RANK_TOL = 1e-12
 
-__all__ = ["RUNNING", "CONVERGED", "MAX_ITERS", "NUMERICAL", "FLAG_NONNEG", "FLAG_LINESEARCH", "MAX_RANK", "MAX_MODES",
-           "num_threads", "norm_sq", "gram", "hadamard", "cholesky", "cholesky_solve", "mttkrp", "mttkrp_element",
+__all__ = ["RUNNING", "CONVERGED", "MAX_ITERS", "NUMERICAL", "FLAG_NONNEG", "FLAG_LINESEARCH", "MAX_RANK", "MAX_MODES", "RANK_TOL",
+           "num_threads", "norm_sq", "gram", "hadamard", "cholesky", "cholesky_definite", "pinv_sym", "cholesky_solve", "mttkrp", "mttkrp_element",
            "nnls_row", "Model", "cp_als", "cals"]
 
 _lib = None
@@ -55,6 +56,10 @@ def lib() -> C.CDLL:
         L.oracle_cals.restype = C.c_int64
         L.oracle_cals.argtypes = [_dp, _i64p, C.c_int, _i32p, C.POINTER(_dp), _dp, _i32p, _u32p, _dp, C.c_int64,
                                   C.c_int, C.POINTER(_dp), _dp, _dp, _dp, _i32p, _i32p, _i32p, _i32p, C.c_int64]
+        L.oracle_cholesky_definite.restype = C.c_int
+        L.oracle_cholesky_definite.argtypes = [_dp, C.c_int, _dp]
+        L.oracle_pinv_sym.restype = C.c_int
+        L.oracle_pinv_sym.argtypes = [_dp, C.c_int, _dp, C.POINTER(C.c_int)]
         _pp = C.POINTER(_dp)
         L.oracle_norm_sq_nd.restype = C.c_double
         L.oracle_norm_sq_nd.argtypes = [_dp, C.c_int, _i64p]
@@ -118,6 +123,23 @@ def cholesky(H: np.ndarray):
     L = np.zeros_like(H, order="F")
     rc = lib().oracle_cholesky(_p(H), H.shape[0], _p(L))
     return rc, L
+
+
+def cholesky_definite(H: np.ndarray):
+    """Cholesky with the relative pivot test of the plain update: (1, .) when H is numerically rank-deficient."""
+    H = _f(H)
+    L = np.zeros_like(H, order="F")
+    rc = lib().oracle_cholesky_definite(_p(H), H.shape[0], _p(L))
+    return rc, L
+
+
+def pinv_sym(H: np.ndarray):
+    """(rc, P, rank): pseudo-inverse of a symmetric positive semi-definite matrix by Jacobi eigen-decomposition."""
+    H = _f(H)
+    P = np.zeros_like(H, order="F")
+    k = C.c_int(0)
+    rc = lib().oracle_pinv_sym(_p(H), H.shape[0], _p(P), C.byref(k))
+    return rc, P, k.value
 
 
 def cholesky_solve(L: np.ndarray, b: np.ndarray) -> np.ndarray:

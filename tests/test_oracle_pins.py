@@ -276,15 +276,122 @@ def test_stop_rule_tolerance_and_iteration_cap():
     assert O.cp_als(T, init, tol=10.0, max_iters=1)["status"] == O.MAX_ITERS
 
 
-def test_singular_normal_equations_stop_the_model():
+def test_cholesky_definite_uses_a_relative_pivot_test():
+    rng = np.random.default_rng(7)
+    A = rng.standard_normal((9, 5))
+    H = A.T @ A
+    rc, L = O.cholesky_definite(H)
+    assert rc == 0 and np.allclose(L, np.linalg.cholesky(H), rtol=1e-12, atol=1e-13)
+    B = np.hstack([A[:, :3], A[:, [1]], A[:, 3:]])             # a repeated column: exactly singular Gramian
+    assert O.cholesky_definite(B.T @ B)[0] == 1
+    assert O.cholesky_definite(np.diag([1.0, 0.0, 2.0]))[0] == 1
+    for rel, want in [(1e-8, 0), (1e-10, 0), (1e-14, 1)]:       # second pivot = rel * its diagonal entry
+        Hs = np.array([[1.0, np.sqrt(1.0 - rel)], [np.sqrt(1.0 - rel), 1.0]])
+        assert O.cholesky_definite(Hs)[0] == want, rel
+    assert O.cholesky_definite(np.array([[np.nan]]))[0] == 1
+
+
+def test_pseudo_inverse_against_lapack_and_the_moore_penrose_conditions():
+    rng = np.random.default_rng(8)
+    for R, k in [(1, 1), (2, 1), (5, 3), (6, 6), (12, 7), (20, 19), (32, 16), (32, 32)]:
+        A = rng.standard_normal((R, k)) * rng.uniform(0.1, 10.0, size=(1, k))
+        H = A @ A.T
+        H = 0.5 * (H + H.T)
+        rc, P, rank = O.pinv_sym(H)
+        assert rc == 0 and rank == k, (R, k, rank)
+        want = np.linalg.pinv(H, rcond=O.RANK_TOL, hermitian=True)
+        ev = np.linalg.eigvalsh(H)[::-1][:k]
+        eps = 1e-14 * ev[0] / ev[-1]                              # rounding, amplified by the condition of the kept part
+        scale = np.abs(want).max()
+        assert np.abs(P - want).max() <= eps * scale, (R, k)
+        nH = np.abs(H).max()
+        assert np.abs(H @ P @ H - H).max() <= eps * nH
+        assert np.abs(P @ H @ P - P).max() <= eps * scale
+        assert np.abs(H @ P - (H @ P).T).max() <= eps and np.abs(P - P.T).max() <= 1e-13 * scale
+    # structure: a zero row/column stays zero; a repeated row/column shares the weight equally
+    H = np.array([[2.0, 0.0, 1.0], [0.0, 0.0, 0.0], [1.0, 0.0, 3.0]])
+    rc, P, rank = O.pinv_sym(H)
+    assert rc == 0 and rank == 2 and np.all(P[1] == 0.0) and np.all(P[:, 1] == 0.0)
+    assert np.allclose(P[np.ix_([0, 2], [0, 2])], np.linalg.inv(H[np.ix_([0, 2], [0, 2])]), rtol=1e-13)
+    rc, P, rank = O.pinv_sym(np.array([[4.0, 4.0], [4.0, 4.0]]))
+    assert rc == 0 and rank == 1 and np.allclose(P, 1.0 / 16.0, rtol=1e-14)
+    assert O.pinv_sym(np.zeros((3, 3)))[0] == 1
+    assert O.pinv_sym(np.array([[1.0, np.inf], [np.inf, 1.0]]))[0] == 1
+
+
+def _lstsq_min_norm_iteration(Tn, U):
+    """One ALS sweep where every update is the MINIMUM-NORM least-squares solution of min ||T_(n)^T - K U_n^T||
+    (LAPACK SVD; singular values of K below sqrt(RANK_TOL) of the largest count as zero)."""
+    U = [u.copy() for u in U]
+    lam = None
+    for n in range(Tn.ndim):
+        K = krp_all([U[m] for m in range(Tn.ndim) if m != n])
+        X = np.linalg.lstsq(K, unfold(Tn, n).T, rcond=math.sqrt(O.RANK_TOL))[0].T
+        lam = np.linalg.norm(X, axis=0)
+        X[:, lam <= 1e-12 * lam.max()] = 0.0            # LAPACK leaves rounding dust where the exact answer is 0
+        lam = np.linalg.norm(X, axis=0)
+        U[n] = X / np.where(lam > 0, lam, 1.0)
+    return U, lam
+
+
+@pytest.mark.parametrize("kind", ["dead", "twin", "dead_and_twin"])
+def test_rank_deficient_update_is_the_minimum_norm_solution_and_the_model_goes_on(kind):
+    # Alg. 1, update line: U = M H^+.  A component that is zero in two modes (H has a zero row and column) and a
+    # component that repeats another one (H has two equal rows and columns) make H exactly singular.
+    dims, R = (7, 6, 5), 4
+    T = random_tensor(dims, 131) + reconstruct(uniform_factors(dims, 2, 133)).transpose(2, 1, 0)
+    init = uniform_factors(dims, R, 132)
+    if "dead" in kind:
+        init[1][:, 1] = 0.0
+        init[2][:, 1] = 0.0
+    if "twin" in kind:
+        for n in range(3):
+            init[n][:, 3] = init[n][:, 0]
+    m = O.Model(T, init, tol=-1.0, max_iters=8)
+    U, lam = init, None
+    nT = np.linalg.norm(T)
+    prev = None
+    # (two identical components are an unstable arrangement: rounding differences between them grow about
+    # sixty-fold per sweep until they separate, so that case is followed for four sweeps only)
+    sweeps = 4 if "twin" in kind else 6
+    for it in range(sweeps):
+        assert m.iterate() == O.RUNNING
+        U, lam = _lstsq_min_norm_iteration(tview(T), U)
+        s = m.state()
+        assert s["iters"] == it + 1
+        if "twin" not in kind or it < 2:
+            # (how two identical components share their weight is decided by rounding dust in the LAPACK route
+            # after a few sweeps; their sum, checked below through the reconstruction, is not)
+            for n in range(3):
+                assert np.allclose(s["U"][n], U[n], rtol=1e-7, atol=1e-9), (it, n)
+            assert np.allclose(s["lam"], lam, rtol=1e-7, atol=1e-9)
+        assert np.allclose(reconstruct(s["U"], s["lam"]), reconstruct(U, lam), rtol=1e-7, atol=1e-9), it
+        e = float(((tview(T) - reconstruct(s["U"], s["lam"])) ** 2).sum())
+        assert abs(s["err"] - e) <= 1e-11 * nT ** 2 and abs(s["fit"] - (1 - math.sqrt(e) / nT)) <= 1e-10
+        assert prev is None or e <= prev * (1 + 1e-12)
+        prev = e
+        if "dead" in kind:
+            assert all(np.all(s["U"][n][:, 1] == 0.0) for n in range(3)) and s["lam"][1] == 0.0
+        if "twin" in kind:
+            assert all(np.allclose(s["U"][n][:, 3], s["U"][n][:, 0], rtol=1e-8, atol=1e-10) for n in range(3))
+    # the same trajectory as the model without the redundant components (twins carry half the weight each)
+    keep = [c for c in range(R) if not ("dead" in kind and c == 1) and not ("twin" in kind and c == 3)]
+    small = O.cp_als(T, [u[:, keep] for u in init], tol=-1.0, max_iters=sweeps)
+    s = m.state()
+    assert abs(small["fit"] - s["fit"]) <= 1e-9
+    assert np.allclose(reconstruct(small["U"], small["lam"]), reconstruct(s["U"], s["lam"]), rtol=1e-7, atol=1e-9)
+
+
+def test_normal_equations_without_a_positive_eigenvalue_stop_the_model():
     dims, R = (6, 5, 4), 2
     T = random_tensor(dims, 131)
     init = uniform_factors(dims, R, 132)
-    init[1][:, 1] = 0.0
-    init[2][:, 1] = 0.0
+    init[1][:] = 0.0                                            # H of the first update is the zero matrix
     r = O.cp_als(T, init, tol=-1.0, max_iters=5)
     assert r["status"] == O.NUMERICAL and r["iters"] == 0
     assert np.array_equal(r["U"][0], init[0])
+    z = O.cp_als(np.zeros((4, 5, 6)), uniform_factors(dims, R, 132), tol=-1.0, max_iters=5)
+    assert z["status"] == O.NUMERICAL and z["iters"] == 0       # all-zero tensor: the second update has H = 0
 
 
 # ------------------------------------------------------------------ queue (Alg. 3)
