@@ -4,6 +4,11 @@
  * advanced in lock-step so that the N MTTKRPs of an iteration are each ONE fused contraction over the
  * concatenated factor matrices.
  *
+ * The update of a mode is U = M H^+ (Alg. 1): through a Cholesky factorisation while H is numerically positive
+ * definite (every pivot above 1e-12 of its diagonal entry), else through the pseudo-inverse from an
+ * eigen-decomposition (eigenvalues up to 1e-12 of the largest count as zero), so a model with dead or duplicated
+ * components keeps running.
+ *
  * The calls follow the problem statement of the paper's full algorithm (Alg. 3): a tensor, an
  * input queue of starting points, a main loop (fill, advance all active instances one iteration,
  * remove converged instances), and an output queue.
@@ -41,7 +46,8 @@ extern "C" {
 #define CALS_RUNNING 0
 #define CALS_CONVERGED 1   /* |fit - fit_prev| < tol at an iteration >= 2            */
 #define CALS_MAX_ITERS 2   /* iteration cap reached                                   */
-#define CALS_NUMERICAL 3   /* normal equations not positive definite; last good point */
+#define CALS_NUMERICAL 3   /* normal equations non-finite or without a positive eigenvalue (plain update), or a
+                              singular block met by the non-negative search; factors of the last good point */
 
 /* per-model flags (cals_enqueue_model) */
 #define CALS_MODEL_NONNEG 1u     /* non-negative factors by an active-set method (Sec. 5)      */

@@ -3,6 +3,7 @@
 //   H = product of the cached Gramians of all other modes        -- Hadamard product of Gramians
 //   H = L L^T                                                    -- Cholesky, no pivoting
 //   U[i,:] = M[i,:] H^-1 for every row i (two triangular solves) -- normal-equation update
+//   (H numerically rank-deficient: U[i,:] = M[i,:] H^+ with H^+ from a Jacobi eigen-decomposition)
 //   last mode only: inner = sum(U * M), normsq = sum(H * U^T U)  -- terms of the fast error formula
 //   lambda_r = ||U[:,r]||_2, U[:,r] /= lambda_r, G = U^T U       -- unit columns, Gramian refresh
 // plus the small utility kernels around it (initial Gramians, ||T||^2, column gather).
@@ -66,17 +67,22 @@ __device__ inline void gram_store(const double (&gacc)[3], int R, double* Gl /* 
   }
 }
 
-// In-place lower Cholesky of the R x R matrix A (LDS, row-major, ld = R).  The updates reach every
-// element in the same order as the textbook column algorithm (k = 0,1,...).  Returns false (to all
-// threads) when a pivot is not a positive finite number.
-__device__ inline bool block_cholesky(double* A, int R, int* flag /* LDS */) {
+// A pivot, or an eigenvalue, counts as zero below this fraction of the diagonal entry it started from, or of the
+// largest eigenvalue: the normal equations are then rank-deficient and the update goes through the pseudo-inverse
+// (Alg. 1 writes the update with the pseudo-inverse of H).
+constexpr double kRankTol = 1e-12;
+
+// In-place lower Cholesky of the R x R matrix A (LDS, row-major, ld = R; H0 = the untouched original).  The
+// updates reach every element in the same order as the textbook column algorithm (k = 0,1,...).  Returns false
+// (to all threads) when a pivot is not finite or not above kRankTol times its original diagonal entry.
+__device__ inline bool block_cholesky(double* A, const double* H0, int R, int* flag /* LDS */) {
   const int tid = threadIdx.x;
   if (tid == 0) *flag = 1;
   __syncthreads();
   for (int j = 0; j < R; ++j) {
     if (tid == 0) {
       const double d = A[j * R + j];
-      if (!(d > 0.0) || !isfinite(d)) *flag = 0;
+      if (!(d > kRankTol * H0[j * R + j]) || !isfinite(d)) *flag = 0;
       else A[j * R + j] = sqrt(d);
     }
     __syncthreads();
@@ -94,6 +100,110 @@ __device__ inline bool block_cholesky(double* A, int R, int* flag /* LDS */) {
   return true;
 }
 
+// Pseudo-inverse of the symmetric positive semi-definite R x R matrix H (LDS) by a two-sided Jacobi
+// eigen-decomposition, all 256 threads of the workgroup: P = sum over eigenpairs with l_i > kRankTol * l_max of
+// v_i v_i^T / l_i.  Rotations of one step act on disjoint index pairs (round-robin tournament over the indices), so
+// a step is: angles from the 2 x 2 blocks, all column rotations (A and V), all row rotations (A).
+// A (R*R; may be H itself), V (R*R), P (R*R), cs (>= 64 doubles; may be red), red (256 doubles) are LDS work areas.
+// Returns false (to all threads) when H has a non-finite entry or no positive eigenvalue.
+__device__ inline bool block_pinv(const double* H, int R, double* A, double* V, double* P, double* cs, double* red,
+                                  int* flag /* LDS */) {
+  const int tid = threadIdx.x;
+  if (tid == 0) *flag = 1;
+  __syncthreads();
+  for (int e = tid; e < R * R; e += 256) {
+    const double h = H[e];
+    if (!isfinite(h)) *flag = 0;
+    A[e] = h;
+    V[e] = (e / R == e % R) ? 1.0 : 0.0;
+  }
+  __syncthreads();
+  if (*flag == 0) return false;
+  const int Re = (R + 1) & ~1;                 // even number of players; index R (when R is odd) sits out
+  const int half = Re / 2;
+  for (int sweep = 0; sweep < 60; ++sweep) {
+    double off = 0.0, all = 0.0;
+    for (int e = tid; e < R * R; e += 256) {
+      const double v = A[e] * A[e];
+      all += v;
+      if (e / R != e % R) off += v;
+    }
+    off = block_sum(off, red);
+    all = block_sum(all, red);
+    if (!(off > 1e-34 * all)) break;
+    for (int step = 0; step < Re - 1; ++step) {
+      if (tid < half) {
+        // circle method: player Re-1 stays, the others rotate
+        int p = (tid == 0) ? Re - 1 : (step + tid) % (Re - 1);
+        int q = (tid == 0) ? step : (step - tid + (Re - 1)) % (Re - 1);
+        if (p > q) { const int t = p; p = q; q = t; }
+        double c = 1.0, sn = 0.0;
+        if (q < R) {
+          const double apq = A[p * R + q];
+          if (apq != 0.0) {
+            const double tau = (A[q * R + q] - A[p * R + p]) / (2.0 * apq);
+            const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+            c = 1.0 / sqrt(1.0 + t * t);
+            sn = t * c;
+          }
+        } else {
+          q = p;                                // sits out: identity on a valid index
+        }
+        cs[4 * tid + 0] = c;
+        cs[4 * tid + 1] = sn;
+        cs[4 * tid + 2] = (double)p;
+        cs[4 * tid + 3] = (double)q;
+      }
+      __syncthreads();
+      for (int w = tid; w < half * R; w += 256) {          // columns p, q of A and of V
+        const int i = w / R, k = w % R;
+        const double c = cs[4 * i], sn = cs[4 * i + 1];
+        const int p = (int)cs[4 * i + 2], q = (int)cs[4 * i + 3];
+        if (p != q) {
+          const double akp = A[k * R + p], akq = A[k * R + q];
+          A[k * R + p] = c * akp - sn * akq;
+          A[k * R + q] = sn * akp + c * akq;
+          const double vkp = V[k * R + p], vkq = V[k * R + q];
+          V[k * R + p] = c * vkp - sn * vkq;
+          V[k * R + q] = sn * vkp + c * vkq;
+        }
+      }
+      __syncthreads();
+      for (int w = tid; w < half * R; w += 256) {          // rows p, q of A
+        const int i = w / R, k = w % R;
+        const double c = cs[4 * i], sn = cs[4 * i + 1];
+        const int p = (int)cs[4 * i + 2], q = (int)cs[4 * i + 3];
+        if (p != q) {
+          const double apk = A[p * R + k], aqk = A[q * R + k];
+          A[p * R + k] = c * apk - sn * aqk;
+          A[q * R + k] = sn * apk + c * aqk;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  if (tid == 0) {
+    double lmax = 0.0;
+    for (int i = 0; i < R; ++i) lmax = A[i * R + i] > lmax ? A[i * R + i] : lmax;
+    red[0] = lmax;
+    if (!(lmax > 0.0)) *flag = 0;
+  }
+  __syncthreads();
+  const double cut = kRankTol * red[0];
+  const bool ok = *flag != 0;
+  for (int e = tid; e < R * R; e += 256) {
+    const int r = e / R, c = e % R;
+    double acc = 0.0;
+    for (int i = 0; i < R; ++i) {
+      const double l = A[i * R + i];
+      if (l > cut) acc += V[r * R + i] * V[c * R + i] / l;
+    }
+    P[e] = acc;
+  }
+  __syncthreads();
+  return ok;
+}
+
 // ---- modes of at most 256 rows: one workgroup per model, one row per thread, everything in one pass ----------
 // The two latency chains of the update are kept out of LDS: the Cholesky factorisation runs in ONE wavefront with
 // row i of the working matrix in lane i's registers (pivot column broadcast through v_readlane; right-looking, so
@@ -106,12 +216,13 @@ __device__ __forceinline__ bool wave_cholesky(const double* H, double* L, int R,
   double arow[RM];
 #pragma unroll
   for (int k = 0; k < RM; ++k) arow[k] = (lane < R && k < R) ? H[lane * R + k] : 0.0;
+  const double diag0 = (lane < R) ? H[lane * R + lane] : 1.0;
   bool ok = true;
 #pragma unroll
   for (int j = 0; j < RM; ++j) {
     if (ok && j < R) {
       const double djj = readlane_f64(arow[j], j);
-      if (!(djj > 0.0) || !isfinite(djj)) {
+      if (!(djj > kRankTol * readlane_f64(diag0, j)) || !isfinite(djj)) {
         ok = false;
       } else {
         const double ljj = sqrt(djj);
@@ -186,6 +297,21 @@ __device__ __forceinline__ void solve_rows_small(const UpdateArgs& a, const Mode
   }
 }
 
+// x = m P for this thread's row (P symmetric R x R in LDS): x is built in the output row (scratch use of memory the
+// caller overwrites anyway) and then staged in xs[. * kXs + tid] like every other solved row.
+__device__ inline void row_times_matrix(const double* P, int R, const double* mrow, double* urow, double* xs) {
+  const int tid = threadIdx.x;
+  for (int r = 0; r < R; ++r) xs[r * kXs + tid] = mrow[r];
+  for (int c = 0; c < R; ++c) {
+    double v = 0.0;
+    for (int k = 0; k < R; ++k) v += xs[k * kXs + tid] * P[k * R + c];
+    urow[c] = v;
+  }
+  for (int r = 0; r < R; ++r) xs[r * kXs + tid] = urow[r];
+}
+
+__device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d, double* lds, int* flagp);
+
 template <int RM>
 __device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDesc& d, int slot, double* lds, int* flag) {
   ModelState* st = a.state + d.sid;
@@ -215,7 +341,12 @@ __device__ __forceinline__ void update_small(const UpdateArgs& a, const ModelDes
   }
   __syncthreads();
   if (*flag == 0) {
-    if (tid == 0) out->status = 3;            // CALS_NUMERICAL; factors of this mode stay untouched
+    if (nonneg) {
+      if (tid == 0) out->status = 3;          // CALS_NUMERICAL; factors of this mode stay untouched
+    } else {
+      __syncthreads();
+      update_wide(a, d, lds, flag);           // rank-deficient normal equations: the general path applies H^+
+    }
     return;
   }
 
@@ -306,6 +437,7 @@ __device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d
   __syncthreads();
   // NONNEG models: the rows were solved by the non-negative update already (a.X); only its outcome is read
   const bool nonneg = (d.flags & 1u) != 0;
+  bool pinv = false;
   if (nonneg) {
     if (tid == 0) {
       flag = a.nn_fail[blockIdx.x];
@@ -316,9 +448,13 @@ __device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d
       if (tid == 0) out->status = 3;
       return;
     }
-  } else if (!block_cholesky(L, R, &flag)) {
-    if (tid == 0) out->status = 3;            // CALS_NUMERICAL; factors of this mode stay untouched
-    return;
+  } else if (!block_cholesky(L, H, R, &flag)) {
+    // rank-deficient: P = H^+ takes the factor's place (work areas: Gl and the row staging block, both free now)
+    if (!block_pinv(H, R, Gl, xs, L, red, red, &flag)) {
+      if (tid == 0) out->status = 3;          // CALS_NUMERICAL; factors of this mode stay untouched
+      return;
+    }
+    pinv = true;
   }
 
   double gacc[3] = {0.0, 0.0, 0.0};
@@ -330,9 +466,12 @@ __device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d
     const int nrows = (a.In - base < kRows) ? (a.In - base) : kRows;
     if (i < a.In) {
       const double* mrow = Mb + (int64_t)i * a.ld;
+      double* urow = Ub + (int64_t)i * a.ld;
       if (nonneg) {
         const double* xrow = a.X + (int64_t)i * a.ld + d.col;
         for (int r = 0; r < R; ++r) xs[r * kXs + tid] = xrow[r];
+      } else if (pinv) {
+        row_times_matrix(L, R, mrow, urow, xs);
       } else {
         for (int r = 0; r < R; ++r) xs[r * kXs + tid] = mrow[r];
         // L y = m
@@ -348,7 +487,6 @@ __device__ __noinline__ void update_wide(const UpdateArgs& a, const ModelDesc& d
           xs[r * kXs + tid] = v / L[r * R + r];
         }
       }
-      double* urow = Ub + (int64_t)i * a.ld;
       double part = 0.0;
       for (int r = 0; r < R; ++r) {
         const double x = xs[r * kXs + tid];
@@ -441,10 +579,15 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
     for (int e = tid; e < R * R; e += 256) H[e] = hadamard_of_others(st, a.nmodes, a.mode, e);
     for (int e = tid; e < RMs * RMs; e += 256) L[e] = (e / RMs == e % RMs && e / RMs >= R) ? 1.0 : 0.0;
   } else {
-    for (int e = tid; e < R * R; e += 256) L[e] = hadamard_of_others(st, a.nmodes, a.mode, e);
+    for (int e = tid; e < R * R; e += 256) {
+      const double h = hadamard_of_others(st, a.nmodes, a.mode, e);
+      H[e] = h;
+      L[e] = h;
+    }
   }
   __syncthreads();
   const bool nonneg = (d.flags & 1u) != 0;
+  bool pinv = false;
   bool failed;
   if (nonneg) {
     if (tid == 0) flag = a.nn_fail[blockIdx.x];   // cleared by update_finish_kernel
@@ -464,7 +607,13 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
     __syncthreads();
     failed = flag == 0;
   } else {
-    failed = !block_cholesky(L, R, &flag);
+    failed = !block_cholesky(L, H, R, &flag);
+  }
+  if (failed && !nonneg) {
+    // rank-deficient: every row block computes the same P = H^+ (in the factor's place; H is used up as work area)
+    __syncthreads();
+    failed = !block_pinv(H, R, H, xs, L, red, red, &flag);
+    pinv = !failed;
   }
   if (failed) {
     if (tid == 0 && blockIdx.y == 0) out->status = 3;   // CALS_NUMERICAL; factors of this mode stay untouched
@@ -479,7 +628,7 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
   double inner = 0.0;
   const double* Mb = a.M + d.col;
   double* Ub = a.U + d.col;
-  if (small) {
+  if (small && !pinv) {
     switch (RMs) {
       case 4: solve_rows_small<4>(a, d, L, xs, nonneg, r0, r1, gacc, inner); break;
       case 8: solve_rows_small<8>(a, d, L, xs, nonneg, r0, r1, gacc, inner); break;
@@ -487,7 +636,7 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
       default: solve_rows_small<16>(a, d, L, xs, nonneg, r0, r1, gacc, inner); break;
     }
   }
-  for (int base = small ? r1 : r0; base < r1; base += kRows) {
+  for (int base = (small && !pinv) ? r1 : r0; base < r1; base += kRows) {
     const int i = base + tid;
     const int nrows = (r1 - base < kRows) ? (r1 - base) : kRows;
     if (i < r1) {
@@ -495,6 +644,8 @@ __global__ void __launch_bounds__(256) update_solve_kernel(UpdateArgs a) {
       if (nonneg) {
         const double* xrow = a.X + (int64_t)i * a.ld + d.col;
         for (int r = 0; r < R; ++r) xs[r * kXs + tid] = xrow[r];
+      } else if (pinv) {
+        row_times_matrix(L, R, mrow, Ub + (int64_t)i * a.ld, xs);
       } else {
         for (int r = 0; r < R; ++r) xs[r * kXs + tid] = mrow[r];
         for (int r = 0; r < R; ++r) {          // L y = m

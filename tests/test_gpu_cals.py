@@ -80,19 +80,52 @@ def test_queue_with_tolerances_slots_and_refill():
 
 
 def test_numerical_failure_retires_only_that_model():
+    # normal equations without a positive eigenvalue (a whole factor is zero) stop that model and no other
     dims = (12, 10, 8)
     T = random_tensor(dims, 77)
     models = []
     for k, r in enumerate([2, 3, 2]):
         init = uniform_factors(dims, r, 950 + k)
         if k == 1:
-            init[1][:, 2] = 0.0
-            init[2][:, 2] = 0.0      # H of the first update has a zero row: not positive definite
+            init[1][:] = 0.0         # H of the first update is the zero matrix
         models.append(dict(rank=r, init=init, tol=-1.0, max_iters=6, flags=0, ls_alpha=1.0))
     ref = O.cals(T, models, 7)
-    assert ref["status"][1] == O.NUMERICAL
+    assert ref["status"][1] == O.NUMERICAL and ref["iters"][1] == 0
     results, facs, _ = run_gpu(T, models, 7)
     compare(results, facs, ref, models)
+
+
+@pytest.mark.parametrize("dims", [(12, 10, 8), (300, 9, 7), (9, 280, 6, 5)])
+def test_rank_deficient_normal_equations_go_through_the_pseudo_inverse(dims):
+    # Alg. 1, update line: U = M H^+.  Dead components (zero in all other modes: H has a zero row and column) and
+    # duplicated components (equal rows and columns) among ordinary models; ranks on both sides of the register /
+    # LDS split of the update kernels; short modes (one workgroup per model) and a tall one (row blocks).
+    N = len(dims)
+    T = np.ascontiguousarray(random_tensor(dims, 78) + 0.5)
+    models = []
+    for k, (r, kind) in enumerate([(3, "dead"), (4, "plain"), (5, "twin"), (17, "dead"), (24, "dead"), (21, "twin"),
+                                   (2, "plain"), (32, "dead")]):
+        init = uniform_factors(dims, r, 960 + k)
+        if kind == "dead":
+            for n in range(1, N):
+                init[n][:, r // 2] = 0.0
+        if kind == "twin":
+            for n in range(N):
+                init[n][:, r - 1] = init[n][:, 0]
+        # (two identical components drift apart through rounding, sixty-fold and more per sweep: two sweeps only)
+        models.append(dict(rank=r, init=init, tol=-1.0, max_iters=2 if kind == "twin" else 7, flags=0, ls_alpha=1.0,
+                           kind=kind))
+    R = sum(m["rank"] for m in models)
+    ref = O.cals(T, models, R)
+    assert all(st == O.MAX_ITERS for st in ref["status"])
+    results, facs, _ = run_gpu(T, models, R, rounds_per_call=2)
+    compare(results, facs, ref, models)
+    for r in results:
+        m = models[r.model_id]
+        U, lam = facs[r.model_id]
+        if m["kind"] == "dead":
+            c = m["rank"] // 2
+            assert lam[c] == 0.0 and all(np.all(U[n][:, c] == 0.0) for n in range(N))
 
 
 def test_argument_errors():
