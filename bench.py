@@ -143,22 +143,13 @@ def run_order_n(which: str, steps: int, warmup: int, reps: int = 3) -> dict:
     (seeded); models as in cfg4 (ranks 1..20 twice, Uniform[0,1) starting points)."""
     import torch
     import paper_2010_04678_amd as P
-    from workloads import get_config, uniform_factors
+    from workloads import get_config, low_rank_tensor_device, uniform_factors
     dims = ORDER_N[which]
     N = len(dims)
     dev = torch.device("cuda:0")
+    T, _ = low_rank_tensor_device(dims, 15, 1000 + N, noise=0.01)
     g = torch.Generator(device=dev)
-    g.manual_seed(1000 + N)
-    F = [torch.rand((d, 15), dtype=torch.float64, device=dev, generator=g) for d in dims]
-    K = F[-1]
-    for U in F[-2:0:-1]:                                     # Khatri-Rao product of modes N..2, mode 2 fastest
-        K = (K[:, None, :] * U[None, :, :]).reshape(-1, 15)
-    T = (K @ F[0].T).reshape(tuple(dims[::-1]))
-    del K
-    sigma = 0.01 * float(T.pow(2).mean().sqrt())
-    step = max(1, T.shape[0] // 8)
-    for i in range(0, T.shape[0], step):                     # noise slab by slab: no second tensor-sized buffer
-        T[i:i + step].add_(sigma * torch.randn(T[i:i + step].shape, dtype=torch.float64, device=dev, generator=g))
+    g.manual_seed(7)
     elems = float(np.prod(dims))
     cfg = get_config(4)
     ranks = list(cfg.ranks)

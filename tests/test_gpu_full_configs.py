@@ -172,3 +172,38 @@ def test_config5_full():
     res2, facs2, st2 = gpu_run(T, models, cfg, keep=sample, ctx_flags=P.CTX_REUSE)
     assert [(r.model_id, r.iters, r.status) for r in res2] == [(r.model_id, r.iters, r.status) for r in res]
     check_models(res2, facs2, models, ref, sample)
+
+
+def test_order_4_at_bench_size_sampled_elements():
+    # the order-4 workload of bench.py (180^4, 8.4 GB, the 40-model mix of configuration 4: width 420), every mode,
+    # sampled elements against the oracle's extended-precision sums
+    import torch
+    import paper_2010_04678_amd as P
+    from workloads import low_rank_tensor_device, uniform_factors
+    cfg = get_config(4)
+    dims = (180,) * 4
+    Td, _ = low_rank_tensor_device(dims, 15, 1004, noise=0.01)
+    T = Td.cpu().numpy()
+    U = [np.hstack([uniform_factors(dims, r, s)[n] for r, s in zip(cfg.ranks, cfg.init_seeds)]) for n in range(4)]
+    R = U[0].shape[1]
+    ld = (R + 15) // 16 * 16
+    ctx = P.Context(max_total_rank=R)
+    ctx.submit_tensor(Td)
+    Ud = []
+    for n in range(4):
+        buf = torch.zeros((dims[n], ld), dtype=torch.float64, device="cuda")
+        buf[:, :R] = torch.from_numpy(np.ascontiguousarray(U[n])).cuda()
+        Ud.append(buf)
+    rng = np.random.default_rng(44)
+    for mode in (1, 2, 3, 4):
+        M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda")
+        ctx.mttkrp(mode, Ud, M, total_rank=R)
+        Mh = M.cpu().numpy()
+        rows = np.concatenate([[0, dims[mode - 1] - 1], rng.integers(0, dims[mode - 1], 10)])
+        cols = np.concatenate([[0, R - 1], rng.integers(0, R, 10)])
+        for i, c in zip(rows, cols):
+            want, scale = O.mttkrp_element(T, U, mode, int(i), int(c))
+            assert abs(Mh[i, c] - want) <= MTTKRP_TOL * scale, (mode, i, c, Mh[i, c], want)
+    ctx.close()
+    del Td, Ud
+    torch.cuda.empty_cache()

@@ -12,4 +12,5 @@ from .generators import (  # noqa: F401
     uniform_factors,
     random_tensor,
     low_rank_tensor,
+    low_rank_tensor_device,
 )

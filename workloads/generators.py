@@ -53,6 +53,28 @@ def low_rank_tensor(dims: Sequence[int], rank: int, seed: int, noise: float = 0.
     return T
 
 
+def low_rank_tensor_device(dims: Sequence[int], rank: int, seed: int, noise: float = 0.0, device: str = "cuda:0"):
+    """The same kind of tensor as low_rank_tensor, built on the GPU with torch (sizes that would take minutes on the
+    host): Uniform[0,1) factors from a torch generator seeded with `seed`, plus Gaussian noise of std
+    noise * rms(noise-free tensor), added slab by slab.  Returns (tensor of shape dims reversed, list of factors)."""
+    import torch
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(int(seed))
+    F = [torch.rand((int(d), int(rank)), dtype=torch.float64, device=dev, generator=g) for d in dims]
+    K = F[-1]
+    for U in F[-2:0:-1]:                                     # Khatri-Rao product of modes N..2, mode 2 fastest
+        K = (K[:, None, :] * U[None, :, :]).reshape(-1, int(rank))
+    T = (K @ F[0].T).reshape(tuple(int(d) for d in dims)[::-1])
+    del K
+    if noise > 0.0:
+        sigma = noise * float(T.pow(2).mean().sqrt())
+        step = max(1, T.shape[0] // 8)
+        for i in range(0, T.shape[0], step):
+            T[i:i + step].add_(sigma * torch.randn(T[i:i + step].shape, dtype=torch.float64, device=dev, generator=g))
+    return T, F
+
+
 def _collinear_factor(I: int, R: int, c: float, seed: int, stream: int) -> np.ndarray:
     """I x R matrix with unit columns whose pairwise cosine is exactly c (up to rounding)."""
     g = _rng(seed, stream)
