@@ -10,7 +10,8 @@ resident in HBM before the timed region.  Prints ONE JSON line.
 
 `--workload cfgNjob` (N = 1..5) instead runs the configuration's whole job once as it is specified (queue, slots,
 tolerances, iteration caps, non-negativity, line search) and reports models completed per second; --steps and
---warmup do not apply.  The default run appends the cfg5 job (the queue workload) under "jobs".
+--warmup do not apply.  The default run appends the cfg5 job (the queue workload) under "jobs" and the order-4
+workload (see below) under "order_n".
 
 `--workload sweepW1000` / `sweepW300` time the fused MTTKRP alone, all three modes, over fused widths 1..1024 on the
 cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1).  `--yardstick` prints the device's compute-unit
@@ -382,6 +383,17 @@ def main() -> int:
     del Td
     if args.workload == "cfg4" and not args.no_jobs:
         out["jobs"] = [run_job(5, reuse=args.reuse)] + ([] if args.reuse else [run_job(5, reuse=True)])
+    if args.workload == "cfg4" and not args.no_jobs and not args.reuse:
+        # the same model mix on an order-4 tensor of the same size (180^4): whole rounds and the fused MTTKRP per mode
+        try:
+            o4 = run_order_n("order4", min(K, 10), W, reps=2)
+            full = o4["mttkrp_alone"][-1]
+            out["order_n"] = [{"workload": "order4", "dims": o4["config"]["dims"], "total_rank": o4["config"]["total_rank"],
+                               "ms_per_step": o4["ms_per_step"], "gflops": o4["value"],
+                               "mttkrp_ms_per_mode": full["kernel_ms"], "mttkrp_tflops_per_mode": full["kernel_tflops"]}]
+        except Exception as e:          # a report line, not a reason to lose the main measurement
+            out["order_n"] = [{"workload": "order4", "error": repr(e)}]
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, T, active)
     print(json.dumps(out))

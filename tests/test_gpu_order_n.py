@@ -133,3 +133,29 @@ def test_order_n_argument_errors_and_reuse_flag():
     ref = O.cp_als(T, init, tol=-1.0, max_iters=5)
     assert r.iters == 5 and abs(r.fit - ref["fit"]) <= 1e-8
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_seeded_random_order_n_queues_match_oracle(seed):
+    # random small jobs on tensors of order 3 to 5: dims, ranks, tolerances, caps, R*, slot limits and all four
+    # combinations of the two extensions (plain, NONNEG, LINESEARCH, both); some with a tall mode
+    rng = np.random.default_rng(8000 + seed)
+    N = int(rng.choice([3, 4, 4, 5]))
+    dims = [int(rng.choice([2, 3, 5, 8, 11, 17])) for _ in range(N)]
+    if seed % 4 == 3:
+        dims[int(rng.integers(0, N))] = int(rng.choice([270, 300]))           # row-blocked update kernels
+    dims = tuple(dims)
+    T = low_rank_tensor(dims, int(rng.integers(2, 5)), 8100 + seed, noise=0.05)
+    models = []
+    for k in range(int(rng.integers(3, 10))):
+        r = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 20, 21, 32]))
+        models.append(dict(rank=r, init=uniform_factors(dims, r, 8200 + 100 * seed + k),
+                           tol=float(rng.choice([-1.0, 1e-3, 1e-5])), max_iters=int(rng.integers(2, 22)),
+                           flags=int(rng.choice([0, 1, 2, 3])), ls_alpha=float(rng.choice([1.1, 1.3, 2.0, 3.0]))))
+    rmax = max(m["rank"] for m in models)
+    rstar = int(rng.integers(rmax, rmax + 40))
+    slots = int(rng.choice([0, 2, 3, 5]))
+    ref = O.cals(T, models, rstar, slots)
+    results, facs, st = run_gpu(T, models, rstar, slots, rounds_per_call=int(rng.integers(1, 9)))
+    compare(results, facs, ref, models)
+    assert st.rounds == ref["rounds"]
