@@ -105,7 +105,8 @@ int cals_destroy(cals_ctx* c);
  * on_device = 1: `data` is a device pointer, BORROWED until cals_destroy (the caller keeps it
  * alive and unchanged); on_device = 0: `data` is a host pointer and is copied.  Computes ||T||^2
  * (needed once by the error formula of Alg. 1) and rejects a tensor with a NaN/Inf entry.
- * One tensor per context: a second call returns CALS_E_STATE. */
+ * One tensor per context: a second call returns CALS_E_STATE, also when the first one failed after its
+ * argument checks (destroy the context and start again). */
 int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], int on_device);
 
 /* The same for a tensor of order ndims (Alg. 1 and Alg. 3 are stated for N modes): 3 <= ndims <= CALS_MAX_MODES,

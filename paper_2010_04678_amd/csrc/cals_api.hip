@@ -710,7 +710,7 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
 int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const int64_t* dims, int on_device) {
   if (!c || !data || !dims) return CALS_E_INVALID;
   if (ndims < 3 || ndims > CALS_MAX_MODES) return CALS_E_INVALID;
-  if (c->has_tensor) return CALS_E_STATE;
+  if (c->has_tensor || c->nmodes != 0) return CALS_E_STATE;   // also after an attempt that failed half-way
   int64_t total = 1;
   for (int n = 0; n < ndims; ++n) {
     if (dims[n] < 1 || dims[n] >= (1LL << 31)) return CALS_E_INVALID;

@@ -165,6 +165,7 @@ struct NnlsArgs {
   int In, ld, mode, n_models, capacity;
   int nmodes;           // tensor order
   int max_rank;         // largest rank among the NONNEG models of this launch
+  int rows_per_block;   // set by launch_nnls
 };
 hipError_t launch_nnls(const NnlsArgs& a, hipStream_t stream);
 

@@ -14,9 +14,14 @@
 //     as a failed Cholesky factorisation;
 //   - feasibility, the step length and the choice of the entering variable are wavefront votes and reductions;
 //     ties in the gradient test go to the lowest index, as in a scalar left-to-right scan;
-//   - all control flow is uniform over the wavefront, so no barrier and no LDS are needed.
+//   - all control flow is uniform over the wavefront, so the search needs no barrier.
+// The chains of dependent register operations make the kernel latency-bound, so what counts is how many wavefronts
+// a SIMD holds: H sits in LDS (one copy per workgroup; a wavefront reloads its working rows from there for every
+// solve), the pivots' reciprocals share one lane-indexed register, and the kernel is instantiated per largest rank
+// class of the launch, so that a queue of low-rank models does not run with the register budget of rank 32.
 #include <cfloat>
 #include <cmath>
+#include <cstdlib>
 
 #include "cals_internal.h"
 
@@ -33,19 +38,17 @@ __device__ inline double wave_min(double v) {
   return v;
 }
 
-constexpr int kNnlsRowsPerBlock = 16;   // 4 wavefronts x 4 rows
+constexpr int kNnlsRowsPerBlock = 4;    // default: 4 wavefronts x 1 row (short critical path per wavefront)
 
 // All rows [row0, row1) with stride 4 from row0 + wave, for one model of rank R <= RM.
 template <int RM>
 __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d, int slot, int row0, int row1, int lane,
-                                          int wave) {
+                                          int wave, const double* Hs /* LDS: (RM+1) rows of RM+1, zero outside R x R */) {
   const int R = d.rank;
-  const ModelState* st = a.state + d.sid;
   const bool live = lane < R;
-  double hrow[RM];                       // row `lane` of H = Ga * Gb (zero outside R x R)
-#pragma unroll
-  for (int k = 0; k < RM; ++k)
-    hrow[k] = (live && k < R) ? hadamard_of_others(st, a.nmodes, a.mode, lane * R + k) : 0.0;
+  // row `lane` of H; lanes beyond the rank read the zero row.  (volatile: every use is a fresh LDS read -- the
+  // compiler would otherwise keep the whole row in registers for the lifetime of the wavefront)
+  const double* hrow = Hs + (live ? lane : RM) * (RM + 1);
   double cs = 0.0;                       // H is symmetric: row sums are column sums
 #pragma unroll
   for (int k = 0; k < RM; ++k) cs += fabs(hrow[k]);
@@ -69,7 +72,7 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
 #pragma unroll
         for (int k = 0; k < RM; ++k) arow[k] = hrow[k];
         double b = m;
-        double rpiv[RM];                   // reciprocals of the pivots (uniform), reused by the back-substitution
+        double rpiv = 0.0;                 // lane j: reciprocal of pivot j, reused by the back-substitution
         bool ok = true;
 #pragma unroll
         for (int j = 0; j < RM; ++j) {
@@ -78,8 +81,9 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
             if (!(dj > 0.0) || !isfinite(dj)) {
               ok = false;
             } else {
-              rpiv[j] = 1.0 / dj;
-              const double mult = (lane > j) ? arow[j] * rpiv[j] : 0.0;
+              const double rp = 1.0 / dj;
+              rpiv = (lane == j) ? rp : rpiv;
+              const double mult = (lane > j) ? arow[j] * rp : 0.0;
               const double bj = readlane_f64(b, j);
               b = fma(-mult, bj, b);
 #pragma unroll
@@ -99,7 +103,7 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
 #pragma unroll
         for (int k = RM - 1; k >= 0; --k) {
           if ((P >> k) & 1u) {
-            const double sk = readlane_f64(b, k) * rpiv[k];
+            const double sk = readlane_f64(b, k) * readlane_f64(rpiv, k);
             s = (lane == k) ? sk : s;
             b = (lane < k) ? fma(-arow[k], sk, b) : b;
           }
@@ -140,31 +144,61 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
   }
 }
 
-__global__ void __launch_bounds__(256) nnls_kernel(NnlsArgs a) {
-  const ModelDesc d = a.desc[blockIdx.x];
-  if (!(d.flags & 1u)) return;
-  if (a.out[d.sid].status != 0) return;
-  const int row0 = blockIdx.y * kNnlsRowsPerBlock;
-  if (row0 >= a.In) return;
-  const int row1 = (row0 + kNnlsRowsPerBlock < a.In) ? (row0 + kNnlsRowsPerBlock) : a.In;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  switch ((d.rank + 3) / 4) {           // register arrays sized to the rank rounded up to a multiple of 4
-    case 1: nnls_rows<4>(a, d, blockIdx.x, row0, row1, lane, wave); break;
-    case 2: nnls_rows<8>(a, d, blockIdx.x, row0, row1, lane, wave); break;
-    case 3: nnls_rows<12>(a, d, blockIdx.x, row0, row1, lane, wave); break;
-    case 4: nnls_rows<16>(a, d, blockIdx.x, row0, row1, lane, wave); break;
-    case 5: nnls_rows<20>(a, d, blockIdx.x, row0, row1, lane, wave); break;
-    case 6: nnls_rows<24>(a, d, blockIdx.x, row0, row1, lane, wave); break;
-    case 7: nnls_rows<28>(a, d, blockIdx.x, row0, row1, lane, wave); break;
-    default: nnls_rows<32>(a, d, blockIdx.x, row0, row1, lane, wave); break;
+// RMAX = the largest rank class among the NONNEG models of the launch: the kernel's register budget is that of
+// its widest instantiation, so a queue of low-rank models runs with many more wavefronts per SIMD.
+template <int RM, int RMAX>
+__device__ __forceinline__ void nnls_class(const NnlsArgs& a, const ModelDesc& d, int row0, int row1, double* Hs) {
+  if constexpr (RM <= RMAX) {
+    const ModelState* st = a.state + d.sid;
+    const int R = d.rank;
+    for (int e = threadIdx.x; e < (RM + 1) * (RM + 1); e += 256) {
+      const int r = e / (RM + 1), k = e % (RM + 1);
+      Hs[e] = (r < R && k < R) ? hadamard_of_others(st, a.nmodes, a.mode, r * R + k) : 0.0;
+    }
+    __syncthreads();
+    nnls_rows<RM>(a, d, blockIdx.x, row0, row1, threadIdx.x & 63, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), Hs);
   }
 }
 
-hipError_t launch_nnls(const NnlsArgs& a, hipStream_t stream) {
-  if (a.n_models < 1 || a.In < 1) return hipSuccess;
-  hipLaunchKernelGGL(nnls_kernel, dim3(a.n_models, (a.In + kNnlsRowsPerBlock - 1) / kNnlsRowsPerBlock), dim3(256), 0,
-                     stream, a);
+template <int RMAX>
+__global__ void __launch_bounds__(256) nnls_kernel(NnlsArgs a) {
+  __shared__ double Hs[(RMAX + 1) * (RMAX + 1)];
+  const ModelDesc d = a.desc[blockIdx.x];
+  if (!(d.flags & 1u)) return;
+  if (a.out[d.sid].status != 0) return;
+  const int row0 = blockIdx.y * a.rows_per_block;
+  if (row0 >= a.In) return;
+  const int row1 = (row0 + a.rows_per_block < a.In) ? (row0 + a.rows_per_block) : a.In;
+  switch ((d.rank + 3) / 4) {           // register arrays sized to the rank rounded up to a multiple of 4
+    case 1: nnls_class<4, RMAX>(a, d, row0, row1, Hs); break;
+    case 2: nnls_class<8, RMAX>(a, d, row0, row1, Hs); break;
+    case 3: nnls_class<12, RMAX>(a, d, row0, row1, Hs); break;
+    case 4: nnls_class<16, RMAX>(a, d, row0, row1, Hs); break;
+    case 5: nnls_class<20, RMAX>(a, d, row0, row1, Hs); break;
+    case 6: nnls_class<24, RMAX>(a, d, row0, row1, Hs); break;
+    case 7: nnls_class<28, RMAX>(a, d, row0, row1, Hs); break;
+    default: nnls_class<32, RMAX>(a, d, row0, row1, Hs); break;
+  }
+}
+
+static int env_rows_per_block() {
+  const char* v = getenv("CALS_NNLS_ROWS");
+  const int r = (v && *v) ? atoi(v) : kNnlsRowsPerBlock;
+  return (r >= 4 && r <= 64 && r % 4 == 0) ? r : kNnlsRowsPerBlock;
+}
+
+hipError_t launch_nnls(const NnlsArgs& a0, hipStream_t stream) {
+  if (a0.n_models < 1 || a0.In < 1) return hipSuccess;
+  NnlsArgs a = a0;
+  a.rows_per_block = env_rows_per_block();
+  const dim3 grid(a.n_models, (a.In + a.rows_per_block - 1) / a.rows_per_block);
+  const int rmax = a.max_rank < 1 ? 1 : a.max_rank;
+  if (rmax <= 8) hipLaunchKernelGGL(nnls_kernel<8>, grid, dim3(256), 0, stream, a);
+  else if (rmax <= 12) hipLaunchKernelGGL(nnls_kernel<12>, grid, dim3(256), 0, stream, a);
+  else if (rmax <= 16) hipLaunchKernelGGL(nnls_kernel<16>, grid, dim3(256), 0, stream, a);
+  else if (rmax <= 20) hipLaunchKernelGGL(nnls_kernel<20>, grid, dim3(256), 0, stream, a);
+  else if (rmax <= 24) hipLaunchKernelGGL(nnls_kernel<24>, grid, dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(nnls_kernel<32>, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
