@@ -64,3 +64,21 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_launch_plan_invariants_on_the_host(tmp_path):
+    # host logic of the fused MTTKRP: tile shape, column blocks and split of the contraction range for ~760 000
+    # shapes (grid of boundary values plus pseudo-random ones); compiled against the built library, no GPU touched
+    import shutil
+    import subprocess
+    import pytest
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not available")
+    exe = str(tmp_path / "plan_check")
+    src = os.path.join(ROOT, "tests", "host", "plan_check.cpp")
+    libdir = os.path.dirname(binding.library_path())
+    r = subprocess.run(["hipcc", "-O1", "-o", exe, src, "-L" + libdir, "-lcals_hip", "-Wl,-rpath," + libdir],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.startswith("ok "), r.stdout[-500:]
