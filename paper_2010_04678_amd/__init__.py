@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     Stats,
     cp_cals,
     suggest_max_total_rank,
+    suggest_two_step,
     library_path,
     load_library,
     FLAG_NONNEG,
@@ -22,4 +23,5 @@ from .binding import (  # noqa: F401
     MAX_ITERS,
     NUMERICAL,
     MAX_RANK,
+    MAX_MODES,
 )

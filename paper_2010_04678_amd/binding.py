@@ -283,15 +283,30 @@ def suggest_max_total_rank(ranks: Sequence[int], plateau: int = 256) -> int:
     return max(max(ranks), min(sum(ranks), int(plateau)))
 
 
+def suggest_two_step(dims: Sequence[int], max_total_rank: int, budget_bytes: int = 32 << 30) -> bool:
+    """Whether two-step sweeps (CTX_REUSE) pay off: they save one of the three passes over the tensor per sweep at
+    the price of an intermediate of I2*I3*ld doubles, and of a few more launches per round.  Measured: 41 -> 29 ms
+    per sweep on 1000^3 at width 420, 112 -> 151 models/s on the 4000x200x50 queue job, 874 -> 1011 on 200^3, but
+    3440 -> 3270 on 32^3, where a round is launch-bound.  So: order 3, at least 2^20 tensor elements, and an
+    intermediate within `budget_bytes`."""
+    dims = [int(d) for d in dims]
+    if len(dims) != 3:
+        return False
+    ld = (int(max_total_rank) + 15) // 16 * 16
+    return dims[0] * dims[1] * dims[2] >= (1 << 20) and dims[1] * dims[2] * ld * 8 <= int(budget_bytes)
+
+
 def cp_cals(T, inits: Sequence[Sequence[np.ndarray]], tol: float = 1e-4, max_iters: int = 50, nonneg: bool = False,
             line_search: bool = False, ls_alpha: float = 1.2, max_total_rank: Optional[int] = None, max_slots: int = 0,
-            two_step: bool = False):
+            two_step: Optional[bool] = None):
     """Runs one CP-ALS model per entry of `inits` (one factor matrix I_n x R_k per mode) concurrently on the tensor T
     (numpy (I_N, ..., I2, I1) C-contiguous, or a CUDA float64 torch tensor of that shape; N = 3 .. MAX_MODES) and
     returns, in the order of `inits`, a list of (Result, [U1, ..., UN], lambda).  Pure marshalling around the C calls
-    (two_step applies to order-3 tensors only)."""
+    two_step: two-step sweeps (CTX_REUSE; order-3 tensors only); None = decide by suggest_two_step."""
     ranks = [int(u[0].shape[1]) for u in inits]
     rstar = int(max_total_rank) if max_total_rank is not None else suggest_max_total_rank(ranks)
+    if two_step is None:
+        two_step = suggest_two_step(tuple(int(d) for d in T.shape)[::-1], rstar)
     flags = (FLAG_NONNEG if nonneg else 0) | (FLAG_LINESEARCH if line_search else 0)
     ctx = Context(max_total_rank=rstar, max_slots=max_slots, flags=CTX_REUSE if two_step else 0)
     try:

@@ -126,7 +126,7 @@ def test_cp_cals_driver_matches_per_model_oracle_runs():
     dims = (30, 26, 22)
     T = _lowrank_tensor(dims, 4, 77, noise=0.05)
     inits = [uniform_factors(dims, r, 700 + k) for k, r in enumerate([2, 5, 3, 7, 4, 1, 6])]
-    for two_step in (False, True):
+    for two_step in (False, True, None):      # None: the driver decides (suggest_two_step)
         out = P.cp_cals(T, inits, tol=1e-5, max_iters=60, max_total_rank=12, two_step=two_step)
         assert len(out) == len(inits)
         for k, (res, U, lam) in enumerate(out):
