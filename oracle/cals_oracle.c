@@ -504,8 +504,11 @@ int oracle_nnls_row(const double* H, const double* m, int R, double* x, uint32_t
         }
       for (int a = 0; a < np; ++a) {
         int j = idx[a];
+        /* a variable that bounds the step has reached zero and leaves the passive set, whatever rounding makes
+         * of x + beta (s - x) for it (it can come out as a tiny positive number, and the search would stall) */
+        const int bounding = !(s[a] > 0.0) && (x[j] / (x[j] - s[a]) == beta);
         x[j] = x[j] + beta * (s[a] - x[j]);
-        if (!(x[j] > 0.0)) { x[j] = 0.0; P &= ~(1u << j); }
+        if (bounding || !(x[j] > 0.0)) { x[j] = 0.0; P &= ~(1u << j); }
       }
       if (++steps > cap) break;
     }

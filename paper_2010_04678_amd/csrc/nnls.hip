@@ -115,9 +115,12 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
           x = inP ? s : 0.0;
           break;
         }
-        const double beta = wave_min(nonpos ? x / (x - s) : 1.0);   // fmin drops the NaN of 0/0
+        const double q = nonpos ? x / (x - s) : 1.0;
+        const double beta = wave_min(q);                            // fmin drops the NaN of 0/0
         const double xn = x + beta * (s - x);
-        const bool keep = inP && (xn > 0.0);
+        // a variable that bounds the step has reached zero and leaves the passive set, whatever rounding makes of
+        // x + beta (s - x) for it (a tiny positive result would stall the search)
+        const bool keep = inP && (xn > 0.0) && !(nonpos && q == beta);
         x = keep ? xn : 0.0;
         P = (uint32_t)__ballot(keep);
         if (++steps > cap) break;
@@ -156,17 +159,18 @@ __device__ __forceinline__ void nnls_class(const NnlsArgs& a, const ModelDesc& d
       Hs[e] = (r < R && k < R) ? hadamard_of_others(st, a.nmodes, a.mode, r * R + k) : 0.0;
     }
     __syncthreads();
-    nnls_rows<RM>(a, d, blockIdx.x, row0, row1, threadIdx.x & 63, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), Hs);
+    nnls_rows<RM>(a, d, blockIdx.y, row0, row1, threadIdx.x & 63, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), Hs);
   }
 }
 
 template <int RMAX>
 __global__ void __launch_bounds__(256) nnls_kernel(NnlsArgs a) {
   __shared__ double Hs[(RMAX + 1) * (RMAX + 1)];
-  const ModelDesc d = a.desc[blockIdx.x];
+  // grid: x = row blocks (a mode can have millions of rows), y = slot positions (at most a few thousand)
+  const ModelDesc d = a.desc[blockIdx.y];
   if (!(d.flags & 1u)) return;
   if (a.out[d.sid].status != 0) return;
-  const int row0 = blockIdx.y * a.rows_per_block;
+  const int row0 = blockIdx.x * a.rows_per_block;
   if (row0 >= a.In) return;
   const int row1 = (row0 + a.rows_per_block < a.In) ? (row0 + a.rows_per_block) : a.In;
   switch ((d.rank + 3) / 4) {           // register arrays sized to the rank rounded up to a multiple of 4
@@ -191,7 +195,8 @@ hipError_t launch_nnls(const NnlsArgs& a0, hipStream_t stream) {
   if (a0.n_models < 1 || a0.In < 1) return hipSuccess;
   NnlsArgs a = a0;
   a.rows_per_block = env_rows_per_block();
-  const dim3 grid(a.n_models, (a.In + a.rows_per_block - 1) / a.rows_per_block);
+  if (a.n_models > 65535) return hipErrorInvalidValue;
+  const dim3 grid((a.In + a.rows_per_block - 1) / a.rows_per_block, a.n_models);
   const int rmax = a.max_rank < 1 ? 1 : a.max_rank;
   if (rmax <= 8) hipLaunchKernelGGL(nnls_kernel<8>, grid, dim3(256), 0, stream, a);
   else if (rmax <= 12) hipLaunchKernelGGL(nnls_kernel<12>, grid, dim3(256), 0, stream, a);

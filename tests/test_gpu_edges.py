@@ -165,3 +165,21 @@ def test_seeded_random_queues_match_oracle(seed):
     for flags in (0, P.CTX_REUSE):
         results, facs, st = run_gpu(T, models, rstar, slots, rounds_per_call=int(rng.integers(1, 9)), ctx_flags=flags)
         compare(results, facs, ref, models)
+
+
+@pytest.mark.parametrize("dims", [(100003, 30, 20), (20, 30, 100003), (7, 200001, 5)])
+def test_very_long_modes(dims):
+    # one mode of 1e5 rows and more: many row blocks in the contraction, the row-blocked update at its block cap,
+    # long contraction ranges for the two short modes; MTTKRP element-wise and three iterations of a small queue
+    from test_gpu_mttkrp import TOL, _abs_scale, _fused, _gpu_mttkrp
+    T = _lowrank_tensor(dims, 3, 4100, noise=0.1)
+    U = _fused(dims, [3, 8, 20, 1], 4200)
+    got = _gpu_mttkrp(T, U, pad_to=37)
+    for mode in (1, 2, 3):
+        want = O.mttkrp(T, U, mode)
+        err = np.abs(got[mode - 1] - want)
+        assert np.all(err <= TOL * _abs_scale(T, U, mode) + 1e-300), mode
+    models = [_model(dims, r, 4300 + r, max_iters=3, flags=f) for r, f in [(2, 0), (5, O.FLAG_LINESEARCH), (3, O.FLAG_NONNEG), (17, 0)]]
+    ref = O.cals(T, models, 27, 0)
+    results, facs, st = run_gpu(T, models, 27, 0, rounds_per_call=2)
+    compare(results, facs, ref, models)

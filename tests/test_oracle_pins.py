@@ -471,6 +471,27 @@ def test_nnls_matches_lawson_hanson_library_and_kkt():
                 assert rc2 == 0 and np.allclose(x2, x, rtol=1e-8, atol=1e-10)
 
 
+def test_nnls_bounding_variable_leaves_the_passive_set():
+    # right-hand sides (tests/golden/nnls_stall_cases.txt, written by make_nnls_stall_cases.py) on which a search
+    # that removes passive variables only by "x <= 0 after the step" stalls at a non-optimal point: the variable
+    # that bounds the step must leave the set even when rounding leaves it a tiny positive value
+    lines = [ln for ln in open(os.path.join(GOLD, "nnls_stall_cases.txt")) if not ln.startswith("#")]
+    H = np.array([float.fromhex(v) for v in lines[0].split()]).reshape(3, 3)
+    rhs = [np.array([float.fromhex(v) for v in ln.split()]) for ln in lines[1:]]
+    assert len(rhs) >= 20
+    L = np.linalg.cholesky(H)
+    for m in rhs:
+        rc, x, P = O.nnls_row(H, m)
+        want, _ = scipy.optimize.nnls(L.T, np.linalg.solve(L, m))
+        f = lambda v: 0.5 * v @ H @ v - m @ v
+        assert rc == 0 and x.min() >= 0.0
+        assert f(x) <= f(want) + 1e-12 * abs(f(want))
+        assert np.allclose(x, want, rtol=1e-7, atol=1e-9)
+        w = m - H @ x                                   # KKT: gradient zero on the support, non-positive elsewhere
+        assert np.all(np.abs(w[x > 0]) <= 1e-9 * np.abs(m).max()) and np.all(w[x == 0] <= 1e-9 * np.abs(m).max())
+        assert P == sum(1 << j for j in range(3) if x[j] > 0)
+
+
 def test_nnls_semidefinite_normal_equations_and_unusable_warm_start():
     # a dead component makes H only semi-definite (zero row and column): it must stay at zero, and a warm
     # start that contains it (so that its sub-block cannot be factorised) is dropped, not fatal
