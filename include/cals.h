@@ -59,7 +59,9 @@ extern "C" {
                               mode-1 multi-matrix (Y[(i2,i3),c] = sum_i1 T * U1) and obtain the mode-2 and mode-3
                               MTTKRPs from Y instead of from the tensor (partial-contraction reuse, the scheme of
                               Phan et al. cited in Sec. 2; same results up to rounding order, one pass over the
-                              tensor fewer per sweep).  Costs a device buffer of I2*I3*ld doubles. */
+                              tensor fewer per sweep).  Costs a device buffer of I2*I3*ld doubles.  Order N > 3
+                              likewise: Y has one row per (i2,...,iN) -- I2*...*IN*ld doubles -- and serves the
+                              MTTKRPs of modes 2..N, so a sweep reads the tensor twice instead of N times. */
 
 #define CALS_MAX_RANK 32 /* largest number of components of one model */
 #define CALS_MAX_MODES 6 /* largest tensor order */
@@ -113,7 +115,7 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
  * dims[0..ndims), first index fastest.  For output mode n the N-1 contracted modes form a fast and a slow run of
  * consecutive modes; a run of more than one mode enters the fused contraction as the explicit Khatri-Rao product of
  * its factor multi-matrices (device buffers of prod(run dims) x ld doubles, allocated here), so every product of
- * the dims of such a run must stay below 2^31.  CALS_CTX_REUSE has no effect for ndims > 3.
+ * the dims of such a run must stay below 2^31.
  * Errors as cals_submit_tensor; INVALID also for ndims out of range. */
 int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const int64_t* dims, int on_device);
 
@@ -162,6 +164,12 @@ int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const
  * INVALID (arguments). */
 int cals_mttkrp_reuse(cals_ctx* c, int32_t total_rank, int64_t ld, const double* const U_dev[3], double* M2_dev,
                       double* M3_dev);
+
+/* The same for any order (needs CALS_CTX_REUSE): Y from U_dev[0], then for every mode n >= 2 the MTTKRP
+ *   M_n[i_n,c] = sum over (i2..iN without i_n) of Y[(i2,..,iN),c] * prod_{m >= 2, m != n} U_m[i_m,c],   c < total_rank,
+ * into M_dev[n-1] (device, row-major I_n x ld; M_dev[0] is ignored and may be null).  U_dev[n] for all N modes.
+ * Errors: STATE (context without CALS_CTX_REUSE or no tensor), INVALID (arguments). */
+int cals_mttkrp_reuse_nd(cals_ctx* c, int32_t total_rank, int64_t ld, const double* const* U_dev, double* const* M_dev);
 
 /* Counters and timings (see cals_stats).  Synchronises the stream when timing is on. */
 int cals_get_stats(cals_ctx* c, cals_stats* s);

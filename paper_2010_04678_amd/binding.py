@@ -23,7 +23,7 @@ MAX_RANK = 32
 MAX_MODES = 6
 
 EXPORTS = ["cals_create", "cals_destroy", "cals_submit_tensor", "cals_submit_tensor_nd", "cals_enqueue_model", "cals_iterate", "cals_run",
-           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_mttkrp_reuse", "cals_get_stats", "cals_yardstick",
+           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_mttkrp_reuse", "cals_mttkrp_reuse_nd", "cals_get_stats", "cals_yardstick",
            "cals_strerror"]
 
 
@@ -106,6 +106,7 @@ def load_library() -> C.CDLL:
     L.cals_get_factors.argtypes = [vp, C.c_int64, C.POINTER(vp), vp]
     L.cals_mttkrp.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(vp), vp]
     L.cals_mttkrp_reuse.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(vp), vp, vp]
+    L.cals_mttkrp_reuse_nd.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(vp), C.POINTER(vp)]
     L.cals_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.cals_yardstick.argtypes = [vp, C.c_int32, vp, C.c_int64, C.c_int32, C.POINTER(C.c_double)]
     L.cals_strerror.argtypes = [C.c_int]
@@ -254,6 +255,25 @@ class Context:
         assert M3_dev.is_cuda and M3_dev.is_contiguous() and M3_dev.shape == (self.dims[2], ld)
         _check(self._L.cals_mttkrp_reuse(self._h, tr, ld, ptrs, M2_dev.data_ptr(), M3_dev.data_ptr()), "cals_mttkrp_reuse")
 
+    # -- cals_mttkrp_reuse_nd
+    def mttkrp_reuse_nd(self, U_dev: Sequence, M_dev: Sequence, total_rank: Optional[int] = None) -> None:
+        """MTTKRPs of modes 2..N through the contraction of the tensor with U_dev[0]; M_dev[n] (I_n x ld) for n >= 1,
+        M_dev[0] may be None."""
+        N = len(self.dims)
+        ld = int(M_dev[1].shape[1])
+        tr = int(total_rank) if total_rank is not None else ld
+        up = (C.c_void_p * N)()
+        mp = (C.c_void_p * N)()
+        for n in range(N):
+            u = U_dev[n]
+            assert u.is_cuda and u.is_contiguous() and u.shape == (self.dims[n], ld)
+            up[n] = u.data_ptr()
+            if n >= 1:
+                m = M_dev[n]
+                assert m.is_cuda and m.is_contiguous() and m.shape == (self.dims[n], ld)
+                mp[n] = m.data_ptr()
+        _check(self._L.cals_mttkrp_reuse_nd(self._h, tr, ld, up, mp), "cals_mttkrp_reuse_nd")
+
     # -- cals_yardstick
     def yardstick(self, kind: int, buf=None, reps: int = 5) -> float:
         """kind 0: fp64 MFMA issue rate (TFLOP/s); kind 1: streaming read of the CUDA tensor `buf` (GB/s)."""
@@ -284,16 +304,17 @@ def suggest_max_total_rank(ranks: Sequence[int], plateau: int = 256) -> int:
 
 
 def suggest_two_step(dims: Sequence[int], max_total_rank: int, budget_bytes: int = 32 << 30) -> bool:
-    """Whether two-step sweeps (CTX_REUSE) pay off: they save one of the three passes over the tensor per sweep at
-    the price of an intermediate of I2*I3*ld doubles, and of a few more launches per round.  Measured: 41 -> 29 ms
-    per sweep on 1000^3 at width 420, 112 -> 151 models/s on the 4000x200x50 queue job, 874 -> 1011 on 200^3, but
-    3440 -> 3270 on 32^3, where a round is launch-bound.  So: order 3, at least 2^20 tensor elements, and an
+    """Whether two-step sweeps (CTX_REUSE) pay off: they read the tensor twice per sweep instead of once per mode, at
+    the price of an intermediate of I2*...*IN*ld doubles and of a few more launches per round.  Measured, order 3:
+    41 -> 29 ms per sweep on 1000^3 at width 420, 112 -> 151 models/s on the 4000x200x50 queue job, 874 -> 1011 on
+    200^3, but 3440 -> 3270 on 32^3, where a round is launch-bound.  So: at least 2^20 tensor elements and an
     intermediate within `budget_bytes`."""
     dims = [int(d) for d in dims]
-    if len(dims) != 3:
-        return False
     ld = (int(max_total_rank) + 15) // 16 * 16
-    return dims[0] * dims[1] * dims[2] >= (1 << 20) and dims[1] * dims[2] * ld * 8 <= int(budget_bytes)
+    elems = 1
+    for d in dims:
+        elems *= d
+    return elems >= (1 << 20) and (elems // dims[0]) * ld * 8 <= int(budget_bytes)
 
 
 def cp_cals(T, inits: Sequence[Sequence[np.ndarray]], tol: float = 1e-4, max_iters: int = 50, nonneg: bool = False,
@@ -302,7 +323,7 @@ def cp_cals(T, inits: Sequence[Sequence[np.ndarray]], tol: float = 1e-4, max_ite
     """Runs one CP-ALS model per entry of `inits` (one factor matrix I_n x R_k per mode) concurrently on the tensor T
     (numpy (I_N, ..., I2, I1) C-contiguous, or a CUDA float64 torch tensor of that shape; N = 3 .. MAX_MODES) and
     returns, in the order of `inits`, a list of (Result, [U1, ..., UN], lambda).  Pure marshalling around the C calls
-    two_step: two-step sweeps (CTX_REUSE; order-3 tensors only); None = decide by suggest_two_step."""
+    two_step: two-step sweeps (CTX_REUSE); None = decide by suggest_two_step."""
     ranks = [int(u[0].shape[1]) for u in inits]
     rstar = int(max_total_rank) if max_total_rank is not None else suggest_max_total_rank(ranks)
     if two_step is None:

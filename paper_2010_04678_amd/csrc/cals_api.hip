@@ -283,8 +283,14 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int nco
 
 // First step of a two-step sweep: Y[(i2,i3), c] = sum_i1 T[i1,i2,i3] * U1[i1,c], i.e. the fused MTTKRP kernel on the
 // (I2*I3) x I1 unfolding with a single row of ones as the second factor.  Timed under mode index 1.
+int64_t rows_without_mode1(const cals_ctx* c) {
+  int64_t rows = 1;
+  for (int n = 1; n < c->nmodes; ++n) rows *= c->dims[n];
+  return rows;
+}
+
 int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld) {
-  const int64_t rows = c->dims[1] * c->dims[2];
+  const int64_t rows = rows_without_mode1(c);
   if (rows >= (1LL << 31) || (int64_t)(c->dims[0] + 64) * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
   MttkrpProblem p{};
   p.T = c->T; p.zeros = c->d_zeros; p.M = c->Y; p.ncols = ncols; p.ld = ld;
@@ -312,12 +318,31 @@ int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld) {
   return CALS_OK;
 }
 
-// Second step: the mode-2 (mode == 1) or mode-3 (mode == 2) MTTKRP from Y and the other remaining factor.
-int run_from_contraction(cals_ctx* c, int mode, const double* Uother, double* M, int ncols, int ld) {
-  const int I2 = (int)c->dims[1], I3 = (int)c->dims[2];
-  if (mode == 1) HIP_TRY(launch_ttv(c->Y, Uother, M, I2, I3, 1, I2, ld, ncols, c->stream));
-  else HIP_TRY(launch_ttv(c->Y, Uother, M, I3, I2, I2, 1, ld, ncols, c->stream));
-  c->mttkrp_flops += 2.0 * ncols * (double)c->dims[0] * (double)c->dims[1] * (double)c->dims[2];
+// Second step: the MTTKRP of mode `mode` (0-based, >= 1) from Y and the factors of the remaining modes.  Order 3:
+// one remaining factor (ttv_kernel).  Higher orders: the remaining modes before and after `mode` form a fast and a
+// slow run; a run of several modes enters as its explicit Khatri-Rao product, an empty one as a row of ones.
+int run_from_contraction(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld) {
+  const int N = c->nmodes;
+  if (N == 3) {
+    const int I2 = (int)c->dims[1], I3 = (int)c->dims[2];
+    if (mode == 1) HIP_TRY(launch_ttv(c->Y, U[2], M, I2, I3, 1, I2, ld, ncols, c->stream));
+    else HIP_TRY(launch_ttv(c->Y, U[1], M, I3, I2, I2, 1, ld, ncols, c->stream));
+  } else {
+    int64_t PL = 1, PR = 1;
+    for (int m = 1; m < mode; ++m) PL *= c->dims[m];
+    for (int m = mode + 1; m < N; ++m) PR *= c->dims[m];
+    if (PL >= (1LL << 31) || PR >= (1LL << 31)) return CALS_E_UNSUPPORTED;
+    const double* KL = c->d_ones;
+    const double* KR = c->d_ones;
+    if (mode > 1) CALS_TRY(run_operand(c, 1, mode, PL, U, c->Kbuf[0], ncols, ld, &KL));
+    if (mode < N - 1) CALS_TRY(run_operand(c, mode + 1, N, PR, U, c->Kbuf[1], ncols, ld, &KR));
+    const int slices = ttv2_slices((int)c->dims[mode], (int)PL, (int)PR, ld, ncols, c->num_cus);
+    if (slices > 1) CALS_TRY(ensure_workspace(c, sizeof(double) * (size_t)slices * c->dims[mode] * ld));
+    HIP_TRY(launch_ttv2(c->Y, KL, (int)PL, KR, (int)PR, M, (int)c->dims[mode], ld, ncols, slices, c->workspace, c->stream));
+  }
+  double elems = 1.0;
+  for (int n = 0; n < N; ++n) elems *= (double)c->dims[n];
+  c->mttkrp_flops += 2.0 * ncols * elems;
   c->mttkrp_launches[mode] += 1;
   return CALS_OK;
 }
@@ -545,7 +570,7 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
     if (c->Y && mode > 0) {
       // two-step sweep: modes 2 and 3 come from the tensor contracted with the mode-1 factors just updated
       if (mode == 1) CALS_TRY(run_contract_mode1(c, c->U[0], c->total_rank, c->ld));
-      CALS_TRY(run_from_contraction(c, mode, mode == 1 ? c->U[2] : c->U[1], c->M, c->total_rank, c->ld));
+      CALS_TRY(run_from_contraction(c, mode, c->U, c->M, c->total_rank, c->ld));
     } else {
       CALS_TRY(run_mttkrp(c, mode, c->U, c->M, c->total_rank, c->ld));
     }
@@ -593,7 +618,7 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
       HIP_TRY(launch_ls_extrapolate(la, c->stream));
       if (c->Y) {
         CALS_TRY(run_contract_mode1(c, c->Unew[0], c->total_rank, c->ld));
-        CALS_TRY(run_from_contraction(c, 2, c->Unew[1], c->M, c->total_rank, c->ld));
+        CALS_TRY(run_from_contraction(c, N - 1, c->Unew, c->M, c->total_rank, c->ld));
       } else {
         CALS_TRY(run_mttkrp(c, N - 1, c->Unew, c->M, c->total_rank, c->ld));
       }
@@ -749,6 +774,13 @@ int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const 
       const Runs r = contraction_runs(c, n);
       if (r.a1 - r.a0 > 1) need[0] = std::max(need[0], r.Ia);
       if (r.b1 - r.b0 > 1) need[1] = std::max(need[1], r.Ib);
+      if ((c->opt.flags & CALS_CTX_REUSE) && ndims > 3 && n >= 1) {   // second step of two-step sweeps: runs 2..n-1, n+1..N
+        int64_t pl = 1, pr = 1;
+        for (int m = 1; m < n; ++m) pl *= dims[m];
+        for (int m = n + 1; m < ndims; ++m) pr *= dims[m];
+        if (n > 2) need[0] = std::max(need[0], pl);
+        if (n < ndims - 2) need[1] = std::max(need[1], pr);
+      }
     }
     for (int q = 0; q < 2; ++q)
       if (need[q] > 0) {
@@ -757,8 +789,8 @@ int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const 
         if (ok) ok = hipMemsetAsync(c->Kbuf[q], 0, bytes, c->stream) == hipSuccess;
       }
   }
-  if ((c->opt.flags & CALS_CTX_REUSE) && ndims == 3 && dims[1] * dims[2] < (1LL << 31)) {
-    ok = ok && hipMalloc(&c->Y, sizeof(double) * (size_t)(dims[1] * dims[2]) * c->ld) == hipSuccess;
+  if ((c->opt.flags & CALS_CTX_REUSE) && rows_without_mode1(c) < (1LL << 31)) {
+    ok = ok && hipMalloc(&c->Y, sizeof(double) * (size_t)rows_without_mode1(c) * c->ld) == hipSuccess;
     ok = ok && hipMalloc(&c->d_ones, sizeof(double) * c->ld) == hipSuccess;
     ok = ok && launch_fill(c->d_ones, c->ld, 1.0, c->stream) == hipSuccess;
   }
@@ -886,9 +918,22 @@ int cals_mttkrp_reuse(cals_ctx* c, int32_t total_rank, int64_t ld, const double*
   for (int n = 0; n < 3; ++n)
     if (!U_dev[n]) return CALS_E_INVALID;
   CALS_TRY(set_device(c));
+  if (c->nmodes != 3) return CALS_E_STATE;
   CALS_TRY(run_contract_mode1(c, U_dev[0], total_rank, (int)ld));
-  CALS_TRY(run_from_contraction(c, 1, U_dev[2], M2_dev, total_rank, (int)ld));
-  CALS_TRY(run_from_contraction(c, 2, U_dev[1], M3_dev, total_rank, (int)ld));
+  CALS_TRY(run_from_contraction(c, 1, U_dev, M2_dev, total_rank, (int)ld));
+  CALS_TRY(run_from_contraction(c, 2, U_dev, M3_dev, total_rank, (int)ld));
+  return CALS_OK;
+}
+
+int cals_mttkrp_reuse_nd(cals_ctx* c, int32_t total_rank, int64_t ld, const double* const* U_dev, double* const* M_dev) {
+  if (!c || !U_dev || !M_dev) return CALS_E_INVALID;
+  if (!c->T || !c->Y) return CALS_E_STATE;
+  if (total_rank < 1 || ld < total_rank || ld > c->ld) return CALS_E_INVALID;
+  for (int n = 0; n < c->nmodes; ++n)
+    if (!U_dev[n] || (n >= 1 && !M_dev[n])) return CALS_E_INVALID;
+  CALS_TRY(set_device(c));
+  CALS_TRY(run_contract_mode1(c, U_dev[0], total_rank, (int)ld));
+  for (int n = 1; n < c->nmodes; ++n) CALS_TRY(run_from_contraction(c, n, U_dev, M_dev[n], total_rank, (int)ld));
   return CALS_OK;
 }
 

@@ -204,6 +204,15 @@ hipError_t launch_ls_apply(const LineSearchArgs& a, hipStream_t stream);
 hipError_t launch_ttv(const double* Y, const double* U, double* M, int no, int ns, int64_t so, int64_t ss, int ld,
                       int ncols, hipStream_t stream);
 hipError_t launch_fill(double* p, int64_t n, double v, hipStream_t stream);
+// Order above 3:  M[o, c] = sum_{r < PR} sum_{l < PL} Y[(l + PL * (o + no * r)) * ld + c] * KL[l * ld + c] * KR[r * ld + c]
+// (fixed summation order); KL / KR are row-major with leading dimension ld (a single row of ones when PL / PR = 1).
+// `slices` (from ttv2_slices) cuts the (l, r) range over several workgroups; with more than one, `workspace` must hold
+// slices * no * ld doubles.
+int ttv2_slices(int no, int PL, int PR, int ld, int ncols, int num_cus);
+hipError_t launch_ttv2(const double* Y, const double* KL, int PL, const double* KR, int PR, double* M, int no, int ld,
+                       int ncols, int slices, double* workspace, hipStream_t stream);
+// Adds `splits` partial panels P[z][n_rows_ld] into M in split order (columns >= ncols of a row are left alone).
+hipError_t launch_splitk_reduce(const double* P, double* M, int64_t n_rows_ld, int ld, int ncols, int splits, hipStream_t stream);
 
 // ---- tensors of order above 3: explicit Khatri-Rao product of a run of consecutive modes ----------------------
 // K[row, c] = prod_{q < nrun} U[q][i_q * ld + c],  row = i_0 + In[0] * (i_1 + In[1] * (...)),  c < ncols; K and the

@@ -41,6 +41,13 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const double* __rest
   }
 }
 
+hipError_t launch_splitk_reduce(const double* P, double* M, int64_t n_rows_ld, int ld, int ncols, int splits, hipStream_t stream) {
+  if (!P || !M || n_rows_ld < 1 || splits < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n_rows_ld + kRedElems - 1) / kRedElems)), dim3(256), 0, stream, P, M,
+                     n_rows_ld, ld, ncols, splits);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------------------
 // variants, plan, launch
 // ---------------------------------------------------------------------------------------------------

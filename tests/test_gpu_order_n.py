@@ -23,6 +23,7 @@ ND_CASES = [
     ((9, 1, 8, 1, 7), [4, 4], False),              # singleton modes inside
     ((4, 3, 2, 3, 2, 4), list(range(1, 9)), True),  # order 6
     ((16, 16, 16, 16), [20] * 13, False),          # 260 columns: several column tiles, split contraction
+    ((5, 7, 23, 19), [6, 11], True),               # two-step: the second step's range cut into ragged slices
 ]
 
 
@@ -122,7 +123,7 @@ def test_order_n_argument_errors_and_reuse_flag():
     ctx.close()
     dims = (6, 5, 4, 3)
     T = random_tensor(dims, 5)
-    ctx = P.Context(max_total_rank=8, flags=P.CTX_REUSE)        # two-step sweeps are an order-3 feature: no effect
+    ctx = P.Context(max_total_rank=8, flags=P.CTX_REUSE)        # two-step sweeps: same results up to rounding order
     ctx.submit_tensor(T)
     with pytest.raises(ValueError):
         ctx.enqueue_model(uniform_factors(dims[:3], 2, 1))      # three matrices for a four-mode tensor
@@ -157,5 +158,54 @@ def test_seeded_random_order_n_queues_match_oracle(seed):
     slots = int(rng.choice([0, 2, 3, 5]))
     ref = O.cals(T, models, rstar, slots)
     results, facs, st = run_gpu(T, models, rstar, slots, rounds_per_call=int(rng.integers(1, 9)))
+    compare(results, facs, ref, models)
+    assert st.rounds == ref["rounds"]
+
+
+def _gpu_mttkrp_reuse_nd(T, U, pad_to):
+    import torch
+    import paper_2010_04678_amd as P
+    dims = tuple(T.shape[::-1])
+    R = U[0].shape[1]
+    ld = pad_to
+    ctx = P.Context(max_total_rank=ld, flags=P.CTX_REUSE)
+    ctx.submit_tensor(torch.from_numpy(T).cuda())
+    Ud, Md = [], []
+    for n in range(T.ndim):
+        buf = torch.full((dims[n], ld), float("nan"), dtype=torch.float64, device="cuda")
+        buf[:, :R] = torch.from_numpy(np.ascontiguousarray(U[n])).cuda()
+        Ud.append(buf)
+        Md.append(torch.full((dims[n], ld), 777.0, dtype=torch.float64, device="cuda"))
+    ctx.mttkrp_reuse_nd(Ud, Md, total_rank=R)
+    torch.cuda.synchronize()
+    out = [m.cpu().numpy() for m in Md]
+    ctx.close()
+    for n in range(1, T.ndim):
+        assert np.all(out[n][:, R:] == 777.0)
+    return [m[:, :R] for m in out]
+
+
+@pytest.mark.parametrize("dims,ranks,signed", ND_CASES)
+def test_two_step_mttkrp_order_n_matches_oracle_elementwise(dims, ranks, signed):
+    T = random_tensor(dims, 17 + dims[0], signed=signed)
+    U = _fused(dims, ranks, 400 + dims[1], signed=signed)
+    pad = (sum(ranks) + 5 + 1) // 2 * 2 if dims[0] % 2 else sum(ranks) + 5       # even and odd leading dimensions
+    got = _gpu_mttkrp_reuse_nd(T, U, pad_to=pad)
+    for mode in range(2, len(dims) + 1):
+        want = O.mttkrp(T, U, mode)
+        scale = _abs_scale(T, U, mode)
+        err = np.abs(got[mode - 1] - want)
+        assert np.all(np.isfinite(got[mode - 1]))
+        assert np.all(err <= TOL * scale + 1e-300), (mode, float((err / (scale + 1e-300)).max()))
+
+
+@pytest.mark.parametrize("dims", [(12, 10, 9, 8), (7, 6, 5, 4, 6), (300, 3, 4, 40)])
+def test_two_step_sweeps_order_n_match_oracle(dims):
+    import paper_2010_04678_amd as P
+    T = np.abs(low_rank_tensor(dims, 4, 500 + dims[0], noise=0.05))
+    ranks = [3, 1, 4, 2, 5, 3, 2, 6]
+    models = _models(dims, ranks, 600, flags=[0, O.FLAG_LINESEARCH, O.FLAG_NONNEG, O.FLAG_NONNEG | O.FLAG_LINESEARCH])
+    ref = O.cals(T, models, 12, 4)
+    results, facs, st = run_gpu(T, models, 12, 4, rounds_per_call=3, ctx_flags=P.CTX_REUSE)
     compare(results, facs, ref, models)
     assert st.rounds == ref["rounds"]

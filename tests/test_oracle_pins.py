@@ -887,3 +887,17 @@ def test_nd_cals_results_do_not_depend_on_co_residents():
                 assert np.array_equal(res["U"][k][n], solo["U"][n])
     assert list(a["retire_order"]) == sorted(range(len(ranks)), key=lambda k: (a["iters"][k], k))
     assert sorted(b["retire_order"]) == list(range(len(ranks)))
+
+
+def test_nd_mttkrp_of_modes_2_to_N_factors_through_the_mode_1_contraction():
+    # the identity behind two-step sweeps for any order: with Y[i2..iN, c] = sum_i1 T U1, the MTTKRP of mode n >= 2
+    # is Y contracted with the factors of the remaining modes, column by column
+    dims, R = (5, 4, 6, 3, 4), 3
+    T = random_tensor(dims, 501, signed=True)
+    U = signed_factors(dims, R, 502)
+    Y = np.einsum("ijklm,ir->jklmr", nview(T), U[0])
+    want = {2: np.einsum("jklmr,kr,lr,mr->jr", Y, U[2], U[3], U[4]), 3: np.einsum("jklmr,jr,lr,mr->kr", Y, U[1], U[3], U[4]),
+            4: np.einsum("jklmr,jr,kr,mr->lr", Y, U[1], U[2], U[4]), 5: np.einsum("jklmr,jr,kr,lr->mr", Y, U[1], U[2], U[3])}
+    for mode, w in want.items():
+        got = O.mttkrp(T, U, mode)
+        assert np.abs(got - w).max() <= 1e-12 * np.abs(w).max(), mode
