@@ -60,8 +60,9 @@ extern "C" {
                               MTTKRPs from Y instead of from the tensor (partial-contraction reuse, the scheme of
                               Phan et al. cited in Sec. 2; same results up to rounding order, one pass over the
                               tensor fewer per sweep).  Costs a device buffer of I2*I3*ld doubles.  Order N > 3
-                              likewise: Y has one row per (i2,...,iN) -- I2*...*IN*ld doubles -- and serves the
-                              MTTKRPs of modes 2..N, so a sweep reads the tensor twice instead of N times. */
+                              likewise: Y has one row per (i2,...,iN) -- I2*...*IN*ld doubles -- and is contracted
+                              further with every updated mode in turn (each level 1/I_k of the one before), so a
+                              sweep reads the tensor twice and Y twice instead of the tensor N times. */
 
 #define CALS_MAX_RANK 32 /* largest number of components of one model */
 #define CALS_MAX_MODES 6 /* largest tensor order */

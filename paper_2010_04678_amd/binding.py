@@ -303,12 +303,12 @@ def suggest_max_total_rank(ranks: Sequence[int], plateau: int = 256) -> int:
     return max(max(ranks), min(sum(ranks), int(plateau)))
 
 
-def suggest_two_step(dims: Sequence[int], max_total_rank: int, budget_bytes: int = 32 << 30) -> bool:
+def suggest_two_step(dims: Sequence[int], max_total_rank: int, budget_bytes: int = 64 << 30) -> bool:
     """Whether two-step sweeps (CTX_REUSE) pay off: they read the tensor twice per sweep instead of once per mode, at
     the price of an intermediate of I2*...*IN*ld doubles and of a few more launches per round.  Measured, order 3:
     41 -> 29 ms per sweep on 1000^3 at width 420, 112 -> 151 models/s on the 4000x200x50 queue job, 874 -> 1011 on
-    200^3, but 3440 -> 3270 on 32^3, where a round is launch-bound.  So: at least 2^20 tensor elements and an
-    intermediate within `budget_bytes`."""
+    200^3, but 3440 -> 3270 on 32^3, where a round is launch-bound; order 4 (180^4) 68 -> 44 ms per round, order 5
+    (60^5) 64 -> 53.  So: at least 2^20 tensor elements and an intermediate within `budget_bytes`."""
     dims = [int(d) for d in dims]
     ld = (int(max_total_rank) + 15) // 16 * 16
     elems = 1

@@ -95,7 +95,8 @@ struct cals_ctx {
   int32_t* h_map = nullptr;      // pinned
   uint32_t* passive[kMaxModes] = {};  // NONNEG only
   double* d_scratch = nullptr;   // 1024 partial sums + result + flag
-  double* Y = nullptr;           // two-step sweeps: the tensor contracted with the mode-1 multi-matrix, (I2*I3) x ld
+  double* Y = nullptr;           // two-step sweeps: the tensor contracted with the mode-1 multi-matrix, (I2*...*IN) x ld
+  double* Ychain[kMaxModes] = {};  // order > 3: Y contracted further with modes 2, 3, ... (index = level, from 2)
   double* d_ones = nullptr;      // two-step sweeps: ld ones (the second "factor" of the first step)
   double* d_sink = nullptr;      // never-written target of the yardstick kernels
   double* d_zeros = nullptr;     // 8 zero doubles (what MTTKRP lanes past the end of a split load)
@@ -318,27 +319,47 @@ int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld) {
   return CALS_OK;
 }
 
-// Second step: the MTTKRP of mode `mode` (0-based, >= 1) from Y and the factors of the remaining modes.  Order 3:
-// one remaining factor (ttv_kernel).  Higher orders: the remaining modes before and after `mode` form a fast and a
-// slow run; a run of several modes enters as its explicit Khatri-Rao product, an empty one as a row of ones.
-int run_from_contraction(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld) {
+// Rows of the chain intermediate of level k (1-based mode k contracted last): one per index tuple (i_{k+1}, ..., i_N).
+int64_t chain_rows(const cals_ctx* c, int level) {
+  int64_t rows = 1;
+  for (int n = level; n < c->nmodes; ++n) rows *= c->dims[n];
+  return rows;
+}
+
+// Order above 3: Y_level = Y_{level-1} contracted with the multi-matrix of (0-based) mode level-1, column by column.
+int advance_chain(cals_ctx* c, int level, const double* const* U, int ncols, int ld) {
+  const int64_t rows = chain_rows(c, level);
+  if (rows >= (1LL << 31)) return CALS_E_UNSUPPORTED;
+  const double* src = (level == 2) ? c->Y : c->Ychain[level - 1];
+  HIP_TRY(launch_ttv2(src, U[level - 1], (int)c->dims[level - 1], c->d_ones, 1, c->Ychain[level], (int)rows, ld, ncols, 1,
+                      nullptr, c->stream));
+  return CALS_OK;
+}
+
+// Second step: the MTTKRP of mode `mode` (0-based, >= 1) from the contraction(s) and the factors of the remaining
+// modes.  Order 3: Y and one remaining factor (ttv_kernel).  Higher orders: a chain Y_1 = Y (mode 1 contracted),
+// Y_2 = Y_1 contracted with mode 2, ... -- level `mode` is formed here from level mode-1 and the mode just updated
+// (sweeps call this in increasing mode order; `rebuild` forms every level from Y, for a call that starts at a later
+// mode) -- and the MTTKRP is Y_mode contracted with the modes after `mode` (their explicit Khatri-Rao product when
+// there are several).  Every level is 1/I_k of the previous one, so a sweep reads Y about twice.
+int run_from_contraction(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld, bool rebuild = false) {
   const int N = c->nmodes;
   if (N == 3) {
     const int I2 = (int)c->dims[1], I3 = (int)c->dims[2];
     if (mode == 1) HIP_TRY(launch_ttv(c->Y, U[2], M, I2, I3, 1, I2, ld, ncols, c->stream));
     else HIP_TRY(launch_ttv(c->Y, U[1], M, I3, I2, I2, 1, ld, ncols, c->stream));
   } else {
-    int64_t PL = 1, PR = 1;
-    for (int m = 1; m < mode; ++m) PL *= c->dims[m];
+    for (int level = rebuild ? 2 : mode; level <= mode; ++level)
+      if (level >= 2) CALS_TRY(advance_chain(c, level, U, ncols, ld));
+    const double* src = (mode == 1) ? c->Y : c->Ychain[mode];
+    int64_t PR = 1;
     for (int m = mode + 1; m < N; ++m) PR *= c->dims[m];
-    if (PL >= (1LL << 31) || PR >= (1LL << 31)) return CALS_E_UNSUPPORTED;
-    const double* KL = c->d_ones;
+    if (PR >= (1LL << 31)) return CALS_E_UNSUPPORTED;
     const double* KR = c->d_ones;
-    if (mode > 1) CALS_TRY(run_operand(c, 1, mode, PL, U, c->Kbuf[0], ncols, ld, &KL));
     if (mode < N - 1) CALS_TRY(run_operand(c, mode + 1, N, PR, U, c->Kbuf[1], ncols, ld, &KR));
-    const int slices = ttv2_slices((int)c->dims[mode], (int)PL, (int)PR, ld, ncols, c->num_cus);
+    const int slices = ttv2_slices((int)c->dims[mode], 1, (int)PR, ld, ncols, c->num_cus);
     if (slices > 1) CALS_TRY(ensure_workspace(c, sizeof(double) * (size_t)slices * c->dims[mode] * ld));
-    HIP_TRY(launch_ttv2(c->Y, KL, (int)PL, KR, (int)PR, M, (int)c->dims[mode], ld, ncols, slices, c->workspace, c->stream));
+    HIP_TRY(launch_ttv2(src, c->d_ones, 1, KR, (int)PR, M, (int)c->dims[mode], ld, ncols, slices, c->workspace, c->stream));
   }
   double elems = 1.0;
   for (int n = 0; n < N; ++n) elems *= (double)c->dims[n];
@@ -618,7 +639,7 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
       HIP_TRY(launch_ls_extrapolate(la, c->stream));
       if (c->Y) {
         CALS_TRY(run_contract_mode1(c, c->Unew[0], c->total_rank, c->ld));
-        CALS_TRY(run_from_contraction(c, N - 1, c->Unew, c->M, c->total_rank, c->ld));
+        CALS_TRY(run_from_contraction(c, N - 1, c->Unew, c->M, c->total_rank, c->ld, /*rebuild=*/true));
       } else {
         CALS_TRY(run_mttkrp(c, N - 1, c->Unew, c->M, c->total_rank, c->ld));
       }
@@ -717,6 +738,7 @@ int cals_destroy(cals_ctx* c) {
     (void)hipFree(c->passive[n]);
   }
   (void)hipFree(c->Kbuf[0]); (void)hipFree(c->Kbuf[1]);
+  for (int n = 0; n < kMaxModes; ++n) (void)hipFree(c->Ychain[n]);
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart); (void)hipFree(c->d_lspart);
   (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
@@ -775,10 +797,8 @@ int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const 
       if (r.a1 - r.a0 > 1) need[0] = std::max(need[0], r.Ia);
       if (r.b1 - r.b0 > 1) need[1] = std::max(need[1], r.Ib);
       if ((c->opt.flags & CALS_CTX_REUSE) && ndims > 3 && n >= 1) {   // second step of two-step sweeps: runs 2..n-1, n+1..N
-        int64_t pl = 1, pr = 1;
-        for (int m = 1; m < n; ++m) pl *= dims[m];
+        int64_t pr = 1;
         for (int m = n + 1; m < ndims; ++m) pr *= dims[m];
-        if (n > 2) need[0] = std::max(need[0], pl);
         if (n < ndims - 2) need[1] = std::max(need[1], pr);
       }
     }
@@ -793,6 +813,8 @@ int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const 
     ok = ok && hipMalloc(&c->Y, sizeof(double) * (size_t)rows_without_mode1(c) * c->ld) == hipSuccess;
     ok = ok && hipMalloc(&c->d_ones, sizeof(double) * c->ld) == hipSuccess;
     ok = ok && launch_fill(c->d_ones, c->ld, 1.0, c->stream) == hipSuccess;
+    for (int level = 2; ndims > 3 && level < ndims; ++level)
+      ok = ok && hipMalloc(&c->Ychain[level], sizeof(double) * (size_t)chain_rows(c, level) * c->ld) == hipSuccess;
   }
   if (update_row_blocks((int)imax) > 1)
     ok = ok && hipMalloc(&c->d_updpart, sizeof(double) * update_part_doubles((int)imax) * c->capacity) == hipSuccess;

@@ -60,7 +60,7 @@ def test_suggested_buffer_width():
     # two-step sweeps: order 3, large enough to be past launch-bound rounds, intermediate within the budget
     assert P.suggest_two_step((1000, 1000, 1000), 420) and P.suggest_two_step((4000, 200, 50), 640)
     assert not P.suggest_two_step((32, 32, 32), 30) and P.suggest_two_step((180, 180, 180, 180), 420)
-    assert not P.suggest_two_step((180, 180, 180, 180), 1024)      # 48 GB intermediate: over the default budget
+    assert not P.suggest_two_step((180, 180, 180, 180), 2048)      # 96 GB intermediate: over the default budget
     assert not P.suggest_two_step((100, 40000, 40000), 64)
 
 
