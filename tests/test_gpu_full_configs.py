@@ -145,7 +145,7 @@ def test_config3_full():
     sample = [0, 7, 16, 22]
     res, facs, st = gpu_run(T, models, cfg, keep=sample + [59])
     iters = {r.model_id: r.iters for r in res}
-    # everything is resident from round 1: the order is (iteration count, slot)
+    # everything is resident from the first pass of the main loop on: the order is (iteration count, slot)
     assert [r.model_id for r in res] == sorted(range(60), key=lambda k: (iters[k], k))
     assert all(r.status in (O.CONVERGED, O.MAX_ITERS) for r in res)
     assert min(u.min() for u in facs[59][0]) >= 0.0
