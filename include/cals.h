@@ -62,7 +62,11 @@ extern "C" {
                               tensor fewer per sweep).  Costs a device buffer of I2*I3*ld doubles.  Order N > 3
                               likewise: Y has one row per (i2,...,iN) -- I2*...*IN*ld doubles -- and is contracted
                               further with every updated mode in turn (each level 1/I_k of the one before), so a
-                              sweep reads the tensor twice and Y twice instead of the tensor N times. */
+                              sweep reads the tensor twice and Y twice instead of the tensor N times.
+                              With line-search models in the queue, up to two more buffers of Y's size may be held
+                              (Y at the point each model kept and at the extrapolated point, which is their
+                              combination: Y is linear in the mode-1 factors); if they cannot be allocated, or would
+                              cost more time than they save, the extrapolated point is contracted on its own. */
 
 #define CALS_MAX_RANK 32 /* largest number of components of one model */
 #define CALS_MAX_MODES 6 /* largest tensor order */

@@ -96,6 +96,8 @@ struct cals_ctx {
   uint32_t* passive[kMaxModes] = {};  // NONNEG only
   double* d_scratch = nullptr;   // 1024 partial sums + result + flag
   double* Y = nullptr;           // two-step sweeps: the tensor contracted with the mode-1 multi-matrix, (I2*...*IN) x ld
+  double* Yprev = nullptr;       // two-step sweeps with line search: Y at the point kept after the previous round ...
+  double* Ynew = nullptr;        // ... and at the extrapolated point (both allocated with the line-search buffers)
   double* Ychain[kMaxModes] = {};  // order > 3: Y contracted further with modes 2, 3, ... (index = level, from 2)
   double* d_ones = nullptr;      // two-step sweeps: ld ones (the second "factor" of the first step)
   double* d_sink = nullptr;      // never-written target of the yardstick kernels
@@ -290,11 +292,12 @@ int64_t rows_without_mode1(const cals_ctx* c) {
   return rows;
 }
 
-int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld) {
+int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld, double* Y = nullptr) {
   const int64_t rows = rows_without_mode1(c);
+  if (!Y) Y = c->Y;
   if (rows >= (1LL << 31) || (int64_t)(c->dims[0] + 64) * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
   MttkrpProblem p{};
-  p.T = c->T; p.zeros = c->d_zeros; p.M = c->Y; p.ncols = ncols; p.ld = ld;
+  p.T = c->T; p.zeros = c->d_zeros; p.M = Y; p.ncols = ncols; p.ld = ld;
   p.In = (int)rows; p.sm = c->dims[0];
   p.Ia = (int)c->dims[0]; p.sa = 1; p.Ua = U1;
   p.Ib = 1; p.sb = c->dims[0]; p.Ub = c->d_ones;
@@ -327,10 +330,10 @@ int64_t chain_rows(const cals_ctx* c, int level) {
 }
 
 // Order above 3: Y_level = Y_{level-1} contracted with the multi-matrix of (0-based) mode level-1, column by column.
-int advance_chain(cals_ctx* c, int level, const double* const* U, int ncols, int ld) {
+int advance_chain(cals_ctx* c, int level, const double* const* U, int ncols, int ld, const double* Y1) {
   const int64_t rows = chain_rows(c, level);
   if (rows >= (1LL << 31)) return CALS_E_UNSUPPORTED;
-  const double* src = (level == 2) ? c->Y : c->Ychain[level - 1];
+  const double* src = (level == 2) ? Y1 : c->Ychain[level - 1];
   HIP_TRY(launch_ttv2(src, U[level - 1], (int)c->dims[level - 1], c->d_ones, 1, c->Ychain[level], (int)rows, ld, ncols, 1,
                       nullptr, c->stream));
   return CALS_OK;
@@ -342,16 +345,18 @@ int advance_chain(cals_ctx* c, int level, const double* const* U, int ncols, int
 // (sweeps call this in increasing mode order; `rebuild` forms every level from Y, for a call that starts at a later
 // mode) -- and the MTTKRP is Y_mode contracted with the modes after `mode` (their explicit Khatri-Rao product when
 // there are several).  Every level is 1/I_k of the previous one, so a sweep reads Y about twice.
-int run_from_contraction(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld, bool rebuild = false) {
+int run_from_contraction(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld, bool rebuild = false,
+                         const double* Y1 = nullptr /* the mode-1 contraction to start from; default: the context's */) {
   const int N = c->nmodes;
+  if (!Y1) Y1 = c->Y;
   if (N == 3) {
     const int I2 = (int)c->dims[1], I3 = (int)c->dims[2];
-    if (mode == 1) HIP_TRY(launch_ttv(c->Y, U[2], M, I2, I3, 1, I2, ld, ncols, c->stream));
-    else HIP_TRY(launch_ttv(c->Y, U[1], M, I3, I2, I2, 1, ld, ncols, c->stream));
+    if (mode == 1) HIP_TRY(launch_ttv(Y1, U[2], M, I2, I3, 1, I2, ld, ncols, c->stream));
+    else HIP_TRY(launch_ttv(Y1, U[1], M, I3, I2, I2, 1, ld, ncols, c->stream));
   } else {
     for (int level = rebuild ? 2 : mode; level <= mode; ++level)
-      if (level >= 2) CALS_TRY(advance_chain(c, level, U, ncols, ld));
-    const double* src = (mode == 1) ? c->Y : c->Ychain[mode];
+      if (level >= 2) CALS_TRY(advance_chain(c, level, U, ncols, ld, Y1));
+    const double* src = (mode == 1) ? Y1 : c->Ychain[mode];
     int64_t PR = 1;
     for (int m = mode + 1; m < N; ++m) PR *= c->dims[m];
     if (PR >= (1LL << 31)) return CALS_E_UNSUPPORTED;
@@ -385,6 +390,16 @@ int ensure_nn_buffers(cals_ctx* c) {
 }
 
 // Buffers only line search needs: the previous and the extrapolated point, column ownership, decisions.
+// Line search under two-step sweeps: the contraction at the extrapolated point is either a pass over the tensor or a
+// combination of two stored contractions (about six passes over an array of the contraction's size per round, with
+// the bookkeeping of the point kept).  Rough times at the context's full width decide which.
+bool combination_beats_contraction(const cals_ctx* c) {
+  const double rows = (double)rows_without_mode1(c), I1 = (double)c->dims[0], w = (double)c->ld;
+  const double combine_s = 6.0 * rows * w * 8.0 / 4.0e12;
+  const double contract_s = std::max(rows * I1 * 8.0 / 5.0e12, 2.0 * rows * I1 * w / 55.0e12);
+  return combine_s < contract_s;
+}
+
 int ensure_ls_buffers(cals_ctx* c) {
   if (c->d_colmodel) return CALS_OK;
   HIP_TRY(hipSetDevice(c->opt.device));
@@ -403,6 +418,16 @@ int ensure_ls_buffers(cals_ctx* c) {
   ok = ok && hipHostMalloc(&c->h_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipMalloc(&c->d_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
   if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  if (c->Y && combination_beats_contraction(c)) {
+    // optional: without them the extrapolated point gets a contraction of its own
+    const size_t bytes = sizeof(double) * (size_t)rows_without_mode1(c) * c->ld;
+    if (hipMalloc(&c->Yprev, bytes) != hipSuccess || hipMalloc(&c->Ynew, bytes) != hipSuccess ||
+        hipMemsetAsync(c->Yprev, 0, bytes, c->stream) != hipSuccess) {
+      (void)hipGetLastError();
+      (void)hipFree(c->Yprev); (void)hipFree(c->Ynew);
+      c->Yprev = c->Ynew = nullptr;
+    }
+  }
   c->desc_dirty = true;
   return CALS_OK;
 }
@@ -561,6 +586,10 @@ int compact(cals_ctx* c, const std::vector<ActiveModel>& survivors) {
         std::swap(c->Uprev[n], c->Ualt[n]);
       }
     }
+    if (c->Yprev) {
+      HIP_TRY(launch_gather_columns(c->Yprev, c->Ynew, c->d_map, (int)rows_without_mode1(c), col, c->ld, c->stream));
+      std::swap(c->Yprev, c->Ynew);
+    }
     // h_map is reused next round: the copy above must have been consumed before it is rewritten
     HIP_TRY(hipStreamSynchronize(c->stream));
   }
@@ -635,9 +664,18 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
     la.M3 = c->M; la.ld = c->ld; la.n_models = n; la.ncols = c->total_rank; la.normT2 = c->normT2;
     la.part = c->d_lspart;
     la.nblk = update_row_blocks((int)*std::max_element(c->dims, c->dims + N));
+    la.Ycur = c->Y; la.Yprev = c->Yprev; la.Ynew = c->Ynew; la.yrows = c->Y ? rows_without_mode1(c) : 0;
     if (ls_takes_part) {
       HIP_TRY(launch_ls_extrapolate(la, c->stream));
-      if (c->Y) {
+      if (c->Y && c->Yprev) {
+        // the extrapolated mode-1 factors are a linear combination unless a NONNEG model's were clipped
+        bool linear = true;
+        for (const ActiveModel& m : c->active)
+          if ((m.flags & CALS_MODEL_LINESEARCH) && (m.flags & CALS_MODEL_NONNEG)) linear = false;
+        if (linear) HIP_TRY(launch_ls_y_combine(la, c->stream));
+        else CALS_TRY(run_contract_mode1(c, c->Unew[0], c->total_rank, c->ld, c->Ynew));
+        CALS_TRY(run_from_contraction(c, N - 1, c->Unew, c->M, c->total_rank, c->ld, /*rebuild=*/true, c->Ynew));
+      } else if (c->Y) {
         CALS_TRY(run_contract_mode1(c, c->Unew[0], c->total_rank, c->ld));
         CALS_TRY(run_from_contraction(c, N - 1, c->Unew, c->M, c->total_rank, c->ld, /*rebuild=*/true));
       } else {
@@ -646,6 +684,7 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
     }
     HIP_TRY(launch_ls_decide(la, c->stream));
     HIP_TRY(launch_ls_apply(la, c->stream));
+    if (c->Yprev) HIP_TRY(launch_ls_y_keep(la, c->stream));   // no model took part: nothing accepted, Yprev = Y
   }
   c->rounds += 1;
   if (!last_of_call && !round_may_retire(c)) {
@@ -742,7 +781,7 @@ int cals_destroy(cals_ctx* c) {
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart); (void)hipFree(c->d_lspart);
   (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
-  (void)hipFree(c->d_sink); (void)hipFree(c->Y); (void)hipFree(c->d_ones);
+  (void)hipFree(c->d_sink); (void)hipFree(c->Y); (void)hipFree(c->Yprev); (void)hipFree(c->Ynew); (void)hipFree(c->d_ones);
   (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);
   (void)hipHostFree(c->h_lambda); (void)hipHostFree(c->h_stage); (void)hipHostFree(c->h_rmap);

@@ -190,6 +190,12 @@ struct LineSearchArgs {
   int nmodes;              // tensor order
   int ld, n_models, ncols;
   double normT2;
+  // two-step sweeps only: the tensor contracted with the mode-1 factors of the current point (Ycur), of the point
+  // kept after the previous round (Yprev) and of the extrapolated point (Ynew); yrows x ld each
+  const double* Ycur;
+  double* Yprev;
+  double* Ynew;
+  int64_t yrows;
 };
 // Unew = Uprev + alpha (A_cur - Uprev) for the models taking part, Unew = A_cur for all other columns.
 hipError_t launch_ls_extrapolate(const LineSearchArgs& a, hipStream_t stream);
@@ -198,6 +204,11 @@ hipError_t launch_ls_extrapolate(const LineSearchArgs& a, hipStream_t stream);
 hipError_t launch_ls_decide(const LineSearchArgs& a, hipStream_t stream);
 // U = Unew for accepted models; Uprev = the point kept (lambda folded into the last mode) for every line-search model.
 hipError_t launch_ls_apply(const LineSearchArgs& a, hipStream_t stream);
+// Two-step sweeps: the contraction with the mode-1 factors is linear in them, so for the extrapolated point it is
+// Ynew = Yprev + alpha (Ycur - Yprev) column by column (Ynew = Ycur for the columns of models not taking part) ...
+hipError_t launch_ls_y_combine(const LineSearchArgs& a, hipStream_t stream);
+// ... and after the decision the contraction of the point each model keeps: Yprev = accepted ? Ynew : Ycur.
+hipError_t launch_ls_y_keep(const LineSearchArgs& a, hipStream_t stream);
 
 // ---- two-step sweep: contraction of the intermediate Y with one factor ---------------------------------------
 // M[o, c] = sum_{s < ns} Y[(o*so + s*ss) * ld + c] * U[s * ld + c],  o < no, c < ncols (fixed summation order).

@@ -2,6 +2,9 @@
 // round's mode updates: P_new = P_prev + alpha (P_cur - P_prev); the extrapolated point replaces P_cur
 // only if its error is lower.  The error of P_new comes from the fast formula of Alg. 1 with ONE extra fused
 // MTTKRP of the last mode over the extrapolated multi-matrices, so the central fused operation is preserved.
+// With two-step sweeps the tensor contracted with the mode-1 factors of the extrapolated point is the same
+// combination of the contractions at P_prev and P_cur (the contraction is linear in those factors), so the extra
+// MTTKRP needs no pass over the tensor.
 #include "cals_internal.h"
 
 namespace cals {
@@ -184,6 +187,46 @@ __global__ void __launch_bounds__(256) ls_apply_kernel(LineSearchArgs a) {
   }
   a.Uprev[mode][e] = v;
 }
+
+// grid (column blocks of 256, row chunks): thread = one column over the chunk's rows (coalesced along the columns)
+template <bool KEEP>
+__global__ void __launch_bounds__(256) ls_y_kernel(LineSearchArgs a, int rows_per_block) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= a.ncols) return;
+  const int k = a.colmodel[c];
+  const ModelDesc d = a.desc[k];
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+  const int64_t r1 = (r0 + rows_per_block < a.yrows) ? (r0 + rows_per_block) : a.yrows;
+  if (KEEP) {
+    const double* src = a.accept[k] ? a.Ynew : a.Ycur;
+    for (int64_t i = r0; i < r1; ++i) a.Yprev[i * a.ld + c] = src[i * a.ld + c];
+  } else {
+    const bool part = ls_takes_part(d, a.out[d.sid]);
+    const double alpha = d.alpha;
+    for (int64_t i = r0; i < r1; ++i) {
+      const double cur = a.Ycur[i * a.ld + c];
+      double v = cur;
+      if (part) {
+        const double prev = a.Yprev[i * a.ld + c];
+        v = prev + alpha * (cur - prev);
+      }
+      a.Ynew[i * a.ld + c] = v;
+    }
+  }
+}
+
+template <bool KEEP>
+static hipError_t launch_ls_y(const LineSearchArgs& a, hipStream_t stream) {
+  if (a.n_models < 1 || a.ncols < 1 || a.yrows < 1) return hipSuccess;
+  if (!a.Ycur || !a.Yprev || !a.Ynew) return hipErrorInvalidValue;
+  int rows_per_block = 8;
+  while ((a.yrows + rows_per_block - 1) / rows_per_block > 65535) rows_per_block *= 2;
+  const dim3 grid((a.ncols + 255) / 256, (unsigned)((a.yrows + rows_per_block - 1) / rows_per_block));
+  hipLaunchKernelGGL(ls_y_kernel<KEEP>, grid, dim3(256), 0, stream, a, rows_per_block);
+  return hipGetLastError();
+}
+hipError_t launch_ls_y_combine(const LineSearchArgs& a, hipStream_t stream) { return launch_ls_y<false>(a, stream); }
+hipError_t launch_ls_y_keep(const LineSearchArgs& a, hipStream_t stream) { return launch_ls_y<true>(a, stream); }
 
 static dim3 elem_grid(const LineSearchArgs& a) {
   int imax = a.In[0];

@@ -266,6 +266,25 @@ def test_nonneg_with_line_search_matches_oracle():
             assert acc > 0
 
 
+def test_two_step_line_search_with_a_long_first_mode():
+    # a first mode much longer than the buffer is wide: the contraction at the extrapolated point is then formed from
+    # the contractions at the previous and the current point instead of a pass over the tensor (models retire at
+    # different rounds, so the stored contraction is compacted with the factors; plain models share the buffer)
+    import paper_2010_04678_amd as P
+    dims = (400, 14, 11)
+    T = _collinear_tensor(dims, 4, 2300)
+    models = []
+    for k, r in enumerate([2, 3, 4, 5, 6, 4, 3, 1, 5]):
+        models.append(dict(rank=r, init=uniform_factors(dims, r, 2310 + k), tol=[1e-6, 1e-5, -1.0][k % 3],
+                           max_iters=[60, 45, 13][k % 3], flags=O.FLAG_LINESEARCH if k % 4 != 3 else 0,
+                           ls_alpha=[1.2, 2.0, 1.6][k % 3]))
+    ref = O.cals(T, models, 12, 3)
+    for rounds_per_call in (3, 50):
+        results, facs, st = run_gpu(T, models, 12, 3, rounds_per_call=rounds_per_call, ctx_flags=P.CTX_REUSE)
+        compare(results, facs, ref, models)
+        assert sum(r.ls_accepted for r in results) > 0
+
+
 def test_config3_recipe_reduced():
     # configuration 3's recipe (fluorescence-shaped non-negative tensor, NONNEG models, tolerance stop), smaller
     cfg = get_config(3)

@@ -199,6 +199,20 @@ def test_two_step_mttkrp_order_n_matches_oracle_elementwise(dims, ranks, signed)
         assert np.all(err <= TOL * scale + 1e-300), (mode, float((err / (scale + 1e-300)).max()))
 
 
+def test_two_step_line_search_order_4_with_a_long_first_mode():
+    # line search only (no clipping), first mode far longer than the buffer is wide: the extrapolated point's
+    # contraction is the combination of the stored ones, and the chain of contractions is rebuilt from it
+    import paper_2010_04678_amd as P
+    dims = (350, 5, 4, 6)
+    T = low_rank_tensor(dims, 3, 850, noise=0.02)
+    models = _models(dims, [3, 1, 4, 2, 5, 3, 2], 860, flags=[O.FLAG_LINESEARCH, O.FLAG_LINESEARCH, 0], alpha=1.5)
+    ref = O.cals(T, models, 10, 3)
+    results, facs, st = run_gpu(T, models, 10, 3, rounds_per_call=4, ctx_flags=P.CTX_REUSE)
+    compare(results, facs, ref, models)
+    assert st.rounds == ref["rounds"]
+    assert sum(r.ls_accepted for r in results) > 0
+
+
 @pytest.mark.parametrize("dims", [(12, 10, 9, 8), (7, 6, 5, 4, 6), (300, 3, 4, 40)])
 def test_two_step_sweeps_order_n_match_oracle(dims):
     import paper_2010_04678_amd as P
