@@ -364,6 +364,33 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 #pragma unroll
     for (int x = 0; x < KS; ++x) fetch_row(x, pua[x], pub[x]);
   }
+  // A wavefront whose rows all lie past the end of the matrix (the tail of a short mode) only helps to produce
+  // the tiles: it issues no tensor loads and no matrix instructions, which leaves its SIMD to the wavefronts of
+  // the other workgroups on the compute unit.
+  auto produce_stage = [&](int cur) {
+    double* next_tile = smem + (cur ^ 1) * TILE;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      if (PACK) {
+        if (s < NIW) {
+          commit_packed(next_tile, s);
+          fetch_packed(s);
+        }
+      } else {
+        commit_row(next_tile, s, pua[s], pub[s]);
+        fetch_row(s, pua[s], pub[s]);
+      }
+    }
+    __syncthreads();
+  };
+  if (m0 >= a.In) {             // uniform over the wavefront
+    __syncthreads();
+    for (int st = 0; st < nstage; st += 2) {
+      produce_stage(0);
+      produce_stage(1);
+    }
+    return;
+  }
   load_a_stage(areg0);
   __syncthreads();
 
