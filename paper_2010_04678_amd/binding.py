@@ -306,7 +306,7 @@ def suggest_max_total_rank(ranks: Sequence[int], plateau: int = 256) -> int:
 def suggest_two_step(dims: Sequence[int], max_total_rank: int, budget_bytes: int = 64 << 30) -> bool:
     """Whether two-step sweeps (CTX_REUSE) pay off: they read the tensor twice per sweep instead of once per mode, at
     the price of an intermediate of I2*...*IN*ld doubles and of a few more launches per round.  Measured, order 3:
-    41 -> 29 ms per sweep on 1000^3 at width 420, 112 -> 151 models/s on the 4000x200x50 queue job, 874 -> 1011 on
+    41 -> 29 ms per sweep on 1000^3 at width 420, 112 -> 207 models/s on the 4000x200x50 line-search queue job, 874 -> 1011 on
     200^3, but 3440 -> 3270 on 32^3, where a round is launch-bound; order 4 (180^4) 68 -> 44 ms per round, order 5
     (60^5) 64 -> 53.  So: at least 2^20 tensor elements and an intermediate within `budget_bytes`."""
     dims = [int(d) for d in dims]
@@ -322,7 +322,7 @@ def cp_cals(T, inits: Sequence[Sequence[np.ndarray]], tol: float = 1e-4, max_ite
             two_step: Optional[bool] = None):
     """Runs one CP-ALS model per entry of `inits` (one factor matrix I_n x R_k per mode) concurrently on the tensor T
     (numpy (I_N, ..., I2, I1) C-contiguous, or a CUDA float64 torch tensor of that shape; N = 3 .. MAX_MODES) and
-    returns, in the order of `inits`, a list of (Result, [U1, ..., UN], lambda).  Pure marshalling around the C calls
+    returns, in the order of `inits`, a list of (Result, [U1, ..., UN], lambda).  Pure marshalling around the C calls.
     two_step: two-step sweeps (CTX_REUSE); None = decide by suggest_two_step."""
     ranks = [int(u[0].shape[1]) for u in inits]
     rstar = int(max_total_rank) if max_total_rank is not None else suggest_max_total_rank(ranks)

@@ -229,6 +229,9 @@ int make_problem(cals_ctx* c, int mode, const double* const* U, double* M, int n
   return CALS_OK;
 }
 
+// Four events for one timed launch, or none (what was taken goes back to the pool).
+bool take_events(cals_ctx* c, hipEvent_t (&ev)[4]);
+
 hipEvent_t take_event(cals_ctx* c) {
   if (!c->event_pool.empty()) {
     hipEvent_t e = c->event_pool.back();
@@ -238,6 +241,18 @@ hipEvent_t take_event(cals_ctx* c) {
   hipEvent_t e = nullptr;
   if (hipEventCreate(&e) != hipSuccess) return nullptr;
   return e;
+}
+
+bool take_events(cals_ctx* c, hipEvent_t (&ev)[4]) {
+  for (int i = 0; i < 4; ++i) {
+    ev[i] = take_event(c);
+    if (!ev[i]) {
+      (void)hipGetLastError();
+      for (int k = 0; k < i; ++k) c->event_pool.push_back(ev[k]);
+      return false;
+    }
+  }
+  return true;
 }
 
 int drain_timings(cals_ctx* c) {
@@ -265,9 +280,7 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int nco
   hipEvent_t* ev = nullptr;
   TimedLaunch t{};
   if (c->opt.flags & CALS_CTX_TIMING) {
-    bool ok = true;
-    for (int i = 0; i < 4; ++i) { t.ev[i] = take_event(c); ok = ok && t.ev[i]; }
-    if (!ok) return CALS_E_HIP;
+    if (!take_events(c, t.ev)) return CALS_E_HIP;
     t.mode = mode;
     t.reduced = pl.splits > 1;
     ev = t.ev;
@@ -307,9 +320,7 @@ int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld, double*
   hipEvent_t* ev = nullptr;
   TimedLaunch t{};
   if (c->opt.flags & CALS_CTX_TIMING) {
-    bool ok = true;
-    for (int i = 0; i < 4; ++i) { t.ev[i] = take_event(c); ok = ok && t.ev[i]; }
-    if (!ok) return CALS_E_HIP;
+    if (!take_events(c, t.ev)) return CALS_E_HIP;
     t.mode = 1;
     t.reduced = pl.splits > 1;
     ev = t.ev;
@@ -385,7 +396,14 @@ int ensure_nn_buffers(cals_ctx* c) {
   }
   ok = ok && hipMalloc(&c->d_nnfail, sizeof(int32_t) * c->capacity) == hipSuccess;
   if (ok) ok = hipMemsetAsync(c->d_nnfail, 0, sizeof(int32_t) * c->capacity, c->stream) == hipSuccess;
-  if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  if (!ok) {
+    // nothing of a failed attempt stays behind: the next NONNEG model tries again from scratch
+    (void)hipGetLastError();
+    (void)hipStreamSynchronize(c->stream);
+    for (int n = 0; n < c->nmodes; ++n) { (void)hipFree(c->passive[n]); c->passive[n] = nullptr; }
+    (void)hipFree(c->d_nnfail); c->d_nnfail = nullptr;
+    return CALS_E_NOMEM;
+  }
   return CALS_OK;
 }
 
@@ -417,7 +435,17 @@ int ensure_ls_buffers(cals_ctx* c) {
   }
   ok = ok && hipHostMalloc(&c->h_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipMalloc(&c->d_colmodel, sizeof(int32_t) * c->ld) == hipSuccess;
-  if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  if (!ok) {
+    (void)hipGetLastError();
+    (void)hipStreamSynchronize(c->stream);
+    for (int n = 0; n < c->nmodes; ++n) {
+      (void)hipFree(c->Uprev[n]); (void)hipFree(c->Unew[n]);
+      c->Uprev[n] = c->Unew[n] = nullptr;
+    }
+    (void)hipFree(c->d_accept); (void)hipFree(c->d_lspart); (void)hipFree(c->d_colmodel); (void)hipHostFree(c->h_colmodel);
+    c->d_accept = nullptr; c->d_lspart = nullptr; c->d_colmodel = nullptr; c->h_colmodel = nullptr;
+    return CALS_E_NOMEM;
+  }
   if (c->Y && combination_beats_contraction(c)) {
     // optional: without them the extrapolated point gets a contraction of its own
     const size_t bytes = sizeof(double) * (size_t)rows_without_mode1(c) * c->ld;
@@ -738,6 +766,18 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
   return CALS_OK;
 }
 
+// No C++ exception leaves the library: the host containers' allocation failures become CALS_E_NOMEM.
+template <class F>
+int guarded(F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return CALS_E_NOMEM;
+  } catch (...) {
+    return CALS_E_STATE;
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -793,7 +833,7 @@ int cals_submit_tensor(cals_ctx* c, const double* data, const int64_t dims[3], i
   return cals_submit_tensor_nd(c, data, 3, dims, on_device);
 }
 
-int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const int64_t* dims, int on_device) {
+static int submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const int64_t* dims, int on_device) {
   if (!c || !data || !dims) return CALS_E_INVALID;
   if (ndims < 3 || ndims > CALS_MAX_MODES) return CALS_E_INVALID;
   if (c->has_tensor || c->nmodes != 0) return CALS_E_STATE;   // also after an attempt that failed half-way
@@ -890,8 +930,12 @@ int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const 
   return CALS_OK;
 }
 
-int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const* init, double tol, int32_t max_iters,
-                       uint32_t flags, double ls_alpha, int64_t* model_id) {
+int cals_submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, const int64_t* dims, int on_device) {
+  return guarded([&] { return submit_tensor_nd(c, data, ndims, dims, on_device); });
+}
+
+static int enqueue_model(cals_ctx* c, int32_t rank, const double* const* init, double tol, int32_t max_iters,
+                         uint32_t flags, double ls_alpha, int64_t* model_id) {
   if (!c || !init) return CALS_E_INVALID;
   if (!c->has_tensor) return CALS_E_STATE;
   if (rank < 1 || rank > CALS_MAX_RANK || rank > c->opt.max_total_rank || max_iters < 1) return CALS_E_INVALID;
@@ -915,7 +959,12 @@ int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const* init, dou
   return CALS_OK;
 }
 
-int cals_iterate(cals_ctx* c, int32_t n_rounds, int32_t* n_retired) {
+int cals_enqueue_model(cals_ctx* c, int32_t rank, const double* const* init, double tol, int32_t max_iters,
+                       uint32_t flags, double ls_alpha, int64_t* model_id) {
+  return guarded([&] { return enqueue_model(c, rank, init, tol, max_iters, flags, ls_alpha, model_id); });
+}
+
+static int iterate(cals_ctx* c, int32_t n_rounds, int32_t* n_retired) {
   if (!c || n_rounds < 0) return CALS_E_INVALID;
   if (!c->has_tensor) return CALS_E_STATE;
   CALS_TRY(set_device(c));
@@ -927,6 +976,10 @@ int cals_iterate(cals_ctx* c, int32_t n_rounds, int32_t* n_retired) {
     if (n_retired) *n_retired = retired_now;
   }
   return CALS_OK;
+}
+
+int cals_iterate(cals_ctx* c, int32_t n_rounds, int32_t* n_retired) {
+  return guarded([&] { return iterate(c, n_rounds, n_retired); });
 }
 
 int cals_run(cals_ctx* c) {
