@@ -353,12 +353,14 @@ def main() -> int:
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS}
     roof["traffic"] = None
-    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    # HBM bytes per MTTKRP from the rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known
+    # size); counters cannot be read from inside this process, so the figure of the committed summary is reported
+    tfile = os.path.join(ROOT, "profiles", "traffic.txt")
     if os.path.exists(tfile):
-        try:
-            roof["traffic"] = json.load(open(tfile)).get(cfg.name)
-        except Exception:
-            roof["traffic"] = None
+        for ln in open(tfile):
+            parts = ln.split()
+            if len(parts) == 2 and parts[0] == cfg.name:
+                roof["traffic"] = float(parts[1])
     roof["kernel"] = "mttkrp_kernel (fused MTTKRP contraction)"
     roof["avg_launch_ms"] = avg_ms
     roof["per_mode_ms"] = per_mode_ms
