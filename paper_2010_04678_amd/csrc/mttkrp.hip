@@ -83,13 +83,11 @@ static int env_int(const char* name, int dflt) {
 
 static constexpr int kMaxWn = 14;     // widest column block of a workgroup, in 16-column tiles
 
-MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
+// The plan for column blocks of at most `wn_max` tiles of 16 columns, and its modelled time in microseconds.
+static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max, double* cost_us) {
   MttkrpPlan pl{};
   const int ntile16 = (p.ncols + 15) / 16;
-  // tuning knobs (development aid): widest column block, row tiles per wavefront, forced split count
-  int wn_max = env_int("CALS_MTTKRP_WNMAX", kMaxWn);
-  wn_max = wn_max < 1 ? 1 : (wn_max > kMaxWn ? kMaxWn : wn_max);
-  // Column blocks: as few as the widest tile allows, widths as even as possible.  Blocks of the wider and of
+  // Column blocks: as few as `wn_max` allows, widths as even as possible.  Blocks of the wider and of
   // the narrower kind run as separate launches, each with the kernel of its own width, so no MFMA works on
   // padding tile columns (the tensor is read once per column block either way).
   const int ny = (ntile16 + wn_max - 1) / wn_max;
@@ -105,14 +103,18 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
   const int wn_top = pl.part[0].wn;
   // row tiles per wavefront: as many as the accumulator budget (WM*WN <= 28 tiles) and the row count allow
   // (more row tiles per wavefront = fewer instructions per MFMA, but rows are padded to 64*wm per workgroup:
-  // the choice minimises padded rows x a measured relative cost per MFMA of 1.0 / 1.08 / 1.25 for wm = 4 / 2 / 1)
+  // the choice minimises padded rows x a measured relative cost per MFMA of 1.08 / 1.25 for wm = 2 / 1; wm = 4
+  // is 1.0 with up to three column tiles (up to six when the rows are contiguous in memory, i.e. mode 1 with its
+  // 16-byte row-pair loads) and 1.12 beyond -- with 16 or more accumulator tiles a wavefront has no co-resident
+  // to hide its waits, and 64 rows per wavefront along a long-stride mode cost more than they save: 1000^3 at
+  // width 96: mode 3 57 TFLOP/s with wm = 4, 63 with wm = 2; mode 1 64 and 62)
   int wm = 1;
   {
     double best = 1e300;
     for (int cand : {4, 2, 1}) {
       if (cand * wn_top > 28) continue;
       const double padded = (double)((p.In + 64 * cand - 1) / (64 * cand)) * (64 * cand);
-      const double cost = padded * (cand == 4 ? 1.0 : (cand == 2 ? 1.08 : 1.25));
+      const double cost = padded * (cand == 4 ? ((wn_top <= 3 || (p.sm == 1 && wn_top <= 6)) ? 1.0 : 1.12) : (cand == 2 ? 1.08 : 1.25));
       if (cost < best) { best = cost; wm = cand; }
     }
   }
@@ -165,10 +167,11 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
       // The workgroups of a CU share its MFMA pipes whether they are resident together or one after the other, so
       // the busiest CU sets the time; co-residents hide each other's fixed cost and, for small tiles, each other's
       // non-MFMA instructions (measured: one / two / three resident workgroups of up to 9 accumulator tiles reach
-      // 0.87 / 0.96 / 1 of the three-resident rate, of 10 to 16 tiles 0.92 / 1).
+      // 0.87 / 0.96 / 1 of the three-resident rate, of 10 to 16 tiles 0.92 / 1; 17 and more tiles leave room for one
+      // workgroup only: 0.93 -- 1000^3 at width 512 runs at 62 TFLOP/s in blocks of 11 tiles, at 67 in blocks of 8).
       const int64_t on_cu = (wgs + num_cus - 1) / num_cus;
       const int resident = (int)std::min<int64_t>(per_cu, on_cu);
-      const double overlap = acc_tiles >= 17 ? 1.0
+      const double overlap = acc_tiles >= 17 ? 0.93
                              : (acc_tiles >= 10 ? (resident >= 2 ? 1.0 : 0.92)
                                                 : (resident >= 3 ? 1.0 : (resident == 2 ? 0.96 : 0.87)));
       const double mfma_us = (double)on_cu * (2.0 * pairs + 6.0 / resident) * us_per_tile_stage * wm * pl.part[q].wn / overlap;
@@ -187,7 +190,26 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
   pl.splits = (int)splits;
   pl.chunk = chunk;
   pl.workspace_bytes = (pl.splits > 1) ? (size_t)pl.splits * p.In * p.ld * sizeof(double) : 0;
+  *cost_us = best_cost;
   return pl;
+}
+
+MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
+  // tuning knob (development aid): widest column block
+  const int forced = env_int("CALS_MTTKRP_WNMAX", 0);
+  double cost = 0.0;
+  if (forced > 0) return plan_for_width(p, num_cus, forced > kMaxWn ? kMaxWn : forced, &cost);
+  // Column blocks of up to 14 tiles read the tensor the fewest times; blocks of up to 8 tiles leave room for a second
+  // workgroup on the CU, which hides waits and barriers (worth it from about 12 tiles of width on: measured +2 % at
+  // 192 columns, +4 % at 320-384, +6-8 % at 512-1024 on 1000^3; +13 % at 420 on 60^5, where the model sees a tie).
+  // The modelled time decides -- it charges the extra passes over the tensor -- and near-ties go to the narrow blocks.
+  MttkrpPlan wide = plan_for_width(p, num_cus, kMaxWn, &cost);
+  if ((p.ncols + 15) / 16 >= 12) {
+    double cost8 = 0.0;
+    const MttkrpPlan narrow = plan_for_width(p, num_cus, 8, &cost8);
+    if (cost8 <= 1.02 * cost) return narrow;
+  }
+  return wide;
 }
 
 hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* workspace, hipStream_t stream,
