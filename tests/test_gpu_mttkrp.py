@@ -63,9 +63,9 @@ CASES = [
     ((70, 9, 150), [7] * 5, True),              # two 16-row tiles + tail, contraction much longer than a stage
     ((5, 3, 2), [1], True),                     # smaller than any tile; contracted index shorter than a stage
     ((3, 130, 2), [20, 20, 20, 3], False),      # tiny fast index for modes 2,3 (general wrap path), 4 column tiles
-    ((129, 65, 33), list(range(1, 21)) + [11] * 20, True),   # 430 columns: the widest single column block
-    ((40, 24, 20), [20] * 30, False),           # 600 columns: two column blocks
-    ((24, 20, 18), [20] * 21, True),            # 420 columns = 27 tiles: column blocks of 14 and 13 tiles, two launches
+    ((129, 65, 33), list(range(1, 21)) + [11] * 20, True),   # 430 columns = 27 tiles: several column blocks, two launches
+    ((40, 24, 20), [20] * 30, False),           # 600 columns = 38 tiles
+    ((24, 20, 18), [20] * 21, True),            # 420 columns = 27 tiles (cfg 4's width)
     ((300, 7, 5), [5] * 3, False),              # odd leading dimension (one column per lane), four row tiles per wavefront
 ]
 
@@ -81,6 +81,28 @@ def test_mttkrp_matches_oracle_elementwise(dims, ranks, signed):
         err = np.abs(got[mode - 1] - want)
         assert np.all(np.isfinite(got[mode - 1]))
         assert np.all(err <= TOL * scale + 1e-300), (mode, float((err / (scale + 1e-300)).max()))
+
+
+@pytest.mark.parametrize("wn_max", [14, 8, 5])
+@pytest.mark.parametrize("dims,ranks,signed", [c for c in CASES if sum(c[1]) >= 192])
+def test_mttkrp_every_column_block_width(dims, ranks, signed, wn_max):
+    # the library chooses between wide column blocks (up to 14 tiles of 16 columns, fewest passes over the tensor) and
+    # narrow ones (up to 8) by a cost model; here each is forced (development knob of the launch planner), so that the
+    # kernels of every block width are compared with the oracle whatever the model prefers for these small tensors
+    import os
+    T = random_tensor(dims, 7 + dims[0], signed=signed)
+    U = _fused(dims, ranks, 100 + dims[1], signed=signed)
+    os.environ["CALS_MTTKRP_WNMAX"] = str(wn_max)
+    try:
+        got = _gpu_mttkrp(T, U, pad_to=sum(ranks) + 5)
+    finally:
+        del os.environ["CALS_MTTKRP_WNMAX"]
+    for mode in (1, 2, 3):
+        want = O.mttkrp(T, U, mode)
+        scale = _abs_scale(T, U, mode)
+        err = np.abs(got[mode - 1] - want)
+        assert np.all(np.isfinite(got[mode - 1]))
+        assert np.all(err <= TOL * scale + 1e-300), (mode, wn_max, float((err / (scale + 1e-300)).max()))
 
 
 def test_mttkrp_config2_shape_reduced_depth():
