@@ -10,7 +10,8 @@ resident in HBM before the timed region.  Prints ONE JSON line.
 
 `--workload cfgNjob` (N = 1..5) instead runs the configuration's whole job once as it is specified (queue, slots,
 tolerances, iteration caps, non-negativity, line search) and reports models completed per second; --steps and
---warmup do not apply.  The default run appends the cfg5 job (the queue workload) under "jobs" and the order-4
+--warmup do not apply; with `--one-at-a-time` the same job runs with a single slot (plain CP-ALS, model after model,
+through the same kernels: the baseline of the paper's speed-up experiments).  The default run appends the cfg5 job (the queue workload) under "jobs" and the order-4
 workload (see below) under "order_n".
 
 `--workload sweepW1000` / `sweepW300` time the fused MTTKRP alone, all three modes, over fused widths 1..1024 on the
@@ -48,6 +49,9 @@ def parse():
     ap.add_argument("--no-jobs", action="store_true", help="skip the whole-job runs appended to the default line")
     ap.add_argument("--reuse", action="store_true",
                     help="two-step sweeps (CALS_CTX_REUSE): modes 2 and 3 from the tensor contracted with the mode-1 factors")
+    ap.add_argument("--one-at-a-time", action="store_true",
+                    help="job workloads: one slot, i.e. plain CP-ALS model after model through the same kernels "
+                         "(the comparison of the paper's speed-up experiments, Sec. 6)")
     ap.add_argument("--yardstick", action="store_true", help="device properties and practical peaks (MFMA-only, read)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain elementwise copy kernel of known size (counter calibration for rocprofv3 --pmc)")
@@ -60,7 +64,7 @@ def workload(name: str):
     return get_config(cid)
 
 
-def run_job(cid: int, T_dev=None, reuse: bool = False) -> dict:
+def run_job(cid: int, T_dev=None, reuse: bool = False, one_at_a_time: bool = False) -> dict:
     """One whole job of configuration `cid`, as specified: every model enqueued with its own tolerance, iteration
     cap and flags; rounds until the queue and the slots are empty.  Tensor resident in HBM before the clock starts."""
     import torch
@@ -70,7 +74,8 @@ def run_job(cid: int, T_dev=None, reuse: bool = False) -> dict:
     models = make_models(cfg)
     if T_dev is None:
         T_dev = torch.from_numpy(make_tensor(cfg, threads=min(16, os.cpu_count() or 8))).to("cuda:0")
-    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots, flags=P.CTX_REUSE if reuse else 0)
+    ctx = P.Context(max_total_rank=max(m["rank"] for m in models) if one_at_a_time else cfg.max_total_rank,
+                    max_slots=1 if one_at_a_time else cfg.max_slots, flags=P.CTX_REUSE if reuse else 0)
     ctx.submit_tensor(T_dev)
     for m in models:
         ctx.enqueue_model(m["init"], m["tol"], m["max_iters"], m["flags"], m["ls_alpha"])
@@ -84,7 +89,7 @@ def run_job(cid: int, T_dev=None, reuse: bool = False) -> dict:
     assert len(res) == len(models)
     iters = sum(r.iters for r in res)
     ctx.close()
-    return {"workload": cfg.name + "_job", "two_step_sweeps": bool(reuse), "models": len(models), "seconds": dt, "models_per_s": len(models) / dt,
+    return {"workload": cfg.name + "_job", "two_step_sweeps": bool(reuse), "one_at_a_time": bool(one_at_a_time), "models": len(models), "seconds": dt, "models_per_s": len(models) / dt,
             "rounds": int(st.rounds), "ms_per_round": dt / max(1, st.rounds) * 1e3, "model_iterations": iters,
             "model_iterations_per_s": iters / dt, "mttkrp_gflops": st.mttkrp_flops / dt * 1e-9}
 
@@ -285,7 +290,7 @@ def main() -> int:
         print(json.dumps(run_order_n(args.workload, min(args.steps, 10), args.warmup)))
         return 0
     if args.workload.endswith("job"):
-        job = run_job(int(args.workload[3]), reuse=args.reuse)
+        job = run_job(int(args.workload[3]), reuse=args.reuse, one_at_a_time=args.one_at_a_time)
         print(json.dumps({"metric": "CP-ALS models completed/sec", "value": job["models_per_s"], "unit": "models/s",
                           "n_gpus": 1, "steps": job["rounds"], "warmup": 0, "ms_per_step": job["ms_per_round"],
                           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
