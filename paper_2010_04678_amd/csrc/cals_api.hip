@@ -1,6 +1,6 @@
 // C boundary and host scheduler of the CALS library: the queue logic of the paper's full algorithm
 // (Alg. 3) around the device kernels.  One round = fill the multi-matrices from the queue front,
-// advance every active model one ALS iteration with three fused MTTKRPs, read back the per-model
+// advance every active model one ALS iteration with one fused MTTKRP per mode, read back the per-model
 // fits, retire in slot order, compact.  The only host-visible data dependency per round is the
 // retire decision.
 #include <algorithm>
@@ -853,7 +853,7 @@ static int submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, cons
     HIP_TRY(hipMemcpy(c->T_owned, data, sizeof(double) * (size_t)total, hipMemcpyHostToDevice));
     c->T = c->T_owned;
   }
-  // buffers: three factor multi-matrices (+ a spare set for compaction), the MTTKRP result, per-model storage
+  // buffers: one factor multi-matrix per mode (+ a spare set for compaction), the MTTKRP result, per-model storage
   const int64_t imax = *std::max_element(dims, dims + ndims);
   bool ok = true;
   for (int n = 0; n < ndims; ++n) {

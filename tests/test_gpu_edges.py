@@ -59,6 +59,30 @@ def test_head_of_line_blocking_when_next_model_does_not_fit():
     assert st.rounds == 3 + 2
 
 
+def test_one_slot_runs_the_models_one_after_the_other_with_the_same_results():
+    # one slot = plain CP-ALS, model after model (what bench.py --one-at-a-time times); the models of a concurrent run
+    # do not influence each other, so both runs agree with the oracle and with each other
+    from workloads import get_config, make_models, make_tensor
+    cfg = get_config(1)
+    T = make_tensor(cfg)
+    models = make_models(cfg)
+    for k, m in enumerate(models):
+        m["tol"] = [-1.0, 1e-5][k % 2]
+    ref = O.cals(T, models, max(m["rank"] for m in models), 1)
+    assert list(ref["retire_order"]) == list(range(len(models)))        # a queue of one slot keeps the input order
+    one, facs1, st1 = run_gpu(T, models, max(m["rank"] for m in models), 1, rounds_per_call=5)
+    compare(one, facs1, ref, models)
+    assert st1.rounds == sum(r.iters for r in one)
+    many, facsm, stm = run_gpu(T, models, cfg.max_total_rank, cfg.max_slots)
+    assert stm.rounds == max(r.iters for r in many)
+    by_id = {r.model_id: r for r in many}
+    for r in one:
+        q = by_id[r.model_id]
+        assert (r.iters, r.status) == (q.iters, q.status) and abs(r.fit - q.fit) <= 1e-8
+        for a, b in zip(facs1[r.model_id][0], facsm[r.model_id][0]):
+            assert np.abs(a - b).max() <= 1e-6 * max(1.0, np.abs(b).max())
+
+
 def test_singleton_dimension():
     dims = (1, 9, 7)                                      # a matrix in disguise: mode-1 factors are 1 x R
     T = random_tensor(dims, 3)
