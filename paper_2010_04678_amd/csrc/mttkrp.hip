@@ -7,19 +7,20 @@
 
 namespace cals {
 
-// Adds the split-K partials in a fixed order (so results are bit-reproducible): the splits are cut into 8
-// consecutive groups, each group is summed in split order by its own eighth of the workgroup, and the eight
-// group sums are added left to right.  32 elements per workgroup x 8 groups keeps many loads in flight and the
-// grid several times the CU count even when the output is small and the split count large.
-constexpr int kRedElems = 32, kRedGroups = 8;
-
+// Adds the split-K partials in a fixed order (so results are bit-reproducible): the splits are cut into G
+// consecutive groups, each group is summed in split order by its own part of the workgroup, and the group sums are
+// added left to right.  G = 8 (32 elements per workgroup) keeps many loads in flight and the grid several times the
+// CU count even when the output is small and the split count large; with few splits fewer groups are used, so
+// that every thread has loads to issue (G = 1: 256 elements per workgroup, each thread sums its element's splits).
+template <int G>
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const double* __restrict__ P, double* __restrict__ M,
                                                             int64_t n_rows_ld, int ld, int ncols, int splits) {
-  __shared__ double part[kRedGroups][kRedElems];
-  const int e = threadIdx.x % kRedElems, g = threadIdx.x / kRedElems;
-  const int64_t idx = (int64_t)blockIdx.x * kRedElems + e;
+  constexpr int E = 256 / G;     // elements per workgroup
+  __shared__ double part[G][E];
+  const int e = threadIdx.x % E, g = threadIdx.x / E;
+  const int64_t idx = (int64_t)blockIdx.x * E + e;
   const bool live = idx < n_rows_ld && (int)(idx % ld) < ncols;
-  const int per = (splits + kRedGroups - 1) / kRedGroups;
+  const int per = (splits + G - 1) / G;
   const int z0 = g * per, z1 = (z0 + per < splits) ? (z0 + per) : splits;
   double s = 0.0;
   if (live) {
@@ -31,20 +32,32 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const double* __rest
     }
     for (; z < z1; ++z, p += n_rows_ld) s += *p;
   }
+  if (G == 1) {
+    if (live) M[idx] = s;
+    return;
+  }
   part[g][e] = s;
   __syncthreads();
   if (g == 0 && live) {
     double t = part[0][e];
 #pragma unroll
-    for (int q = 1; q < kRedGroups; ++q) t += part[q][e];
+    for (int q = 1; q < G; ++q) t += part[q][e];
     M[idx] = t;
   }
 }
 
 hipError_t launch_splitk_reduce(const double* P, double* M, int64_t n_rows_ld, int ld, int ncols, int splits, hipStream_t stream) {
   if (!P || !M || n_rows_ld < 1 || splits < 1) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n_rows_ld + kRedElems - 1) / kRedElems)), dim3(256), 0, stream, P, M,
-                     n_rows_ld, ld, ncols, splits);
+  // the group count depends on the split count alone, so a given launch shape always adds in the same order
+  if (splits <= 4) {
+    hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3((unsigned)((n_rows_ld + 255) / 256)), dim3(256), 0, stream, P, M, n_rows_ld, ld, ncols, splits);
+  } else if (splits <= 8) {
+    hipLaunchKernelGGL(splitk_reduce_kernel<2>, dim3((unsigned)((n_rows_ld + 127) / 128)), dim3(256), 0, stream, P, M, n_rows_ld, ld, ncols, splits);
+  } else if (splits <= 16) {
+    hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)((n_rows_ld + 63) / 64)), dim3(256), 0, stream, P, M, n_rows_ld, ld, ncols, splits);
+  } else {
+    hipLaunchKernelGGL(splitk_reduce_kernel<8>, dim3((unsigned)((n_rows_ld + 31) / 32)), dim3(256), 0, stream, P, M, n_rows_ld, ld, ncols, splits);
+  }
   return hipGetLastError();
 }
 
@@ -267,10 +280,8 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   if (pl.splits > 1) {
     const int64_t n = a.pstride;
     if (ev) (void)hipEventRecord(ev[2], stream);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n + kRedElems - 1) / kRedElems)), dim3(256), 0, stream,
-                       (const double*)workspace, p.M, n, p.ld, p.ncols, pl.splits);
+    e = launch_splitk_reduce(workspace, p.M, n, p.ld, p.ncols, pl.splits, stream);
     if (ev) (void)hipEventRecord(ev[3], stream);
-    e = hipGetLastError();
   }
   return e;
 }
