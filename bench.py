@@ -18,6 +18,9 @@ workload (see below) under "order_n".
 cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1).  `--yardstick` prints the device's compute-unit
 count and clock and its practical peaks (back-to-back fp64 MFMA; streaming read of a 4 GiB buffer).
 
+`--workload e400_100` / `e400_200` / `e400_300` run the workload of the paper's efficiency and GPU experiments (400
+models of ranks 1..20, 50 fixed iterations, m^3 tensor) and quote the paper's own total next to the result.
+
 `--workload order4` / `order5` time the path on a tensor of order 4 (180^4) / 5 (60^5), 8.4 and 6.2 GB: the fused
 MTTKRP alone per mode at several widths (contraction kernel by events, and the whole call including the explicit
 partial Khatri-Rao products), and timed rounds of the 40-model, width-420 mix of cfg4.
@@ -142,6 +145,46 @@ def run_sweep(which: str, reps: int = 3) -> dict:
 
 
 ORDER_N = {"order4": (180,) * 4, "order5": (60,) * 5}
+
+# The paper's efficiency and GPU experiments (Sec. 6, "Efficiency" and "GPU"): 400 models, 20 of each rank 1..20
+# (total rank 4200), exactly 50 iterations, on m x m x m tensors.  Its published totals for CALS with one V100 and 24
+# CPU threads (context only: other hardware, factor updates on the CPU): seconds for the whole job.
+PAPER_400_MODELS = {"e400_100": (100, 3.7), "e400_200": (200, 6.9), "e400_300": (300, 11.7)}
+
+
+def run_400_models(which: str, reuse: bool = False, one_at_a_time: bool = False) -> dict:
+    """400 concurrent models (ranks 1..20, 20 starting points each, R* = 4200), 50 fixed iterations, on a seeded
+    m^3 tensor (rank-10 Uniform[0,1) factors + 5 % noise, generated on the device)."""
+    import torch
+    import paper_2010_04678_amd as P
+    from workloads import low_rank_tensor_device, uniform_factors
+    m, paper_s = PAPER_400_MODELS[which]
+    dims = (m, m, m)
+    T, _ = low_rank_tensor_device(dims, 10, 4000 + m, noise=0.05)
+    ranks = [r for r in range(1, 21) for _ in range(20)]
+    rstar = max(ranks) if one_at_a_time else sum(ranks)
+    ctx = P.Context(max_total_rank=rstar, max_slots=1 if one_at_a_time else 0, flags=P.CTX_REUSE if reuse else 0)
+    ctx.submit_tensor(T)
+    for k, r in enumerate(ranks):
+        ctx.enqueue_model(uniform_factors(dims, r, 40000 + 1000 * (m // 100) + k), tol=-1.0, max_iters=50)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st = ctx.stats()
+    res = ctx.poll_retired(len(ranks) + 1)
+    assert len(res) == len(ranks) and all(r.iters == 50 for r in res)
+    ctx.close()
+    flops = 6.0 * sum(ranks) * float(m) ** 3 * 50
+    return {"metric": "CP-ALS models completed/sec", "value": len(ranks) / dt, "unit": "models/s", "n_gpus": 1,
+            "steps": int(st.rounds), "warmup": 0, "ms_per_step": dt / max(1, st.rounds) * 1e3, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": (len(ranks) / dt) / (len(ranks) / paper_s), "dtype": "f64", "data": "synthetic",
+            "config": {"workload": which, "dims": list(dims), "models": len(ranks), "total_rank": sum(ranks),
+                       "iterations": 50, "two_step_sweeps": bool(reuse), "one_at_a_time": bool(one_at_a_time)},
+            "seconds": dt, "mttkrp_gflops": flops / dt * 1e-9,
+            "paper": {"seconds": paper_s, "models_per_s": len(ranks) / paper_s,
+                      "hardware": "one V100 + 24 threads of a Xeon Platinum 8160 (CALS with CUDA offload of the MTTKRP)"}}
 
 
 def run_order_n(which: str, steps: int, warmup: int, reps: int = 3) -> dict:
@@ -288,6 +331,9 @@ def main() -> int:
         return 0
     if args.workload in ORDER_N:
         print(json.dumps(run_order_n(args.workload, min(args.steps, 10), args.warmup)))
+        return 0
+    if args.workload in PAPER_400_MODELS:
+        print(json.dumps(run_400_models(args.workload, reuse=args.reuse, one_at_a_time=args.one_at_a_time)))
         return 0
     if args.workload.endswith("job"):
         job = run_job(int(args.workload[3]), reuse=args.reuse, one_at_a_time=args.one_at_a_time)
