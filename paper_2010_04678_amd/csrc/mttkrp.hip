@@ -153,6 +153,9 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   // resident workgroups per CU: bounded by registers (accumulators) and LDS
   const int acc_tiles = wm * wn_top;
   int per_cu = (acc_tiles >= 17) ? 1 : (acc_tiles >= 10 ? 2 : (acc_tiles >= 8 ? 3 : 4));
+  // one row tile per wavefront with 12 or more column tiles: the B fragments and the factor rows in flight take
+  // so many registers next to the accumulators that only one workgroup fits (compiler's resource report)
+  if (wm == 1 && wn_top >= 12) per_cu = 1;
   const int lds_fit = (int)(160 * 1024 / ((size_t)2 * pl.ka * 16 * wn_top * sizeof(double)));
   if (per_cu > lds_fit) per_cu = lds_fit;
   per_cu = env_int("CALS_MTTKRP_PERCU", per_cu);
@@ -184,7 +187,7 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
       // workgroup only: 0.93 -- 1000^3 at width 512 runs at 62 TFLOP/s in blocks of 11 tiles, at 67 in blocks of 8).
       const int64_t on_cu = (wgs + num_cus - 1) / num_cus;
       const int resident = (int)std::min<int64_t>(per_cu, on_cu);
-      const double overlap = acc_tiles >= 17 ? 0.93
+      const double overlap = (acc_tiles >= 17 || per_cu == 1) ? 0.93
                              : (acc_tiles >= 10 ? (resident >= 2 ? 1.0 : 0.92)
                                                 : (resident >= 3 ? 1.0 : (resident == 2 ? 0.96 : 0.87)));
       const double mfma_us = (double)on_cu * (2.0 * pairs + 6.0 / resident) * us_per_tile_stage * wm * pl.part[q].wn / overlap;
