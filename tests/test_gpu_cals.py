@@ -285,6 +285,21 @@ def test_two_step_line_search_with_a_long_first_mode():
         assert sum(r.ls_accepted for r in results) > 0
 
 
+def test_400_models_at_once():
+    # the paper's efficiency experiment in small (Sec. 6: 20 models of each rank 1..20, total rank 4200, all in the
+    # buffer at once), on a tensor the oracle handles in seconds; fixed counts and tolerance stops mixed
+    dims = (40, 36, 30)
+    T = _collinear_tensor(dims, 6, 2500)
+    models = []
+    for k, r in enumerate([r for r in range(1, 21) for _ in range(20)]):
+        models.append(dict(rank=r, init=uniform_factors(dims, r, 2600 + k), tol=[-1.0, 1e-4, 1e-6][k % 3],
+                           max_iters=[6, 25, 40][k % 3], flags=0, ls_alpha=1.0))
+    ref = O.cals(T, models, 4200, 0)
+    results, facs, st = run_gpu(T, models, 4200, 0, rounds_per_call=5)
+    compare(results, facs, ref, models)
+    assert st.rounds == ref["rounds"]
+
+
 def test_config3_recipe_reduced():
     # configuration 3's recipe (fluorescence-shaped non-negative tensor, NONNEG models, tolerance stop), smaller
     cfg = get_config(3)
