@@ -689,6 +689,11 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
     for (int k = 0; k < N; ++k) {
       la.U[k] = c->U[k]; la.Uprev[k] = c->Uprev[k]; la.Unew[k] = c->Unew[k]; la.In[k] = (int)c->dims[k];
     }
+    // the extra MTTKRP: of the longest mode (best-shaped contraction: most rows, e.g. 4000 instead of 50), or of the
+    // last mode when it comes from the contraction of a two-step sweep
+    int ls_mode = N - 1;
+    if (!c->Y) ls_mode = (int)(std::max_element(c->dims, c->dims + N) - c->dims);
+    la.ls_mode = ls_mode;
     la.M3 = c->M; la.ld = c->ld; la.n_models = n; la.ncols = c->total_rank; la.normT2 = c->normT2;
     la.part = c->d_lspart;
     la.nblk = update_row_blocks((int)*std::max_element(c->dims, c->dims + N));
@@ -707,7 +712,7 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
         CALS_TRY(run_contract_mode1(c, c->Unew[0], c->total_rank, c->ld));
         CALS_TRY(run_from_contraction(c, N - 1, c->Unew, c->M, c->total_rank, c->ld, /*rebuild=*/true));
       } else {
-        CALS_TRY(run_mttkrp(c, N - 1, c->Unew, c->M, c->total_rank, c->ld));
+        CALS_TRY(run_mttkrp(c, ls_mode, c->Unew, c->M, c->total_rank, c->ld));
       }
     }
     HIP_TRY(launch_ls_decide(la, c->stream));

@@ -182,7 +182,8 @@ struct LineSearchArgs {
   double* U[kMaxModes];     // current factors
   double* Uprev[kMaxModes]; // point after the previous iteration
   double* Unew[kMaxModes];  // extrapolated point
-  const double* M3;        // MTTKRP of the last mode at the extrapolated point, row-major I_N x ld
+  const double* M3;        // MTTKRP of mode `ls_mode` at the extrapolated point, row-major I_mode x ld
+  int ls_mode;             // 0-based mode whose MTTKRP gives the inner product <T, model> of the extrapolated point
   double* part;            // per (slot position, mode, row block): partial Gramian and inner product of the
                            // extrapolated point, kUpdatePartStride doubles each
   int nblk;                // row blocks (update_row_blocks of the longest mode)

@@ -1,7 +1,9 @@
 // Line search for CALS (Sec. 5 of the paper, "Line search"), applied to each model independently after a
 // round's mode updates: P_new = P_prev + alpha (P_cur - P_prev); the extrapolated point replaces P_cur
 // only if its error is lower.  The error of P_new comes from the fast formula of Alg. 1 with ONE extra fused
-// MTTKRP of the last mode over the extrapolated multi-matrices, so the central fused operation is preserved.
+// MTTKRP over the extrapolated multi-matrices, so the central fused operation is preserved.  The inner product
+// <T, model> is sum(A_n * M_n) for any mode n, so the host picks the mode whose MTTKRP runs best (the longest one;
+// the last one when it comes from the two-step contraction).
 // With two-step sweeps the tensor contracted with the mode-1 factors of the extrapolated point is the same
 // combination of the contractions at P_prev and P_cur (the contraction is linear in those factors), so the extra
 // MTTKRP needs no pass over the tensor.
@@ -74,7 +76,7 @@ __global__ void __launch_bounds__(256) ls_gram_kernel(LineSearchArgs a) {
       for (int r = 0; r < R; ++r) {
         const double x = Ub[(int64_t)i * a.ld + r];
         xs[r * kXs + tid] = x;
-        if (mode == a.nmodes - 1) part += x * a.M3[(int64_t)i * a.ld + d.col + r];
+        if (mode == a.ls_mode) part += x * a.M3[(int64_t)i * a.ld + d.col + r];
       }
       inner += part;
     }
@@ -100,7 +102,7 @@ __global__ void __launch_bounds__(256) ls_gram_kernel(LineSearchArgs a) {
     const int p = tid + 256 * q;
     if (p < npairs) part[p] = gacc[q];
   }
-  if (mode == a.nmodes - 1) {
+  if (mode == a.ls_mode) {
     const double tot = ls_block_sum(inner, red);
     if (tid == 0) part[528] = tot;
   }
@@ -134,7 +136,7 @@ __global__ void __launch_bounds__(256) ls_decide_kernel(LineSearchArgs a) {
     }
   }
   if (tid == 0) {
-    const double* pm = a.part + ((size_t)blockIdx.x * a.nmodes + (a.nmodes - 1)) * a.nblk * kUpdatePartStride;
+    const double* pm = a.part + ((size_t)blockIdx.x * a.nmodes + a.ls_mode) * a.nblk * kUpdatePartStride;
     double in = 0.0;
     for (int b = 0; b < a.nblk; ++b) in += pm[(size_t)b * kUpdatePartStride + 528];
     st->inner_ls = in;
