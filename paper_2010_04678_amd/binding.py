@@ -304,17 +304,23 @@ def suggest_max_total_rank(ranks: Sequence[int], plateau: int = 256) -> int:
 
 
 def suggest_two_step(dims: Sequence[int], max_total_rank: int, budget_bytes: int = 64 << 30) -> bool:
-    """Whether two-step sweeps (CTX_REUSE) pay off: they read the tensor twice per sweep instead of once per mode, at
-    the price of an intermediate of I2*...*IN*ld doubles and of a few more launches per round.  Measured, order 3:
-    41 -> 29 ms per sweep on 1000^3 at width 420, 112 -> 207 models/s on the 4000x200x50 line-search queue job, 874 -> 1011 on
-    200^3, but 3440 -> 3270 on 32^3, where a round is launch-bound; order 4 (180^4) 68 -> 44 ms per round, order 5
-    (60^5) 64 -> 53.  So: at least 2^20 tensor elements and an intermediate within `budget_bytes`."""
+    """Whether two-step sweeps (CTX_REUSE) pay off.  They replace N-2 of a sweep's N fused MTTKRPs by reads of an
+    intermediate of I2*...*IN*ld doubles (about two passes over it per sweep) and add a few launches per round.
+    Measured, order 3: 40 -> 28 ms per sweep on 1000^3 at width 420, 123 -> 222 models/s on the 4000x200x50 line-search
+    queue job, 930 -> 1010 on 200^3, but 3440 -> 3270 on 32^3, where a round is launch-bound; order 4 (180^4)
+    60 -> 41 ms per round, order 5 (60^5) 60 -> 50.  So: at least 2^20 tensor elements, an intermediate within
+    `budget_bytes`, and two passes over it (at 4.5 TB/s) cheaper than the MTTKRPs they replace (each the larger of
+    its flops at 60 TFLOP/s and one pass over the tensor at 5.5 TB/s) -- which fails when the first mode is short,
+    e.g. 50x200x4000, whose intermediate is 13 times the tensor at width 640."""
     dims = [int(d) for d in dims]
     ld = (int(max_total_rank) + 15) // 16 * 16
     elems = 1
     for d in dims:
         elems *= d
-    return elems >= (1 << 20) and (elems // dims[0]) * ld * 8 <= int(budget_bytes)
+    y_bytes = (elems // dims[0]) * ld * 8
+    t_mttkrp = max(2.0 * ld * elems / 60e12, 8.0 * elems / 5.5e12)
+    return (elems >= (1 << 20) and y_bytes <= int(budget_bytes)
+            and 2.0 * y_bytes / 4.5e12 < (len(dims) - 2) * t_mttkrp)
 
 
 def cp_cals(T, inits: Sequence[Sequence[np.ndarray]], tol: float = 1e-4, max_iters: int = 50, nonneg: bool = False,

@@ -62,6 +62,8 @@ def test_suggested_buffer_width():
     assert not P.suggest_two_step((32, 32, 32), 30) and P.suggest_two_step((180, 180, 180, 180), 420)
     assert not P.suggest_two_step((180, 180, 180, 180), 2048)      # 96 GB intermediate: over the default budget
     assert not P.suggest_two_step((100, 40000, 40000), 64)
+    # a short first mode: the intermediate (I2*I3 x width) is many times the tensor, its passes cost more than they save
+    assert not P.suggest_two_step((50, 200, 4000), 640) and P.suggest_two_step((200, 50, 4000), 64)
 
 
 def test_bench_refuses_more_than_one_gpu():
