@@ -207,3 +207,28 @@ def test_order_4_at_bench_size_sampled_elements():
     ctx.close()
     del Td, Ud
     torch.cuda.empty_cache()
+
+
+def test_paper_dataset_size_with_400_models():
+    # the size of the paper's largest fluorescence dataset (299 x 301 x 41: no dimension a multiple of a tile, two of
+    # them odd, so the unaligned kernel variants run at scale) with its 400-model queue (20 per rank 1..20, total rank
+    # 4200, everything active at once), tolerance stops, iteration cap lowered so that the oracle can follow sampled models
+    from types import SimpleNamespace
+    from workloads import uniform_factors
+    dims = (299, 301, 41)
+    T = make_tensor(get_config(3), dims=dims)
+    ranks = [r for r in range(1, 21) for _ in range(20)]
+    models = [dict(rank=r, init=uniform_factors(dims, r, 60000 + k), tol=1e-6, max_iters=40, flags=0, ls_alpha=1.0)
+              for k, r in enumerate(ranks)]
+    shape = SimpleNamespace(max_total_rank=sum(ranks), max_slots=0)
+    sample = [3, 127, 250, 399]                                  # ranks 1, 7, 13, 20
+    res, facs, st = gpu_run(T, models, shape, keep=sample)
+    assert st.rounds == max(r.iters for r in res) <= 40
+    order = replay_queue(ranks, [r.iters for r in sorted(res, key=lambda r: r.model_id)], shape.max_total_rank, 0)
+    assert [r.model_id for r in res] == order
+    ref = O.cals(T, [models[k] for k in sample], shape.max_total_rank, 0)
+    check_models(res, facs, models, ref, sample)
+    import paper_2010_04678_amd as P
+    res2, facs2, st2 = gpu_run(T, models, shape, keep=sample, ctx_flags=P.CTX_REUSE)
+    assert [(r.model_id, r.iters, r.status) for r in res2] == [(r.model_id, r.iters, r.status) for r in res]
+    check_models(res2, facs2, models, ref, sample)
