@@ -1,4 +1,5 @@
-"""The five configurations at FULL size, in the launch configuration bench.py times (same R*, slots, flags).
+"""The five configurations at FULL size, in the launch configuration bench.py times (same R*, slots, flags), and the
+size of the paper's largest dataset with its 400-model queue.
 
 The oracle cannot run these whole in test time, so it checks what it can compute one by one: sampled MTTKRP
 elements (extended precision), sampled models run solo (models are numerically independent of their
