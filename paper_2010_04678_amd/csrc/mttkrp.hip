@@ -80,7 +80,7 @@ hipError_t mttkrp_init() {
     int n = 0;
     const Variant* t = (wm == 1) ? mttkrp_variants_wm1(&n) : (wm == 2 ? mttkrp_variants_wm2(&n) : mttkrp_variants_wm4(&n));
     for (int i = 0; i < n; ++i)
-      for (int m = 0; m < 10; ++m) {
+      for (int m = 0; m < 12; ++m) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(t[i].fn[m >> 1][m & 1]),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)variant_lds_bytes(t[i]));
         if (e != hipSuccess) return e;
@@ -92,6 +92,32 @@ hipError_t mttkrp_init() {
 static int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
   return (v && *v) ? atoi(v) : dflt;
+}
+
+// How the kernel reads the tensor along the contraction (see the mode list in mttkrp_kernel.h), and the length of
+// the fast contracted index as the kernel counts it: kContig4U pads every run of Ia contiguous elements to a
+// multiple of 4 positions, so the contraction range it is launched on is Ia_pad * Ib.
+static int tensor_read_mode(const MttkrpProblem& p, int wm, int* ia_counted) {
+  const int ka = 16;
+  *ia_counted = p.Ia;
+  int mode = (p.Ia < ka) ? kGeneral : ((p.sb == (int64_t)p.Ia * p.sa) ? kAffine : kWrap);
+  if (mode != kGeneral && p.sa == 1 && env_int("CALS_MTTKRP_NOCONTIG", 0) == 0) {
+    // rows contiguous along the contraction: four consecutive indices per lane, 16-byte loads
+    if (p.Ia % 4 == 0 && p.sm % 2 == 0 && p.sb % 2 == 0 && (reinterpret_cast<uintptr_t>(p.T) & 15) == 0) return kContig4;
+    // not aligned: the same layout with padded runs and shifted loads pays while the launch is bound by memory
+    // (999 x 1001 x 997, modes 2 and 3: 5.9 / 4.9 -> 9.5 / 9.0 TFLOP/s at 8 columns, 32 / 27 -> 37 / 35 at 48); its extra
+    // selects per tensor fragment cost MFMA issue time once the launch is compute-bound (47 / 44 -> 41 / 40 at 64)
+    const int force = env_int("CALS_MTTKRP_CONTIGU", -1);
+    if (force == 1 || (force != 0 && p.ncols <= 48)) {
+      *ia_counted = (p.Ia + 3) / 4 * 4;
+      return kContig4U;
+    }
+  }
+  // rows contiguous in memory (mode 1), even row count, 16-byte aligned columns: two rows per 16-byte load
+  if (mode == kAffine && p.sm == 1 && wm % 2 == 0 && p.In % 2 == 0 && p.sa % 2 == 0 && p.sb % 2 == 0 &&
+      (reinterpret_cast<uintptr_t>(p.T) & 15) == 0 && env_int("CALS_MTTKRP_NOROWPAIR", 0) == 0)
+    return kRowPair;
+  return mode;
 }
 
 static constexpr int kMaxWn = 14;     // widest column block of a workgroup, in 16-column tiles
@@ -131,7 +157,9 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
       if (cost < best) { best = cost; wm = cand; }
     }
   }
-  const int64_t K = (int64_t)p.Ia * p.Ib;
+  int ia_counted = p.Ia;
+  (void)tensor_read_mode(p, 2, &ia_counted);
+  const int64_t K = (int64_t)ia_counted * p.Ib;
   // the tensor once per column block at the practical read rate (tensors of up to 1 GiB are largely served by the
   // last-level cache: about twice the rate)
   const double tensor_bytes = (double)p.In * (double)K * 8.0;
@@ -233,7 +261,10 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   if (pl.nparts < 1 || pl.nparts > 2) return hipErrorInvalidValue;
   if (p.ncols < 1 || p.ncols > p.ld || p.In < 1 || p.Ia < 1 || p.Ib < 1) return hipErrorInvalidValue;
   if ((int64_t)pl.mtiles * 64 * pl.wm < p.In) return hipErrorInvalidValue;
-  if (pl.chunk % pl.ka != 0 || (int64_t)pl.splits * pl.chunk < (int64_t)p.Ia * p.Ib) return hipErrorInvalidValue;
+  int ia_counted = p.Ia;
+  const int mode = tensor_read_mode(p, pl.wm, &ia_counted);
+  if (pl.ka != 16) return hipErrorInvalidValue;
+  if (pl.chunk % pl.ka != 0 || (int64_t)pl.splits * pl.chunk < (int64_t)ia_counted * p.Ib) return hipErrorInvalidValue;
   if (pl.splits > 1 && !workspace) return hipErrorInvalidValue;
   if (!p.zeros || (reinterpret_cast<uintptr_t>(p.zeros) & 15)) return hipErrorInvalidValue;
   // the parts tile the columns without gaps
@@ -247,21 +278,12 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   a.T = p.T; a.Ua = p.Ua; a.Ub = p.Ub; a.zeros = p.zeros;
   a.P = (pl.splits > 1) ? workspace : p.M;
   a.sm = p.sm; a.sa = p.sa; a.sb = p.sb;
-  a.K = (int64_t)p.Ia * p.Ib; a.chunk = pl.chunk;
+  a.K = (int64_t)ia_counted * p.Ib; a.chunk = pl.chunk;
   a.pstride = (int64_t)p.In * p.ld;
-  a.In = p.In; a.Ia = p.Ia; a.Ib = p.Ib;
+  a.In = p.In; a.Ia = ia_counted; a.Iav = p.Ia; a.Ib = p.Ib;
   a.ncols = p.ncols; a.ld = p.ld;
   a.mtiles = pl.mtiles; a.splits = pl.splits;
   a.pinned = (pl.splits % 8 == 0) ? 1 : 0;
-  int mode = (p.Ia < pl.ka) ? kGeneral : ((p.sb == (int64_t)p.Ia * p.sa) ? kAffine : kWrap);
-  // rows contiguous along the contraction and 16-byte aligned: the coalesced 4-indices-per-lane path
-  if (mode != kGeneral && p.sa == 1 && p.Ia % 4 == 0 && p.sm % 2 == 0 && p.sb % 2 == 0 && pl.ka == 16 &&
-      (reinterpret_cast<uintptr_t>(p.T) & 15) == 0 && env_int("CALS_MTTKRP_NOCONTIG", 0) == 0)
-    mode = kContig4;
-  // rows contiguous in memory (mode 1), even row count, 16-byte aligned columns: two rows per 16-byte load
-  if (mode == kAffine && p.sm == 1 && pl.wm % 2 == 0 && p.In % 2 == 0 && p.sa % 2 == 0 && p.sb % 2 == 0 &&
-      (reinterpret_cast<uintptr_t>(p.T) & 15) == 0 && env_int("CALS_MTTKRP_NOROWPAIR", 0) == 0)
-    mode = kRowPair;
   // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao tile production
   const int pair = (p.ld % 2 == 0 && ((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub)) & 15) == 0 &&
                     env_int("CALS_MTTKRP_NOPAIR", 0) == 0) ? 1 : 0;

@@ -46,7 +46,8 @@ struct MttkrpKernelArgs {
   int64_t sm, sa, sb; // element strides of T: output row, fast contracted index, slow contracted index
   int64_t K, chunk;   // contraction length Ia*Ib; indices per split (multiple of KA)
   int64_t pstride;    // In * ld
-  int In, Ia, Ib;
+  int In, Ia, Ib;     // Ia: length of the fast contracted index as the kernel counts it (kContig4U: rounded up to 4)
+  int Iav;            // its valid length (rows of Ua, elements per run in memory); equals Ia except for kContig4U
   int ncols, ld;
   int mtiles, ny, splits;   // logical grid: row blocks, column blocks, splits
   int col0;                 // first column of column block 0
@@ -64,7 +65,16 @@ struct MttkrpKernelArgs {
 //             adjacent rows with one 16-byte load and feeds them to two row tiles, so row tile 2p holds the even
 //             and row tile 2p+1 the odd rows of the wavefront's p-th group of 32 rows (needs WM even; kernels
 //             with odd WM treat it as kAffine and are never launched with it).
-enum { kAffine = 0, kWrap = 1, kGeneral = 2, kContig4 = 3, kRowPair = 4 };
+//   kContig4U: sa == 1, Ia >= KA, but Ia not a multiple of 4 or rows not 16-byte aligned (odd-sized tensors): the
+//             same lane-owns-4-consecutive-indices layout on a contraction index PADDED to a multiple of 4 per run
+//             (k = ia + Ia_pad*ib, positions ia >= Iav load zeros), with 16-byte loads at 8-byte alignment; a load
+//             that would straddle the end of a run is moved back by one element and its values are shifted, so no
+//             byte outside the run is ever read.  One load instruction then touches whole cache lines of 16 rows
+//             instead of one 32-byte sector each.  The extra selects cost issue slots, so the host uses it for narrow,
+//             memory-bound launches only.
+enum { kAffine = 0, kWrap = 1, kGeneral = 2, kContig4 = 3, kRowPair = 4, kContig4U = 5 };
+
+typedef double double2_u __attribute__((ext_vector_type(2), aligned(8)));   // 16-byte load at 8-byte alignment
 
 template <int WM, int WN, int KA, int MODE, bool PAIR>
 __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
@@ -132,7 +142,7 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   int a_ia = 0;                               // only tracked when the offset is not affine in k
   int a_left;                                 // contraction indices left before ke, from this lane's k
   {
-    const int64_t k = kb + (MODE == kContig4 ? 4 * lq : lq);
+    const int64_t k = kb + ((MODE == kContig4 || MODE == kContig4U) ? 4 * lq : lq);
     if (AFF) {
       koff = k * a.sa;
     } else {
@@ -165,6 +175,30 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
         dst[1][t] = v01.y;
         dst[2][t] = v23.x;
         dst[3][t] = v23.y;
+      }
+      a_left -= KA;
+      koff += KA;
+      a_ia += KA;
+      if (a_ia >= Ia) { a_ia -= Ia; koff += a_wrap; }
+      return;
+    }
+    if (MODE == kContig4U) {
+      static_assert(MODE != kContig4U || KA == 16, "a lane's run of 4 indices times 4 lane groups is one stage");
+      // valid elements among the lane's four: all (>= 4), the first 3, 2 or 1, or none (padding, or past the split)
+      const int nvalid = (a_left > 0) ? (a.Iav - a_ia) : 0;
+      const bool lo2 = nvalid >= 2, lo1 = nvalid == 1, hi2 = nvalid >= 4, hi1 = nvalid == 3;
+#pragma unroll
+      for (int t = 0; t < WM; ++t) {
+        const double* p = Prow[t] + koff;
+        // halves (elements 0,1) and (2,3); a half with only its first element valid reads one element earlier
+        const double* p0 = lo2 ? p : (lo1 ? p - 1 : zeros);
+        const double* p1 = hi2 ? p + 2 : (hi1 ? p + 1 : zeros);
+        const double2_u v0 = *reinterpret_cast<const double2_u*>(p0);
+        const double2_u v1 = *reinterpret_cast<const double2_u*>(p1);
+        dst[0][t] = lo1 ? v0.y : v0.x;
+        dst[1][t] = lo1 ? 0.0 : v0.y;
+        dst[2][t] = hi1 ? v1.y : v1.x;
+        dst[3][t] = hi1 ? 0.0 : v1.y;
       }
       a_left -= KA;
       koff += KA;
@@ -218,7 +252,8 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   // right after row x of the next tile has been written), so that a miss in L2 never stalls the wavefront.
   double pua[KS][CU][PW], pub[KS][CU][PW];
   const unsigned row_bytes = 8u * (unsigned)a.ld;
-  const __amdgpu_buffer_rsrc_t rsrc_a = factor_rsrc(a.Ua, row_bytes * (unsigned)Ia);   // < 2^32 (checked on the host)
+  const __amdgpu_buffer_rsrc_t rsrc_a = factor_rsrc(a.Ua, row_bytes * (unsigned)a.Iav);   // < 2^32 (checked on the host);
+                                                   // kContig4U: rows Iav .. Ia-1 are out of range and read as zeros
   const __amdgpu_buffer_rsrc_t rsrc_b = factor_rsrc(a.Ub, row_bytes * (unsigned)a.Ib);
   // Byte offsets of the factor rows (ia, ib) of this wavefront's row x of the tile to fetch next: uniform over
   // the wavefront, kept in scalar registers and advanced by KA rows per fetch (one compare for the wrap of ia).
@@ -311,7 +346,7 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 
   double breg[2][WN];
   auto load_b = [&](const double* tile, int s, double (&b)[WN]) {
-    const double* brow = tile + (MODE == kContig4 ? 4 * lq + s : 4 * s + lq) * NC + li;
+    const double* brow = tile + ((MODE == kContig4 || MODE == kContig4U) ? 4 * lq + s : 4 * s + lq) * NC + li;
 #pragma unroll
     for (int j = 0; j < WN; ++j) b[j] = brow[16 * j];
   };
@@ -422,7 +457,7 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
 typedef void (*mttkrp_fn)(MttkrpKernelArgs);
 struct Variant {
   int wm, wn, ka;
-  mttkrp_fn fn[5][2]; // indexed by kAffine / kWrap / kGeneral / kContig4 / kRowPair, and by PAIR
+  mttkrp_fn fn[6][2]; // indexed by kAffine / kWrap / kGeneral / kContig4 / kRowPair / kContig4U, and by PAIR
 };
 #define CALS_VARIANT(WM_, WN_, KA_)                                                                       \
   {                                                                                                       \
@@ -431,7 +466,8 @@ struct Variant {
           {mttkrp_kernel<WM_, WN_, KA_, kWrap, false>, mttkrp_kernel<WM_, WN_, KA_, kWrap, true>},        \
           {mttkrp_kernel<WM_, WN_, KA_, kGeneral, false>, mttkrp_kernel<WM_, WN_, KA_, kGeneral, true>},  \
           {mttkrp_kernel<WM_, WN_, KA_, kContig4, false>, mttkrp_kernel<WM_, WN_, KA_, kContig4, true>},  \
-          {mttkrp_kernel<WM_, WN_, KA_, kRowPair, false>, mttkrp_kernel<WM_, WN_, KA_, kRowPair, true>}   \
+          {mttkrp_kernel<WM_, WN_, KA_, kRowPair, false>, mttkrp_kernel<WM_, WN_, KA_, kRowPair, true>},  \
+          {mttkrp_kernel<WM_, WN_, KA_, kContig4U, false>, mttkrp_kernel<WM_, WN_, KA_, kContig4U, true>} \
     }                                                                                                     \
   }
 

@@ -105,6 +105,29 @@ def test_mttkrp_every_column_block_width(dims, ranks, signed, wn_max):
         assert np.all(err <= TOL * scale + 1e-300), (mode, wn_max, float((err / (scale + 1e-300)).max()))
 
 
+@pytest.mark.parametrize("force", ["1", "0"])
+@pytest.mark.parametrize("dims,ranks,signed", [c for c in CASES if c[0][0] >= 16 and c[0][0] % 4 != 0] +
+                         [((19, 6, 5), [2, 3], True), ((33, 4, 3), [16] * 3, False), ((255, 7, 3), [5, 9, 20], True)])
+def test_mttkrp_first_mode_not_a_multiple_of_four(dims, ranks, signed, force):
+    # tensors whose first mode is not a multiple of 4 (the paper's datasets: 405, 255, 299): modes 2 and up read runs of
+    # I1 contiguous elements that are not 16-byte aligned.  Narrow launches read them with padded runs and shifted
+    # 16-byte loads, wide ones element by element; here each way is forced at every width (development knob)
+    import os
+    T = random_tensor(dims, 11 + dims[0], signed=signed)
+    U = _fused(dims, ranks, 300 + dims[1], signed=signed)
+    os.environ["CALS_MTTKRP_CONTIGU"] = force
+    try:
+        got = _gpu_mttkrp(T, U, pad_to=sum(ranks) + 3)
+    finally:
+        del os.environ["CALS_MTTKRP_CONTIGU"]
+    for mode in (1, 2, 3):
+        want = O.mttkrp(T, U, mode)
+        scale = _abs_scale(T, U, mode)
+        err = np.abs(got[mode - 1] - want)
+        assert np.all(np.isfinite(got[mode - 1]))
+        assert np.all(err <= TOL * scale + 1e-300), (mode, force, float((err / (scale + 1e-300)).max()))
+
+
 def test_mttkrp_config2_shape_reduced_depth():
     # configuration 2's fused width (110) on a tensor with its row count but fewer slabs (oracle stays fast)
     cfg = get_config(2)
