@@ -104,11 +104,13 @@ static int tensor_read_mode(const MttkrpProblem& p, int wm, int* ia_counted) {
   if (mode != kGeneral && p.sa == 1 && env_int("CALS_MTTKRP_NOCONTIG", 0) == 0) {
     // rows contiguous along the contraction: four consecutive indices per lane, 16-byte loads
     if (p.Ia % 4 == 0 && p.sm % 2 == 0 && p.sb % 2 == 0 && (reinterpret_cast<uintptr_t>(p.T) & 15) == 0) return kContig4;
-    // not aligned: the same layout with padded runs and shifted loads pays while the launch is bound by memory
-    // (999 x 1001 x 997, modes 2 and 3: 5.9 / 4.9 -> 9.5 / 9.0 TFLOP/s at 8 columns, 32 / 27 -> 37 / 35 at 48); its extra
-    // selects per tensor fragment cost MFMA issue time once the launch is compute-bound (47 / 44 -> 41 / 40 at 64)
+    // not aligned: the same layout with padded runs and shifted loads.  It pays while the launch is bound by memory
+    // (999 x 1001 x 997, modes 2 and 3: 5.9 / 4.9 -> 9.5 / 9.0 TFLOP/s at 8 columns, 32 / 27 -> 39 / 38 at 48) and,
+    // on tensors too large for the last-level cache, at every width (62 / 50 -> 64 / 64 at 256); small tensors at
+    // larger widths are as fast or faster read element by element
     const int force = env_int("CALS_MTTKRP_CONTIGU", -1);
-    if (force == 1 || (force != 0 && p.ncols <= 48)) {
+    const double tensor_bytes = 8.0 * (double)p.In * (double)p.Ia * (double)p.Ib;
+    if (force == 1 || (force != 0 && (p.ncols <= 48 || tensor_bytes > 1073741824.0))) {
       *ia_counted = (p.Ia + 3) / 4 * 4;
       return kContig4U;
     }

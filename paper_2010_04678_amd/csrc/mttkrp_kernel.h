@@ -186,19 +186,36 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
       static_assert(MODE != kContig4U || KA == 16, "a lane's run of 4 indices times 4 lane groups is one stage");
       // valid elements among the lane's four: all (>= 4), the first 3, 2 or 1, or none (padding, or past the split)
       const int nvalid = (a_left > 0) ? (a.Iav - a_ia) : 0;
-      const bool lo2 = nvalid >= 2, lo1 = nvalid == 1, hi2 = nvalid >= 4, hi1 = nvalid == 3;
+      // Wide column blocks (compute-bound): when no lane of the wavefront sits on the end of a run -- the usual case --
+      // a branch skips the selects, which would cost MFMA issue time.  Narrow blocks (memory-bound) always take the
+      // general form: there the branch costs more than the selects (it keeps the loads from being issued early).
+      if (WN > 3 && __builtin_amdgcn_ballot_w64(nvalid > 0 && nvalid < 4) == 0) {
+        const bool ok = nvalid > 0;
 #pragma unroll
-      for (int t = 0; t < WM; ++t) {
-        const double* p = Prow[t] + koff;
-        // halves (elements 0,1) and (2,3); a half with only its first element valid reads one element earlier
-        const double* p0 = lo2 ? p : (lo1 ? p - 1 : zeros);
-        const double* p1 = hi2 ? p + 2 : (hi1 ? p + 1 : zeros);
-        const double2_u v0 = *reinterpret_cast<const double2_u*>(p0);
-        const double2_u v1 = *reinterpret_cast<const double2_u*>(p1);
-        dst[0][t] = lo1 ? v0.y : v0.x;
-        dst[1][t] = lo1 ? 0.0 : v0.y;
-        dst[2][t] = hi1 ? v1.y : v1.x;
-        dst[3][t] = hi1 ? 0.0 : v1.y;
+        for (int t = 0; t < WM; ++t) {
+          const double* p = ok ? Prow[t] + koff : zeros;
+          const double2_u v0 = *reinterpret_cast<const double2_u*>(p);
+          const double2_u v1 = *reinterpret_cast<const double2_u*>(p + 2);
+          dst[0][t] = v0.x;
+          dst[1][t] = v0.y;
+          dst[2][t] = v1.x;
+          dst[3][t] = v1.y;
+        }
+      } else {
+        const bool lo2 = nvalid >= 2, lo1 = nvalid == 1, hi2 = nvalid >= 4, hi1 = nvalid == 3;
+#pragma unroll
+        for (int t = 0; t < WM; ++t) {
+          const double* p = Prow[t] + koff;
+          // halves (elements 0,1) and (2,3); a half with only its first element valid reads one element earlier
+          const double* p0 = lo2 ? p : (lo1 ? p - 1 : zeros);
+          const double* p1 = hi2 ? p + 2 : (hi1 ? p + 1 : zeros);
+          const double2_u v0 = *reinterpret_cast<const double2_u*>(p0);
+          const double2_u v1 = *reinterpret_cast<const double2_u*>(p1);
+          dst[0][t] = lo1 ? v0.y : v0.x;
+          dst[1][t] = lo1 ? 0.0 : v0.y;
+          dst[2][t] = hi1 ? v1.y : v1.x;
+          dst[3][t] = hi1 ? 0.0 : v1.y;
+        }
       }
       a_left -= KA;
       koff += KA;
