@@ -14,8 +14,8 @@ tolerances, iteration caps, non-negativity, line search) and reports models comp
 through the same kernels: the baseline of the paper's speed-up experiments).  The default run appends the cfg5 job (the queue workload) under "jobs" and the order-4
 workload (see below) under "order_n".
 
-`--workload sweepW1000` / `sweepW300` time the fused MTTKRP alone, all three modes, over fused widths 1..1024 on the
-cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1).  `--yardstick` prints the device's compute-unit
+`--workload sweepW1000` / `sweepW300` / `sweepWodd` time the fused MTTKRP alone, all three modes, over fused widths
+1..1024 on the cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1) / a 999 x 1001 x 997 tensor.  `--yardstick` prints the device's compute-unit
 count and clock and its practical peaks (back-to-back fp64 MFMA; streaming read of a 4 GiB buffer).
 
 `--workload e400_100` / `e400_200` / `e400_300` run the workload of the paper's efficiency and GPU experiments (400
@@ -113,10 +113,11 @@ def run_sweep(which: str, reps: int = 3) -> dict:
         T = torch.from_numpy(make_tensor(cfg, threads=min(16, os.cpu_count() or 8))).to("cuda:0")
         dims = tuple(cfg.dims)
     else:
-        dims = (300, 300, 300)
+        # 300^3 (fits the last-level cache), or an 8 GB tensor with no dimension a multiple of 4 (the unaligned reads)
+        dims = (300, 300, 300) if which == "sweepW300" else (999, 1001, 997)
         g = torch.Generator(device="cuda:0")
         g.manual_seed(300)
-        T = torch.rand((300, 300, 300), dtype=torch.float64, device="cuda:0", generator=g)
+        T = torch.rand(dims[::-1], dtype=torch.float64, device="cuda:0", generator=g)
     I1, I2, I3 = dims
     ctx = P.Context(max_total_rank=max(SWEEP_WIDTHS), flags=P.CTX_TIMING)
     ctx.submit_tensor(T)
