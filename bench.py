@@ -58,6 +58,9 @@ def parse():
     ap.add_argument("--one-at-a-time", action="store_true",
                     help="job workloads: one slot, i.e. plain CP-ALS model after model through the same kernels "
                          "(the comparison of the paper's speed-up experiments, Sec. 6)")
+    ap.add_argument("--trace", action="store_true",
+                    help="job workloads: time every round on the device (events) and report the MTTKRP rate over "
+                         "tenths of the job's flops (the paper's efficiency-over-the-run measurement, Sec. 6)")
     ap.add_argument("--yardstick", action="store_true", help="device properties and practical peaks (MFMA-only, read)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain elementwise copy kernel of known size (counter calibration for rocprofv3 --pmc)")
@@ -70,7 +73,7 @@ def workload(name: str):
     return get_config(cid)
 
 
-def run_job(cid: int, T_dev=None, reuse: bool = False, one_at_a_time: bool = False) -> dict:
+def run_job(cid: int, T_dev=None, reuse: bool = False, one_at_a_time: bool = False, trace: bool = False) -> dict:
     """One whole job of configuration `cid`, as specified: every model enqueued with its own tolerance, iteration
     cap and flags; rounds until the queue and the slots are empty.  Tensor resident in HBM before the clock starts."""
     import torch
@@ -81,7 +84,8 @@ def run_job(cid: int, T_dev=None, reuse: bool = False, one_at_a_time: bool = Fal
     if T_dev is None:
         T_dev = torch.from_numpy(make_tensor(cfg, threads=min(16, os.cpu_count() or 8))).to("cuda:0")
     ctx = P.Context(max_total_rank=max(m["rank"] for m in models) if one_at_a_time else cfg.max_total_rank,
-                    max_slots=1 if one_at_a_time else cfg.max_slots, flags=P.CTX_REUSE if reuse else 0)
+                    max_slots=1 if one_at_a_time else cfg.max_slots,
+                    flags=(P.CTX_REUSE if reuse else 0) | (P.CTX_TIMING if trace else 0))
     ctx.submit_tensor(T_dev)
     for m in models:
         ctx.enqueue_model(m["init"], m["tol"], m["max_iters"], m["flags"], m["ls_alpha"])
@@ -94,7 +98,31 @@ def run_job(cid: int, T_dev=None, reuse: bool = False, one_at_a_time: bool = Fal
     res = ctx.poll_retired(len(models) + 1)
     assert len(res) == len(models)
     iters = sum(r.iters for r in res)
+    profile = efficiency_profile(ctx.round_log(cap=1 << 20)) if trace else None
     ctx.close()
+    out = job_summary(cfg, reuse, one_at_a_time, models, dt, st, iters)
+    if profile is not None:
+        out["efficiency_profile"] = profile
+    return out
+
+
+def efficiency_profile(log) -> list:
+    """Rounds grouped into tenths of the job's algorithmic MTTKRP flops: device time, mean fused width and the rate
+    flops / time of each tenth (time of whole rounds: MTTKRPs, updates, line search)."""
+    total = sum(r[4] for r in log)
+    out, acc, k = [], 0.0, 0
+    for tenth in range(1, 11):
+        fl = ms = w = 0.0
+        n = 0
+        while k < len(log) and (acc + log[k][4] <= total * tenth / 10.0 * (1 + 1e-12) or tenth == 10):
+            acc += log[k][4]; fl += log[k][4]; ms += log[k][3]; w += log[k][2]; n += 1; k += 1
+        if n:
+            out.append({"upto_fraction_of_flops": tenth / 10.0, "rounds": n, "mean_width": w / n, "ms": ms,
+                        "tflops": fl / (ms * 1e-3) * 1e-12 if ms > 0 else None})
+    return out
+
+
+def job_summary(cfg, reuse, one_at_a_time, models, dt, st, iters) -> dict:
     return {"workload": cfg.name + "_job", "two_step_sweeps": bool(reuse), "one_at_a_time": bool(one_at_a_time), "models": len(models), "seconds": dt, "models_per_s": len(models) / dt,
             "rounds": int(st.rounds), "ms_per_round": dt / max(1, st.rounds) * 1e3, "model_iterations": iters,
             "model_iterations_per_s": iters / dt, "mttkrp_gflops": st.mttkrp_flops / dt * 1e-9}
@@ -383,7 +411,7 @@ def main() -> int:
         print(json.dumps(run_400_models(args.workload, reuse=args.reuse, one_at_a_time=args.one_at_a_time)))
         return 0
     if args.workload.endswith("job"):
-        job = run_job(int(args.workload[3]), reuse=args.reuse, one_at_a_time=args.one_at_a_time)
+        job = run_job(int(args.workload[3]), reuse=args.reuse, one_at_a_time=args.one_at_a_time, trace=args.trace)
         print(json.dumps({"metric": "CP-ALS models completed/sec", "value": job["models_per_s"], "unit": "models/s",
                           "n_gpus": 1, "steps": job["rounds"], "warmup": 0, "ms_per_step": job["ms_per_round"],
                           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",

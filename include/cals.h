@@ -104,6 +104,14 @@ typedef struct {
   int64_t mttkrp_launches[CALS_MAX_MODES];
 } cals_stats;
 
+typedef struct {
+  int64_t round;       /* 0-based index of the main-loop round (Alg. 3)                                        */
+  int32_t n_active;    /* models advanced in this round                                                        */
+  int32_t total_rank;  /* fused width of this round's MTTKRPs                                                  */
+  double ms;           /* device time of the round's kernels (needs CALS_CTX_TIMING, else 0)                   */
+  double mttkrp_flops; /* algorithmic flops of the round's fused MTTKRPs (2 * width * prod(I) each)            */
+} cals_round_record;
+
 /* Create / destroy a context.  `opt` is copied.  Errors: INVALID (null, R* < 1, slots < 0), HIP. */
 int cals_create(cals_ctx** out, const cals_options* opt);
 int cals_destroy(cals_ctx* c);
@@ -175,6 +183,12 @@ int cals_mttkrp_reuse(cals_ctx* c, int32_t total_rank, int64_t ld, const double*
  * into M_dev[n-1] (device, row-major I_n x ld; M_dev[0] is ignored and may be null).  U_dev[n] for all N modes.
  * Errors: STATE (context without CALS_CTX_REUSE or no tensor), INVALID (arguments). */
 int cals_mttkrp_reuse_nd(cals_ctx* c, int32_t total_rank, int64_t ld, const double* const* U_dev, double* const* M_dev);
+
+/* One record per round of the main loop, in order: the segments of the paper's efficiency measurement (Sec. 6,
+ * "Efficiency": time and flop count per CALS iteration).  Copies the records of rounds first_round, first_round+1, ...
+ * (up to `cap`) to `out` (host); *n receives how many.  At most the first 2^20 rounds of a context are recorded.
+ * Synchronises the stream when timing is on.  Errors: INVALID (arguments). */
+int cals_get_round_log(cals_ctx* c, int64_t first_round, cals_round_record* out, int32_t cap, int32_t* n);
 
 /* Counters and timings (see cals_stats).  Synchronises the stream when timing is on. */
 int cals_get_stats(cals_ctx* c, cals_stats* s);

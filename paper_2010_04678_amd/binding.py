@@ -23,7 +23,7 @@ MAX_RANK = 32
 MAX_MODES = 6
 
 EXPORTS = ["cals_create", "cals_destroy", "cals_submit_tensor", "cals_submit_tensor_nd", "cals_enqueue_model", "cals_iterate", "cals_run",
-           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_mttkrp_reuse", "cals_mttkrp_reuse_nd", "cals_get_stats", "cals_yardstick",
+           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_mttkrp_reuse", "cals_mttkrp_reuse_nd", "cals_get_round_log", "cals_get_stats", "cals_yardstick",
            "cals_strerror"]
 
 
@@ -41,6 +41,11 @@ class _Options(C.Structure):
 class _Result(C.Structure):
     _fields_ = [("model_id", C.c_int64), ("rank", C.c_int32), ("iters", C.c_int32), ("status", C.c_int32),
                 ("ls_accepted", C.c_int32), ("fit", C.c_double), ("error", C.c_double)]
+
+
+class _RoundRecord(C.Structure):
+    _fields_ = [("round", C.c_int64), ("n_active", C.c_int32), ("total_rank", C.c_int32), ("ms", C.c_double),
+                ("mttkrp_flops", C.c_double)]
 
 
 class _Stats(C.Structure):
@@ -107,6 +112,7 @@ def load_library() -> C.CDLL:
     L.cals_mttkrp.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(vp), vp]
     L.cals_mttkrp_reuse.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(vp), vp, vp]
     L.cals_mttkrp_reuse_nd.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(vp), C.POINTER(vp)]
+    L.cals_get_round_log.argtypes = [vp, C.c_int64, C.POINTER(_RoundRecord), C.c_int32, C.POINTER(C.c_int32)]
     L.cals_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.cals_yardstick.argtypes = [vp, C.c_int32, vp, C.c_int64, C.c_int32, C.POINTER(C.c_double)]
     L.cals_strerror.argtypes = [C.c_int]
@@ -282,6 +288,14 @@ class Context:
         nbytes = int(buf.numel() * buf.element_size()) if buf is not None else 0
         _check(self._L.cals_yardstick(self._h, int(kind), ptr, C.c_int64(nbytes), int(reps), C.byref(v)), "cals_yardstick")
         return v.value
+
+    # -- cals_get_round_log
+    def round_log(self, first_round: int = 0, cap: int = 1 << 16):
+        """[(round, n_active, total_rank, ms, mttkrp_flops), ...] for rounds first_round, first_round + 1, ..."""
+        buf = (_RoundRecord * cap)()
+        n = C.c_int32(0)
+        _check(self._L.cals_get_round_log(self._h, int(first_round), buf, cap, C.byref(n)), "cals_get_round_log")
+        return [(r.round, r.n_active, r.total_rank, r.ms, r.mttkrp_flops) for r in buf[:n.value]]
 
     # -- cals_get_stats
     def stats(self) -> Stats:

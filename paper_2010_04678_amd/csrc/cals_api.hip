@@ -63,6 +63,7 @@ struct RetiredModel {
 };
 
 struct TimedLaunch { hipEvent_t ev[4]; int mode; bool reduced; };
+struct TimedRound { hipEvent_t ev[2]; size_t index; };   // index into the round log
 
 }  // namespace
 
@@ -130,6 +131,8 @@ struct cals_ctx {
   double mttkrp_ms[kMaxModes] = {}, reduce_ms[kMaxModes] = {};
   int64_t mttkrp_launches[kMaxModes] = {};
   std::vector<TimedLaunch> timed;
+  std::vector<TimedRound> timed_rounds;
+  std::vector<cals_round_record> round_log;   // one record per round (bounded)
   std::vector<hipEvent_t> event_pool;
 };
 
@@ -256,7 +259,7 @@ bool take_events(cals_ctx* c, hipEvent_t (&ev)[4]) {
 }
 
 int drain_timings(cals_ctx* c) {
-  if (c->timed.empty()) return CALS_OK;
+  if (c->timed.empty() && c->timed_rounds.empty()) return CALS_OK;
   HIP_TRY(hipStreamSynchronize(c->stream));
   for (TimedLaunch& t : c->timed) {
     float ms = 0.f;
@@ -265,6 +268,13 @@ int drain_timings(cals_ctx* c) {
     for (int i = 0; i < 4; ++i) c->event_pool.push_back(t.ev[i]);
   }
   c->timed.clear();
+  for (TimedRound& t : c->timed_rounds) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, t.ev[0], t.ev[1]) == hipSuccess) c->round_log[t.index].ms = ms;
+    c->event_pool.push_back(t.ev[0]);
+    c->event_pool.push_back(t.ev[1]);
+  }
+  c->timed_rounds.clear();
   return CALS_OK;
 }
 
@@ -644,6 +654,30 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
   if (n == 0) return CALS_OK;
   CALS_TRY(upload_desc(c));
   const int N = c->nmodes;
+  // one log record per round (the segments of the paper's efficiency measurement), timed by a pair of events
+  constexpr size_t kMaxRoundLog = (size_t)1 << 20;
+  const bool logged = c->round_log.size() < kMaxRoundLog;
+  const double flops_before = c->mttkrp_flops;
+  TimedRound tr{};
+  bool round_timed = false;
+  if (logged) {
+    cals_round_record rec{};
+    rec.round = c->rounds; rec.n_active = n; rec.total_rank = c->total_rank; rec.ms = 0.0; rec.mttkrp_flops = 0.0;
+    c->round_log.push_back(rec);
+    if (c->opt.flags & CALS_CTX_TIMING) {
+      tr.ev[0] = take_event(c);
+      tr.ev[1] = take_event(c);
+      if (tr.ev[0] && tr.ev[1]) {
+        tr.index = c->round_log.size() - 1;
+        round_timed = hipEventRecord(tr.ev[0], c->stream) == hipSuccess;
+      }
+      if (!round_timed) {
+        (void)hipGetLastError();
+        if (tr.ev[0]) c->event_pool.push_back(tr.ev[0]);
+        if (tr.ev[1]) c->event_pool.push_back(tr.ev[1]);
+      }
+    }
+  }
   for (int mode = 0; mode < N; ++mode) {
     if (c->Y && mode > 0) {
       // two-step sweep: modes 2 and 3 come from the tensor contracted with the mode-1 factors just updated
@@ -718,6 +752,12 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
     HIP_TRY(launch_ls_decide(la, c->stream));
     HIP_TRY(launch_ls_apply(la, c->stream));
     if (c->Yprev) HIP_TRY(launch_ls_y_keep(la, c->stream));   // no model took part: nothing accepted, Yprev = Y
+  }
+  if (logged) c->round_log.back().mttkrp_flops = c->mttkrp_flops - flops_before;
+  if (round_timed) {
+    (void)hipEventRecord(tr.ev[1], c->stream);
+    c->timed_rounds.push_back(tr);
+    if (c->timed_rounds.size() > 4096) CALS_TRY(drain_timings(c));
   }
   c->rounds += 1;
   if (!last_of_call && !round_may_retire(c)) {
@@ -816,6 +856,8 @@ int cals_destroy(cals_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (TimedLaunch& t : c->timed)
     for (int i = 0; i < 4; ++i) (void)hipEventDestroy(t.ev[i]);
+  for (TimedRound& t : c->timed_rounds)
+    for (int i = 0; i < 2; ++i) (void)hipEventDestroy(t.ev[i]);
   for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
   for (int n = 0; n < kMaxModes; ++n) {
     (void)hipFree(c->U[n]); (void)hipFree(c->Ualt[n]); (void)hipFree(c->Uprev[n]); (void)hipFree(c->Unew[n]);
@@ -1053,6 +1095,16 @@ int cals_mttkrp_reuse_nd(cals_ctx* c, int32_t total_rank, int64_t ld, const doub
   CALS_TRY(set_device(c));
   CALS_TRY(run_contract_mode1(c, U_dev[0], total_rank, (int)ld));
   for (int n = 1; n < c->nmodes; ++n) CALS_TRY(run_from_contraction(c, n, U_dev, M_dev[n], total_rank, (int)ld));
+  return CALS_OK;
+}
+
+int cals_get_round_log(cals_ctx* c, int64_t first_round, cals_round_record* out, int32_t cap, int32_t* n) {
+  if (!c || !n || cap < 0 || first_round < 0 || (cap > 0 && !out)) return CALS_E_INVALID;
+  CALS_TRY(set_device(c));
+  CALS_TRY(drain_timings(c));
+  int k = 0;
+  for (size_t i = (size_t)first_round; i < c->round_log.size() && k < cap; ++i) out[k++] = c->round_log[i];
+  *n = k;
   return CALS_OK;
 }
 

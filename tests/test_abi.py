@@ -38,6 +38,7 @@ def test_struct_layouts_match_header():
     assert C.sizeof(binding._Result) == 40
     assert binding.MAX_MODES == 6      # CALS_MAX_MODES
     assert C.sizeof(binding._Stats) == 8 * 3 + 4 * 2 + 8 * 2 + 3 * 8 * binding.MAX_MODES
+    assert C.sizeof(binding._RoundRecord) == 32
 
 
 def test_product_package_does_not_import_the_oracle():

@@ -83,6 +83,42 @@ def test_one_slot_runs_the_models_one_after_the_other_with_the_same_results():
             assert np.abs(a - b).max() <= 1e-6 * max(1.0, np.abs(b).max())
 
 
+def test_round_log_follows_the_queue():
+    # one record per round: fused width and number of active models as Alg. 3's fill and removal loops leave them
+    import torch
+    import paper_2010_04678_amd as P
+    dims = (20, 16, 12)
+    T = _lowrank_tensor(dims, 3, 4100)
+    ranks, iters = [4, 3, 5, 2, 6], [3, 5, 2, 4, 3]
+    for flags in (0, P.CTX_TIMING):
+        ctx = P.Context(max_total_rank=10, max_slots=2, flags=flags)
+        ctx.submit_tensor(torch.from_numpy(T).cuda())
+        for k, (r, it) in enumerate(zip(ranks, iters)):
+            ctx.enqueue_model(uniform_factors(dims, r, 4200 + k), tol=-1.0, max_iters=it)
+        ctx.iterate(4)
+        part = ctx.round_log()
+        ctx.run()
+        log = ctx.round_log()
+        st = ctx.stats()
+        assert log[:len(part)] == part or flags               # timings of earlier rounds do not change afterwards
+        assert [r[0] for r in log] == list(range(st.rounds))
+        # replay: two slots, R* = 10: (4,3) -> 3 rounds, model 0 leaves; (3,5): 5+3 > 10 blocks ... computed by hand below
+        active, nxt, left, want = [], 0, list(iters), []
+        while nxt < len(ranks) or active:
+            while nxt < len(ranks) and len(active) < 2 and sum(ranks[k] for k in active) + ranks[nxt] <= 10:
+                active.append(nxt); nxt += 1
+            want.append((len(active), sum(ranks[k] for k in active)))
+            for k in active:
+                left[k] -= 1
+            active = [k for k in active if left[k] > 0]
+        assert [(r[1], r[2]) for r in log] == want
+        assert abs(sum(r[4] for r in log) - st.mttkrp_flops) <= 1e-9 * st.mttkrp_flops
+        assert all(r[4] == 2.0 * 3 * r[2] * 20 * 16 * 12 for r in log)
+        assert all((r[3] > 0.0) == bool(flags) for r in log)
+        assert ctx.round_log(first_round=2, cap=3) == log[2:5]
+        ctx.close()
+
+
 def test_singleton_dimension():
     dims = (1, 9, 7)                                      # a matrix in disguise: mode-1 factors are 1 x R
     T = random_tensor(dims, 3)
