@@ -199,6 +199,36 @@ def test_cp_cals_driver_matches_per_model_oracle_runs():
                 assert (np.linalg.norm(a - b, axis=0) / np.linalg.norm(b, axis=0)).max() <= 1e-6
 
 
+def test_cp_cals_with_modes_reordered_by_length():
+    # reorder_modes: the library gets the tensor with its modes sorted by decreasing length and sweeps them in that
+    # order; the result is the oracle's CP-ALS on that transposed tensor, handed back in the caller's mode order
+    import torch
+    import paper_2010_04678_amd as P
+    dims = (12, 40, 25)                                   # I1, I2, I3 -> order of decreasing length: modes 2, 3, 1
+    T = _lowrank_tensor(dims, 3, 91, noise=0.05)          # numpy shape (I3, I2, I1)
+    inits = [uniform_factors(dims, r, 900 + k) for k, r in enumerate([2, 4, 3, 5])]
+    order = [1, 2, 0]
+    Tp = np.ascontiguousarray(np.transpose(T, [2 - order[j] for j in (2, 1, 0)]))
+    assert Tp.shape == (12, 25, 40)
+    assert Tp[3, 7, 11] == T[7, 11, 3]                    # element (i2, i3, i1) of the new tensor = (i1, i2, i3) of the old
+    for Tin in (T, torch.from_numpy(T).cuda()):
+        out = P.cp_cals(Tin, inits, tol=1e-6, max_iters=40, reorder_modes=True)
+        for k, (res, U, lam) in enumerate(out):
+            ref = O.cp_als(Tp, [inits[k][order[j]] for j in range(3)], tol=1e-6, max_iters=40)
+            assert res.iters == ref["iters"] and res.status == ref["status"] and abs(res.fit - ref["fit"]) <= 1e-8
+            assert [u.shape[0] for u in U] == list(dims)
+            assert np.abs(lam - ref["lam"]).max() <= 1e-6 * np.abs(ref["lam"]).max()
+            for j in range(3):
+                a, b = U[order[j]], ref["U"][j]
+                assert (np.linalg.norm(a - b, axis=0) / np.linalg.norm(b, axis=0)).max() <= 1e-6
+    # already sorted: nothing is copied, same result as without the option
+    T2 = _lowrank_tensor((40, 25, 12), 3, 92, noise=0.05)
+    in2 = [uniform_factors((40, 25, 12), 3, 950)]
+    a = P.cp_cals(T2, in2, tol=-1.0, max_iters=5, reorder_modes=True)[0]
+    b = P.cp_cals(T2, in2, tol=-1.0, max_iters=5)[0]
+    assert a[0].fit == b[0].fit and all(np.array_equal(x, y) for x, y in zip(a[1], b[1]))
+
+
 @pytest.mark.parametrize("seed", list(range(10)))
 def test_seeded_random_queues_match_oracle(seed):
     # random small jobs: dims, ranks, tolerances, iteration caps, R*, slot limits and a mix of plain, non-negative and
