@@ -551,6 +551,8 @@ typedef struct oracle_model {
   double* Aprev[ORACLE_MAX_MODES];     /* LINESEARCH: the point after the previous iteration */
   double* Anew[ORACLE_MAX_MODES];
   int ls_accepted;      /* number of accepted extrapolations */
+  double ls_err_als, ls_err_new; /* the two errors the last line-search decision compared: after the iteration and
+                                    at the extrapolated point (NaN before the first); kept for reporting only */
   double* scratch;
 } oracle_model;
 
@@ -579,6 +581,7 @@ oracle_model* oracle_model_create_nd(int N, const int64_t* dims, int R, const do
   for (int r = 0; r < R; ++r) m->lambda[r] = 1.0;
   m->tol = tol; m->alpha = alpha; m->max_iters = max_iters; m->flags = flags;
   m->fit = 0.0; m->fit_prev = 0.0; m->err = 0.0; m->iters = 0; m->status = ORACLE_RUNNING;
+  m->ls_err_als = NAN; m->ls_err_new = NAN;
   return m;
 }
 
@@ -717,6 +720,7 @@ int oracle_model_iterate(oracle_model* m, const double* T, double normT2) {
         normsq2 += h;
       }
       const double err2 = normT2 + normsq2 - 2.0 * inner2;
+      m->ls_err_als = m->err; m->ls_err_new = err2;
       if (err2 < m->err) {
         for (int n = 0; n < N; ++n) {
           memcpy(m->U[n], m->Anew[n], sizeof(double) * (size_t)(m->I[n] * R));
@@ -755,6 +759,13 @@ void oracle_model_get_nd(const oracle_model* m, double* const* out, double* lamb
   if (iters) *iters = m->iters;
   if (status) *status = m->status;
   if (ls_accepted) *ls_accepted = m->ls_accepted;
+}
+
+/* Reporting only: the two errors that the last line-search decision compared (NaN if there was none yet), so
+ * that a caller can tell how close that decision was. */
+void oracle_model_last_ls_errors(const oracle_model* m, double* err_als, double* err_new) {
+  *err_als = m->ls_err_als;
+  *err_new = m->ls_err_new;
 }
 
 void oracle_model_get(const oracle_model* m, double* U1, double* U2, double* U3, double* lambda, double* fit,

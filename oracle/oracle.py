@@ -53,6 +53,8 @@ def lib() -> C.CDLL:
         L.oracle_model_iterate.restype = C.c_int
         L.oracle_model_iterate.argtypes = [C.c_void_p, _dp, C.c_double]
         L.oracle_model_get.argtypes = [C.c_void_p, _dp, _dp, _dp, _dp, _dp, _dp, _i32p, _i32p, _i32p]
+        L.oracle_model_last_ls_errors.restype = None
+        L.oracle_model_last_ls_errors.argtypes = [C.c_void_p, _dp, _dp]
         L.oracle_cals.restype = C.c_int64
         L.oracle_cals.argtypes = [_dp, _i64p, C.c_int, _i32p, C.POINTER(_dp), _dp, _i32p, _u32p, _dp, C.c_int64,
                                   C.c_int, C.POINTER(_dp), _dp, _dp, _dp, _i32p, _i32p, _i32p, _i32p, C.c_int64]
@@ -210,7 +212,23 @@ class Model:
     def iterate(self) -> int:
         return int(lib().oracle_model_iterate(self.h, _p(self.T), self.normT2))
 
-    def state(self) -> dict:
+    def last_ls_errors(self):
+        """(error after the iteration, error of the extrapolated point) as compared by the last line-search decision;
+        NaNs before the first."""
+        a, b = C.c_double(), C.c_double()
+        lib().oracle_model_last_ls_errors(self.h, C.byref(a), C.byref(b))
+        return a.value, b.value
+
+    def state(self, factors: bool = True) -> dict:
+        if not factors:
+            fit, err = C.c_double(), C.c_double()
+            it, st, acc = C.c_int32(), C.c_int32(), C.c_int32()
+            if self.T.ndim != 3:
+                lib().oracle_model_get_nd(self.h, None, None, C.byref(fit), C.byref(err), C.byref(it), C.byref(st), C.byref(acc))
+            else:
+                lib().oracle_model_get(self.h, None, None, None, None, C.byref(fit), C.byref(err), C.byref(it),
+                                       C.byref(st), C.byref(acc))
+            return dict(fit=fit.value, err=err.value, iters=it.value, status=st.value, ls_accepted=acc.value)
         U = [np.zeros((int(self.dims[n]), self.R), order="F") for n in range(self.T.ndim)]
         lam = np.zeros(self.R)
         fit, err = C.c_double(), C.c_double()

@@ -71,6 +71,7 @@ struct cals_ctx {
   cals_options opt;
   hipStream_t stream = nullptr;
   int num_cus = 0;
+  MttkrpTuning tune;          // development overrides of the launch planner, read once at creation
   bool has_tensor = false;
   int nmodes = 0;             // tensor order N (3 .. kMaxModes)
   int64_t dims[kMaxModes] = {0, 0, 0, 0, 0, 0};
@@ -278,13 +279,18 @@ int drain_timings(cals_ctx* c) {
   return CALS_OK;
 }
 
+// Returns the events of a timed launch that was not enqueued to the pool.
+void give_back_events(cals_ctx* c, hipEvent_t (&ev)[4]) {
+  for (int i = 0; i < 4; ++i) c->event_pool.push_back(ev[i]);
+}
+
 int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld) {
   MttkrpProblem p{};
   CALS_TRY(make_problem(c, mode, U, M, ncols, ld, &p));
   // factor matrices are addressed with 32-bit byte offsets
   // (with room for the rows a workgroup requests past the end of its range)
   if ((int64_t)(p.Ia + 64) * ld * 8 >= (1LL << 32) || (int64_t)(p.Ib + 64) * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
-  MttkrpPlan pl = mttkrp_plan(p, c->num_cus);
+  MttkrpPlan pl = mttkrp_plan(p, c->num_cus, c->tune);
   if (pl.chunk >= (1LL << 31)) return CALS_E_UNSUPPORTED;
   CALS_TRY(ensure_workspace(c, pl.workspace_bytes));
   hipEvent_t* ev = nullptr;
@@ -295,7 +301,14 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int nco
     t.reduced = pl.splits > 1;
     ev = t.ev;
   }
-  HIP_TRY(mttkrp_launch(p, pl, c->workspace, c->stream, ev));
+  {
+    const hipError_t e = mttkrp_launch(p, pl, c->workspace, c->stream, ev);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (ev) give_back_events(c, t.ev);
+      return CALS_E_HIP;
+    }
+  }
   if (ev) {
     c->timed.push_back(t);
     if (c->timed.size() > 2048) CALS_TRY(drain_timings(c));
@@ -324,7 +337,7 @@ int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld, double*
   p.In = (int)rows; p.sm = c->dims[0];
   p.Ia = (int)c->dims[0]; p.sa = 1; p.Ua = U1;
   p.Ib = 1; p.sb = c->dims[0]; p.Ub = c->d_ones;
-  MttkrpPlan pl = mttkrp_plan(p, c->num_cus);
+  MttkrpPlan pl = mttkrp_plan(p, c->num_cus, c->tune);
   if (pl.chunk >= (1LL << 31)) return CALS_E_UNSUPPORTED;
   CALS_TRY(ensure_workspace(c, pl.workspace_bytes));
   hipEvent_t* ev = nullptr;
@@ -335,7 +348,14 @@ int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld, double*
     t.reduced = pl.splits > 1;
     ev = t.ev;
   }
-  HIP_TRY(mttkrp_launch(p, pl, c->workspace, c->stream, ev));
+  {
+    const hipError_t e = mttkrp_launch(p, pl, c->workspace, c->stream, ev);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (ev) give_back_events(c, t.ev);
+      return CALS_E_HIP;
+    }
+  }
   if (ev) {
     c->timed.push_back(t);
     if (c->timed.size() > 2048) CALS_TRY(drain_timings(c));
@@ -843,6 +863,7 @@ int cals_create(cals_ctx** out, const cals_options* opt) {
     rc = CALS_E_HIP;
   }
   if (rc != CALS_OK) { delete c; return rc; }
+  c->tune = mttkrp_tuning_from_env();
   c->num_cus = prop.multiProcessorCount;
   c->ld = (int)((opt->max_total_rank + 15) / 16 * 16);
   c->capacity = opt->max_slots > 0 ? opt->max_slots : (int)std::min<int64_t>(opt->max_total_rank, 4096);

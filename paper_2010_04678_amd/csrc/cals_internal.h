@@ -49,6 +49,19 @@ struct MttkrpPart {  // one kernel launch: `ny` column blocks of `wn` 16-column 
   int wn, ny, col0;
 };
 
+// Development overrides of the launch planner (zero / negative = let the planner decide).  A context reads them
+// once, when it is created, from the environment variables CALS_MTTKRP_WNMAX, _WM, _PERCU, _SPLITS, _CONTIGU,
+// _NOCONTIG, _NOROWPAIR, _NOPAIR; nothing on the launch path looks at the environment.
+struct MttkrpTuning {
+  int wn_max = 0;        // widest column block, in 16-column tiles
+  int wm = 0;            // row tiles per wavefront (1, 2 or 4)
+  int per_cu = 0;        // resident workgroups per compute unit assumed by the cost model
+  int splits = 0;        // split-K factor
+  int contig_u = -1;     // padded-run reads of unaligned tensors: 1 always, 0 never, -1 by width and size
+  bool no_contig = false, no_rowpair = false, no_pair = false;   // switch off a read or production variant
+};
+MttkrpTuning mttkrp_tuning_from_env();
+
 struct MttkrpPlan {
   int wm;          // 16-row MFMA tiles per wavefront
   int ka;          // contraction rows per LDS stage
@@ -58,10 +71,13 @@ struct MttkrpPlan {
   int64_t chunk;   // contraction indices per split
   int mtiles;      // row blocks of 64*wm rows
   size_t workspace_bytes;  // split-K partials: splits * In * ld doubles (0 when splits == 1)
+  int read_mode;   // how the kernel reads the tensor along the contraction (kAffine ... kContig4U)
+  int ia_counted;  // length of the fast contracted index as the kernel counts it (kContig4U: Ia rounded up to 4)
+  int pair;        // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao production
 };
 
-// Chooses tile shape and split-K for a problem on a device with `num_cus` compute units.
-MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus);
+// Chooses tile shape, tensor read mode and split-K for a problem on a device with `num_cus` compute units.
+MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& tune = MttkrpTuning());
 // Enqueues contraction (+ ordered split-K reduction when plan.splits > 1) on `stream`.
 // `workspace` must hold plan.workspace_bytes.  ev[0..3], when non-null, are recorded around the
 // contraction kernel (ev[0], ev[1]) and around the reduction kernel (ev[2], ev[3]).

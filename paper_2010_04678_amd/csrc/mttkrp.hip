@@ -94,21 +94,34 @@ static int env_int(const char* name, int dflt) {
   return (v && *v) ? atoi(v) : dflt;
 }
 
+MttkrpTuning mttkrp_tuning_from_env() {
+  MttkrpTuning t;
+  t.wn_max = env_int("CALS_MTTKRP_WNMAX", 0);
+  t.wm = env_int("CALS_MTTKRP_WM", 0);
+  t.per_cu = env_int("CALS_MTTKRP_PERCU", 0);
+  t.splits = env_int("CALS_MTTKRP_SPLITS", 0);
+  t.contig_u = env_int("CALS_MTTKRP_CONTIGU", -1);
+  t.no_contig = env_int("CALS_MTTKRP_NOCONTIG", 0) != 0;
+  t.no_rowpair = env_int("CALS_MTTKRP_NOROWPAIR", 0) != 0;
+  t.no_pair = env_int("CALS_MTTKRP_NOPAIR", 0) != 0;
+  return t;
+}
+
 // How the kernel reads the tensor along the contraction (see the mode list in mttkrp_kernel.h), and the length of
 // the fast contracted index as the kernel counts it: kContig4U pads every run of Ia contiguous elements to a
 // multiple of 4 positions, so the contraction range it is launched on is Ia_pad * Ib.
-static int tensor_read_mode(const MttkrpProblem& p, int wm, int* ia_counted) {
+static int tensor_read_mode(const MttkrpProblem& p, int wm, const MttkrpTuning& tune, int* ia_counted) {
   const int ka = 16;
   *ia_counted = p.Ia;
   int mode = (p.Ia < ka) ? kGeneral : ((p.sb == (int64_t)p.Ia * p.sa) ? kAffine : kWrap);
-  if (mode != kGeneral && p.sa == 1 && env_int("CALS_MTTKRP_NOCONTIG", 0) == 0) {
+  if (mode != kGeneral && p.sa == 1 && !tune.no_contig) {
     // rows contiguous along the contraction: four consecutive indices per lane, 16-byte loads
     if (p.Ia % 4 == 0 && p.sm % 2 == 0 && p.sb % 2 == 0 && (reinterpret_cast<uintptr_t>(p.T) & 15) == 0) return kContig4;
     // not aligned: the same layout with padded runs and shifted loads.  It pays while the launch is bound by memory
     // (999 x 1001 x 997, modes 2 and 3: 5.9 / 4.9 -> 9.5 / 9.0 TFLOP/s at 8 columns, 32 / 27 -> 39 / 38 at 48) and,
     // on tensors too large for the last-level cache, at every width (62 / 50 -> 64 / 64 at 256); small tensors at
     // larger widths are as fast or faster read element by element
-    const int force = env_int("CALS_MTTKRP_CONTIGU", -1);
+    const int force = tune.contig_u;
     const double tensor_bytes = 8.0 * (double)p.In * (double)p.Ia * (double)p.Ib;
     if (force == 1 || (force != 0 && (p.ncols <= 48 || tensor_bytes > 1073741824.0))) {
       *ia_counted = (p.Ia + 3) / 4 * 4;
@@ -117,7 +130,7 @@ static int tensor_read_mode(const MttkrpProblem& p, int wm, int* ia_counted) {
   }
   // rows contiguous in memory (mode 1), even row count, 16-byte aligned columns: two rows per 16-byte load
   if (mode == kAffine && p.sm == 1 && wm % 2 == 0 && p.In % 2 == 0 && p.sa % 2 == 0 && p.sb % 2 == 0 &&
-      (reinterpret_cast<uintptr_t>(p.T) & 15) == 0 && env_int("CALS_MTTKRP_NOROWPAIR", 0) == 0)
+      (reinterpret_cast<uintptr_t>(p.T) & 15) == 0 && !tune.no_rowpair)
     return kRowPair;
   return mode;
 }
@@ -125,7 +138,7 @@ static int tensor_read_mode(const MttkrpProblem& p, int wm, int* ia_counted) {
 static constexpr int kMaxWn = 14;     // widest column block of a workgroup, in 16-column tiles
 
 // The plan for column blocks of at most `wn_max` tiles of 16 columns, and its modelled time in microseconds.
-static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max, double* cost_us) {
+static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max, const MttkrpTuning& tune, double* cost_us) {
   MttkrpPlan pl{};
   const int ntile16 = (p.ncols + 15) / 16;
   // Column blocks: as few as `wn_max` allows, widths as even as possible.  Blocks of the wider and of
@@ -160,7 +173,7 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
     }
   }
   int ia_counted = p.Ia;
-  (void)tensor_read_mode(p, 2, &ia_counted);
+  (void)tensor_read_mode(p, 2, tune, &ia_counted);
   const int64_t K = (int64_t)ia_counted * p.Ib;
   // the tensor once per column block at the practical read rate (tensors of up to 1 GiB are largely served by the
   // last-level cache: about twice the rate)
@@ -174,7 +187,7 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
     const double mfma4_us = 2.0 * padded4 * (double)K * 16.0 * ntile16 / (78.6e6 * 0.8);
     if (mfma4_us < 0.6 * tensor_us * ny) wm = 4;
   }
-  wm = env_int("CALS_MTTKRP_WM", wm);
+  if (tune.wm > 0) wm = tune.wm;
   if (wm != 1 && wm != 2 && wm != 4) wm = 2;
   if (wm == 4 && wn_top > 7) wm = 2;
   pl.wm = wm;
@@ -188,7 +201,7 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   if (wm == 1 && wn_top >= 12) per_cu = 1;
   const int lds_fit = (int)(160 * 1024 / ((size_t)2 * pl.ka * 16 * wn_top * sizeof(double)));
   if (per_cu > lds_fit) per_cu = lds_fit;
-  per_cu = env_int("CALS_MTTKRP_PERCU", per_cu);
+  if (tune.per_cu > 0) per_cu = tune.per_cu;
   // Split of the contraction range, by a cost model in microseconds.  A stage of a workgroup with t accumulator
   // tiles per wavefront takes t x 4 MFMAs x 64 cycles at about 80 % MFMA utilisation, plus a fixed cost of about 6
   // stages per workgroup.  More than one split adds the partials' way through memory: written once, read once by
@@ -196,7 +209,7 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   // there are 8 or more, so that the XCD-pinned block order gives every XCD the same number of splits; with
   // fewer splits the blocks of a split are spread over the XCDs instead.
   const int64_t max_splits = std::max<int64_t>(1, K / (4 * pl.ka));   // at least two stage pairs per split
-  const int force_splits = env_int("CALS_MTTKRP_SPLITS", 0);
+  const int force_splits = tune.splits;
   const double us_per_tile_stage = 4.0 * 64.0 / 2400.0 / 0.8;          // one accumulator tile, one stage (KA = 16)
   const double panel_us = (double)p.In * p.ncols * 8.0 / 3.0e6;        // one In x ncols panel through memory
   // the practical read rate needs enough loads in flight: two workgroups per CU with four row tiles per wavefront,
@@ -236,23 +249,26 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   pl.splits = (int)splits;
   pl.chunk = chunk;
   pl.workspace_bytes = (pl.splits > 1) ? (size_t)pl.splits * p.In * p.ld * sizeof(double) : 0;
+  pl.read_mode = tensor_read_mode(p, pl.wm, tune, &pl.ia_counted);
+  // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao tile production
+  pl.pair = (p.ld % 2 == 0 && ((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub)) & 15) == 0 && !tune.no_pair) ? 1 : 0;
   *cost_us = best_cost;
   return pl;
 }
 
-MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus) {
+MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& tune) {
   // tuning knob (development aid): widest column block
-  const int forced = env_int("CALS_MTTKRP_WNMAX", 0);
+  const int forced = tune.wn_max;
   double cost = 0.0;
-  if (forced > 0) return plan_for_width(p, num_cus, forced > kMaxWn ? kMaxWn : forced, &cost);
+  if (forced > 0) return plan_for_width(p, num_cus, forced > kMaxWn ? kMaxWn : forced, tune, &cost);
   // Column blocks of up to 14 tiles read the tensor the fewest times; blocks of up to 8 tiles leave room for a second
   // workgroup on the CU, which hides waits and barriers (worth it from about 12 tiles of width on: measured +2 % at
   // 192 columns, +4 % at 320-384, +6-8 % at 512-1024 on 1000^3; +13 % at 420 on 60^5, where the model sees a tie).
   // The modelled time decides -- it charges the extra passes over the tensor -- and near-ties go to the narrow blocks.
-  MttkrpPlan wide = plan_for_width(p, num_cus, kMaxWn, &cost);
+  MttkrpPlan wide = plan_for_width(p, num_cus, kMaxWn, tune, &cost);
   if ((p.ncols + 15) / 16 >= 12) {
     double cost8 = 0.0;
-    const MttkrpPlan narrow = plan_for_width(p, num_cus, 8, &cost8);
+    const MttkrpPlan narrow = plan_for_width(p, num_cus, 8, tune, &cost8);
     if (cost8 <= 1.02 * cost) return narrow;
   }
   return wide;
@@ -263,8 +279,9 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   if (pl.nparts < 1 || pl.nparts > 2) return hipErrorInvalidValue;
   if (p.ncols < 1 || p.ncols > p.ld || p.In < 1 || p.Ia < 1 || p.Ib < 1) return hipErrorInvalidValue;
   if ((int64_t)pl.mtiles * 64 * pl.wm < p.In) return hipErrorInvalidValue;
-  int ia_counted = p.Ia;
-  const int mode = tensor_read_mode(p, pl.wm, &ia_counted);
+  const int ia_counted = pl.ia_counted;
+  const int mode = pl.read_mode;
+  if (mode < kAffine || mode > kContig4U || ia_counted < p.Ia || ia_counted > p.Ia + 3) return hipErrorInvalidValue;
   if (pl.ka != 16) return hipErrorInvalidValue;
   if (pl.chunk % pl.ka != 0 || (int64_t)pl.splits * pl.chunk < (int64_t)ia_counted * p.Ib) return hipErrorInvalidValue;
   if (pl.splits > 1 && !workspace) return hipErrorInvalidValue;
@@ -286,9 +303,7 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   a.ncols = p.ncols; a.ld = p.ld;
   a.mtiles = pl.mtiles; a.splits = pl.splits;
   a.pinned = (pl.splits % 8 == 0) ? 1 : 0;
-  // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao tile production
-  const int pair = (p.ld % 2 == 0 && ((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub)) & 15) == 0 &&
-                    env_int("CALS_MTTKRP_NOPAIR", 0) == 0) ? 1 : 0;
+  const int pair = pl.pair ? 1 : 0;
   if (ev) (void)hipEventRecord(ev[0], stream);
   for (int q = 0; q < pl.nparts; ++q) {
     const Variant* v = find_variant(pl.wm, pl.part[q].wn);

@@ -269,14 +269,17 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   // right after row x of the next tile has been written), so that a miss in L2 never stalls the wavefront.
   double pua[KS][CU][PW], pub[KS][CU][PW];
   const unsigned row_bytes = 8u * (unsigned)a.ld;
-  const __amdgpu_buffer_rsrc_t rsrc_a = factor_rsrc(a.Ua, row_bytes * (unsigned)a.Iav);   // < 2^32 (checked on the host);
-                                                   // kContig4U: rows Iav .. Ia-1 are out of range and read as zeros
+  const __amdgpu_buffer_rsrc_t rsrc_a = factor_rsrc(a.Ua, row_bytes * (unsigned)a.Iav);   // < 2^32 (checked on the host)
   const __amdgpu_buffer_rsrc_t rsrc_b = factor_rsrc(a.Ub, row_bytes * (unsigned)a.Ib);
   // Byte offsets of the factor rows (ia, ib) of this wavefront's row x of the tile to fetch next: uniform over
   // the wavefront, kept in scalar registers and advanced by KA rows per fetch (one compare for the wrap of ia).
   unsigned row_oa[KS], row_ob[KS];
   const unsigned wrap_a = row_bytes * (unsigned)Ia;
   const unsigned last_b = row_bytes * (unsigned)(a.Ib - 1);
+  // kContig4U counts Ia rounded up to 4: the padding rows Iav .. Ia-1 do not exist in Ua.  They only ever meet zero
+  // tensor fragments, so any valid row serves; the offset is clamped to the last one (a scalar row offset is not
+  // covered by the descriptor's range check).
+  const unsigned last_a = row_bytes * (unsigned)(a.Iav - 1);
 #pragma unroll
   for (int x = 0; x < KS; ++x) {
     const int64_t k = kb + wave + 4 * x;
@@ -286,7 +289,7 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   }
 
   auto fetch_row = [&](int x, double (&ua)[CU][PW], double (&ub)[CU][PW]) {
-    const unsigned oa = row_oa[x];
+    const unsigned oa = (MODE == kContig4U && row_oa[x] > last_a) ? last_a : row_oa[x];
     const unsigned ob = row_ob[x] < last_b ? row_ob[x] : last_b;   // rows past the end of K: any valid row
 #pragma unroll
     for (int u = 0; u < CU; ++u) {
@@ -346,7 +349,8 @@ __global__ void __launch_bounds__(256) mttkrp_kernel(MttkrpKernelArgs a) {
   }
   auto fetch_packed = [&](int i) {
     const unsigned ob = pk_ob[i] < last_b ? pk_ob[i] : last_b;
-    const double2 va = buffer_load_f64x2(rsrc_a, pk_oa[i] + pk_col, 0u);
+    const unsigned oa = (MODE == kContig4U && pk_oa[i] > last_a) ? last_a : pk_oa[i];
+    const double2 va = buffer_load_f64x2(rsrc_a, oa + pk_col, 0u);
     const double2 vb = buffer_load_f64x2(rsrc_b, ob + pk_col, 0u);
     pk_ua[i][0] = va.x; pk_ua[i][1] = va.y;
     pk_ub[i][0] = vb.x; pk_ub[i][1] = vb.y;

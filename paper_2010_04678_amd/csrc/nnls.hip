@@ -185,16 +185,10 @@ __global__ void __launch_bounds__(256) nnls_kernel(NnlsArgs a) {
   }
 }
 
-static int env_rows_per_block() {
-  const char* v = getenv("CALS_NNLS_ROWS");
-  const int r = (v && *v) ? atoi(v) : kNnlsRowsPerBlock;
-  return (r >= 4 && r <= 64 && r % 4 == 0) ? r : kNnlsRowsPerBlock;
-}
-
 hipError_t launch_nnls(const NnlsArgs& a0, hipStream_t stream) {
   if (a0.n_models < 1 || a0.In < 1) return hipSuccess;
   NnlsArgs a = a0;
-  a.rows_per_block = env_rows_per_block();
+  a.rows_per_block = kNnlsRowsPerBlock;
   if (a.n_models > 65535) return hipErrorInvalidValue;
   const dim3 grid((a.In + a.rows_per_block - 1) / a.rows_per_block, a.n_models);
   const int rmax = a.max_rank < 1 ? 1 : a.max_rank;

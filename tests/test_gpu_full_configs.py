@@ -2,8 +2,8 @@
 size of the paper's largest dataset with its 400-model queue.
 
 The oracle cannot run these whole in test time, so it checks what it can compute one by one: sampled MTTKRP
-elements (extended precision), sampled models run solo (models are numerically independent of their
-co-residents: the paper's "without numerically affecting any of the invocations"), and properties that hold
+elements (extended precision), sampled models run solo (a model's numbers do not depend on which other models
+share the buffers with it: Sec. 1, contributions; Alg. 2), and properties that hold
 at any size (retirement order replayed from the iteration counts, non-negativity, fit ranges)."""
 import numpy as np
 import pytest

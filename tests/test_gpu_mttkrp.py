@@ -30,7 +30,9 @@ def _abs_scale(T, U, mode):
     return O.mttkrp(np.abs(T), [np.abs(u) for u in U], mode)
 
 
-def _gpu_mttkrp(T, U, pad_to=None, poison=True):
+def _gpu_mttkrp(T, U, pad_to=None, poison=True, rows_after=0):
+    """rows_after: the multi-matrices are views of larger device buffers with that many NaN rows after the last
+    factor row (every read of the kernel stays in mapped memory, and a read past the last row poisons the result)."""
     import paper_2010_04678_amd as P
     torch = _torch()
     dims = tuple(T.shape[::-1])
@@ -41,7 +43,8 @@ def _gpu_mttkrp(T, U, pad_to=None, poison=True):
     ctx.submit_tensor(Td)
     Ud = []
     for n in range(T.ndim):
-        buf = torch.full((dims[n], ld), float("nan") if poison else 0.0, dtype=torch.float64, device="cuda")
+        big = torch.full((dims[n] + rows_after, ld), float("nan") if poison else 0.0, dtype=torch.float64, device="cuda")
+        buf = big[:dims[n]]
         buf[:, :R] = torch.from_numpy(np.ascontiguousarray(U[n])).cuda()
         Ud.append(buf)
     out = []
@@ -126,6 +129,28 @@ def test_mttkrp_first_mode_not_a_multiple_of_four(dims, ranks, signed, force):
         err = np.abs(got[mode - 1] - want)
         assert np.all(np.isfinite(got[mode - 1]))
         assert np.all(err <= TOL * scale + 1e-300), (mode, force, float((err / (scale + 1e-300)).max()))
+
+
+@pytest.mark.parametrize("dims,ranks,pad", [((37, 5, 4), [20] * 4, 3), ((37, 5, 4), [20] * 4, 4), ((255, 7, 3), [5, 9, 20], 3),
+                                            ((255, 7, 3), [5, 9, 20], 2), ((33, 4, 3), [16] * 3, 0), ((19, 6, 5), [2, 3], 1)])
+def test_padded_run_reads_never_touch_rows_after_the_factor(dims, ranks, pad):
+    # padded-run reads count the first mode rounded up to 4; the up to three padding positions have no factor row.
+    # The multi-matrices here are followed in memory by NaN rows: a kernel that fetched a row past the end would turn
+    # every output of that column into NaN (0 * NaN).  Odd and even leading dimensions (one / two columns per lane),
+    # widths below and above 64 columns (packed and per-row production of the Khatri-Rao tile)
+    import os
+    T = random_tensor(dims, 13 + dims[0], signed=True)
+    U = _fused(dims, ranks, 400 + dims[1], signed=True)
+    os.environ["CALS_MTTKRP_CONTIGU"] = "1"
+    try:
+        got = _gpu_mttkrp(T, U, pad_to=sum(ranks) + pad, rows_after=8)
+    finally:
+        del os.environ["CALS_MTTKRP_CONTIGU"]
+    for mode in (1, 2, 3):
+        want = O.mttkrp(T, U, mode)
+        scale = _abs_scale(T, U, mode)
+        assert np.all(np.isfinite(got[mode - 1])), mode
+        assert np.all(np.abs(got[mode - 1] - want) <= TOL * scale + 1e-300), (mode, pad)
 
 
 def test_mttkrp_config2_shape_reduced_depth():

@@ -423,8 +423,43 @@ def test_queue_schedules_computed_by_hand(case):
     assert list(out["iters"]) == mits
 
 
+def test_golden_writer_steps_the_queue_like_the_oracle():
+    # tests/golden/make_full_config_goldens.py steps Alg. 3 round by round over oracle.Model objects (to see every
+    # iteration's fit); on a shrunken configuration 5 (line search, tolerance stops, 8 slots) its loop must give what
+    # oracle.cals gives: order, rounds, iteration counts, statuses, fits -- bit for bit
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("make_full_config_goldens", os.path.join(GOLD, "make_full_config_goldens.py"))
+    G = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(G)
+    from workloads import get_config, make_models, make_tensor
+    cfg = get_config(5)
+    dims = (40, 14, 13)
+    T = make_tensor(cfg, dims=dims)
+    models = make_models(cfg, dims=dims)[::4]
+    for m in models:
+        m["max_iters"] = 60
+    rec, order, rounds, normT2 = G.lockstep(T, models, 60, 8, threads=2)
+    ref = O.cals(T, models, 60, 8)
+    assert order == list(ref["retire_order"]) and rounds == ref["rounds"] and normT2 == O.norm_sq(T)
+    for k in range(len(models)):
+        assert rec[k]["iters"] == ref["iters"][k] and rec[k]["status"] == ref["status"][k]
+        assert rec[k]["fit"] == ref["fit"][k] and rec[k]["err"] == ref["err"][k]
+        assert rec[k]["tol_margin"] >= 0.0 and len(rec[k]["fits"]) == rec[k]["iters"]
+    # fixed iteration counts, everything resident: following a subset gives the same numbers and the same order
+    cfg1 = get_config(1)
+    T1 = make_tensor(cfg1)
+    m1 = make_models(cfg1)
+    for m in m1:
+        m["max_iters"] = 5
+    rec1, order1, rounds1, _ = G.lockstep(T1, m1, cfg1.max_total_rank, 0, threads=2, only={1, 7})
+    ref1 = O.cals(T1, m1, cfg1.max_total_rank, 0)
+    assert order1 == list(ref1["retire_order"]) and rounds1 == 5
+    assert [k for k, r in enumerate(rec1) if r is not None] == [1, 7]
+    assert rec1[7]["fit"] == ref1["fit"][7] and np.array_equal(rec1[7]["U"][0], ref1["U"][7][0])
+
+
 def test_cals_results_do_not_depend_on_co_residents():
-    # "without numerically affecting any of the invocations": lock-step CALS == solo CP-ALS, bit for bit
+    # co-resident models do not influence each other (Sec. 1, contributions; Alg. 2): lock-step CALS == solo CP-ALS, bit for bit
     dims = (9, 8, 7)
     T = random_tensor(dims, 161) + reconstruct(uniform_factors(dims, 2, 162)).transpose(2, 1, 0)
     ranks = [1, 2, 3, 2, 4, 1]
