@@ -76,11 +76,31 @@ def low_rank_tensor_device(dims: Sequence[int], rank: int, seed: int, noise: flo
 
 
 def _collinear_factor(I: int, R: int, c: float, seed: int, stream: int) -> np.ndarray:
-    """I x R matrix with unit columns whose pairwise cosine is exactly c (up to rounding)."""
+    """I x R matrix with unit columns whose pairwise cosine is exactly c (up to rounding): an orthonormal basis
+    (Gram-Schmidt of a seeded Gaussian matrix, each projection applied twice) times the transposed Cholesky factor of
+    c 11^T + (1 - c) I.  Every sum is an exactly rounded one (math.fsum) and every product is element-wise, so the
+    result does not depend on the host's linear-algebra library, thread count or vector width: expected values
+    stored for this tensor stay valid on any machine."""
     g = _rng(seed, stream)
-    Q, _ = np.linalg.qr(g.standard_normal((I, R)))
-    C = np.linalg.cholesky(c * np.ones((R, R)) + (1.0 - c) * np.eye(R))
-    return np.asfortranarray(Q @ C.T)
+    G = g.standard_normal((I, R))
+    Q = np.empty((I, R))
+    for j in range(R):
+        v = G[:, j].copy()
+        for _ in range(2):
+            for i in range(j):
+                v -= math.fsum(Q[:, i] * v) * Q[:, i]
+        Q[:, j] = v / math.sqrt(math.fsum(v * v))
+    L = np.zeros((R, R))                                   # lower Cholesky factor, column by column
+    for j in range(R):
+        d = 1.0 - math.fsum(L[j, k] * L[j, k] for k in range(j))
+        L[j, j] = math.sqrt(d)
+        for i in range(j + 1, R):
+            L[i, j] = (c - math.fsum(L[i, k] * L[j, k] for k in range(j))) / L[j, j]
+    out = np.zeros((I, R), order="F")
+    for j in range(R):
+        for k in range(j + 1):                             # column j = sum_k Q[:, k] L[j, k], k ascending
+            out[:, j] += Q[:, k] * L[j, k]
+    return out
 
 
 def _eem_factors(dims: Sequence[int], R: int, seed: int) -> List[np.ndarray]:
@@ -111,10 +131,18 @@ def true_factors(cfg: WorkloadConfig) -> List[np.ndarray]:
 
 
 def _low_rank_norm_sq(F: Sequence[np.ndarray]) -> float:
-    G = np.ones((F[0].shape[1],) * 2)
+    """Squared norm of the tensor with factors F, from the factor Gramians; exactly rounded sums (math.fsum) of
+    element-wise products, so the value is the same on every machine."""
+    R = F[0].shape[1]
+    G = np.ones((R, R))
     for U in F:
-        G = G * (U.T @ U)
-    return float(G.sum())
+        for r in range(R):
+            for q in range(r, R):
+                g = math.fsum(U[:, r] * U[:, q])
+                G[r, q] *= g
+                if q != r:
+                    G[q, r] *= g
+    return math.fsum(G.reshape(-1))
 
 
 def make_tensor(cfg: WorkloadConfig, dims: Sequence[int] | None = None, threads: int = 8,
@@ -122,6 +150,9 @@ def make_tensor(cfg: WorkloadConfig, dims: Sequence[int] | None = None, threads:
     """Low-rank tensor plus Gaussian noise of std eta * rms(noise-free tensor), slab by slab.
 
     `dims` may shrink the configuration (same recipe, smaller tensor) for quick tests.
+    Every slab is accumulated component by component with element-wise products and sums (no library matrix
+    product, whose order of additions depends on the host), so the tensor is bit-identical on every machine and
+    expected values stored for it stay valid.
     """
     if dims is not None and tuple(dims) != tuple(cfg.dims):
         cfg = WorkloadConfig(**{**cfg.__dict__, "dims": tuple(int(d) for d in dims)})
@@ -131,10 +162,16 @@ def make_tensor(cfg: WorkloadConfig, dims: Sequence[int] | None = None, threads:
     T = out if out is not None else np.empty((I3, I2, I1), dtype=np.float64)
     assert T.shape == (I3, I2, I1) and T.dtype == np.float64 and T.flags.c_contiguous
     At = np.ascontiguousarray(A.T)
+    R = At.shape[0]
 
     def slab(i3: int) -> None:
         S = T[i3]
-        np.matmul(B * C[i3][None, :], At, out=S)
+        Bc = B * C[i3][None, :]
+        np.multiply(Bc[:, 0:1], At[0:1, :], out=S)         # S[i2, i1] = sum_r B[i2,r] C[i3,r] A[i1,r], r ascending
+        tmp = np.empty_like(S)
+        for r in range(1, R):
+            np.multiply(Bc[:, r:r + 1], At[r:r + 1, :], out=tmp)
+            S += tmp
         if sigma > 0.0:
             S += sigma * _rng(cfg.noise_seed, i3 + 16).standard_normal((I2, I1))
         if cfg.clip_at_zero:
