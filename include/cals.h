@@ -41,6 +41,7 @@ extern "C" {
 #define CALS_E_HIP (-4)         /* a HIP runtime call failed                                    */
 #define CALS_E_UNSUPPORTED (-5) /* valid request the library does not implement                 */
 #define CALS_E_NOTFOUND (-6)    /* unknown model id / model not finished                        */
+#define CALS_E_TOOLARGE (-7)    /* cals_mttkrp_noalloc: the launch needs more scratch than the fixed buffer holds */
 
 /* model status (cals_result.status) */
 #define CALS_RUNNING 0
@@ -167,6 +168,21 @@ int cals_get_factors(cals_ctx* c, int64_t model_id, double* const* U, double* la
  * the context's Khatri-Rao buffers).  Uses the context's tensor, stream and workspace. */
 int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const* U_dev,
                 double* M_dev);
+
+/* cals_mttkrp for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same launch plan and therefore bit-identical results; the
+ * split-K partial panels go to a fixed device array of CALS_NOALLOC_SCRATCH_BYTES that every GPU the library runs
+ * on holds from the first cals_create on it until the process ends (instead of the context's workspace, which
+ * cals_mttkrp grows on demand).  The call allocates and frees nothing on host-visible HIP paths: no device memory,
+ * no events (such a launch is never timed, whatever CALS_CTX_TIMING says).  A launch whose partials
+ * (split count x I_mode x ld doubles, the split count chosen by the planner) exceed the array returns
+ * CALS_E_TOOLARGE and enqueues nothing.  All calls on one GPU share that GPU's array: it keeps the previous call's
+ * contents (every element a launch reads it has written first, so nothing needs clearing), and calls that overlap on
+ * one GPU -- other streams, other contexts, other threads -- race; serialise them.
+ * Other errors as cals_mttkrp. */
+#define CALS_NOALLOC_SCRATCH_BYTES (256u << 20)
+int cals_mttkrp_noalloc(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const* U_dev,
+                        double* M_dev);
 
 /* The two MTTKRPs of a two-step sweep alone, for parity runs (needs CALS_CTX_REUSE): Y from U_dev[0], then
  *   M2[i2,c] = sum_i3 Y[(i2,i3),c] * U3[i3,c]   and   M3[i3,c] = sum_i2 Y[(i2,i3),c] * U2[i2,c],   c < total_rank,

@@ -19,11 +19,13 @@ FLAG_NONNEG, FLAG_LINESEARCH = 1, 2
 CTX_TIMING = 1
 CTX_REUSE = 2
 RUNNING, CONVERGED, MAX_ITERS, NUMERICAL = 0, 1, 2, 3
+E_TOOLARGE = -7
+NOALLOC_SCRATCH_BYTES = 256 << 20
 MAX_RANK = 32
 MAX_MODES = 6
 
 EXPORTS = ["cals_create", "cals_destroy", "cals_submit_tensor", "cals_submit_tensor_nd", "cals_enqueue_model", "cals_iterate", "cals_run",
-           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_mttkrp_reuse", "cals_mttkrp_reuse_nd", "cals_get_round_log", "cals_get_stats", "cals_yardstick",
+           "cals_poll_retired", "cals_get_factors", "cals_mttkrp", "cals_mttkrp_noalloc", "cals_mttkrp_reuse", "cals_mttkrp_reuse_nd", "cals_get_round_log", "cals_get_stats", "cals_yardstick",
            "cals_strerror"]
 
 
@@ -110,6 +112,7 @@ def load_library() -> C.CDLL:
     L.cals_poll_retired.argtypes = [vp, C.POINTER(_Result), C.c_int32, C.POINTER(C.c_int32)]
     L.cals_get_factors.argtypes = [vp, C.c_int64, C.POINTER(vp), vp]
     L.cals_mttkrp.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(vp), vp]
+    L.cals_mttkrp_noalloc.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(vp), vp]
     L.cals_mttkrp_reuse.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(vp), vp, vp]
     L.cals_mttkrp_reuse_nd.argtypes = [vp, C.c_int32, C.c_int64, C.POINTER(vp), C.POINTER(vp)]
     L.cals_get_round_log.argtypes = [vp, C.c_int64, C.POINTER(_RoundRecord), C.c_int32, C.POINTER(C.c_int32)]
@@ -231,9 +234,10 @@ class Context:
         return U, lam
 
     # -- cals_mttkrp
-    def mttkrp(self, mode: int, U_dev: Sequence, M_dev, total_rank: Optional[int] = None) -> None:
+    def mttkrp(self, mode: int, U_dev: Sequence, M_dev, total_rank: Optional[int] = None, no_alloc: bool = False) -> None:
         """U_dev[n]: torch CUDA float64 (I_n, ld) row-major multi-matrices (the one for `mode` may be None);
-        M_dev: (I_mode, ld), columns [0,total_rank) overwritten."""
+        M_dev: (I_mode, ld), columns [0,total_rank) overwritten.  no_alloc: through cals_mttkrp_noalloc (fixed
+        scratch array, nothing allocated)."""
         ld = int(M_dev.shape[1])
         tr = int(total_rank) if total_rank is not None else ld
         ptrs = (C.c_void_p * len(self.dims))()
@@ -245,6 +249,9 @@ class Context:
             assert u.is_cuda and u.is_contiguous() and u.shape[1] == ld and u.shape[0] == self.dims[n]
             ptrs[n] = u.data_ptr()
         assert M_dev.is_cuda and M_dev.is_contiguous() and M_dev.shape[0] == self.dims[mode - 1]
+        if no_alloc:
+            _check(self._L.cals_mttkrp_noalloc(self._h, int(mode), tr, ld, ptrs, M_dev.data_ptr()), "cals_mttkrp_noalloc")
+            return
         _check(self._L.cals_mttkrp(self._h, int(mode), tr, ld, ptrs, M_dev.data_ptr()), "cals_mttkrp")
 
     # -- cals_mttkrp_reuse

@@ -9,6 +9,7 @@
 #include <cstring>
 #include <deque>
 #include <map>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -65,6 +66,36 @@ struct RetiredModel {
 struct TimedLaunch { hipEvent_t ev[4]; int mode; bool reduced; };
 struct TimedRound { hipEvent_t ev[2]; size_t index; };   // index into the round log
 
+constexpr int kMaxDevices = 64;
+constexpr size_t kScratchDoubles = CALS_NOALLOC_SCRATCH_BYTES / sizeof(double);
+
+}  // namespace
+
+// Fixed scratch of the entry point that allocates nothing (cals_mttkrp_noalloc): the split-K partial panels of one
+// fused MTTKRP.  Every GPU the library runs on holds its own copy of this array, at its own address, until the
+// process ends.  In host code the name below is only a handle: the device address comes from hipGetSymbolAddress,
+// taken once per device in cals_create with that device current, and only that address is ever handed to kernels.
+static __device__ __align__(256) double scratch[kScratchDoubles];
+
+namespace {
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};   // per device: the device address of `scratch`
+
+// The address of this device's copy of the scratch array (the device must be current).
+int scratch_address(int device, double** out) {
+  if (device < 0 || device >= kMaxDevices) return CALS_E_INVALID;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    double* ptr = nullptr;
+    if (hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return CALS_E_HIP;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return CALS_OK;
+}
 }  // namespace
 
 struct cals_ctx {
@@ -72,6 +103,7 @@ struct cals_ctx {
   hipStream_t stream = nullptr;
   int num_cus = 0;
   MttkrpTuning tune;          // development overrides of the launch planner, read once at creation
+  double* scratch_dev = nullptr;   // this device's copy of the fixed scratch array (cals_mttkrp_noalloc)
   bool has_tensor = false;
   int nmodes = 0;             // tensor order N (3 .. kMaxModes)
   int64_t dims[kMaxModes] = {0, 0, 0, 0, 0, 0};
@@ -284,7 +316,10 @@ void give_back_events(cals_ctx* c, hipEvent_t (&ev)[4]) {
   for (int i = 0; i < 4; ++i) c->event_pool.push_back(ev[i]);
 }
 
-int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld) {
+// no_alloc: the split-K partials go to the fixed scratch array instead of the context's workspace, nothing is
+// allocated (no workspace growth, no events: such a launch is not timed), and a launch whose partials do not fit
+// is refused.
+int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld, bool no_alloc = false) {
   MttkrpProblem p{};
   CALS_TRY(make_problem(c, mode, U, M, ncols, ld, &p));
   // factor matrices are addressed with 32-bit byte offsets
@@ -292,17 +327,25 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int nco
   if ((int64_t)(p.Ia + 64) * ld * 8 >= (1LL << 32) || (int64_t)(p.Ib + 64) * ld * 8 >= (1LL << 32)) return CALS_E_UNSUPPORTED;
   MttkrpPlan pl = mttkrp_plan(p, c->num_cus, c->tune);
   if (pl.chunk >= (1LL << 31)) return CALS_E_UNSUPPORTED;
-  CALS_TRY(ensure_workspace(c, pl.workspace_bytes));
+  double* partials = nullptr;
+  if (no_alloc) {
+    if (pl.workspace_bytes > CALS_NOALLOC_SCRATCH_BYTES) return CALS_E_TOOLARGE;
+    if (!c->scratch_dev) return CALS_E_STATE;
+    partials = c->scratch_dev;
+  } else {
+    CALS_TRY(ensure_workspace(c, pl.workspace_bytes));
+    partials = c->workspace;
+  }
   hipEvent_t* ev = nullptr;
   TimedLaunch t{};
-  if (c->opt.flags & CALS_CTX_TIMING) {
+  if ((c->opt.flags & CALS_CTX_TIMING) && !no_alloc) {
     if (!take_events(c, t.ev)) return CALS_E_HIP;
     t.mode = mode;
     t.reduced = pl.splits > 1;
     ev = t.ev;
   }
   {
-    const hipError_t e = mttkrp_launch(p, pl, c->workspace, c->stream, ev);
+    const hipError_t e = mttkrp_launch(p, pl, partials, c->stream, ev);
     if (e != hipSuccess) {
       (void)hipGetLastError();
       if (ev) give_back_events(c, t.ev);
@@ -851,6 +894,7 @@ int cals_create(cals_ctx** out, const cals_options* opt) {
   if (!out || !opt) return CALS_E_INVALID;
   *out = nullptr;
   if (opt->max_total_rank < 1 || opt->max_total_rank > (1 << 20) || opt->max_slots < 0) return CALS_E_INVALID;
+  if (opt->device < 0 || opt->device >= kMaxDevices) return CALS_E_INVALID;
   cals_ctx* c = new (std::nothrow) cals_ctx();
   if (!c) return CALS_E_NOMEM;
   c->opt = *opt;
@@ -862,6 +906,7 @@ int cals_create(cals_ctx** out, const cals_options* opt) {
     (void)hipGetLastError();
     rc = CALS_E_HIP;
   }
+  if (rc == CALS_OK) rc = scratch_address(opt->device, &c->scratch_dev);   // the device is current here
   if (rc != CALS_OK) { delete c; return rc; }
   c->tune = mttkrp_tuning_from_env();
   c->num_cus = prop.multiProcessorCount;
@@ -1092,6 +1137,18 @@ int cals_mttkrp(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const
   return run_mttkrp(c, mode - 1, U_dev, M_dev, total_rank, (int)ld);
 }
 
+int cals_mttkrp_noalloc(cals_ctx* c, int32_t mode, int32_t total_rank, int64_t ld, const double* const* U_dev,
+                        double* M_dev) {
+  if (!c || !U_dev || !M_dev) return CALS_E_INVALID;
+  if (!c->has_tensor) return CALS_E_STATE;
+  if (mode < 1 || mode > c->nmodes || total_rank < 1 || ld < total_rank || ld >= (1LL << 24)) return CALS_E_INVALID;
+  if (c->nmodes > 3 && ld > c->ld) return CALS_E_INVALID;
+  for (int n = 0; n < c->nmodes; ++n)
+    if (n != mode - 1 && !U_dev[n]) return CALS_E_INVALID;
+  CALS_TRY(set_device(c));
+  return run_mttkrp(c, mode - 1, U_dev, M_dev, total_rank, (int)ld, /*no_alloc=*/true);
+}
+
 int cals_mttkrp_reuse(cals_ctx* c, int32_t total_rank, int64_t ld, const double* const U_dev[3], double* M2_dev,
                       double* M3_dev) {
   if (!c || !U_dev || !M2_dev || !M3_dev) return CALS_E_INVALID;
@@ -1176,6 +1233,7 @@ const char* cals_strerror(int code) {
     case CALS_E_HIP: return "HIP runtime error";
     case CALS_E_UNSUPPORTED: return "not supported";
     case CALS_E_NOTFOUND: return "model not found or not finished";
+    case CALS_E_TOOLARGE: return "launch needs more scratch than the fixed buffer of the no-allocation entry point holds";
     default: return "unknown error code";
   }
 }
