@@ -103,6 +103,8 @@ typedef struct {
   double mttkrp_ms[CALS_MAX_MODES];  /* per mode, main contraction kernel only (needs CALS_CTX_TIMING) */
   double reduce_ms[CALS_MAX_MODES];  /* per mode, split-K reduction kernel (needs CALS_CTX_TIMING)     */
   int64_t mttkrp_launches[CALS_MAX_MODES];
+  int64_t mttkrp_rows_launches;      /* of those, how many the planner gave to the rows kernel (short modes, few column
+                                        groups) rather than the tile kernel                                         */
 } cals_stats;
 
 typedef struct {

@@ -54,7 +54,7 @@ class _Stats(C.Structure):
     _fields_ = [("rounds", C.c_int64), ("models_retired", C.c_int64), ("models_queued", C.c_int64),
                 ("n_active", C.c_int32), ("total_rank", C.c_int32), ("tensor_norm_sq", C.c_double),
                 ("mttkrp_flops", C.c_double), ("mttkrp_ms", C.c_double * MAX_MODES), ("reduce_ms", C.c_double * MAX_MODES),
-                ("mttkrp_launches", C.c_int64 * MAX_MODES)]
+                ("mttkrp_launches", C.c_int64 * MAX_MODES), ("mttkrp_rows_launches", C.c_int64)]
 
 
 @dataclass
@@ -80,6 +80,7 @@ class Stats:
     mttkrp_ms: List[float]
     reduce_ms: List[float]
     mttkrp_launches: List[int]
+    mttkrp_rows_launches: int = 0
 
 
 _lib: Optional[C.CDLL] = None
@@ -309,7 +310,7 @@ class Context:
         s = _Stats()
         _check(self._L.cals_get_stats(self._h, C.byref(s)), "cals_get_stats")
         return Stats(s.rounds, s.models_retired, s.models_queued, s.n_active, s.total_rank, s.tensor_norm_sq,
-                     s.mttkrp_flops, list(s.mttkrp_ms), list(s.reduce_ms), list(s.mttkrp_launches))
+                     s.mttkrp_flops, list(s.mttkrp_ms), list(s.reduce_ms), list(s.mttkrp_launches), int(s.mttkrp_rows_launches))
 
 
 # ---- convenience driver in the spirit of the paper's cp_cals interface (Sec. 5, "interfaces") -----------------

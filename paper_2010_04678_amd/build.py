@@ -14,10 +14,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcals_hip.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["mttkrp_wm1.hip", "mttkrp_wm2.hip", "mttkrp_wm4.hip", "mttkrp.hip", "update.hip", "linesearch.hip", "nnls.hip", "yardstick.hip", "reuse.hip", "krp.hip", "cals_api.hip"]
+SOURCES = ["mttkrp_wm1.hip", "mttkrp_wm2.hip", "mttkrp_wm4.hip", "mttkrp_rows_a.hip", "mttkrp_rows_b.hip", "mttkrp.hip", "update.hip", "linesearch.hip", "nnls.hip", "yardstick.hip", "reuse.hip", "krp.hip", "cals_api.hip"]
 # yardstick.hip: its MFMA-only loop must keep the accumulators in place (VGPR form of the matrix instructions;
 # otherwise the compiler copies them between register files every iteration and the probe measures the copies)
-EXTRA_FLAGS = {"yardstick.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+# mttkrp_rows_*.hip: with the default (accumulation-register) form of the matrix instructions the register allocator
+# keeps these kernels' accumulators in vector registers and copies all of them in and out around every row tile; in
+# the vector-register form they stay in place (the variants are sized to fit 256 vector registers)
+EXTRA_FLAGS = {"yardstick.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+               "mttkrp_rows_a.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+               "mttkrp_rows_b.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -163,6 +163,7 @@ struct cals_ctx {
   double mttkrp_flops = 0.0;
   double mttkrp_ms[kMaxModes] = {}, reduce_ms[kMaxModes] = {};
   int64_t mttkrp_launches[kMaxModes] = {};
+  int64_t mttkrp_rows_launches = 0;
   std::vector<TimedLaunch> timed;
   std::vector<TimedRound> timed_rounds;
   std::vector<cals_round_record> round_log;   // one record per round (bounded)
@@ -360,6 +361,7 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int nco
   for (int n = 0; n < c->nmodes; ++n) elems *= (double)c->dims[n];
   c->mttkrp_flops += 2.0 * ncols * elems;
   c->mttkrp_launches[mode] += 1;
+  if (pl.kind == 1) c->mttkrp_rows_launches += 1;
   return CALS_OK;
 }
 
@@ -1202,6 +1204,7 @@ int cals_get_stats(cals_ctx* c, cals_stats* s) {
     s->reduce_ms[n] = c->reduce_ms[n];
     s->mttkrp_launches[n] = c->mttkrp_launches[n];
   }
+  s->mttkrp_rows_launches = c->mttkrp_rows_launches;
   return CALS_OK;
 }
 

@@ -59,6 +59,8 @@ struct MttkrpTuning {
   int splits = 0;        // split-K factor
   int contig_u = -1;     // padded-run reads of unaligned tensors: 1 always, 0 never, -1 by width and size
   bool no_contig = false, no_rowpair = false, no_pair = false;   // switch off a read or production variant
+  int kernel = 0;        // 1: the tile kernel only; 2: the rows kernel wherever it is eligible; 0: by modelled time
+  int rows_wmb = 0, rows_wnb = 0, rows_nsb = 0;   // rows kernel: variant and workgroup-level split count
 };
 MttkrpTuning mttkrp_tuning_from_env();
 
@@ -74,6 +76,16 @@ struct MttkrpPlan {
   int read_mode;   // how the kernel reads the tensor along the contraction (kAffine ... kContig4U)
   int ia_counted;  // length of the fast contracted index as the kernel counts it (kContig4U: Ia rounded up to 4)
   int pair;        // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao production
+  // kind 1: the rows kernel (every wavefront holds all row tiles of a row block; see mttkrp_rows_kernel.h).  Then
+  // `chunk` counts contraction indices per WAVEFRONT, `splits` the partial panels (workgroup-level splits), and
+  // wm / ka / nparts / part / mtiles / read_mode / ia_counted / pair are unused.
+  int kind;        // 0: tile kernel, 1: rows kernel
+  int rows_wmb, rows_wnb;   // kernel variant: row tiles and column tiles per wavefront
+  int rows_amode;           // kRowsContig / kRowsPair
+  int rows_tpb;             // row tiles per row block (<= rows_wmb)
+  int rows_nrb, rows_ncg;   // row blocks, column groups
+  int rows_rem;             // column groups with rows_wnb tiles (the others have one fewer)
+  double cost_us;           // modelled time
 };
 
 // Chooses tile shape, tensor read mode and split-K for a problem on a device with `num_cus` compute units.

@@ -4,6 +4,7 @@
 #include <cstdlib>
 
 #include "mttkrp_kernel.h"
+#include "mttkrp_rows_kernel.h"
 
 namespace cals {
 
@@ -86,6 +87,16 @@ hipError_t mttkrp_init() {
         if (e != hipSuccess) return e;
       }
   }
+  for (int grp = 0; grp < 2; ++grp) {
+    int n = 0;
+    const RowsVariant* t = grp == 0 ? mttkrp_rows_variants_a(&n) : mttkrp_rows_variants_b(&n);
+    for (int i = 0; i < n; ++i)
+      for (int m = 0; m < 2; ++m) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(t[i].fn[m]), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)rows_lds_bytes(t[i].wmb, t[i].wnb));
+        if (e != hipSuccess) return e;
+      }
+  }
   return hipSuccess;
 }
 
@@ -104,6 +115,10 @@ MttkrpTuning mttkrp_tuning_from_env() {
   t.no_contig = env_int("CALS_MTTKRP_NOCONTIG", 0) != 0;
   t.no_rowpair = env_int("CALS_MTTKRP_NOROWPAIR", 0) != 0;
   t.no_pair = env_int("CALS_MTTKRP_NOPAIR", 0) != 0;
+  t.kernel = env_int("CALS_MTTKRP_KERNEL", 0);
+  t.rows_wmb = env_int("CALS_MTTKRP_ROWS_WMB", 0);
+  t.rows_wnb = env_int("CALS_MTTKRP_ROWS_WNB", 0);
+  t.rows_nsb = env_int("CALS_MTTKRP_ROWS_NSB", 0);
   return t;
 }
 
@@ -252,11 +267,13 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   pl.read_mode = tensor_read_mode(p, pl.wm, tune, &pl.ia_counted);
   // factor rows 16-byte aligned: two columns per lane in the Khatri-Rao tile production
   pl.pair = (p.ld % 2 == 0 && ((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub)) & 15) == 0 && !tune.no_pair) ? 1 : 0;
+  pl.kind = 0;
+  pl.cost_us = best_cost;
   *cost_us = best_cost;
   return pl;
 }
 
-MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& tune) {
+static MttkrpPlan tile_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& tune) {
   // tuning knob (development aid): widest column block
   const int forced = tune.wn_max;
   double cost = 0.0;
@@ -274,10 +291,163 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& 
   return wide;
 }
 
+// ---------------------------------------------------------------------------------------------------
+// rows kernel: plan and launch
+// ---------------------------------------------------------------------------------------------------
+
+static const RowsVariant* find_rows_variant(int wmb, int wnb) {
+  for (int grp = 0; grp < 2; ++grp) {
+    int n = 0;
+    const RowsVariant* t = grp == 0 ? mttkrp_rows_variants_a(&n) : mttkrp_rows_variants_b(&n);
+    for (int i = 0; i < n; ++i)
+      if (t[i].wmb == wmb && t[i].wnb == wnb) return &t[i];
+  }
+  return nullptr;
+}
+
+// Which way the rows kernel can read this problem's tensor, or -1 when it cannot take the problem at all: it needs a
+// fast contracted index whose length is a multiple of 4 and at least a stage (a lane's 4 indices then share the slow
+// index), 16-byte aligned factor rows, and one of its two aligned tensor layouts.
+static int rows_read_mode(const MttkrpProblem& p, const MttkrpTuning& tune) {
+  if (p.Ia < 16 || p.Ia % 4 != 0 || p.ld % 2 != 0 || tune.no_pair) return -1;
+  if (((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub) | reinterpret_cast<uintptr_t>(p.T)) & 15) != 0) return -1;
+  if (p.sa == 1 && p.sm % 2 == 0 && p.sb % 2 == 0 && !tune.no_contig) return kRowsContig;
+  if (p.sm == 1 && p.sb == (int64_t)p.Ia * p.sa && p.In % 2 == 0 && p.sa % 2 == 0 && !tune.no_rowpair) return kRowsPair;
+  return -1;
+}
+
+// The best launch of the rows kernel for the problem by modelled time, or false when no variant can take it.
+static bool rows_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& tune, MttkrpPlan* out) {
+  const int amode = rows_read_mode(p, tune);
+  if (amode < 0) return false;
+  const int64_t K = (int64_t)p.Ia * p.Ib;
+  const int tiles_m = (p.In + 15) / 16, tiles_n = (p.ncols + 15) / 16;
+  const double tensor_bytes = (double)p.In * (double)K * 8.0;
+  const double hbm_us = tensor_bytes / (tensor_bytes > 1073741824.0 ? 5.5e6 : 11.0e6);
+  const double panel_us = (double)p.In * p.ncols * 8.0 / 3.0e6;
+  bool found = false;
+  MttkrpPlan best{};
+  best.cost_us = 1e300;
+  for (int grp = 0; grp < 2; ++grp) {
+    int nv = 0;
+    const RowsVariant* tab = grp == 0 ? mttkrp_rows_variants_a(&nv) : mttkrp_rows_variants_b(&nv);
+    for (int i = 0; i < nv; ++i) {
+      const int wmb = tab[i].wmb, wnb = tab[i].wnb;
+      if ((tune.rows_wmb > 0 && wmb != tune.rows_wmb) || (tune.rows_wnb > 0 && wnb != tune.rows_wnb)) continue;
+      // row blocks: as few as the variant allows, of equal size (an even number of tiles when rows are read in pairs
+      // and there is more than one block)
+      int nrb = (tiles_m + wmb - 1) / wmb, tpb = 0;
+      for (;; ++nrb) {
+        tpb = (tiles_m + nrb - 1) / nrb;
+        if (amode == kRowsPair && nrb > 1 && tpb % 2 == 1) ++tpb;
+        if (tpb <= wmb) break;
+      }
+      nrb = (tiles_m + tpb - 1) / tpb;
+      // Measured against the tile kernel (200^3, 300^3, 300x300x40, 4000x200x50, 64x512x512 and others, widths 64 to
+      // 640): this kernel wins, by 3 to 20 %, where one row block holds the whole mode and the column groups are
+      // few -- every group reads the whole tensor, and beyond about eight groups the caches behind L1 no longer keep
+      // up (and run-to-run times scatter by a factor of 1.5).  Elsewhere it is left to the tile kernel, unless forced.
+      // A row block that leaves more than a sixth of the variant's row tiles empty (they are computed all the same:
+      // 40 rows in a 4-tile variant) and launches of a few microseconds (32^3) also go to the tile kernel.
+      const bool forced = tune.kernel == 2;
+      if (!forced && (nrb != 1 || 6 * tiles_m < 5 * wmb || (double)p.In * (double)K * p.ncols < 1.0e8)) continue;
+      // column groups of wnb tiles, some of wnb - 1
+      const int ncg = (tiles_n + wnb - 1) / wnb;
+      const int fewer = ncg * wnb - tiles_n;
+      if (fewer > ncg || (wnb == 1 && fewer > 0)) continue;
+      if (!forced && ncg > 8) continue;
+      // Workgroup-level splits by modelled time.  A wavefront's stage is wmb x wnb accumulator tiles (all of the
+      // variant's row tiles are computed, live or not) x 4 matrix instructions of 64 cycles, at the 72 % of the issue
+      // rate these kernels reach; a workgroup pays a fixed 3 us (first loads, the exchange of the four accumulator
+      // sets, stores); compute units take workgroups in rounds.  Every column group reads the whole tensor: measured,
+      // the groups together draw about 6 TB/s from the caches behind L1 (200^3 at 7 groups: 81 us; 4000x200x50,
+      // mode 2, at 4 / 11 / 20 groups: 195 / 709 / 1168 us), which bounds wide launches.
+      const double stage_us = (double)wmb * wnb * 4.0 * 64.0 / 2400.0 / 0.72;
+      const int64_t max_nsb = std::max<int64_t>(1, K / 128);     // at least two stages per wavefront
+      for (int64_t nsb = 1; nsb <= std::min<int64_t>(max_nsb, 2048); nsb = nsb < 16 ? nsb + 1 : nsb + (nsb < 64 ? 2 : 8)) {
+        if (tune.rows_nsb > 0 && nsb != tune.rows_nsb && nsb != 1) continue;
+        if (tune.rows_nsb > 0 && nsb == 1 && tune.rows_nsb != 1) continue;
+        int64_t chunk = (K + 4 * nsb - 1) / (4 * nsb);
+        chunk = (chunk + 15) / 16 * 16;
+        const int64_t nsb_eff = (K + 4 * chunk - 1) / (4 * chunk);
+        const int64_t blocks = (int64_t)nrb * ncg * nsb_eff;
+        const int64_t rounds = (blocks + num_cus - 1) / num_cus;
+        const double compute_us = (double)rounds * ((double)(chunk / 16) * stage_us + 3.0);
+        const double mem_us = std::max(hbm_us, (double)ncg * tensor_bytes / 6.0e6);
+        double cost = std::max(compute_us, mem_us);
+        if (nsb_eff > 1) cost += (double)(nsb_eff + 1) * panel_us + 3.0;
+        if (cost < best.cost_us) {
+          found = true;
+          best.cost_us = cost;
+          best.kind = 1;
+          best.rows_wmb = wmb; best.rows_wnb = wnb; best.rows_amode = amode; best.rows_tpb = tpb;
+          best.rows_nrb = nrb; best.rows_ncg = ncg; best.rows_rem = ncg - fewer;
+          best.splits = (int)nsb_eff;
+          best.chunk = chunk;
+          best.workspace_bytes = nsb_eff > 1 ? (size_t)nsb_eff * p.In * p.ld * sizeof(double) : 0;
+        }
+      }
+    }
+  }
+  if (found) *out = best;
+  return found;
+}
+
+MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& tune) {
+  MttkrpPlan tiles = tile_plan(p, num_cus, tune);
+  if (tune.kernel == 1) return tiles;
+  MttkrpPlan rows{};
+  if (!rows_plan(p, num_cus, tune, &rows)) return tiles;
+  if (tune.kernel == 2) return rows;
+  return rows.cost_us < 0.95 * tiles.cost_us ? rows : tiles;    // the tile kernel's model is the better calibrated one
+}
+
+static hipError_t rows_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* workspace, hipStream_t stream,
+                              hipEvent_t* ev) {
+  const RowsVariant* v = find_rows_variant(pl.rows_wmb, pl.rows_wnb);
+  if (!v || (pl.rows_amode != kRowsContig && pl.rows_amode != kRowsPair)) return hipErrorInvalidValue;
+  // what the kernel assumes about its operands
+  if (p.Ia < 16 || p.Ia % 4 != 0 || p.ld % 2 != 0) return hipErrorInvalidValue;
+  if (((reinterpret_cast<uintptr_t>(p.Ua) | reinterpret_cast<uintptr_t>(p.Ub) | reinterpret_cast<uintptr_t>(p.T)) & 15) != 0) return hipErrorInvalidValue;
+  if (pl.rows_amode == kRowsContig && (p.sa != 1 || p.sm % 2 != 0 || p.sb % 2 != 0)) return hipErrorInvalidValue;
+  if (pl.rows_amode == kRowsPair && (p.sm != 1 || p.sb != (int64_t)p.Ia * p.sa || p.In % 2 != 0 || p.sa % 2 != 0)) return hipErrorInvalidValue;
+  const int64_t K = (int64_t)p.Ia * p.Ib;
+  if (pl.rows_tpb < 1 || pl.rows_tpb > pl.rows_wmb || (int64_t)pl.rows_nrb * pl.rows_tpb * 16 < p.In) return hipErrorInvalidValue;
+  if (pl.rows_amode == kRowsPair && pl.rows_nrb > 1 && pl.rows_tpb % 2 != 0) return hipErrorInvalidValue;
+  if (pl.rows_rem < 0 || pl.rows_rem > pl.rows_ncg || (pl.rows_wnb == 1 && pl.rows_rem != pl.rows_ncg)) return hipErrorInvalidValue;
+  if (16 * (pl.rows_rem * pl.rows_wnb + (pl.rows_ncg - pl.rows_rem) * (pl.rows_wnb - 1)) < p.ncols) return hipErrorInvalidValue;
+  if (pl.chunk < 16 || pl.chunk % 16 != 0 || pl.chunk >= (1LL << 31) || (int64_t)pl.splits * 4 * pl.chunk < K) return hipErrorInvalidValue;
+  if (pl.splits > 1 && !workspace) return hipErrorInvalidValue;
+  RowsKernelArgs a;
+  a.T = p.T; a.Ua = p.Ua; a.Ub = p.Ub;
+  a.P = pl.splits > 1 ? workspace : p.M;
+  a.sm = p.sm; a.sa = p.sa; a.sb = p.sb;
+  a.K = K; a.chunk = pl.chunk;
+  a.pstride = (int64_t)p.In * p.ld;
+  a.In = p.In; a.Ia = p.Ia; a.Ib = p.Ib; a.ncols = p.ncols; a.ld = p.ld;
+  a.nrb = pl.rows_nrb; a.ncg = pl.rows_ncg; a.nsb = pl.splits; a.tpb = pl.rows_tpb;
+  a.col0 = 0; a.rem = pl.rows_rem;
+  const int64_t groups = ((int64_t)a.nrb * a.nsb + 7) / 8 * 8;
+  const int64_t nblocks = groups * a.ncg;
+  if (nblocks >= (1LL << 31)) return hipErrorInvalidValue;
+  if (ev) (void)hipEventRecord(ev[0], stream);
+  hipLaunchKernelGGL(v->fn[pl.rows_amode], dim3((unsigned)nblocks), dim3(256), rows_lds_bytes(v->wmb, v->wnb), stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (ev) (void)hipEventRecord(ev[1], stream);
+  if (pl.splits > 1) {
+    if (ev) (void)hipEventRecord(ev[2], stream);
+    e = launch_splitk_reduce(workspace, p.M, a.pstride, p.ld, p.ncols, pl.splits, stream);
+    if (ev) (void)hipEventRecord(ev[3], stream);
+  }
+  return e;
+}
+
 hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* workspace, hipStream_t stream,
                          hipEvent_t* ev) {
-  if (pl.nparts < 1 || pl.nparts > 2) return hipErrorInvalidValue;
   if (p.ncols < 1 || p.ncols > p.ld || p.In < 1 || p.Ia < 1 || p.Ib < 1) return hipErrorInvalidValue;
+  if (pl.kind == 1) return rows_launch(p, pl, workspace, stream, ev);
+  if (pl.nparts < 1 || pl.nparts > 2) return hipErrorInvalidValue;
   if ((int64_t)pl.mtiles * 64 * pl.wm < p.In) return hipErrorInvalidValue;
   const int ia_counted = pl.ia_counted;
   const int mode = pl.read_mode;

@@ -8,13 +8,51 @@
 
 using namespace cals;
 
-static int check(int In, int Ia, int Ib, int ncols, int cus) {
+// The rows kernel's launch (kind 1): what its launcher checks and its kernel assumes.
+static const char* check_rows(const MttkrpProblem& p, const MttkrpPlan& pl) {
+  const long long K = (long long)p.Ia * p.Ib;
+  if (p.Ia < 16 || p.Ia % 4 != 0 || p.ld % 2 != 0) return "rows: operand shape";
+  if (pl.rows_amode != 0 && pl.rows_amode != 1) return "rows: read mode";
+  if (pl.rows_amode == 0 && (p.sa != 1 || p.sm % 2 != 0 || p.sb % 2 != 0)) return "rows: contiguous read mode on the wrong strides";
+  if (pl.rows_amode == 1 && (p.sm != 1 || p.sb != (long long)p.Ia * p.sa || p.In % 2 != 0 || p.sa % 2 != 0)) return "rows: pair read mode on the wrong strides";
+  if (pl.rows_wmb * pl.rows_wnb > 26 || pl.rows_wnb < 1) return "rows: variant";
+  if (pl.rows_tpb < 1 || pl.rows_tpb > pl.rows_wmb) return "rows: tiles per block";
+  if ((long long)pl.rows_nrb * pl.rows_tpb * 16 < p.In || (long long)(pl.rows_nrb - 1) * pl.rows_tpb * 16 >= p.In) return "rows: row blocks";
+  if (pl.rows_amode == 1 && pl.rows_nrb > 1 && pl.rows_tpb % 2 != 0) return "rows: odd row block in pair mode";
+  if (pl.rows_rem < 0 || pl.rows_rem > pl.rows_ncg || (pl.rows_wnb == 1 && pl.rows_rem != pl.rows_ncg)) return "rows: column groups";
+  if (16 * (pl.rows_rem * pl.rows_wnb + (pl.rows_ncg - pl.rows_rem) * (pl.rows_wnb - 1)) != 16 * ((p.ncols + 15) / 16)) return "rows: column groups must cover exactly the tiles";
+  if (pl.chunk < 16 || pl.chunk % 16 != 0 || pl.splits < 1) return "rows: chunk";
+  if ((long long)pl.splits * 4 * pl.chunk < K || (long long)(pl.splits - 1) * 4 * pl.chunk >= K) return "rows: splits cover K exactly once";
+  if (pl.workspace_bytes != (pl.splits > 1 ? (size_t)pl.splits * p.In * p.ld * sizeof(double) : 0)) return "rows: workspace";
+  return nullptr;
+}
+
+static long g_rows_plans = 0;
+
+// `layout`: 0 = no strides given (the tile kernel's plan only), 1 = output mode 1 of an In x Ia x Ib tensor (rows
+// contiguous), 2 = an output mode whose fast contracted index is the tensor's first (contraction contiguous).
+static int check(int In, int Ia, int Ib, int ncols, int cus, int layout = 0) {
   MttkrpProblem p{};
   p.In = In; p.Ia = Ia; p.Ib = Ib; p.ncols = ncols; p.ld = (ncols + 15) / 16 * 16;
+  if (layout == 1) { p.sm = 1; p.sa = In; p.sb = (long long)In * Ia; }
+  if (layout == 2) { p.sa = 1; p.sm = Ia; p.sb = (long long)Ia * In; }
   const MttkrpPlan pl = mttkrp_plan(p, cus);
-  const long long K = (long long)Ia * Ib;
+  // the contraction range as the tile kernel counts it (padded runs for unaligned contiguous reads)
+  const long long K = (long long)(pl.kind == 0 ? pl.ia_counted : Ia) * Ib;
   const char* why = nullptr;
-  if (pl.wm != 1 && pl.wm != 2 && pl.wm != 4) why = "wm";
+  if (pl.kind == 0 && (pl.ia_counted < Ia || pl.ia_counted > Ia + 3)) why = "counted length of the fast index";
+  if (pl.kind == 1) {
+    ++g_rows_plans;
+    why = check_rows(p, pl);
+    if (why) {
+      printf("FAIL %s: In=%d Ia=%d Ib=%d ncols=%d cus=%d layout=%d -> wmb=%d wnb=%d tpb=%d nrb=%d ncg=%d rem=%d splits=%d chunk=%lld\n", why, In, Ia, Ib,
+             ncols, cus, layout, pl.rows_wmb, pl.rows_wnb, pl.rows_tpb, pl.rows_nrb, pl.rows_ncg, pl.rows_rem, pl.splits, (long long)pl.chunk);
+      return 1;
+    }
+    return 0;
+  }
+  if (why) {}
+  else if (pl.wm != 1 && pl.wm != 2 && pl.wm != 4) why = "wm";
   else if (pl.ka != 16) why = "ka";
   else if (pl.nparts < 1 || pl.nparts > 2) why = "nparts";
   else if ((long long)pl.mtiles * 64 * pl.wm < In || (long long)(pl.mtiles - 1) * 64 * pl.wm >= In) why = "mtiles";
@@ -51,8 +89,10 @@ int main() {
         for (int c = 0; c < nd; ++c) {
           if ((long long)dims[a] * dims[b] * dims[c] > (1LL << 36)) continue;
           for (int w = 0; w < nw; ++w) {
-            if (check(dims[a], dims[b], dims[c], widths[w], cus)) return 1;
-            ++count;
+            for (int layout = 0; layout < 3; ++layout) {
+              if (check(dims[a], dims[b], dims[c], widths[w], cus, layout)) return 1;
+              ++count;
+            }
           }
         }
   // pseudo-random shapes
@@ -61,9 +101,10 @@ int main() {
   for (int i = 0; i < 20000; ++i) {
     const int In = 1 + (int)(next() % 5000), Ia = 1 + (int)(next() % 3000), Ib = 1 + (int)(next() % 3000);
     const int nc = 1 + (int)(next() % 1500);
-    if (check(In, Ia, Ib, nc, 256)) return 1;
+    if (check(In, Ia, Ib, nc, 256, i % 3)) return 1;
     ++count;
   }
-  printf("ok %ld\n", count);
+  if (g_rows_plans < 1000) { printf("FAIL: the sweep reached the rows kernel's planner only %ld times\n", g_rows_plans); return 1; }
+  printf("ok %ld (%ld of them rows-kernel plans)\n", count, g_rows_plans);
   return 0;
 }

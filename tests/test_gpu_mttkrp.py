@@ -30,7 +30,7 @@ def _abs_scale(T, U, mode):
     return O.mttkrp(np.abs(T), [np.abs(u) for u in U], mode)
 
 
-def _gpu_mttkrp(T, U, pad_to=None, poison=True, rows_after=0):
+def _gpu_mttkrp(T, U, pad_to=None, poison=True, rows_after=0, stats_out=None):
     """rows_after: the multi-matrices are views of larger device buffers with that many NaN rows after the last
     factor row (every read of the kernel stays in mapped memory, and a read past the last row poisons the result)."""
     import paper_2010_04678_amd as P
@@ -55,6 +55,8 @@ def _gpu_mttkrp(T, U, pad_to=None, poison=True, rows_after=0):
         Mh = M.cpu().numpy()
         assert np.all(Mh[:, R:] == 777.0), "columns beyond total_rank must not be touched"
         out.append(Mh[:, :R])
+    if stats_out is not None:
+        stats_out.append(ctx.stats())
     ctx.close()
     return out
 
@@ -151,6 +153,67 @@ def test_padded_run_reads_never_touch_rows_after_the_factor(dims, ranks, pad):
         scale = _abs_scale(T, U, mode)
         assert np.all(np.isfinite(got[mode - 1])), mode
         assert np.all(np.abs(got[mode - 1] - want) <= TOL * scale + 1e-300), (mode, pad)
+
+
+ROWS_CASES = [
+    # dims, ranks, signed: fast contracted index a multiple of 4 and at least 16 in every mode
+    ((200, 24, 20), list(range(1, 11)) * 2, False),      # configuration 2's row count and width (110): 13 row tiles
+    ((48, 40, 36), [2, 7, 1, 12, 9], True),              # 3 row tiles, 2 column tiles
+    ((52, 200, 16), [20] * 6 + [8], True),               # 52 rows (mode 1), 200 (mode 2), 16 (mode 3); 128 columns
+    ((180, 20, 16), [16, 20, 20, 8], False),             # 12 of 13 row tiles live
+    ((100, 36, 20), [13, 20, 7], True),                  # 7 row tiles
+    ((300, 20, 16), [20] * 5 + [3], False),              # several row blocks when a small variant is forced
+    ((64, 32, 28), [1], True),                           # a single column
+]
+
+
+@pytest.mark.parametrize("variant", [(4, 2), (4, 4), (7, 2), (13, 2)])
+@pytest.mark.parametrize("dims,ranks,signed", ROWS_CASES)
+def test_mttkrp_rows_kernel_every_variant(dims, ranks, signed, variant):
+    # the second kernel of the fused MTTKRP (a wavefront holds all row tiles of its row block, lanes form their own
+    # Khatri-Rao values, four wavefronts share the contraction range): every variant forced in turn (development
+    # knobs of the launch planner, read when the context is created), both tensor read modes (mode 1: row pairs; modes
+    # 2 and 3: contiguous contraction), full and ragged tiles, one and several row blocks and column groups
+    import os
+    T = random_tensor(dims, 17 + dims[0], signed=signed)
+    U = _fused(dims, ranks, 500 + dims[1], signed=signed)
+    R = sum(ranks)
+    env = {"CALS_MTTKRP_KERNEL": "2", "CALS_MTTKRP_ROWS_WMB": str(variant[0]), "CALS_MTTKRP_ROWS_WNB": str(variant[1])}
+    for pad in (R + (R % 2), (R + 15) // 16 * 16 + 16):
+        st = []
+        os.environ.update(env)
+        try:
+            got = _gpu_mttkrp(T, U, pad_to=pad, stats_out=st)
+        finally:
+            for k in env:
+                del os.environ[k]
+        # a variant takes a width when its column tiles split into groups of wnb and wnb - 1 tiles
+        nt, wnb = (R + 15) // 16, variant[1]
+        groups = (nt + wnb - 1) // wnb
+        takes = groups * wnb - nt <= groups
+        assert st[0].mttkrp_rows_launches == (3 if takes else 0), "every mode of these shapes suits the rows kernel"
+        for mode in (1, 2, 3):
+            want = O.mttkrp(T, U, mode)
+            scale = _abs_scale(T, U, mode)
+            assert np.all(np.isfinite(got[mode - 1]))
+            assert np.all(np.abs(got[mode - 1] - want) <= TOL * scale + 1e-300), (mode, variant, pad)
+
+
+def test_mttkrp_rows_kernel_is_chosen_for_short_modes_and_is_bit_reproducible():
+    # left to itself the planner gives the 200-row modes of a configuration-2-shaped problem to the rows kernel
+    # (one row block, four column groups); its four-wavefront exchange and the split-K reduction add in a fixed order
+    cfg = get_config(2)
+    dims = (200, 200, 40)
+    T = make_tensor(cfg, dims)
+    U = _fused(dims, cfg.ranks, 300)
+    st = []
+    a = _gpu_mttkrp(T, U, pad_to=112, stats_out=st)
+    b = _gpu_mttkrp(T, U, pad_to=112)
+    assert st[0].mttkrp_rows_launches >= 2
+    for mode in range(3):
+        assert np.array_equal(a[mode], b[mode])
+        want = O.mttkrp(T, U, mode + 1)
+        assert np.all(np.abs(a[mode] - want) <= TOL * np.abs(want))
 
 
 def test_mttkrp_config2_shape_reduced_depth():
