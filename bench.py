@@ -10,19 +10,14 @@ resident in HBM before the timed region.  Prints ONE JSON line.
 
 `--workload cfgNjob` (N = 1..5) instead runs the configuration's whole job once as it is specified (queue, slots,
 tolerances, iteration caps, non-negativity, line search) and reports models completed per second; --steps and
---warmup do not apply; with `--one-at-a-time` the same job runs with a single slot (plain CP-ALS, model after model,
-through the same kernels: the baseline of the paper's speed-up experiments).  The default run appends the cfg5 job (the queue workload) under "jobs" and the order-4
-workload (see below) under "order_n".
+--warmup do not apply.  The default run appends, to the one JSON line: the whole jobs of configurations 1, 2, 3 and 5
+under "jobs"; the fused MTTKRP alone at each of those configurations' full width under "mttkrp_by_config"; a
+low-width point on the cfg4 tensor (16 columns: the bandwidth-bound regime) under "low_width"; the order-4 workload
+(see below) under "order_n"; and the oracle's side of every figure under "cpu_baseline".
 
 `--workload sweepW1000` / `sweepW300` / `sweepWodd` time the fused MTTKRP alone, all three modes, over fused widths
 1..1024 on the cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1) / a 999 x 1001 x 997 tensor.  `--yardstick` prints the device's compute-unit
 count and clock and its practical peaks (back-to-back fp64 MFMA; streaming read of a 4 GiB buffer).
-
-`--workload e400_100` / `e400_200` / `e400_300` run the workload of the paper's efficiency and GPU experiments (400
-models of ranks 1..20, 50 fixed iterations, m^3 tensor) and quote the paper's own total next to the result.
-
-`--workload real_405` / `real_255` / `real_299`: the paper's real-application experiment (400 models, tolerance 1e-6, at
-most 1000 iterations) on a seeded fluorescence-shaped tensor of the size of each of its three datasets.
 
 `--workload order4` / `order5` time the path on a tensor of order 4 (180^4) / 5 (60^5), 8.4 and 6.2 GB: the fused
 MTTKRP alone per mode at several widths (contraction kernel by events, and the whole call including the explicit
@@ -55,9 +50,6 @@ def parse():
     ap.add_argument("--no-jobs", action="store_true", help="skip the whole-job runs appended to the default line")
     ap.add_argument("--reuse", action="store_true",
                     help="two-step sweeps (CALS_CTX_REUSE): modes 2 and 3 from the tensor contracted with the mode-1 factors")
-    ap.add_argument("--one-at-a-time", action="store_true",
-                    help="job workloads: one slot, i.e. plain CP-ALS model after model through the same kernels "
-                         "(the comparison of the paper's speed-up experiments, Sec. 6)")
     ap.add_argument("--trace", action="store_true",
                     help="job workloads: time every round on the device (events) and report the MTTKRP rate over "
                          "tenths of the job's flops (the paper's efficiency-over-the-run measurement, Sec. 6)")
@@ -73,7 +65,7 @@ def workload(name: str):
     return get_config(cid)
 
 
-def run_job(cid: int, T_dev=None, reuse: bool = False, one_at_a_time: bool = False, trace: bool = False) -> dict:
+def run_job(cid: int, T_dev=None, reuse: bool = False, trace: bool = False) -> dict:
     """One whole job of configuration `cid`, as specified: every model enqueued with its own tolerance, iteration
     cap and flags; rounds until the queue and the slots are empty.  Tensor resident in HBM before the clock starts."""
     import torch
@@ -83,8 +75,7 @@ def run_job(cid: int, T_dev=None, reuse: bool = False, one_at_a_time: bool = Fal
     models = make_models(cfg)
     if T_dev is None:
         T_dev = torch.from_numpy(make_tensor(cfg, threads=min(16, os.cpu_count() or 8))).to("cuda:0")
-    ctx = P.Context(max_total_rank=max(m["rank"] for m in models) if one_at_a_time else cfg.max_total_rank,
-                    max_slots=1 if one_at_a_time else cfg.max_slots,
+    ctx = P.Context(max_total_rank=cfg.max_total_rank, max_slots=cfg.max_slots,
                     flags=(P.CTX_REUSE if reuse else 0) | (P.CTX_TIMING if trace else 0))
     ctx.submit_tensor(T_dev)
     for m in models:
@@ -100,7 +91,7 @@ def run_job(cid: int, T_dev=None, reuse: bool = False, one_at_a_time: bool = Fal
     iters = sum(r.iters for r in res)
     profile = efficiency_profile(ctx.round_log(cap=1 << 20)) if trace else None
     ctx.close()
-    out = job_summary(cfg, reuse, one_at_a_time, models, dt, st, iters)
+    out = job_summary(cfg, reuse, models, dt, st, iters)
     if profile is not None:
         out["efficiency_profile"] = profile
     return out
@@ -122,8 +113,8 @@ def efficiency_profile(log) -> list:
     return out
 
 
-def job_summary(cfg, reuse, one_at_a_time, models, dt, st, iters) -> dict:
-    return {"workload": cfg.name + "_job", "two_step_sweeps": bool(reuse), "one_at_a_time": bool(one_at_a_time), "models": len(models), "seconds": dt, "models_per_s": len(models) / dt,
+def job_summary(cfg, reuse, models, dt, st, iters) -> dict:
+    return {"workload": cfg.name + "_job", "two_step_sweeps": bool(reuse), "models": len(models), "seconds": dt, "ms": dt * 1e3, "models_per_s": len(models) / dt,
             "rounds": int(st.rounds), "ms_per_round": dt / max(1, st.rounds) * 1e3, "model_iterations": iters,
             "model_iterations_per_s": iters / dt, "mttkrp_gflops": st.mttkrp_flops / dt * 1e-9}
 
@@ -176,88 +167,65 @@ def run_sweep(which: str, reps: int = 3) -> dict:
             "reps": reps, "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "peak_hbm_gbs": PEAK_HBM_GBS, "rows": rows}
 
 
+def mttkrp_alone(T_dev, dims, width: int, reps: int = 5) -> dict:
+    """The fused MTTKRP alone (cals_mttkrp) at `width` columns of random factors on the resident tensor, all three
+    modes: per mode the contraction and the split-K reduction from HIP events inside the library (launch stream)."""
+    import torch
+    import paper_2010_04678_amd as P
+    ctx = P.Context(max_total_rank=width, flags=P.CTX_TIMING)
+    ctx.submit_tensor(T_dev)
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(7)
+    ld = (width + 15) // 16 * 16
+    U = [torch.rand((d, ld), dtype=torch.float64, device="cuda:0", generator=g) for d in dims]
+    contraction, reduce = [], []
+    for mode in (1, 2, 3):
+        M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda:0")
+        ctx.mttkrp(mode, U, M, total_rank=width)
+        torch.cuda.synchronize()
+        s0 = ctx.stats()
+        for _ in range(reps):
+            ctx.mttkrp(mode, U, M, total_rank=width)
+        s1 = ctx.stats()
+        contraction.append((s1.mttkrp_ms[mode - 1] - s0.mttkrp_ms[mode - 1]) / reps)
+        reduce.append((s1.reduce_ms[mode - 1] - s0.reduce_ms[mode - 1]) / reps)
+    st = ctx.stats()
+    ctx.close()
+    I1, I2, I3 = dims
+    flops = 2.0 * width * I1 * I2 * I3
+    nbytes = 8.0 * I1 * I2 * I3 + 8.0 * width * (I1 + I2 + I3)
+    total = [c + r for c, r in zip(contraction, reduce)]
+    return {"width": width, "contraction_ms": contraction, "reduce_ms": reduce,
+            "tflops": [flops / (t * 1e-3) * 1e-12 for t in total],
+            "frac_of_mfma_peak": [flops / (t * 1e-3) * 1e-12 / PEAK_FP64_MFMA_TFLOPS for t in total],
+            "algorithmic_gb_per_s": [nbytes / (t * 1e-3) * 1e-9 for t in total],
+            "rows_kernel_launches": int(st.mttkrp_rows_launches), "launches": int(sum(st.mttkrp_launches))}
+
+
+def config_leg(cid: int) -> dict:
+    """Configuration `cid` on its own tensor: the whole job as specified, and the fused MTTKRP alone at the width the
+    job starts with (all models that fit the buffers side by side)."""
+    import torch
+    from workloads import get_config, make_models, make_tensor
+    cfg = get_config(cid)
+    T_dev = torch.from_numpy(make_tensor(cfg, threads=min(16, os.cpu_count() or 8))).to("cuda:0")
+    models = make_models(cfg)
+    width, n = 0, 0
+    for m in models:
+        if width + m["rank"] > cfg.max_total_rank or (cfg.max_slots and n >= cfg.max_slots):
+            break
+        width += m["rank"]
+        n += 1
+    out = {"job": run_job(cid, T_dev=T_dev), "mttkrp": dict(workload=cfg.name, dims=list(cfg.dims), **mttkrp_alone(T_dev, tuple(cfg.dims), width))}
+    if cid == 5:      # the queue job also with two-step sweeps, and the fused MTTKRP at the full buffer width
+        out["job_two_step"] = run_job(cid, T_dev=T_dev, reuse=True)
+        out["mttkrp_full_buffer"] = dict(workload=cfg.name, dims=list(cfg.dims), **mttkrp_alone(T_dev, tuple(cfg.dims), cfg.max_total_rank))
+    del T_dev
+    torch.cuda.empty_cache()
+    return out
+
+
 ORDER_N = {"order4": (180,) * 4, "order5": (60,) * 5}
-
-# The paper's efficiency and GPU experiments (Sec. 6, "Efficiency" and "GPU"): 400 models, 20 of each rank 1..20
-# (total rank 4200), exactly 50 iterations, on m x m x m tensors.  Its published totals for CALS with one V100 and 24
-# CPU threads (context only: other hardware, factor updates on the CPU): seconds for the whole job.
-PAPER_400_MODELS = {"e400_100": (100, 3.7), "e400_200": (200, 6.9), "e400_300": (300, 11.7)}
-
-
-# The paper's real-application experiment (Sec. 6, "Real Applications"): 400 models (20 per rank 1..20), tolerance
-# 1e-6, at most 1000 iterations, on three fluorescence datasets; the datasets are not available here, so a seeded
-# fluorescence-shaped tensor of the same size stands in (the recipe of configuration 3).  Published totals for CALS
-# with one V100 and 24 CPU threads, in seconds (context only).
-PAPER_REAL = {"real_405": ((405, 136, 19), 24.0), "real_255": ((255, 286, 25), 21.0), "real_299": ((299, 301, 41), 30.0)}
-
-
-def run_real_shape(which: str, reuse: bool = False, one_at_a_time: bool = False) -> dict:
-    import torch
-    import paper_2010_04678_amd as P
-    from workloads import get_config, make_tensor, uniform_factors
-    dims, paper_s = PAPER_REAL[which]
-    T = torch.from_numpy(make_tensor(get_config(3), dims=dims)).to("cuda:0")
-    ranks = [r for r in range(1, 21) for _ in range(20)]
-    rstar = max(ranks) if one_at_a_time else sum(ranks)
-    ctx = P.Context(max_total_rank=rstar, max_slots=1 if one_at_a_time else 0, flags=P.CTX_REUSE if reuse else 0)
-    ctx.submit_tensor(T)
-    for k, r in enumerate(ranks):
-        ctx.enqueue_model(uniform_factors(dims, r, 50000 + dims[0] * 1000 + k), tol=1e-6, max_iters=1000)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ctx.run()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    st = ctx.stats()
-    res = ctx.poll_retired(len(ranks) + 1)
-    assert len(res) == len(ranks)
-    iters = sum(r.iters for r in res)
-    ctx.close()
-    return {"metric": "CP-ALS models completed/sec", "value": len(ranks) / dt, "unit": "models/s", "n_gpus": 1,
-            "steps": int(st.rounds), "warmup": 0, "ms_per_step": dt / max(1, st.rounds) * 1e3, "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic (stand-in for the paper's dataset of this size)",
-            "config": {"workload": which, "dims": list(dims), "models": len(ranks), "total_rank": sum(ranks), "tol": 1e-6,
-                       "max_iters": 1000, "two_step_sweeps": bool(reuse), "one_at_a_time": bool(one_at_a_time)},
-            "seconds": dt, "model_iterations": iters, "converged": sum(1 for r in res if r.status == P.CONVERGED),
-            "mttkrp_gflops": st.mttkrp_flops / dt * 1e-9,
-            "paper": {"seconds": paper_s, "models_per_s": len(ranks) / paper_s, "data": "the real dataset (different content, so different iteration counts)",
-                      "hardware": "one V100 + 24 threads of a Xeon Platinum 8160 (CALS with CUDA offload of the MTTKRP)"}}
-
-
-def run_400_models(which: str, reuse: bool = False, one_at_a_time: bool = False) -> dict:
-    """400 concurrent models (ranks 1..20, 20 starting points each, R* = 4200), 50 fixed iterations, on a seeded
-    m^3 tensor (rank-10 Uniform[0,1) factors + 5 % noise, generated on the device)."""
-    import torch
-    import paper_2010_04678_amd as P
-    from workloads import low_rank_tensor_device, uniform_factors
-    m, paper_s = PAPER_400_MODELS[which]
-    dims = (m, m, m)
-    T, _ = low_rank_tensor_device(dims, 10, 4000 + m, noise=0.05)
-    ranks = [r for r in range(1, 21) for _ in range(20)]
-    rstar = max(ranks) if one_at_a_time else sum(ranks)
-    ctx = P.Context(max_total_rank=rstar, max_slots=1 if one_at_a_time else 0, flags=P.CTX_REUSE if reuse else 0)
-    ctx.submit_tensor(T)
-    for k, r in enumerate(ranks):
-        ctx.enqueue_model(uniform_factors(dims, r, 40000 + 1000 * (m // 100) + k), tol=-1.0, max_iters=50)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ctx.run()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    st = ctx.stats()
-    res = ctx.poll_retired(len(ranks) + 1)
-    assert len(res) == len(ranks) and all(r.iters == 50 for r in res)
-    ctx.close()
-    flops = 6.0 * sum(ranks) * float(m) ** 3 * 50
-    return {"metric": "CP-ALS models completed/sec", "value": len(ranks) / dt, "unit": "models/s", "n_gpus": 1,
-            "steps": int(st.rounds), "warmup": 0, "ms_per_step": dt / max(1, st.rounds) * 1e3, "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": (len(ranks) / dt) / (len(ranks) / paper_s), "dtype": "f64", "data": "synthetic",
-            "config": {"workload": which, "dims": list(dims), "models": len(ranks), "total_rank": sum(ranks),
-                       "iterations": 50, "two_step_sweeps": bool(reuse), "one_at_a_time": bool(one_at_a_time)},
-            "seconds": dt, "mttkrp_gflops": flops / dt * 1e-9,
-            "paper": {"seconds": paper_s, "models_per_s": len(ranks) / paper_s,
-                      "hardware": "one V100 + 24 threads of a Xeon Platinum 8160 (CALS with CUDA offload of the MTTKRP)"}}
-
 
 def run_order_n(which: str, steps: int, warmup: int, reps: int = 3) -> dict:
     """Tensors of order above 3: rank-15 Uniform[0,1) factors plus 1 % Gaussian noise, generated on the device
@@ -371,9 +339,32 @@ def cpu_baseline(cfg, T: np.ndarray, models) -> dict:
         O.mttkrp(Ts, Us, mode)
     dt = time.perf_counter() - t
     flops = 3 * 2.0 * R * I1 * I2 * slabs
-    return {"value": flops / dt * 1e-9, "unit": "GFLOP/s", "cores": O.num_threads(), "kind": "oracle",
-            "sample": "oracle fused MTTKRP, all 3 modes, width %d, first %d of %d slabs (i3) of the %s tensor, %.1f s"
-                      % (R, slabs, I3, cfg.name, dt)}
+    out = {"value": flops / dt * 1e-9, "unit": "GFLOP/s", "cores": O.num_threads(), "kind": "oracle",
+           "sample": "oracle fused MTTKRP, all 3 modes, width %d, first %d of %d slabs (i3) of the %s tensor, %.1f s"
+                     % (R, slabs, I3, cfg.name, dt)}
+    # the other half of the metric (models completed per second, ALS iterations per second): the oracle's whole jobs
+    # of configurations 1 and 2, and this workload's rate extrapolated from the MTTKRP sample above (its sweeps are
+    # MTTKRP to 99 %: the per-model steps are not in the sample)
+    from workloads import get_config, make_models, make_tensor
+    jobs = []
+    for cid in (1, 2):
+        c = get_config(cid)
+        Tc = make_tensor(c)
+        mc = make_models(c)
+        t = time.perf_counter()
+        ref = O.cals(Tc, mc, c.max_total_rank, c.max_slots)
+        dj = time.perf_counter() - t
+        its = int(sum(ref["iters"]))
+        jobs.append({"workload": c.name + "_job", "models": len(mc), "seconds": dj, "models_per_s": len(mc) / dj,
+                     "model_iterations_per_s": its / dj, "kind": "oracle, whole job"})
+    sweep_s = dt * (I3 / float(slabs))                       # one sweep = three fused MTTKRPs over all slabs
+    its = cfg.max_iters
+    jobs.append({"workload": cfg.name, "models": len(models), "models_per_s": len(models) / (its * sweep_s),
+                 "model_iterations_per_s": len(models) / sweep_s, "sweeps_per_s": 1.0 / sweep_s,
+                 "kind": "oracle, extrapolated from the timed MTTKRP sample (%d of %d slabs, three modes) to %d sweeps"
+                         % (slabs, I3, its)})
+    out["jobs"] = jobs
+    return out
 
 
 def main() -> int:
@@ -404,14 +395,8 @@ def main() -> int:
     if args.workload in ORDER_N:
         print(json.dumps(run_order_n(args.workload, min(args.steps, 10), args.warmup)))
         return 0
-    if args.workload in PAPER_REAL:
-        print(json.dumps(run_real_shape(args.workload, reuse=args.reuse, one_at_a_time=args.one_at_a_time)))
-        return 0
-    if args.workload in PAPER_400_MODELS:
-        print(json.dumps(run_400_models(args.workload, reuse=args.reuse, one_at_a_time=args.one_at_a_time)))
-        return 0
     if args.workload.endswith("job"):
-        job = run_job(int(args.workload[3]), reuse=args.reuse, one_at_a_time=args.one_at_a_time, trace=args.trace)
+        job = run_job(int(args.workload[3]), reuse=args.reuse, trace=args.trace)
         print(json.dumps({"metric": "CP-ALS models completed/sec", "value": job["models_per_s"], "unit": "models/s",
                           "n_gpus": 1, "steps": job["rounds"], "warmup": 0, "ms_per_step": job["ms_per_round"],
                           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
@@ -487,6 +472,7 @@ def main() -> int:
             parts = ln.split()
             if len(parts) == 2 and parts[0] == cfg.name:
                 roof["traffic"] = float(parts[1])
+                roof["traffic_from"] = "profiles/traffic.txt (stored rocprofv3 FETCH_SIZE + WRITE_SIZE run of this workload; not measured in this run)"
     roof["kernel"] = "mttkrp_kernel (fused MTTKRP contraction)"
     roof["avg_launch_ms"] = avg_ms
     roof["per_mode_ms"] = per_mode_ms
@@ -515,9 +501,25 @@ def main() -> int:
         out["two_step_sweeps"] = {"ms_per_step": (r1 - r0) / K * 1e3, "sweeps_per_s": K / (r1 - r0),
                                   "models_per_s": len(active) / (r1 - r0),
                                   "effective_gflops": flops / (r1 - r0) * 1e-9}
+    if args.workload == "cfg4" and not args.no_jobs and not args.reuse:
+        # the bandwidth-bound regime on the same (HBM-resident) tensor: 16 fused columns, all three modes
+        lw = mttkrp_alone(Td, tuple(cfg.dims), 16)
+        lw_bytes = 8.0 * I1 * I2 * I3 + 8.0 * 16 * (I1 + I2 + I3)
+        lw_ms = sum(lw["contraction_ms"]) / 3.0
+        out["low_width"] = {"workload": cfg.name, "width": 16, "per_mode": lw,
+                            "roofline": {"bound": "hbm", "achieved": lw_bytes / (lw_ms * 1e-3) * 1e-9, "peak": PEAK_HBM_GBS,
+                                         "unit": "GB/s", "frac": lw_bytes / (lw_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS,
+                                         "kernel": "mttkrp_kernel (contraction launches, mean of the three modes)",
+                                         "avg_launch_ms": lw_ms}}
     del Td
+    torch.cuda.empty_cache()
     if args.workload == "cfg4" and not args.no_jobs:
-        out["jobs"] = [run_job(5, reuse=args.reuse)] + ([] if args.reuse else [run_job(5, reuse=True)])
+        if args.reuse:
+            out["jobs"] = [run_job(5, reuse=True)]
+        else:
+            legs = {cid: config_leg(cid) for cid in (1, 2, 3, 5)}
+            out["jobs"] = [legs[cid]["job"] for cid in (1, 2, 3, 5)] + [legs[5]["job_two_step"]]
+            out["mttkrp_by_config"] = [legs[cid]["mttkrp"] for cid in (1, 2, 3, 5)] + [legs[5]["mttkrp_full_buffer"]]
     if args.workload == "cfg4" and not args.no_jobs and not args.reuse:
         # the same model mix on an order-4 tensor of the same size (180^4): whole rounds and the fused MTTKRP per mode
         try:
