@@ -19,6 +19,10 @@ low-width point on the cfg4 tensor (16 columns: the bandwidth-bound regime) unde
 1..1024 on the cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1) / a 999 x 1001 x 997 tensor.  `--yardstick` prints the device's compute-unit
 count and clock and its practical peaks (back-to-back fp64 MFMA; streaming read of a 4 GiB buffer).
 
+`--workload mttkrpN` (N = 1..5) times the fused MTTKRP alone, all three modes, on configuration N's tensor at the width
+its job starts with (cfg5: also at the full buffer width, 640); `mttkrp300` does so on a 300^3 tensor at width 420.
+These are the launches whose counters profiles/short_modes_mttkrp.md holds.
+
 `--workload order4` / `order5` time the path on a tensor of order 4 (180^4) / 5 (60^5), 8.4 and 6.2 GB: the fused
 MTTKRP alone per mode at several widths (contraction kernel by events, and the whole call including the explicit
 partial Khatri-Rao products), and timed rounds of the 40-model, width-420 mix of cfg4.
@@ -394,6 +398,28 @@ def main() -> int:
         return 0
     if args.workload in ORDER_N:
         print(json.dumps(run_order_n(args.workload, min(args.steps, 10), args.warmup)))
+        return 0
+    if args.workload.startswith("mttkrp"):
+        from workloads import get_config
+        if args.workload == "mttkrp300":
+            g = torch.Generator(device="cuda:0")
+            g.manual_seed(300)
+            T300 = torch.rand((300, 300, 300), dtype=torch.float64, device="cuda:0", generator=g)
+            rows = [dict(workload="300cube", dims=[300, 300, 300], **mttkrp_alone(T300, (300, 300, 300), 420, reps=3))]
+        else:
+            cid = int(args.workload[6:])
+            cfgm = get_config(cid)
+            Tm = torch.from_numpy(make_tensor(cfgm, threads=min(16, os.cpu_count() or 8))).to("cuda:0")
+            width, n = 0, 0
+            for r in cfgm.ranks:
+                if width + r > cfgm.max_total_rank or (cfgm.max_slots and n >= cfgm.max_slots):
+                    break
+                width += r
+                n += 1
+            widths = [width] + ([cfgm.max_total_rank] if cfgm.max_total_rank != width else [])
+            rows = [dict(workload=cfgm.name, dims=list(cfgm.dims), **mttkrp_alone(Tm, tuple(cfgm.dims), w, reps=3)) for w in widths]
+        print(json.dumps({"metric": "fused MTTKRP alone, all three modes", "workload": args.workload,
+                          "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "rows": rows}))
         return 0
     if args.workload.endswith("job"):
         job = run_job(int(args.workload[3]), reuse=args.reuse, trace=args.trace)

@@ -246,9 +246,10 @@ int run_operand(cals_ctx* c, int m0, int m1, int64_t rows, const double* const* 
   return CALS_OK;
 }
 
-// Problem description of the fused MTTKRP for output mode `mode` (0-based) over given multi-matrices.  Enqueues the
-// Khatri-Rao products of runs of more than one mode (tensors of order above 3).
-int make_problem(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld, MttkrpProblem* out) {
+int64_t rows_without_mode1(const cals_ctx* c);
+
+// Shape of the fused MTTKRP for output mode `mode` (0-based): everything but the two factor operands.
+int problem_shape(const cals_ctx* c, int mode, double* M, int ncols, int ld, MttkrpProblem* out, Runs* runs) {
   const Runs r = contraction_runs(c, mode);
   if (r.Ia >= (1LL << 31) || r.Ib >= (1LL << 31)) return CALS_E_UNSUPPORTED;
   MttkrpProblem p{};
@@ -260,10 +261,48 @@ int make_problem(cals_ctx* c, int mode, const double* const* U, double* M, int n
   p.In = (int)c->dims[mode]; p.sm = mode_stride(c, mode);
   p.Ia = (int)r.Ia; p.sa = mode_stride(c, r.a0);
   p.Ib = (int)r.Ib; p.sb = mode_stride(c, r.b0);
+  *out = p;
+  *runs = r;
+  return CALS_OK;
+}
+
+// Problem description of the fused MTTKRP for output mode `mode` (0-based) over given multi-matrices.  Enqueues the
+// Khatri-Rao products of runs of more than one mode (tensors of order above 3).
+int make_problem(cals_ctx* c, int mode, const double* const* U, double* M, int ncols, int ld, MttkrpProblem* out) {
+  MttkrpProblem p{};
+  Runs r{};
+  CALS_TRY(problem_shape(c, mode, M, ncols, ld, &p, &r));
   CALS_TRY(run_operand(c, r.a0, r.a1, r.Ia, U, c->Kbuf[0], ncols, ld, &p.Ua));
   CALS_TRY(run_operand(c, r.b0, r.b1, r.Ib, U, c->Kbuf[1], ncols, ld, &p.Ub));
   *out = p;
   return CALS_OK;
+}
+
+// The largest split-K workspace any round of this context can ask for: every mode at every fused width (in steps of
+// one 16-column tile up to R*), and the first contraction of two-step sweeps.  Allocated once when the tensor
+// arrives, so that no round has to stop the stream and reallocate (ensure_workspace stays as the fallback for
+// cals_mttkrp calls with a leading dimension of their own).
+size_t largest_round_workspace(const cals_ctx* c) {
+  size_t need = 0;
+  for (int w = 16; w <= c->ld; w += 16) {
+    const int ncols = w < (int)c->opt.max_total_rank ? w : (int)c->opt.max_total_rank;
+    for (int mode = 0; mode < c->nmodes; ++mode) {
+      MttkrpProblem p{};
+      Runs r{};
+      if (problem_shape(c, mode, c->M, ncols, c->ld, &p, &r) != CALS_OK) continue;
+      p.Ua = c->U[0]; p.Ub = c->U[0];        // the planner looks at their alignment only
+      need = std::max(need, mttkrp_plan(p, c->num_cus, c->tune).workspace_bytes);
+    }
+    if (c->Y && rows_without_mode1(c) < (1LL << 31)) {
+      MttkrpProblem p{};
+      p.T = c->T; p.zeros = c->d_zeros; p.M = c->Y; p.ncols = ncols; p.ld = c->ld;
+      p.In = (int)rows_without_mode1(c); p.sm = c->dims[0];
+      p.Ia = (int)c->dims[0]; p.sa = 1; p.Ua = c->U[0];
+      p.Ib = 1; p.sb = c->dims[0]; p.Ub = c->U[0];
+      need = std::max(need, mttkrp_plan(p, c->num_cus, c->tune).workspace_bytes);
+    }
+  }
+  return need;
 }
 
 // Four events for one timed launch, or none (what was taken goes back to the pool).
@@ -1027,6 +1066,7 @@ static int submit_tensor_nd(cals_ctx* c, const double* data, int32_t ndims, cons
   ok = ok && hipMalloc(&c->d_rmap, sizeof(int32_t) * c->ld) == hipSuccess;
   ok = ok && hipHostMalloc(&c->h_rmap, sizeof(int32_t) * c->ld) == hipSuccess;
   if (!ok) { (void)hipGetLastError(); return CALS_E_NOMEM; }
+  CALS_TRY(ensure_workspace(c, largest_round_workspace(c)));
   HIP_TRY(hipMemsetAsync(c->d_out, 0, sizeof(ModelOut) * c->capacity, c->stream));
   c->free_sids.clear();
   for (int s = c->capacity - 1; s >= 0; --s) c->free_sids.push_back(s);

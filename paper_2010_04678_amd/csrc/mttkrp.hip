@@ -66,6 +66,8 @@ hipError_t launch_splitk_reduce(const double* P, double* M, int64_t n_rows_ld, i
 // variants, plan, launch
 // ---------------------------------------------------------------------------------------------------
 
+static constexpr int kMaxWnTiles = 14;
+
 static size_t variant_lds_bytes(const Variant& v) { return (size_t)2 * v.ka * 16 * v.wn * sizeof(double); }
 
 static const Variant* find_variant(int wm, int wn) {
@@ -77,16 +79,9 @@ static const Variant* find_variant(int wm, int wn) {
 }
 
 hipError_t mttkrp_init() {
-  for (int wm : {1, 2, 4}) {
-    int n = 0;
-    const Variant* t = (wm == 1) ? mttkrp_variants_wm1(&n) : (wm == 2 ? mttkrp_variants_wm2(&n) : mttkrp_variants_wm4(&n));
-    for (int i = 0; i < n; ++i)
-      for (int m = 0; m < 12; ++m) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(t[i].fn[m >> 1][m & 1]),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)variant_lds_bytes(t[i]));
-        if (e != hipSuccess) return e;
-      }
-  }
+  // The tile kernel's variants need at most 14 x 4 KiB of dynamic LDS, within the default limit of 64 KiB: no
+  // attribute to set.  The rows kernel's exchange buffers go beyond it.
+  static_assert((size_t)2 * 16 * 16 * kMaxWnTiles * sizeof(double) <= 64 * 1024, "tile kernel LDS within the default limit");
   for (int grp = 0; grp < 2; ++grp) {
     int n = 0;
     const RowsVariant* t = grp == 0 ? mttkrp_rows_variants_a(&n) : mttkrp_rows_variants_b(&n);
@@ -150,7 +145,7 @@ static int tensor_read_mode(const MttkrpProblem& p, int wm, const MttkrpTuning& 
   return mode;
 }
 
-static constexpr int kMaxWn = 14;     // widest column block of a workgroup, in 16-column tiles
+static constexpr int kMaxWn = kMaxWnTiles;     // widest column block of a workgroup, in 16-column tiles
 
 // The plan for column blocks of at most `wn_max` tiles of 16 columns, and its modelled time in microseconds.
 static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max, const MttkrpTuning& tune, double* cost_us) {
