@@ -214,21 +214,33 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   if (tune.per_cu > 0) per_cu = tune.per_cu;
   // Split of the contraction range, by a cost model in microseconds.  A stage of a workgroup with t accumulator
   // tiles per wavefront takes t x 4 MFMAs x 64 cycles at about 80 % MFMA utilisation, plus a fixed cost of about 6
-  // stages per workgroup.  More than one split adds the partials' way through memory: written once, read once by
-  // the reduction, plus the result (about 3 TB/s for these strided panels).  Splits are whole multiples of 8 when
-  // there are 8 or more, so that the XCD-pinned block order gives every XCD the same number of splits; with
-  // fewer splits the blocks of a split are spread over the XCDs instead.
+  // stages per workgroup.  More than one split adds the partials' way through memory (below).  For a tensor that
+  // streams from HBM the candidates are 1..7 and the multiples of 8, so that the XCD-pinned block order gives every
+  // XCD the same number of splits and the column blocks of a split share the tensor tile in that XCD's L2.  A tensor
+  // that the last-level cache holds does not need that, and what decides there is how evenly the workgroups fill
+  // the compute units, so every split count is a candidate (300 x 300 x 40 at 630 columns, modes 1 and 2: 16 splits
+  // = 400 workgroups 36-40 TFLOP/s, 20 splits = 500 workgroups 46-47; 300^3 at 420 columns 48 -> 51 splits +4 %;
+  // 4000 x 200 x 50 at 640 columns, mode 2, 48 -> 51 splits +6 %); splits that are not a multiple of 8 are spread
+  // over the XCDs.
   const int64_t max_splits = std::max<int64_t>(1, K / (4 * pl.ka));   // at least two stage pairs per split
   const int force_splits = tune.splits;
   const double us_per_tile_stage = 4.0 * 64.0 / 2400.0 / 0.8;          // one accumulator tile, one stage (KA = 16)
-  const double panel_us = (double)p.In * p.ncols * 8.0 / 3.0e6;        // one In x ncols panel through memory
+  // One In x ncols panel of partial sums: written by the contraction (mostly hidden behind its MFMAs: 4000 x 200 x 50
+  // mode 1 at 640 columns, 20 MB panels, 24 -> 128 splits: 0.80 -> 0.98 ms), read once by the reduction kernel, which
+  // measured takes about 5 us plus the bytes at 4-5 TB/s, or at 8 TB/s while all panels together stay in the caches.
+  const double panel_bytes = (double)p.In * p.ncols * 8.0;
   // the practical read rate needs enough loads in flight: two workgroups per CU with four row tiles per wavefront,
   // three with two, four with one; and the workgroups share the bandwidth, so a launch lasts about as long as the
   // CU with the most of them
   const int64_t wgs_for_rate = (int64_t)num_cus * (wm == 4 ? 2 : (wm == 2 ? 3 : 4));
   int64_t splits = 1;
   double best_cost = 1e300;
-  for (int64_t cand = 1; cand <= std::min<int64_t>(max_splits, 4096); cand = (cand < 8) ? cand + 1 : cand + 8) {
+  const bool cache_resident = tensor_bytes <= 1073741824.0;
+  auto next_candidate = [cache_resident](int64_t c) -> int64_t {
+    if (!cache_resident) return c < 8 ? c + 1 : c + 8;
+    return c < 64 ? c + 1 : (c < 128 ? c + 2 : c + 8);
+  };
+  for (int64_t cand = 1; cand <= std::min<int64_t>(max_splits, 4096); cand = next_candidate(cand)) {
     const int64_t pairs = (K + cand * 2 * pl.ka - 1) / (cand * 2 * pl.ka);
     double cost = 0.0;
     for (int q = 0; q < pl.nparts; ++q) {
@@ -249,7 +261,8 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
       const double hbm_us = tensor_us * pl.part[q].ny * fill;
       cost += mfma_us > hbm_us ? mfma_us : hbm_us;
     }
-    if (cand > 1) cost += (2.0 * cand + 1.0) * panel_us;
+    if (cand > 1)
+      cost += 5.0 + (double)(cand + 1) * panel_bytes / ((double)cand * panel_bytes <= 64.0e6 ? 8.0e6 : 4.5e6) + (double)cand * panel_bytes / 1.2e7;
     if (cost < best_cost) { best_cost = cost; splits = cand; }
   }
   if (force_splits > 0) splits = force_splits;
