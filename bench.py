@@ -134,7 +134,8 @@ def steady_mttkrp(ctx, mode: int, U, M, width: int, min_reps: int = 3, max_reps:
     """Times cals_mttkrp(mode) in steady state: repeats the call untimed until STEADY_WARM_MS of launches have gone by,
     then times as many calls as fill STEADY_MS (at least min_reps).  A job keeps the GPU busy for its whole length, and
     a sub-millisecond launch sequence measured right after an idle stretch runs 10-17 % slower than the same launches
-    some tens of milliseconds into continuous work.  Returns (contraction ms, reduction ms, host ms per call, reps)."""
+    some tens of milliseconds into continuous work.  Returns (contraction ms, reduction ms, host ms per call, timed
+    calls, all calls)."""
     import torch
     n = mode - 1
     s0 = ctx.stats()
@@ -142,7 +143,8 @@ def steady_mttkrp(ctx, mode: int, U, M, width: int, min_reps: int = 3, max_reps:
     torch.cuda.synchronize()
     s1 = ctx.stats()
     one = max(1e-3, s1.mttkrp_ms[n] - s0.mttkrp_ms[n] + s1.reduce_ms[n] - s0.reduce_ms[n])
-    for k in range(min(8 * max_reps, int(STEADY_WARM_MS / one))):
+    warm = min(8 * max_reps, int(STEADY_WARM_MS / one))
+    for k in range(warm):
         ctx.mttkrp(mode, U, M, total_rank=width)
         if k % 64 == 63:
             ctx.stats()          # reads the launches' events back, so that the library reuses them
@@ -156,7 +158,7 @@ def steady_mttkrp(ctx, mode: int, U, M, width: int, min_reps: int = 3, max_reps:
     t1 = time.perf_counter()
     s1 = ctx.stats()
     return ((s1.mttkrp_ms[n] - s0.mttkrp_ms[n]) / reps, (s1.reduce_ms[n] - s0.reduce_ms[n]) / reps,
-            (t1 - t0) / reps * 1e3, reps)
+            (t1 - t0) / reps * 1e3, reps, 1 + warm + reps)
 
 
 def run_sweep(which: str, reps: int = 3) -> dict:
@@ -186,12 +188,13 @@ def run_sweep(which: str, reps: int = 3) -> dict:
         ms = []
         for mode in (1, 2, 3):
             M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda:0")
-            ms.append(steady_mttkrp(ctx, mode, U, M, R, min_reps=reps)[:2])
+            ms.append(steady_mttkrp(ctx, mode, U, M, R, min_reps=reps))
         flops = 2.0 * R * I1 * I2 * I3
         nbytes = 8.0 * I1 * I2 * I3 + 8.0 * R * (I1 + I2 + I3)
         rows.append({"width": R, "contraction_ms": [m[0] for m in ms], "reduce_ms": [m[1] for m in ms],
                      "tflops": [flops / (m[0] * 1e-3) * 1e-12 for m in ms],
-                     "algorithmic_tb_per_s": [nbytes / (m[0] * 1e-3) * 1e-12 for m in ms]})
+                     "algorithmic_tb_per_s": [nbytes / (m[0] * 1e-3) * 1e-12 for m in ms],
+                     "timed_calls": [m[3] for m in ms], "calls": [m[4] for m in ms]})
     ctx.close()
     return {"metric": "fused MTTKRP alone, widths 1..1024 (sweep W)", "workload": which, "dims": list(dims),
             "reps": "at least %d, and as many as fill %.0f ms after %.0f ms of untimed calls" % (reps, STEADY_MS, STEADY_WARM_MS), "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "peak_hbm_gbs": PEAK_HBM_GBS, "rows": rows}
@@ -208,12 +211,13 @@ def mttkrp_alone(T_dev, dims, width: int, reps: int = 5) -> dict:
     g.manual_seed(7)
     ld = (width + 15) // 16 * 16
     U = [torch.rand((d, ld), dtype=torch.float64, device="cuda:0", generator=g) for d in dims]
-    contraction, reduce = [], []
+    contraction, reduce, calls = [], [], []
     for mode in (1, 2, 3):
         M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda:0")
-        c, r, _, _ = steady_mttkrp(ctx, mode, U, M, width, min_reps=reps)
+        c, r, _, _, n = steady_mttkrp(ctx, mode, U, M, width, min_reps=reps)
         contraction.append(c)
         reduce.append(r)
+        calls.append(n)
     st = ctx.stats()
     ctx.close()
     I1, I2, I3 = dims
@@ -224,7 +228,7 @@ def mttkrp_alone(T_dev, dims, width: int, reps: int = 5) -> dict:
             "tflops": [flops / (t * 1e-3) * 1e-12 for t in total],
             "frac_of_mfma_peak": [flops / (t * 1e-3) * 1e-12 / PEAK_FP64_MFMA_TFLOPS for t in total],
             "algorithmic_gb_per_s": [nbytes / (t * 1e-3) * 1e-9 for t in total],
-            "rows_kernel_launches": int(st.mttkrp_rows_launches), "launches": int(sum(st.mttkrp_launches))}
+            "rows_kernel_launches": int(st.mttkrp_rows_launches), "launches": int(sum(st.mttkrp_launches)), "calls": calls}
 
 
 def settled_job(cid: int, T_dev, reuse: bool = False) -> dict:
@@ -290,7 +294,7 @@ def run_order_n(which: str, steps: int, warmup: int, reps: int = 3) -> dict:
         kern, call = [], []
         for mode in range(1, N + 1):
             M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device=dev)
-            c, r, host_ms, _ = steady_mttkrp(ctx, mode, U, M, R, min_reps=reps)
+            c, r, host_ms, _, _ = steady_mttkrp(ctx, mode, U, M, R, min_reps=reps)
             kern.append(c + r)
             call.append(host_ms)
         flops = 2.0 * R * elems
