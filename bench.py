@@ -11,9 +11,11 @@ resident in HBM before the timed region.  Prints ONE JSON line.
 `--workload cfgNjob` (N = 1..5) instead runs the configuration's whole job once as it is specified (queue, slots,
 tolerances, iteration caps, non-negativity, line search) and reports models completed per second; --steps and
 --warmup do not apply.  The default run appends, to the one JSON line: the whole jobs of configurations 1, 2, 3 and 5
-under "jobs"; the fused MTTKRP alone at each of those configurations' full width under "mttkrp_by_config"; a
-low-width point on the cfg4 tensor (16 columns: the bandwidth-bound regime) under "low_width"; the order-4 workload
-(see below) under "order_n"; and the oracle's side of every figure under "cpu_baseline".
+under "jobs" (a job of under a quarter of a second is run twice and the second run reported); the fused MTTKRP alone
+at each of those configurations' full width under "mttkrp_by_config"; a low-width point on the cfg4 tensor (16
+columns: the bandwidth-bound regime, with its own roofline object against the HBM peak) under "low_width"; the order-4
+workload (see below) under "order_n"; and the oracle's side of every figure under "cpu_baseline".  The fused MTTKRP
+alone is always timed in steady state (steady_mttkrp: 100 ms of untimed calls, then at least 25 ms of timed ones).
 
 `--workload sweepW1000` / `sweepW300` / `sweepWodd` time the fused MTTKRP alone, all three modes, over fused widths
 1..1024 on the cfg4 tensor / a 300^3 tensor (the analogue of the paper's Fig. 1) / a 999 x 1001 x 997 tensor.  `--yardstick` prints the device's compute-unit

@@ -384,13 +384,18 @@ int run_mttkrp(cals_ctx* c, int mode, const double* const* U, double* M, int nco
     t.reduced = pl.splits > 1;
     ev = t.ev;
   }
+  bool timed = false;
   {
-    const hipError_t e = mttkrp_launch(p, pl, partials, c->stream, ev);
+    const hipError_t e = mttkrp_launch(p, pl, partials, c->stream, ev, &timed);
     if (e != hipSuccess) {
       (void)hipGetLastError();
       if (ev) give_back_events(c, t.ev);
       return CALS_E_HIP;
     }
+  }
+  if (ev && !timed) {        // an event could not be recorded: the launch stands, it is just not timed
+    give_back_events(c, t.ev);
+    ev = nullptr;
   }
   if (ev) {
     c->timed.push_back(t);
@@ -432,13 +437,18 @@ int run_contract_mode1(cals_ctx* c, const double* U1, int ncols, int ld, double*
     t.reduced = pl.splits > 1;
     ev = t.ev;
   }
+  bool timed = false;
   {
-    const hipError_t e = mttkrp_launch(p, pl, c->workspace, c->stream, ev);
+    const hipError_t e = mttkrp_launch(p, pl, c->workspace, c->stream, ev, &timed);
     if (e != hipSuccess) {
       (void)hipGetLastError();
       if (ev) give_back_events(c, t.ev);
       return CALS_E_HIP;
     }
+  }
+  if (ev && !timed) {        // an event could not be recorded: the launch stands, it is just not timed
+    give_back_events(c, t.ev);
+    ev = nullptr;
   }
   if (ev) {
     c->timed.push_back(t);

@@ -92,9 +92,10 @@ struct MttkrpPlan {
 MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& tune = MttkrpTuning());
 // Enqueues contraction (+ ordered split-K reduction when plan.splits > 1) on `stream`.
 // `workspace` must hold plan.workspace_bytes.  ev[0..3], when non-null, are recorded around the
-// contraction kernel (ev[0], ev[1]) and around the reduction kernel (ev[2], ev[3]).
+// contraction kernel (ev[0], ev[1]) and around the reduction kernel (ev[2], ev[3]); *timed (when non-null) tells
+// whether every record succeeded -- if not, the launch stands but its events must not be read.
 hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& plan, double* workspace, hipStream_t stream,
-                         hipEvent_t* ev);
+                         hipEvent_t* ev, bool* timed = nullptr);
 // One-time per-process kernel attribute set-up (dynamic LDS sizes).
 hipError_t mttkrp_init();
 

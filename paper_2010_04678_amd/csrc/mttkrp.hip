@@ -410,8 +410,17 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& 
   return rows.cost_us < 0.95 * tiles.cost_us ? rows : tiles;    // the tile kernel's model is the better calibrated one
 }
 
+// Records a timing event; a failed record only marks the launch as untimed (the error is cleared, the work goes on).
+static inline void record_event(hipEvent_t* ev, int i, hipStream_t stream, bool* timed) {
+  if (!ev) return;
+  if (hipEventRecord(ev[i], stream) != hipSuccess) {
+    (void)hipGetLastError();
+    *timed = false;
+  }
+}
+
 static hipError_t rows_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* workspace, hipStream_t stream,
-                              hipEvent_t* ev) {
+                              hipEvent_t* ev, bool* timed) {
   const RowsVariant* v = find_rows_variant(pl.rows_wmb, pl.rows_wnb);
   if (!v || (pl.rows_amode != kRowsContig && pl.rows_amode != kRowsPair)) return hipErrorInvalidValue;
   // what the kernel assumes about its operands
@@ -438,23 +447,26 @@ static hipError_t rows_launch(const MttkrpProblem& p, const MttkrpPlan& pl, doub
   const int64_t groups = ((int64_t)a.nrb * a.nsb + 7) / 8 * 8;
   const int64_t nblocks = groups * a.ncg;
   if (nblocks >= (1LL << 31)) return hipErrorInvalidValue;
-  if (ev) (void)hipEventRecord(ev[0], stream);
+  record_event(ev, 0, stream, timed);
   hipLaunchKernelGGL(v->fn[pl.rows_amode], dim3((unsigned)nblocks), dim3(256), rows_lds_bytes(v->wmb, v->wnb), stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (ev) (void)hipEventRecord(ev[1], stream);
+  record_event(ev, 1, stream, timed);
   if (pl.splits > 1) {
-    if (ev) (void)hipEventRecord(ev[2], stream);
+    record_event(ev, 2, stream, timed);
     e = launch_splitk_reduce(workspace, p.M, a.pstride, p.ld, p.ncols, pl.splits, stream);
-    if (ev) (void)hipEventRecord(ev[3], stream);
+    record_event(ev, 3, stream, timed);
   }
   return e;
 }
 
 hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* workspace, hipStream_t stream,
-                         hipEvent_t* ev) {
+                         hipEvent_t* ev, bool* timed_out) {
+  bool timed_local = true;
+  bool* timed = timed_out ? timed_out : &timed_local;
+  *timed = (ev != nullptr);
   if (p.ncols < 1 || p.ncols > p.ld || p.In < 1 || p.Ia < 1 || p.Ib < 1) return hipErrorInvalidValue;
-  if (pl.kind == 1) return rows_launch(p, pl, workspace, stream, ev);
+  if (pl.kind == 1) return rows_launch(p, pl, workspace, stream, ev, timed);
   if (pl.nparts < 1 || pl.nparts > 2) return hipErrorInvalidValue;
   if ((int64_t)pl.mtiles * 64 * pl.wm < p.In) return hipErrorInvalidValue;
   const int ia_counted = pl.ia_counted;
@@ -482,7 +494,7 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
   a.mtiles = pl.mtiles; a.splits = pl.splits;
   a.pinned = (pl.splits % 8 == 0) ? 1 : 0;
   const int pair = pl.pair ? 1 : 0;
-  if (ev) (void)hipEventRecord(ev[0], stream);
+  record_event(ev, 0, stream, timed);
   for (int q = 0; q < pl.nparts; ++q) {
     const Variant* v = find_variant(pl.wm, pl.part[q].wn);
     if (!v || v->ka != pl.ka) return hipErrorInvalidValue;
@@ -495,13 +507,13 @@ hipError_t mttkrp_launch(const MttkrpProblem& p, const MttkrpPlan& pl, double* w
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  if (ev) (void)hipEventRecord(ev[1], stream);
+  record_event(ev, 1, stream, timed);
   hipError_t e = hipSuccess;
   if (pl.splits > 1) {
     const int64_t n = a.pstride;
-    if (ev) (void)hipEventRecord(ev[2], stream);
+    record_event(ev, 2, stream, timed);
     e = launch_splitk_reduce(workspace, p.M, n, p.ld, p.ncols, pl.splits, stream);
-    if (ev) (void)hipEventRecord(ev[3], stream);
+    record_event(ev, 3, stream, timed);
   }
   return e;
 }
