@@ -25,6 +25,9 @@ count and clock and its practical peaks (back-to-back fp64 MFMA; streaming read 
 its job starts with (cfg5: also at the full buffer width, 640); `mttkrp300` does so on a 300^3 tensor at width 420.
 These are the launches whose counters profiles/short_modes_mttkrp.md holds.
 
+`--workload splitscan` / `ridgescan` time the fused MTTKRP under forced plans (split counts on the cache-resident
+short-mode shapes; row tiles per wavefront x split counts at widths 32-96 on 1000^3): profiles/forced_plan_scans.md.
+
 `--workload order4` / `order5` time the path on a tensor of order 4 (180^4) / 5 (60^5), 8.4 and 6.2 GB: the fused
 MTTKRP alone per mode at several widths (contraction kernel by events, and the whole call including the explicit
 partial Khatri-Rao products), and timed rounds of the 40-model, width-420 mix of cfg4.
@@ -233,6 +236,68 @@ def mttkrp_alone(T_dev, dims, width: int, reps: int = 5) -> dict:
             "rows_kernel_launches": int(st.mttkrp_rows_launches), "launches": int(sum(st.mttkrp_launches)), "calls": calls}
 
 
+
+# Forced-plan scans (development knobs of the library, read from the environment when a context is created): the
+# measurements the split planner and the row-tile choice were fitted to and checked against.
+SCANS = {
+    # tensors the last-level cache holds: split count against the planner's own choice (first row of each block)
+    "splitscan": [((300, 300, 40), 630, [None], [None, 8, 10, 12, 16, 20, 24, 30, 32, 40, 50, 64, 100, 128, 150]),
+                  ((300, 300, 300), 420, [None], [None, 32, 40, 48, 51, 56, 64]),
+                  ((4000, 200, 50), 640, [None], [None, 3, 4, 6, 24, 48, 51, 64, 100, 102, 128, 152]),
+                  ((200, 200, 200), 110, [None], [None, 63, 84, 125])],
+    # the ridge on the cfg 4 shape: row tiles per wavefront x split count at widths around the ridge point
+    "ridgescan": [((1000, 1000, 1000), w, [None, 4, 2], [None, 64, 128, 192, 256, 384]) for w in (32, 48, 64, 96)],
+}
+
+
+def run_scan(which: str) -> dict:
+    import torch
+    import paper_2010_04678_amd as P
+    rows = []
+    for dims, width, wms, splits in SCANS[which]:
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(1)
+        T = torch.rand(dims[::-1], dtype=torch.float64, device="cuda:0", generator=g)
+        ld = (width + 15) // 16 * 16
+        U = [torch.rand((d, ld), dtype=torch.float64, device="cuda:0", generator=g) for d in dims]
+        flops = 2.0 * width * dims[0] * dims[1] * dims[2]
+        first = True
+        for wm in wms:
+            for sp in [None] + list(splits) if first else splits:     # the very first pass over a tensor is not reported
+                env = {}
+                if wm is not None or sp is not None:
+                    env["CALS_MTTKRP_KERNEL"] = "1"            # forced plans are plans of the tile kernel
+                if wm is not None:
+                    env["CALS_MTTKRP_WM"] = str(wm)
+                if sp is not None:
+                    env["CALS_MTTKRP_SPLITS"] = str(sp)
+                for k in [k for k in os.environ if k.startswith("CALS_MTTKRP_")]:
+                    del os.environ[k]
+                os.environ.update(env)
+                ctx = P.Context(max_total_rank=width, flags=P.CTX_TIMING)
+                for k in env:
+                    del os.environ[k]
+                ctx.submit_tensor(T)
+                ms = []
+                for mode in (1, 2, 3):
+                    M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda:0")
+                    c, r, _, _, _ = steady_mttkrp(ctx, mode, U, M, width)
+                    ms.append((c, r))
+                st = ctx.stats()
+                ctx.close()
+                if first:
+                    first = False
+                    continue
+                rows.append({"dims": list(dims), "width": width, "wm": wm, "splits": sp,
+                             "contraction_ms": [m[0] for m in ms], "reduce_ms": [m[1] for m in ms],
+                             "tflops": [flops / ((m[0] + m[1]) * 1e-3) * 1e-12 for m in ms],
+                             "rows_kernel_launches": int(st.mttkrp_rows_launches)})
+        del T
+        torch.cuda.empty_cache()
+    return {"metric": "fused MTTKRP alone under forced plans (contraction + reduction, steady state)", "workload": which,
+            "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "rows": rows}
+
+
 def settled_job(cid: int, T_dev, reuse: bool = False) -> dict:
     """run_job; a job shorter than a quarter of a second is run a second time and that run is reported (the first run of
     a few milliseconds also pays for loading the kernels it is the first to launch, which is no part of its rate)."""
@@ -427,6 +492,9 @@ def main() -> int:
         return 0
     if args.workload.startswith("sweepW"):
         print(json.dumps(run_sweep(args.workload)))
+        return 0
+    if args.workload in SCANS:
+        print(json.dumps(run_scan(args.workload)))
         return 0
     if args.workload in ORDER_N:
         print(json.dumps(run_order_n(args.workload, min(args.steps, 10), args.warmup)))
