@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcals_hip.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["mttkrp_wm1.hip", "mttkrp_wm2.hip", "mttkrp_wm4.hip", "mttkrp_rows_a.hip", "mttkrp_rows_b.hip", "mttkrp.hip", "update.hip", "linesearch.hip", "nnls.hip", "yardstick.hip", "reuse.hip", "krp.hip", "cals_api.hip"]
+SOURCES = ["mttkrp_wm1.hip", "mttkrp_wm2.hip", "mttkrp_wm3.hip", "mttkrp_wm4.hip", "mttkrp_rows_a.hip", "mttkrp_rows_b.hip", "mttkrp.hip", "update.hip", "linesearch.hip", "nnls.hip", "yardstick.hip", "reuse.hip", "krp.hip", "cals_api.hip"]
 # yardstick.hip: its MFMA-only loop must keep the accumulators in place (VGPR form of the matrix instructions;
 # otherwise the compiler copies them between register files every iteration and the probe measures the copies)
 # mttkrp_rows_*.hip: with the default (accumulation-register) form of the matrix instructions the register allocator

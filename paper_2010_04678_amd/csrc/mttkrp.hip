@@ -72,7 +72,7 @@ static size_t variant_lds_bytes(const Variant& v) { return (size_t)2 * v.ka * 16
 
 static const Variant* find_variant(int wm, int wn) {
   int n = 0;
-  const Variant* t = (wm == 1) ? mttkrp_variants_wm1(&n) : (wm == 2 ? mttkrp_variants_wm2(&n) : mttkrp_variants_wm4(&n));
+  const Variant* t = (wm == 1) ? mttkrp_variants_wm1(&n) : (wm == 2 ? mttkrp_variants_wm2(&n) : (wm == 3 ? mttkrp_variants_wm3(&n) : mttkrp_variants_wm4(&n)));
   for (int i = 0; i < n; ++i)
     if (t[i].wn == wn) return &t[i];
   return nullptr;
@@ -172,13 +172,21 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   // 16-byte row-pair loads) and 1.12 beyond -- with 16 or more accumulator tiles a wavefront has no co-resident
   // to hide its waits, and 64 rows per wavefront along a long-stride mode cost more than they save: 1000^3 at
   // width 96: mode 3 57 TFLOP/s with wm = 4, 63 with wm = 2; mode 1 64 and 62)
+  // Three row tiles per wavefront (192-row workgroups) are a candidate for modes read along the contraction whose
+  // rows lie at most 1 MiB apart -- measured on 180^4 against one row tile per wavefront (the same 192 padded rows):
+  // inner modes +10-12 % at 64 columns, +7-10 % at 128 and 256, +2-4 % at 420 in blocks of 9 tiles; the first mode
+  // (rows contiguous, no row-pair loads with an odd tile count) and the last (rows 46 MB apart) gain nothing or lose
+  // 2 %: relative cost 1.14.
+  const bool wm3_ok = p.sa == 1 && p.sm > 1 && (double)p.sm * 8.0 <= 1048576.0;
   int wm = 1;
   {
     double best = 1e300;
-    for (int cand : {4, 2, 1}) {
+    for (int cand : {4, 3, 2, 1}) {
       if (cand * wn_top > 28) continue;
+      if (cand == 3 && !wm3_ok) continue;
       const double padded = (double)((p.In + 64 * cand - 1) / (64 * cand)) * (64 * cand);
-      const double cost = padded * (cand == 4 ? ((wn_top <= 3 || (p.sm == 1 && wn_top <= 6)) ? 1.0 : 1.12) : (cand == 2 ? 1.08 : 1.25));
+      const double cost = padded * (cand == 4 ? ((wn_top <= 3 || (p.sm == 1 && wn_top <= 6)) ? 1.0 : 1.12)
+                                              : (cand == 3 ? 1.14 : (cand == 2 ? 1.08 : 1.25)));
       if (cost < best) { best = cost; wm = cand; }
     }
   }
@@ -198,8 +206,9 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
     if (mfma4_us < 0.6 * tensor_us * ny) wm = 4;
   }
   if (tune.wm > 0) wm = tune.wm;
-  if (wm != 1 && wm != 2 && wm != 4) wm = 2;
+  if (wm < 1 || wm > 4) wm = 2;
   if (wm == 4 && wn_top > 7) wm = 2;
+  if (wm == 3 && wn_top > 9) wm = 2;
   pl.wm = wm;
   pl.ka = 16;
   pl.mtiles = (p.In + 64 * wm - 1) / (64 * wm);
@@ -209,6 +218,9 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   // one row tile per wavefront with 12 or more column tiles: the B fragments and the factor rows in flight take
   // so many registers next to the accumulators that only one workgroup fits (compiler's resource report)
   if (wm == 1 && wn_top >= 12) per_cu = 1;
+  // three row tiles per wavefront: the tensor fragments of three tiles in flight leave room for two workgroups up to
+  // five column tiles (compiler's resource report)
+  if (wm == 3 && per_cu > 2) per_cu = (wn_top <= 1) ? 3 : 2;
   const int lds_fit = (int)(160 * 1024 / ((size_t)2 * pl.ka * 16 * wn_top * sizeof(double)));
   if (per_cu > lds_fit) per_cu = lds_fit;
   if (tune.per_cu > 0) per_cu = tune.per_cu;
@@ -232,7 +244,7 @@ static MttkrpPlan plan_for_width(const MttkrpProblem& p, int num_cus, int wn_max
   // the practical read rate needs enough loads in flight: two workgroups per CU with four row tiles per wavefront,
   // three with two, four with one; and the workgroups share the bandwidth, so a launch lasts about as long as the
   // CU with the most of them
-  const int64_t wgs_for_rate = (int64_t)num_cus * (wm == 4 ? 2 : (wm == 2 ? 3 : 4));
+  const int64_t wgs_for_rate = (int64_t)num_cus * (wm == 4 ? 2 : (wm >= 2 ? 3 : 4));
   int64_t splits = 1;
   double best_cost = 1e300;
   const bool cache_resident = tensor_bytes <= 1073741824.0;
@@ -293,7 +305,14 @@ static MttkrpPlan tile_plan(const MttkrpProblem& p, int num_cus, const MttkrpTun
   MttkrpPlan wide = plan_for_width(p, num_cus, kMaxWn, tune, &cost);
   if ((p.ncols + 15) / 16 >= 12) {
     double cost8 = 0.0;
-    const MttkrpPlan narrow = plan_for_width(p, num_cus, 8, tune, &cost8);
+    MttkrpPlan narrow = plan_for_width(p, num_cus, 8, tune, &cost8);
+    if (narrow.wm == 3) {
+      // three row tiles per wavefront take blocks of up to 9 tiles (420 columns as 9+9+9 instead of 7+7+7+6: one
+      // launch and one pass over the tensor fewer; 180^4 inner modes 59.2 / 58.2 -> 60.6 / 59.9 TFLOP/s)
+      double cost9 = 0.0;
+      const MttkrpPlan nine = plan_for_width(p, num_cus, 9, tune, &cost9);
+      if (nine.wm == 3 && cost9 <= cost8) { narrow = nine; cost8 = cost9; }
+    }
     if (cost8 <= 1.02 * cost) return narrow;
   }
   return wide;

@@ -492,23 +492,25 @@ struct Variant {
     }                                                                                                     \
   }
 
-// One row tile per wavefront cannot pair rows: the planner never asks for kRowPair there, and the slot holds the
-// kAffine kernel (which is what a kRowPair kernel with odd WM would be) instead of a second copy of it.
-#define CALS_VARIANT_WM1(WN_, KA_)                                                                        \
-  {                                                                                                       \
-    1, WN_, KA_, {                                                                                        \
-      {mttkrp_kernel<1, WN_, KA_, kAffine, false>, mttkrp_kernel<1, WN_, KA_, kAffine, true>},            \
-          {mttkrp_kernel<1, WN_, KA_, kWrap, false>, mttkrp_kernel<1, WN_, KA_, kWrap, true>},            \
-          {mttkrp_kernel<1, WN_, KA_, kGeneral, false>, mttkrp_kernel<1, WN_, KA_, kGeneral, true>},      \
-          {mttkrp_kernel<1, WN_, KA_, kContig4, false>, mttkrp_kernel<1, WN_, KA_, kContig4, true>},      \
-          {mttkrp_kernel<1, WN_, KA_, kAffine, false>, mttkrp_kernel<1, WN_, KA_, kAffine, true>},        \
-          {mttkrp_kernel<1, WN_, KA_, kContig4U, false>, mttkrp_kernel<1, WN_, KA_, kContig4U, true>}     \
-    }                                                                                                     \
+// An odd number of row tiles per wavefront cannot pair rows: the planner never asks for kRowPair there, and the slot
+// holds the kAffine kernel (which is what a kRowPair kernel with odd WM would be) instead of a second copy of it.
+#define CALS_VARIANT_ODD(WM_, WN_, KA_)                                                                     \
+  {                                                                                                         \
+    WM_, WN_, KA_, {                                                                                        \
+      {mttkrp_kernel<WM_, WN_, KA_, kAffine, false>, mttkrp_kernel<WM_, WN_, KA_, kAffine, true>},          \
+          {mttkrp_kernel<WM_, WN_, KA_, kWrap, false>, mttkrp_kernel<WM_, WN_, KA_, kWrap, true>},          \
+          {mttkrp_kernel<WM_, WN_, KA_, kGeneral, false>, mttkrp_kernel<WM_, WN_, KA_, kGeneral, true>},    \
+          {mttkrp_kernel<WM_, WN_, KA_, kContig4, false>, mttkrp_kernel<WM_, WN_, KA_, kContig4, true>},    \
+          {mttkrp_kernel<WM_, WN_, KA_, kAffine, false>, mttkrp_kernel<WM_, WN_, KA_, kAffine, true>},      \
+          {mttkrp_kernel<WM_, WN_, KA_, kContig4U, false>, mttkrp_kernel<WM_, WN_, KA_, kContig4U, true>}   \
+    }                                                                                                       \
   }
+#define CALS_VARIANT_WM1(WN_, KA_) CALS_VARIANT_ODD(1, WN_, KA_)
 
 // Variant tables, one translation unit per WM (compiled in parallel).
 const Variant* mttkrp_variants_wm1(int* n);
 const Variant* mttkrp_variants_wm2(int* n);
+const Variant* mttkrp_variants_wm3(int* n);
 const Variant* mttkrp_variants_wm4(int* n);
 
 }  // namespace cals

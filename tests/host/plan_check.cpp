@@ -52,7 +52,7 @@ static int check(int In, int Ia, int Ib, int ncols, int cus, int layout = 0) {
     return 0;
   }
   if (why) {}
-  else if (pl.wm != 1 && pl.wm != 2 && pl.wm != 4) why = "wm";
+  else if (pl.wm < 1 || pl.wm > 4) why = "wm";
   else if (pl.ka != 16) why = "ka";
   else if (pl.nparts < 1 || pl.nparts > 2) why = "nparts";
   else if ((long long)pl.mtiles * 64 * pl.wm < In || (long long)(pl.mtiles - 1) * 64 * pl.wm >= In) why = "mtiles";
@@ -66,6 +66,7 @@ static int check(int In, int Ia, int Ib, int ncols, int cus, int layout = 0) {
     else if (pt.wn < 1 || pt.wn > 14 || pt.ny < 1) why = "part shape";
     else if (pl.wm * pt.wn > 28) why = "accumulator budget";
     else if (pl.wm == 4 && pt.wn > 7) why = "wm 4 needs wn <= 7";
+    else if (pl.wm == 3 && pt.wn > 9) why = "wm 3 needs wn <= 9";
     else if ((size_t)2 * pl.ka * 16 * pt.wn * sizeof(double) > 160 * 1024) why = "LDS";
     covered += 16 * pt.wn * pt.ny;
   }

@@ -110,6 +110,37 @@ def test_mttkrp_every_column_block_width(dims, ranks, signed, wn_max):
         assert np.all(err <= TOL * scale + 1e-300), (mode, wn_max, float((err / (scale + 1e-300)).max()))
 
 
+WM_CASES = [((180, 20, 16), [20] * 5, True),          # 180 rows = one 192-row workgroup of three row tiles per wavefront
+            ((16, 180, 20), [20] * 7, False),         # the same for an inner mode, 9 column tiles
+            ((20, 16, 200), [11] * 4, True),          # two such workgroups in the last mode
+            ((129, 65, 33), list(range(1, 21)) + [11] * 20, True),
+            ((70, 9, 150), [7] * 5, True)]
+
+
+@pytest.mark.parametrize("wm", [1, 2, 3, 4])
+@pytest.mark.parametrize("dims,ranks,signed", WM_CASES)
+def test_mttkrp_every_row_tile_count(dims, ranks, signed, wm):
+    # the planner picks 1, 2, 3 or 4 row tiles per wavefront from the row count, the width and the mode's layout; here
+    # each is forced on the tile kernel (development knobs, column blocks of up to 9 tiles so that three row tiles
+    # stay within the accumulator budget), so that every count meets every read mode whatever the planner prefers
+    import os
+    T = random_tensor(dims, 11 + dims[0], signed=signed)
+    U = _fused(dims, ranks, 200 + dims[1], signed=signed)
+    env = {"CALS_MTTKRP_WM": str(wm), "CALS_MTTKRP_KERNEL": "1", "CALS_MTTKRP_WNMAX": "7" if wm == 4 else "9"}
+    os.environ.update(env)
+    try:
+        got = _gpu_mttkrp(T, U, pad_to=sum(ranks) + 2)
+    finally:
+        for k in env:
+            del os.environ[k]
+    for mode in (1, 2, 3):
+        want = O.mttkrp(T, U, mode)
+        scale = _abs_scale(T, U, mode)
+        err = np.abs(got[mode - 1] - want)
+        assert np.all(np.isfinite(got[mode - 1]))
+        assert np.all(err <= TOL * scale + 1e-300), (mode, wm, float((err / (scale + 1e-300)).max()))
+
+
 @pytest.mark.parametrize("force", ["1", "0"])
 @pytest.mark.parametrize("dims,ranks,signed", [c for c in CASES if c[0][0] >= 16 and c[0][0] % 4 != 0] +
                          [((19, 6, 5), [2, 3], True), ((33, 4, 3), [16] * 3, False), ((255, 7, 3), [5, 9, 20], True)])
