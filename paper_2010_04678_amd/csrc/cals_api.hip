@@ -148,6 +148,8 @@ struct cals_ctx {
   double* d_lspart = nullptr;    // line search: per (slot position, mode, row block) partial sums
   double* d_updpart = nullptr;   // update of tall modes: per (slot position, row block) partial sums
   int32_t* d_nnfail = nullptr;   // non-negativity: per slot position, failure flag of the current mode update
+  int32_t* d_nnorder = nullptr;  // slot positions sorted for the non-negative update (NONNEG first, high ranks first)
+  int32_t* h_nnorder = nullptr;  // pinned
   std::deque<PendingModel> queue;
   std::vector<ActiveModel> active;
   std::vector<int> free_sids;
@@ -520,12 +522,17 @@ int ensure_nn_buffers(cals_ctx* c) {
   }
   ok = ok && hipMalloc(&c->d_nnfail, sizeof(int32_t) * c->capacity) == hipSuccess;
   if (ok) ok = hipMemsetAsync(c->d_nnfail, 0, sizeof(int32_t) * c->capacity, c->stream) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_nnorder, sizeof(int32_t) * c->capacity) == hipSuccess;
+  ok = ok && hipHostMalloc(&c->h_nnorder, sizeof(int32_t) * c->capacity) == hipSuccess;
+  if (ok) c->desc_dirty = true;      // the order travels with the descriptors
   if (!ok) {
     // nothing of a failed attempt stays behind: the next NONNEG model tries again from scratch
     (void)hipGetLastError();
     (void)hipStreamSynchronize(c->stream);
     for (int n = 0; n < c->nmodes; ++n) { (void)hipFree(c->passive[n]); c->passive[n] = nullptr; }
     (void)hipFree(c->d_nnfail); c->d_nnfail = nullptr;
+    (void)hipFree(c->d_nnorder); c->d_nnorder = nullptr;
+    (void)hipHostFree(c->h_nnorder); c->h_nnorder = nullptr;
     return CALS_E_NOMEM;
   }
   return CALS_OK;
@@ -594,6 +601,18 @@ int upload_desc(cals_ctx* c) {
     c->h_desc[k] = d;
   }
   if (n > 0) HIP_TRY(hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(ModelDesc) * n, hipMemcpyHostToDevice, c->stream));
+  if (c->d_nnorder && n > 0) {
+    // the non-negative update's grid order: NONNEG models first, highest rank first (a row's search costs about
+    // rank^2 per solve), ties in slot order
+    for (int k = 0; k < n; ++k) c->h_nnorder[k] = k;
+    std::stable_sort(c->h_nnorder, c->h_nnorder + n, [c](int32_t x, int32_t y) {
+      const ActiveModel& a = c->active[x];
+      const ActiveModel& b = c->active[y];
+      const int ka = (a.flags & CALS_MODEL_NONNEG) ? a.rank : 0, kb = (b.flags & CALS_MODEL_NONNEG) ? b.rank : 0;
+      return ka > kb;
+    });
+    HIP_TRY(hipMemcpyAsync(c->d_nnorder, c->h_nnorder, sizeof(int32_t) * n, hipMemcpyHostToDevice, c->stream));
+  }
   if (c->d_colmodel && n > 0) {
     for (int k = 0; k < n; ++k)
       for (int q = 0; q < c->active[k].rank; ++q) c->h_colmodel[c->active[k].col + q] = k;
@@ -811,7 +830,7 @@ int one_round(cals_ctx* c, int* retired_now, bool last_of_call) {
       // rows of the NONNEG models, solved into the spare multi-matrix (free between compactions)
       NnlsArgs na{};
       na.desc = c->d_desc; na.state = c->d_state; na.out = c->d_out; na.M = c->M; na.X = c->Ualt[mode];
-      na.passive = c->passive[mode]; na.fail = c->d_nnfail;
+      na.passive = c->passive[mode]; na.fail = c->d_nnfail; na.order = c->d_nnorder;
       na.In = (int)c->dims[mode]; na.ld = c->ld; na.mode = mode; na.nmodes = N; na.n_models = n; na.capacity = c->capacity; na.max_rank = nn_max_rank;
       HIP_TRY(launch_nnls(na, c->stream));
     }
@@ -984,7 +1003,7 @@ int cals_destroy(cals_ctx* c) {
   for (int n = 0; n < kMaxModes; ++n) (void)hipFree(c->Ychain[n]);
   (void)hipFree(c->M); (void)hipFree(c->workspace); (void)hipFree(c->d_desc); (void)hipFree(c->d_state);
   (void)hipFree(c->d_out); (void)hipFree(c->d_map); (void)hipFree(c->d_scratch); (void)hipFree(c->T_owned); (void)hipFree(c->d_updpart); (void)hipFree(c->d_lspart);
-  (void)hipFree(c->d_nnfail); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
+  (void)hipFree(c->d_nnfail); (void)hipFree(c->d_nnorder); (void)hipHostFree(c->h_nnorder); (void)hipFree(c->d_colmodel); (void)hipFree(c->d_accept); (void)hipHostFree(c->h_colmodel);
   (void)hipFree(c->d_sink); (void)hipFree(c->Y); (void)hipFree(c->Yprev); (void)hipFree(c->Ynew); (void)hipFree(c->d_ones);
   (void)hipFree(c->d_zeros); (void)hipFree(c->d_lambda); (void)hipFree(c->d_stage); (void)hipFree(c->d_rmap);
   (void)hipHostFree(c->h_desc); (void)hipHostFree(c->h_out); (void)hipHostFree(c->h_map);

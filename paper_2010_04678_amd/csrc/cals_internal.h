@@ -191,6 +191,7 @@ struct NnlsArgs {
   double* X;            // out: solved rows of the NONNEG models, row-major In x ld (other columns untouched)
   uint32_t* passive;    // per (row, sid) passive-set masks of this mode, In x capacity; read (warm start) and written
   int32_t* fail;        // per slot position; or-ed with 1 on failure
+  const int32_t* order; // slot positions in the order the grid takes them (costliest models first), n_models entries
   int In, ld, mode, n_models, capacity;
   int nmodes;           // tensor order
   int max_rank;         // largest rank among the NONNEG models of this launch

@@ -150,7 +150,7 @@ __device__ __forceinline__ void nnls_rows(const NnlsArgs& a, const ModelDesc& d,
 // RMAX = the largest rank class among the NONNEG models of the launch: the kernel's register budget is that of
 // its widest instantiation, so a queue of low-rank models runs with many more wavefronts per SIMD.
 template <int RM, int RMAX>
-__device__ __forceinline__ void nnls_class(const NnlsArgs& a, const ModelDesc& d, int row0, int row1, double* Hs) {
+__device__ __forceinline__ void nnls_class(const NnlsArgs& a, const ModelDesc& d, int slot, int row0, int row1, double* Hs) {
   if constexpr (RM <= RMAX) {
     const ModelState* st = a.state + d.sid;
     const int R = d.rank;
@@ -159,34 +159,38 @@ __device__ __forceinline__ void nnls_class(const NnlsArgs& a, const ModelDesc& d
       Hs[e] = (r < R && k < R) ? hadamard_of_others(st, a.nmodes, a.mode, r * R + k) : 0.0;
     }
     __syncthreads();
-    nnls_rows<RM>(a, d, blockIdx.y, row0, row1, threadIdx.x & 63, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), Hs);
+    nnls_rows<RM>(a, d, slot, row0, row1, threadIdx.x & 63, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), Hs);
   }
 }
 
 template <int RMAX>
 __global__ void __launch_bounds__(256) nnls_kernel(NnlsArgs a) {
   __shared__ double Hs[(RMAX + 1) * (RMAX + 1)];
-  // grid: x = row blocks (a mode can have millions of rows), y = slot positions (at most a few thousand)
-  const ModelDesc d = a.desc[blockIdx.y];
+  // grid: x = row blocks (a mode can have millions of rows), y = slot positions (at most a few thousand), taken in
+  // the order the host gives: workgroups are handed out y by y, and a launch ends with its last workgroup, so the
+  // models whose rows take longest (the highest ranks) go first
+  const int slot = a.order[blockIdx.y];
+  const ModelDesc d = a.desc[slot];
   if (!(d.flags & 1u)) return;
   if (a.out[d.sid].status != 0) return;
   const int row0 = blockIdx.x * a.rows_per_block;
   if (row0 >= a.In) return;
   const int row1 = (row0 + a.rows_per_block < a.In) ? (row0 + a.rows_per_block) : a.In;
   switch ((d.rank + 3) / 4) {           // register arrays sized to the rank rounded up to a multiple of 4
-    case 1: nnls_class<4, RMAX>(a, d, row0, row1, Hs); break;
-    case 2: nnls_class<8, RMAX>(a, d, row0, row1, Hs); break;
-    case 3: nnls_class<12, RMAX>(a, d, row0, row1, Hs); break;
-    case 4: nnls_class<16, RMAX>(a, d, row0, row1, Hs); break;
-    case 5: nnls_class<20, RMAX>(a, d, row0, row1, Hs); break;
-    case 6: nnls_class<24, RMAX>(a, d, row0, row1, Hs); break;
-    case 7: nnls_class<28, RMAX>(a, d, row0, row1, Hs); break;
-    default: nnls_class<32, RMAX>(a, d, row0, row1, Hs); break;
+    case 1: nnls_class<4, RMAX>(a, d, slot, row0, row1, Hs); break;
+    case 2: nnls_class<8, RMAX>(a, d, slot, row0, row1, Hs); break;
+    case 3: nnls_class<12, RMAX>(a, d, slot, row0, row1, Hs); break;
+    case 4: nnls_class<16, RMAX>(a, d, slot, row0, row1, Hs); break;
+    case 5: nnls_class<20, RMAX>(a, d, slot, row0, row1, Hs); break;
+    case 6: nnls_class<24, RMAX>(a, d, slot, row0, row1, Hs); break;
+    case 7: nnls_class<28, RMAX>(a, d, slot, row0, row1, Hs); break;
+    default: nnls_class<32, RMAX>(a, d, slot, row0, row1, Hs); break;
   }
 }
 
 hipError_t launch_nnls(const NnlsArgs& a0, hipStream_t stream) {
   if (a0.n_models < 1 || a0.In < 1) return hipSuccess;
+  if (!a0.order) return hipErrorInvalidValue;
   NnlsArgs a = a0;
   a.rows_per_block = kNnlsRowsPerBlock;
   if (a.n_models > 65535) return hipErrorInvalidValue;
