@@ -125,6 +125,8 @@ def main() -> int:
     ap.add_argument("--threads", type=int, default=max(1, (os.cpu_count() or 8)))
     ap.add_argument("--sample", default="", help="fixed-iteration configurations: comma-separated model ids to follow")
     ap.add_argument("--entries", type=int, default=48, help="sampled factor entries stored per followed model and mode")
+    ap.add_argument("--factors", action="store_true",
+                    help="queue configurations: also store lambda and --entries sampled factor entries per mode of EVERY model")
     ap.add_argument("--out", default="")
     a = ap.parse_args()
     cfg = get_config(a.cfg)
@@ -147,8 +149,8 @@ def main() -> int:
     rng = np.random.default_rng(7000 + a.cfg)
     with open(out, "w") as f:
         f.write("# Configuration %d at full size, as specified, run by the CPU oracle (lock-step queue of Alg. 3).\n" % a.cfg)
-        f.write("# Written by tests/golden/make_full_config_goldens.py --cfg %d%s; calls only oracle/ and workloads/.\n"
-                % (a.cfg, (" --sample " + a.sample) if a.sample else ""))
+        f.write("# Written by tests/golden/make_full_config_goldens.py --cfg %d%s%s; calls only oracle/ and workloads/.\n"
+                % (a.cfg, (" --sample " + a.sample) if a.sample else "", (" --factors --entries %d" % a.entries) if a.factors else ""))
         f.write("# model lines: id rank iters status ls_accepted fit error tol_margin ls_margin\n")
         f.write("input_sha256 %s\n" % digest)
         f.write("norm_sq %s\n" % fmt(normT2))
@@ -161,6 +163,7 @@ def main() -> int:
                                                            fmt(r["fit"]), fmt(r["err"]), fmt(r["tol_margin"]), fmt(r["ls_margin"])))
             if only is not None:
                 f.write("fits %d %s\n" % (k, " ".join(fmt(x) for x in r["fits"])))
+            if only is not None or a.factors:
                 f.write("lambda %d %s\n" % (k, " ".join(fmt(x) for x in r["lam"])))
                 for n, U in enumerate(r["U"]):
                     rows = rng.integers(0, U.shape[0], a.entries)

@@ -158,6 +158,24 @@ def check_against_golden(res, g, cfg, what):
     return loose
 
 
+def check_stored_factors(res, facs, g, loose, what):
+    """lambda and the sampled factor entries the stored oracle run holds, for every model that has them and whose
+    decisions are not at rounding level (columns have unit norm, so an entry-wise bound is relative to the column)."""
+    by_id = {r.model_id: r for r in res}
+    checked = 0
+    for k in sorted(g["lam"]):
+        if k in loose or by_id[k].iters != g["models"][k]["iters"]:
+            continue
+        U, lam = facs[k]
+        want = g["lam"][k]
+        assert np.all(np.abs(lam - want) <= FACTOR_TOL * np.maximum(np.abs(want), 1e-300)), (what, k, lam, want)
+        for n in range(3):
+            for i, c, v in g["entries"][(k, n)]:
+                assert abs(U[n][i, c] - v) <= FACTOR_TOL, (what, k, n, i, c, U[n][i, c], v)
+        checked += 1
+    return checked
+
+
 def fused_inputs(cfg, models):
     import torch
     dims = cfg.dims
@@ -246,9 +264,11 @@ def test_config3_full():
     full_mttkrp_check(T, cfg, models, 31)
     g = read_golden(3, T, models)
     sample = [0, 7, 16, 22, 41, 59]                                # ranks 1, 3, 6, 8, 14, 20
-    res, facs, st = gpu_run(T, models, cfg, keep=sample)
+    res, facs, st = gpu_run(T, models, cfg)
     assert abs(st.tensor_norm_sq - g["norm_sq"]) <= 1e-12 * g["norm_sq"]
     loose = check_against_golden(res, g, cfg, "cfg 3")
+    # lambda and sampled factor entries of ALL 60 models against the stored run
+    assert check_stored_factors(res, facs, g, loose, "cfg 3") >= len(models) - len(loose) == len(g["lam"]) - len(loose)
     assert all(r.status in (O.CONVERGED, O.MAX_ITERS) for r in res) and st.rounds == max(r.iters for r in res)
     assert min(u.min() for u in facs[59][0]) >= 0.0
     live = [k for k in sample if k not in loose]
