@@ -325,17 +325,20 @@ def test_config5_full():
     full_mttkrp_check(T, cfg, models[:cfg.max_slots], 51, signed=True)
     g = read_golden(5, T, models)
     sample = [0, 3, 12, 25, 77, 140, 199]                          # ranks 1, 1, 2, 3, 8, 15, 20
-    res, facs, st = gpu_run(T, models, cfg, keep=sample)
+    res, facs, st = gpu_run(T, models, cfg)
     loose = check_against_golden(res, g, cfg, "cfg 5")
     assert all(r.status in (O.CONVERGED, O.MAX_ITERS) for r in res)
+    # lambda and sampled factor entries of ALL 200 models against the stored run
+    assert check_stored_factors(res, facs, g, loose, "cfg 5") >= len(models) - len(loose) == len(g["lam"]) - len(loose)
     if not loose:
         assert st.rounds == g["rounds"]
     live = [k for k in sample if k not in loose]
     ref = O.cals(T, [models[k] for k in live], cfg.max_total_rank, cfg.max_slots)
     check_models(res, facs, models, ref, live)
     # the same job with two-step sweeps (line-search MTTKRP included): same decisions, fits and factors
-    res2, facs2, st2 = gpu_run(T, models, cfg, keep=sample, ctx_flags=P.CTX_REUSE)
+    res2, facs2, st2 = gpu_run(T, models, cfg, ctx_flags=P.CTX_REUSE)
     loose2 = check_against_golden(res2, g, cfg, "cfg 5, two-step")
+    assert check_stored_factors(res2, facs2, g, loose2, "cfg 5, two-step") >= len(models) - len(loose2)
     check_models(res2, facs2, models, ref, [k for k in live if k not in loose2])
 
 
