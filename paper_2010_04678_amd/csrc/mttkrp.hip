@@ -397,8 +397,12 @@ static bool rows_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& t
         int64_t chunk = (K + 4 * nsb - 1) / (4 * nsb);
         chunk = (chunk + 15) / 16 * 16;
         const int64_t nsb_eff = (K + 4 * chunk - 1) / (4 * chunk);
-        const int64_t blocks = (int64_t)nrb * ncg * nsb_eff;
-        const int64_t rounds = (blocks + num_cus - 1) / num_cus;
+        // (row block, split) pairs go to the 8 XCDs in turn, each with all its column groups; a workgroup has a
+        // compute unit to itself, so the busiest XCD sets the number of rounds (200^3 at 192 columns: 42 splits x 6
+        // groups put 36 workgroups on two XCDs of 32 compute units and took 119 us; 40 splits take 77)
+        const int64_t per_xcd = ((int64_t)nrb * nsb_eff + 7) / 8 * ncg;
+        const int64_t cus_per_xcd = std::max<int64_t>(1, num_cus / 8);
+        const int64_t rounds = (per_xcd + cus_per_xcd - 1) / cus_per_xcd;
         const double compute_us = (double)rounds * ((double)(chunk / 16) * stage_us + 3.0);
         const double mem_us = std::max(hbm_us, (double)ncg * tensor_bytes / 6.0e6);
         double cost = std::max(compute_us, mem_us);
