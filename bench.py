@@ -26,7 +26,9 @@ its job starts with (cfg5: also at the full buffer width, 640); `mttkrp300` does
 These are the launches whose counters profiles/short_modes_mttkrp.md holds.
 
 `--workload splitscan` / `ridgescan` time the fused MTTKRP under forced plans (split counts on the cache-resident
-short-mode shapes; row tiles per wavefront x split counts at widths 32-96 on 1000^3): profiles/forced_plan_scans.md.
+short-mode shapes; row tiles per wavefront x split counts at widths 32-96 on 1000^3); `--workload kernelscan` times
+the planner's choice against the tile kernel and the rows kernel forced over a grid of shapes and widths:
+profiles/forced_plan_scans.md.
 
 `--workload order4` / `order5` time the path on a tensor of order 4 (180^4) / 5 (60^5), 8.4 and 6.2 GB: the fused
 MTTKRP alone per mode at several widths (contraction kernel by events, and the whole call including the explicit
@@ -298,6 +300,61 @@ def run_scan(which: str) -> dict:
             "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "rows": rows}
 
 
+# Planner's choice against each kernel forced (CALS_MTTKRP_KERNEL = 1 tile kernel, 2 rows kernel wherever it can
+# run): the grid the rows kernel's selection rule was fitted to.  (dims, modes, widths)
+KERNEL_SCAN_WIDTHS = [48, 64, 80, 96, 112, 128, 144, 160, 176, 192, 208, 224, 240, 256, 320, 420]
+KERNEL_SCAN = [((200, 200, 200), [1, 2], KERNEL_SCAN_WIDTHS + [512, 640, 1024]), ((160, 160, 160), [1, 3], KERNEL_SCAN_WIDTHS),
+               ((128, 300, 300), [1], KERNEL_SCAN_WIDTHS), ((4000, 200, 50), [2, 3], KERNEL_SCAN_WIDTHS + [512, 640]),
+               ((100, 100, 100), [1, 3], KERNEL_SCAN_WIDTHS), ((64, 512, 512), [1], KERNEL_SCAN_WIDTHS),
+               ((300, 300, 40), [1, 2, 3], [64, 128, 192, 256, 320, 420, 512, 630]), ((208, 64, 1000), [1], KERNEL_SCAN_WIDTHS),
+               ((96, 400, 400), [1], KERNEL_SCAN_WIDTHS), ((300, 300, 300), [1, 2], [64, 128, 256, 420]),
+               ((500, 500, 500), [1, 3], [64, 128, 256, 420]), ((180, 180, 2000), [1, 2], [64, 128, 256, 420]),
+               ((1000, 1000, 1000), [1, 2, 3], [16, 32, 64, 128])]
+
+
+def run_kernel_scan() -> dict:
+    import torch
+    import paper_2010_04678_amd as P
+    rows = []
+    for dims, modes, widths in KERNEL_SCAN:
+        g = torch.Generator(device="cuda:0")
+        g.manual_seed(1)
+        T = torch.rand(dims[::-1], dtype=torch.float64, device="cuda:0", generator=g)
+        flops1 = 2.0 * dims[0] * dims[1] * dims[2]
+        first = True
+        for width in widths:
+            ld = (width + 15) // 16 * 16
+            U = [torch.rand((d, ld), dtype=torch.float64, device="cuda:0", generator=g) for d in dims]
+            rec = {"dims": list(dims), "width": width, "modes": modes}
+            for name, forced in ([("warm", None)] if first else []) + [("planner", None), ("tile", "1"), ("rows", "2")]:
+                for k in [k for k in os.environ if k.startswith("CALS_MTTKRP_")]:
+                    del os.environ[k]
+                if forced:
+                    os.environ["CALS_MTTKRP_KERNEL"] = forced
+                ctx = P.Context(max_total_rank=width, flags=P.CTX_TIMING)
+                os.environ.pop("CALS_MTTKRP_KERNEL", None)
+                ctx.submit_tensor(T)
+                ms = []
+                for mode in modes:
+                    M = torch.zeros((dims[mode - 1], ld), dtype=torch.float64, device="cuda:0")
+                    c, r, _, _, _ = steady_mttkrp(ctx, mode, U, M, width)
+                    ms.append(c + r)
+                st = ctx.stats()
+                ctx.close()
+                if name != "warm":
+                    rec[name + "_ms"] = ms
+                    rec[name + "_tflops"] = [flops1 * width / (m * 1e-3) * 1e-12 for m in ms]
+                    if name == "planner":
+                        rec["planner_rows_kernel_launches"] = int(st.mttkrp_rows_launches)
+                        rec["planner_launches"] = int(sum(st.mttkrp_launches))
+            first = False
+            rows.append(rec)
+        del T
+        torch.cuda.empty_cache()
+    return {"metric": "fused MTTKRP alone: the planner's choice against each kernel forced (contraction + reduction, steady state)",
+            "workload": "kernelscan", "peak_mfma_tflops": PEAK_FP64_MFMA_TFLOPS, "rows": rows}
+
+
 def settled_job(cid: int, T_dev, reuse: bool = False) -> dict:
     """run_job; a job shorter than a quarter of a second is run a second time and that run is reported (the first run of
     a few milliseconds also pays for loading the kernels it is the first to launch, which is no part of its rate)."""
@@ -495,6 +552,9 @@ def main() -> int:
         return 0
     if args.workload in SCANS:
         print(json.dumps(run_scan(args.workload)))
+        return 0
+    if args.workload == "kernelscan":
+        print(json.dumps(run_kernel_scan()))
         return 0
     if args.workload in ORDER_N:
         print(json.dumps(run_order_n(args.workload, min(args.steps, 10), args.warmup)))
