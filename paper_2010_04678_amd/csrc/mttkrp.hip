@@ -370,14 +370,14 @@ static bool rows_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& t
         if (tpb <= wmb) break;
       }
       nrb = (tiles_m + tpb - 1) / tpb;
-      // Measured against the tile kernel in steady state (twelve shapes from 100^3 to 1000^3, widths 16 to 1024,
+      // Measured against the tile kernel in steady state (thirteen shapes from 100^3 to 1000^3, widths 16 to 1024,
       // every mode).  Tensors the last-level cache holds (up to 256 MiB): the modelled times of the two kernels pick
-      // the faster one, or one within a few per cent of it, in nearly every case (mean loss 0.6 %), so nothing else
+      // the faster one, or one within a few per cent of it, in nearly every case (mean loss 0.8 %), so nothing else
       // is asked -- except of launches of a few microseconds (32^3), which stay with the tile kernel.  Larger tensors:
-      // this kernel wins only where one row block holds the whole mode and the column groups are few -- every group
-      // reads the whole tensor, and beyond about eight groups the caches behind L1 no longer keep up -- and a row
-      // block that leaves more than a sixth of the variant's row tiles empty loses too; 500^3, 180 x 180 x 2000 and
-      // 1000^3 are 5 to 40 % slower with it at every width.
+      // only a row block that holds the whole mode and leaves at most a sixth of the variant's row tiles empty
+      // (4000 x 200 x 50, mode 2: 13 row tiles in one block 2-13 % faster than the tile kernel at 33 of 35 widths from
+      // 96 to 640, two blocks of 7 up to 12 % slower); every column group reads the whole tensor, which the model
+      // charges: 500^3, 180 x 180 x 2000 and 1000^3 are 5 to 40 % slower with this kernel at every width.
       const bool forced = tune.kernel == 2;
       const bool cache_resident = tensor_bytes <= 268435456.0;
       if (!forced && (double)p.In * (double)K * p.ncols < (cache_resident ? 1.0e7 : 1.0e8)) continue;
@@ -386,7 +386,6 @@ static bool rows_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& t
       const int ncg = (tiles_n + wnb - 1) / wnb;
       const int fewer = ncg * wnb - tiles_n;
       if (fewer > ncg || (wnb == 1 && fewer > 0)) continue;
-      if (!forced && !cache_resident && ncg > 8) continue;
       // Workgroup-level splits by modelled time.  A wavefront's stage is wmb x wnb accumulator tiles (all of the
       // variant's row tiles are computed, live or not) x 4 matrix instructions of 64 cycles, at the 72 % of the issue
       // rate these kernels reach; a workgroup pays a fixed 3 us (first loads, the exchange of the four accumulator
@@ -434,10 +433,7 @@ MttkrpPlan mttkrp_plan(const MttkrpProblem& p, int num_cus, const MttkrpTuning& 
   MttkrpPlan rows{};
   if (!rows_plan(p, num_cus, tune, &rows)) return tiles;
   if (tune.kernel == 2) return rows;
-  // for tensors beyond the last-level cache the rows kernel has to win clearly (its model is the less calibrated
-  // one there); for cache-resident ones the plain comparison did best on the measured grid
-  const bool cache_resident = (double)p.In * (double)p.Ia * (double)p.Ib * 8.0 <= 268435456.0;
-  return rows.cost_us < (cache_resident ? 1.0 : 0.95) * tiles.cost_us ? rows : tiles;
+  return rows.cost_us < tiles.cost_us ? rows : tiles;
 }
 
 // Records a timing event; a failed record only marks the launch as untimed (the error is cleared, the work goes on).
